@@ -1,0 +1,133 @@
+"""Seeded synthetic-input generator (host side, numpy).
+
+This module produces the *inputs* of the decode-attention path -- activations
+q, new K/V rows and sequence lengths -- and nothing else.  It contains none of
+the method's arithmetic (no quantizer, no layout, no attention).  The CPU
+oracle's tests and the HIP path's tests both draw their inputs from here, so
+that both sides see bit-identical source values.  ``gen.hip`` next to this file
+implements exactly the same counter-based generator on the device, so that tens
+of GiB of KV can be produced in HBM without crossing PCIe.
+
+Generator definition (all integer arithmetic modulo 2**64):
+
+    mix64(z): z ^= z >> 30; z *= 0xBF58476D1CE4E5B9; z ^= z >> 27;
+              z *= 0x94D049BB133111EB; z ^= z >> 31          (splitmix64 finalizer)
+    key  = mix64(mix64(seed ^ GOLD*(model+1)) + (layer << 34) + (which << 32) + seq)
+    word(w) = mix64(key + GOLD*(w+1))
+    element e = (pos*H + head)*D + dim  takes 16 bits of word(e >> 2):
+    u = (word >> 16*(e & 3)) & 0xFFFF ;  x = TABLE[u]
+
+TABLE[i] = float32(Phi^-1((i + 0.5) / 65536)), a 65536-entry inverse-normal
+table, so the elements are N(0,1) deviates truncated to about +-4.17.  The table
+is built once on the host (scipy) and the very same array is uploaded for the
+device generator, so no transcendental function is evaluated twice.
+
+``which``: 0 = K rows, 1 = V rows, 2 = q.
+"""
+from __future__ import annotations
+
+import functools
+
+import numpy as np
+
+GOLD = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+MASTER_SEED = 20250906
+
+WHICH_K, WHICH_V, WHICH_Q = 0, 1, 2
+
+
+def mix64(z):
+    """splitmix64 output function on uint64 scalars or arrays."""
+    with np.errstate(over="ignore"):
+        z = np.asarray(z, dtype=np.uint64)
+        z = z ^ (z >> np.uint64(30))
+        z = z * _M1
+        z = z ^ (z >> np.uint64(27))
+        z = z * _M2
+        z = z ^ (z >> np.uint64(31))
+    return z
+
+
+@functools.lru_cache(maxsize=1)
+def normal_table() -> np.ndarray:
+    """The 65536-entry float32 inverse-normal table shared by host and device."""
+    from scipy.special import ndtri
+
+    i = np.arange(65536, dtype=np.float64)
+    t = ndtri((i + 0.5) / 65536.0).astype(np.float32)
+    t.setflags(write=False)
+    return t
+
+
+def stream_key(seed: int, model: int, layer: int, which: int, seq) -> np.ndarray:
+    """Key of one (model, layer, K|V|q, sequence) stream; ``seq`` may be an array."""
+    with np.errstate(over="ignore"):
+        a = mix64(np.uint64(seed) ^ (GOLD * np.uint64(model + 1)))
+        seq = np.asarray(seq, dtype=np.uint64)
+        b = a + (np.uint64(layer) << np.uint64(34)) + (np.uint64(which) << np.uint64(32)) + seq
+    return mix64(b)
+
+
+def _u16(key, e):
+    """16-bit draw for element counters ``e`` (uint64 array) under ``key``."""
+    with np.errstate(over="ignore"):
+        w = mix64(key + GOLD * ((e >> np.uint64(2)) + np.uint64(1)))
+        sh = (e & np.uint64(3)) * np.uint64(16)
+    return ((w >> sh) & np.uint64(0xFFFF)).astype(np.int64)
+
+
+def normal_rows(seed: int, model: int, layer: int, which: int, seq: int, pos, n_heads: int,
+                head_dim: int) -> np.ndarray:
+    """float32 [len(pos)][n_heads][head_dim] source rows of one sequence.
+
+    Row ``i`` is the K (which=0) or V (which=1) vector of token position
+    ``pos[i]`` of global sequence number ``seq``.
+    """
+    pos = np.asarray(pos, dtype=np.uint64).reshape(-1)
+    key = stream_key(seed, model, layer, which, seq)
+    hd = np.uint64(n_heads * head_dim)
+    e = pos[:, None] * hd + np.arange(n_heads * head_dim, dtype=np.uint64)[None, :]
+    x = normal_table()[_u16(key, e)]
+    return x.reshape(len(pos), n_heads, head_dim)
+
+
+def normal_q(seed: int, model: int, layer: int, seq_ids, n_q_heads: int, head_dim: int) -> np.ndarray:
+    """float16 [n_seq][n_q_heads][head_dim] query activations (N(0,1) rounded to fp16)."""
+    seq_ids = np.asarray(seq_ids, dtype=np.int64).reshape(-1)
+    out = np.empty((len(seq_ids), n_q_heads, head_dim), dtype=np.float16)
+    for i, s in enumerate(seq_ids):
+        out[i] = normal_rows(seed, model, layer, WHICH_Q, int(s), [0], n_q_heads, head_dim)[0].astype(np.float16)
+    return out
+
+
+def _draw64(seed: int, tag: int, n: int) -> np.ndarray:
+    key = stream_key(seed, 0xFFFF, 0, 3, tag)
+    with np.errstate(over="ignore"):
+        return mix64(key + GOLD * (np.arange(n, dtype=np.uint64) + np.uint64(1)))
+
+
+def uniform_lengths(seed: int, tag: int, n: int, lo: int, hi: int) -> np.ndarray:
+    """n integer lengths uniform in [lo, hi] (inclusive)."""
+    w = _draw64(seed, tag, n)
+    return (lo + (w % np.uint64(hi - lo + 1)).astype(np.int64)).astype(np.int32)
+
+
+def lognormal_lengths(seed: int, tag: int, n: int, median: float, sigma: float, cap: int) -> np.ndarray:
+    """n lengths round(median*exp(sigma*z)), z ~ N(0,1) from the table, clamped to [1, cap]."""
+    w = _draw64(seed, tag, n)
+    z = normal_table()[(w & np.uint64(0xFFFF)).astype(np.int64)].astype(np.float64)
+    ln = np.rint(median * np.exp(sigma * z))
+    return np.clip(ln, 1, cap).astype(np.int32)
+
+
+def uniform_ints(seed: int, tag: int, n: int, hi: int) -> np.ndarray:
+    """n integers uniform in [0, hi) -- used for churn traces and shuffles."""
+    w = _draw64(seed, tag, n)
+    return (w % np.uint64(hi)).astype(np.int64)
+
+
+def permutation(seed: int, tag: int, n: int) -> np.ndarray:
+    """A seeded permutation of range(n) (argsort of n 64-bit draws)."""
+    return np.argsort(_draw64(seed, tag, n), kind="stable").astype(np.int64)
