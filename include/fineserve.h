@@ -1,0 +1,183 @@
+/*
+ * fineserve.h -- C ABI of the KV-slab decode-attention library for AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path implied by FineServe's KV Slab
+ * (arXiv 2509.06261, Sec. 5): one pre-allocated shared KV tensor per GPU, carved into
+ * fixed-byte slabs; every co-located model formats slabs into blocks of its own token
+ * layout (Sec. 3.2: block size = TokensPerBlock x TokenSize + Quant.Params) and indexes
+ * them through its own logical block table (Sec. 5.1 view mapping, Sec. 5.2 block-id
+ * equation).  On top of that pool it runs the decode-phase attention read that Sec. 2.1
+ * names as the memory-bound bottleneck, for KV stored as FP16, FP8-E4M3, INT8 or packed
+ * INT4 (the KV formats of Sec. 2.2).
+ *
+ * Conventions
+ *  - Every function returns FS_OK (0) or a negative fs_status; nothing throws or aborts.
+ *    fs_last_error() gives a thread-local text for the last failure.
+ *  - Arguments are validated on the host before any kernel is launched.
+ *  - "device pointer" = HIP device memory of the current device; "host pointer" = ordinary
+ *    process memory.  The library never frees caller memory.
+ *  - Device calls are asynchronous on the given hipStream_t (passed as void*; NULL = the
+ *    default stream).  The caller keeps every buffer alive until the stream has passed the call.
+ *  - A pool is driven by one host thread at a time (one slab manager per GPU, Sec. 4).
+ */
+#ifndef FINESERVE_H_
+#define FINESERVE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fs_pool fs_pool; /* opaque, owned by the library, released by fs_pool_destroy */
+typedef int32_t fs_model_t;     /* small index, valid until fs_model_unregister */
+
+enum fs_kv_dtype { FS_KV_FP16 = 0, FS_KV_FP8_E4M3 = 1, FS_KV_INT8 = 2, FS_KV_INT4 = 3 };
+enum fs_src_dtype { FS_SRC_FP16 = 0, FS_SRC_FP32 = 1 };
+enum fs_status {
+  FS_OK = 0,
+  FS_ERR_INVALID = -1, /* bad argument */
+  FS_ERR_NOMEM = -2,   /* pool exhausted / workspace too small */
+  FS_ERR_STATE = -3,   /* double free, block of another model, model still holds blocks */
+  FS_ERR_DEVICE = -4   /* a HIP call failed; see fs_last_error() */
+};
+enum fs_slab_state { FS_SLAB_FREE = 0, FS_SLAB_PARTIAL = 1, FS_SLAB_FULL = 2 };
+
+/* Block layout of one model (all sizes in bytes).  A block holds tokens_per_block tokens of
+ * every layer: layers consecutive, inside a layer the KV heads consecutive, inside a head
+ * chunk  K tile | V tile | K params | V params,  a tile row being one token's head_dim
+ * elements (INT4: element 2j in the low nibble of byte j).  Params per token: INT8 one fp16
+ * scale; INT4 fp16 scale then fp16 zero-point; FP16/FP8 none.  (Sec. 3.2 fixes only the two
+ * size equations; this byte layout is the library's own.) */
+typedef struct {
+  int32_t kv_dtype, n_kv_heads, head_dim, n_layers;
+  int32_t tokens_per_block, param_bytes;
+  int32_t blocks_per_slab, reserved;
+  uint64_t block_budget; /* bytes reserved per block; block b starts at b * block_budget */
+  uint64_t row_bytes, kv_tile, par_tile, head_chunk, layer_bytes, block_bytes;
+} fs_geometry_t;
+
+typedef struct {
+  int64_t n_slabs, slabs_free, slabs_partial, slabs_full;
+  int64_t live_blocks;   /* over all models */
+  int64_t n_models;
+  uint64_t stranded_bytes; /* bytes of live blocks not covered by their layout (budget - block_bytes) */
+} fs_pool_stats_t;
+
+/* ---- Pool (Sec. 5.1: one pre-allocated shared KV tensor per GPU, uniform slabs) -------------
+ * slab_bytes: multiple of 256.  pool_bytes: multiple of slab_bytes, pool_bytes/slab_bytes < 2^31.
+ * device_base: device pointer to pool_bytes bytes, 256-byte aligned, owned by the caller and
+ * outliving the pool; or NULL, in which case the library allocates (and later frees) the memory.
+ * The memory is not cleared.  *out receives the pool. */
+int fs_pool_create(uint64_t slab_bytes, uint64_t pool_bytes, void* device_base, fs_pool** out);
+int fs_pool_destroy(fs_pool* pool);
+/* Device address of the pool's first byte (for tests that inspect slab bytes). */
+void* fs_pool_base(fs_pool* pool);
+
+/* ---- Models (Sec. 3.2 equations, inverted: the block byte budget is fixed, tokens derived) --
+ * Registers a model whose blocks take one whole slab each (fs_model_register) or
+ * block_budget_bytes each (fs_model_register_ex; must divide slab_bytes and be a multiple of
+ * 256), and returns tokens_per_block (> 0) or a negative fs_status.  n_kv_heads is the per-GPU
+ * (post tensor-parallel) count, as in the token-size equation.  head_dim must be a power of
+ * two between 8 and 512.  *out receives the model index.  At most 64 models per pool. */
+int fs_model_register(fs_pool* pool, int kv_dtype, int n_kv_heads, int head_dim, int n_layers, fs_model_t* out);
+int fs_model_register_ex(fs_pool* pool, int kv_dtype, int n_kv_heads, int head_dim, int n_layers,
+                         uint64_t block_budget_bytes, fs_model_t* out);
+/* FP8 models: static fp32 scales per (layer, KV head), separate for K and V; host pointers to
+ * [n_layers][n_kv_heads] floats, all > 0.  Copied to the device synchronously.  Must be called
+ * before the first append/attention of an FP8 model. */
+int fs_model_set_fp8_scales(fs_pool* pool, fs_model_t model, const float* k_scale, const float* v_scale);
+int fs_model_unregister(fs_pool* pool, fs_model_t model); /* FS_ERR_STATE while it holds blocks */
+int fs_model_geometry(fs_pool* pool, fs_model_t model, fs_geometry_t* out);
+
+/* ---- Slab bookkeeping (Sec. 5.2), host only: no device work and no driver calls ------------
+ * fs_block_alloc: takes a free block of a PARTIAL slab keyed to this model (lowest slab id,
+ * lowest local id), else carves the most recently freed FREE slab (initially slab 0, 1, 2, ...);
+ * returns Blk ID = slab ID x blocks_per_slab + local block ID.  FS_ERR_NOMEM leaves the pool
+ * unchanged.  fs_block_free: FS_ERR_STATE for a block that is not live or not this model's;
+ * a slab whose last block is freed returns to the shared tensor as FREE. */
+int fs_block_alloc(fs_pool* pool, fs_model_t model, int32_t* blk_id_out);
+int fs_block_free(fs_pool* pool, fs_model_t model, int32_t blk_id);
+int fs_pool_stats(fs_pool* pool, fs_pool_stats_t* out);
+/* Copies the slab table for bit-exact comparison: state/key(model or -1)/used per slab
+ * ([n_slabs] each) and the free stack bottom-to-top ([n_slabs] capacity, *n_free entries). */
+int fs_pool_dump(fs_pool* pool, int32_t* slab_state, int32_t* slab_key, int32_t* slab_used, int32_t* free_stack,
+                 int64_t* n_free);
+/* Occupancy of every block id of a model: live[n_slabs * blocks_per_slab] bytes, 0 or 1. */
+int fs_model_dump_live(fs_pool* pool, fs_model_t model, uint8_t* live);
+
+/* ---- fs_kv_append (Sec. 2.1: every new token appends its keys and values) -------------------
+ * Quantizes the new K/V rows of n_tokens tokens of one layer and scatters them, with their
+ * per-token parameters, into the slab blocks named by the block tables.
+ *   k_new, v_new : device, [n_tokens][n_kv_heads][head_dim], fp16 or fp32 (src_dtype)
+ *   seq_idx, pos : device int32 [n_tokens]; token i is position pos[i] of sequence seq_idx[i]
+ *   block_tables : device int32 [n_seq][max_blocks]; entry [s][p / tokens_per_block] is the Blk ID
+ * Quantizers (fp32, round-to-nearest-even, true division; finite inputs):
+ *   FP16: nearest fp16.   FP8: nearest E4M3 of x / scale[layer][head], saturating at +-448.
+ *   INT8: s = fp16(amax/127) per (token, head) (1 if that is 0), q = clamp(rne(x/s), -127, 127).
+ *   INT4: lo = min(x, 0), hi = max(x, 0) over the row, s = fp16((hi-lo)/15) (1 if 0),
+ *         z = clamp(rne(-lo/s), 0, 15), q = clamp(rne(x/s) + z, 0, 15); z stored as fp16.
+ * Two tokens of one call must not name the same (sequence, position). */
+int fs_kv_append(fs_pool* pool, fs_model_t model, int layer, const void* k_new, const void* v_new, int src_dtype,
+                 const int32_t* seq_idx, const int32_t* pos, const int32_t* block_tables, int max_blocks,
+                 int64_t n_tokens, void* stream);
+
+/* ---- Decode attention (Sec. 2.1 / 2.3: one query per sequence reads all its cached tokens
+ * through the block table as if the KV were contiguous) ---------------------------------------
+ * For sequence b (length n_b >= 1), query head h, KV head g = h / (n_q_heads / n_kv_heads):
+ *   s_t = sm_scale * <q[b][h], K^[b][t][g]>,  p = softmax_t(s),  out[b][h] = sum_t p_t V^[b][t][g]
+ * with K^, V^ the dequantized cache.  Long sequences are split along t over several
+ * workgroups (split-K) and merged.
+ *   q, out       : device fp16 [n_seq][n_q_heads][head_dim]
+ *   block_tables : device int32 [n_seq][max_blocks]
+ *   seq_lens     : device int32 [n_seq], 1 <= n_b <= max_blocks * tokens_per_block
+ *   seq_lens_host: optional host copy of seq_lens, used only to size the workspace tightly
+ *   lse          : optional device fp32 [n_seq][n_q_heads], receives max_t s_t + ln sum_t e^(s_t - max)
+ * n_q_heads must be a multiple of n_kv_heads with ratio <= 16. */
+typedef struct {
+  fs_model_t model;
+  int32_t layer;
+  int32_t n_q_heads;
+  float sm_scale;
+  const void* q;
+  const int32_t* block_tables;
+  const int32_t* seq_lens;
+  const int32_t* seq_lens_host;
+  int32_t n_seq;
+  int32_t max_blocks;
+  void* out;
+  float* lse;
+} fs_batch_t;
+
+/* Bytes of device workspace fs_decode_attention[_multi] needs for these batches (0 on invalid
+ * arguments).  Without seq_lens_host the bound max_blocks * tokens_per_block is assumed for
+ * every sequence. */
+uint64_t fs_decode_workspace_bytes(fs_pool* pool, const fs_batch_t* batches, int n_batches);
+
+/* One model's batch.  workspace: device memory of at least fs_decode_workspace_bytes bytes,
+ * 256-byte aligned, private to this call until the stream has passed it. */
+int fs_decode_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,
+                        const int32_t* block_tables, const int32_t* seq_lens, int n_seq, int max_blocks, void* out,
+                        float* lse, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Several models' batches (host array, at most 8) in one launch over one work queue. */
+int fs_decode_attention_multi(fs_pool* pool, const fs_batch_t* batches, int n_batches, void* workspace,
+                              uint64_t workspace_bytes, void* stream);
+
+/* After the stream has passed a decode call: 0 if every sequence length was in range and the
+ * workspace sufficed, else a bit mask (1: length out of range, clamped; 2: workspace too small,
+ * affected sequences left unwritten).  Synchronizes the stream. */
+int fs_decode_status(const void* workspace, void* stream);
+
+/* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
+ * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
+int fs_set_kernel_mode(int mode);
+/* Target KV bytes per split-K work item (default 512 KiB); tokens per item are rounded to 32. */
+int fs_set_split_bytes(uint64_t bytes);
+
+const char* fs_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FINESERVE_H_ */

@@ -1,0 +1,275 @@
+"""Thin ctypes binding of libfineserve.so: argument marshalling only.
+
+Every function has the name and meaning of its C-ABI twin in include/fineserve.h.  Device
+buffers are torch tensors (torch owns device memory and names the stream); nothing is computed
+here.  Importing this module fails loudly when the HIP library has not been built -- there is no
+CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+FS_KV_FP16, FS_KV_FP8_E4M3, FS_KV_INT8, FS_KV_INT4 = 0, 1, 2, 3
+FS_SRC_FP16, FS_SRC_FP32 = 0, 1
+FS_OK, FS_ERR_INVALID, FS_ERR_NOMEM, FS_ERR_STATE, FS_ERR_DEVICE = 0, -1, -2, -3, -4
+FS_SLAB_FREE, FS_SLAB_PARTIAL, FS_SLAB_FULL = 0, 1, 2
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_DIR, "libfineserve.so")
+
+EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
+           "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
+           "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
+           "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_set_kernel_mode",
+           "fs_set_split_bytes", "fs_last_error"]
+
+
+class fs_geometry_t(ctypes.Structure):
+    _fields_ = [("kv_dtype", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_layers", ctypes.c_int32), ("tokens_per_block", ctypes.c_int32), ("param_bytes", ctypes.c_int32),
+                ("blocks_per_slab", ctypes.c_int32), ("reserved", ctypes.c_int32), ("block_budget", ctypes.c_uint64),
+                ("row_bytes", ctypes.c_uint64), ("kv_tile", ctypes.c_uint64), ("par_tile", ctypes.c_uint64),
+                ("head_chunk", ctypes.c_uint64), ("layer_bytes", ctypes.c_uint64), ("block_bytes", ctypes.c_uint64)]
+
+
+class fs_pool_stats_t(ctypes.Structure):
+    _fields_ = [("n_slabs", ctypes.c_int64), ("slabs_free", ctypes.c_int64), ("slabs_partial", ctypes.c_int64),
+                ("slabs_full", ctypes.c_int64), ("live_blocks", ctypes.c_int64), ("n_models", ctypes.c_int64),
+                ("stranded_bytes", ctypes.c_uint64)]
+
+
+class fs_batch_t(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_int32), ("layer", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("sm_scale", ctypes.c_float), ("q", ctypes.c_void_p), ("block_tables", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p), ("seq_lens_host", ctypes.c_void_p), ("n_seq", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                          "(python paper_2509_06261_amd/build.py); there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float
+    pi32 = ctypes.POINTER(ctypes.c_int32)
+    sig = {
+        "fs_pool_create": (i32, [u64, u64, vp, ctypes.POINTER(vp)]),
+        "fs_pool_destroy": (i32, [vp]),
+        "fs_pool_base": (vp, [vp]),
+        "fs_model_register": (i32, [vp, i32, i32, i32, i32, pi32]),
+        "fs_model_register_ex": (i32, [vp, i32, i32, i32, i32, u64, pi32]),
+        "fs_model_set_fp8_scales": (i32, [vp, i32, vp, vp]),
+        "fs_model_unregister": (i32, [vp, i32]),
+        "fs_model_geometry": (i32, [vp, i32, ctypes.POINTER(fs_geometry_t)]),
+        "fs_block_alloc": (i32, [vp, i32, pi32]),
+        "fs_block_free": (i32, [vp, i32, ctypes.c_int32]),
+        "fs_pool_stats": (i32, [vp, ctypes.POINTER(fs_pool_stats_t)]),
+        "fs_pool_dump": (i32, [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int64)]),
+        "fs_model_dump_live": (i32, [vp, i32, vp]),
+        "fs_kv_append": (i32, [vp, i32, i32, vp, vp, i32, vp, vp, vp, i32, i64, vp]),
+        "fs_decode_workspace_bytes": (u64, [vp, ctypes.POINTER(fs_batch_t), i32]),
+        "fs_decode_attention": (i32, [vp, i32, i32, i32, f32, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
+        "fs_decode_attention_multi": (i32, [vp, ctypes.POINTER(fs_batch_t), i32, vp, u64, vp]),
+        "fs_decode_status": (i32, [vp, vp]),
+        "fs_set_kernel_mode": (i32, [i32]),
+        "fs_set_split_bytes": (i32, [u64]),
+        "fs_last_error": (ctypes.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        f = getattr(L, name)
+        f.restype = res
+        f.argtypes = args
+    return L
+
+
+_L = _load()
+
+
+class FsError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        msg = _L.fs_last_error()
+        super().__init__(f"{where} failed with {code}: {msg.decode() if msg else ''}")
+
+
+def _dp(t):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def fs_last_error() -> str:
+    m = _L.fs_last_error()
+    return m.decode() if m else ""
+
+
+# ------------------------------------------------------------------ pool / models / blocks
+def fs_pool_create(slab_bytes: int, pool_bytes: int, device_base=None):
+    """device_base: a torch uint8 CUDA tensor of pool_bytes bytes (kept alive by the caller), a raw
+    address, or None to let the library allocate."""
+    out = ctypes.c_void_p()
+    base = device_base if isinstance(device_base, (int, type(None))) else _dp(device_base)
+    rc = _L.fs_pool_create(slab_bytes, pool_bytes, base, ctypes.byref(out))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_pool_create")
+    return out
+
+
+def fs_pool_destroy(pool):
+    return _L.fs_pool_destroy(pool)
+
+
+def fs_pool_base(pool) -> int:
+    return _L.fs_pool_base(pool)
+
+
+def fs_model_register(pool, kv_dtype, n_kv_heads, head_dim, n_layers, block_budget_bytes=None):
+    """Returns (tokens_per_block, model); block_budget_bytes selects fs_model_register_ex."""
+    m = ctypes.c_int32(-1)
+    if block_budget_bytes is None:
+        rc = _L.fs_model_register(pool, kv_dtype, n_kv_heads, head_dim, n_layers, ctypes.byref(m))
+    else:
+        rc = _L.fs_model_register_ex(pool, kv_dtype, n_kv_heads, head_dim, n_layers, block_budget_bytes,
+                                     ctypes.byref(m))
+    if rc < 0:
+        raise FsError(rc, "fs_model_register")
+    return rc, m.value
+
+
+def fs_model_set_fp8_scales(pool, model, k_scale, v_scale):
+    k = np.ascontiguousarray(k_scale, dtype=np.float32)
+    v = np.ascontiguousarray(v_scale, dtype=np.float32)
+    rc = _L.fs_model_set_fp8_scales(pool, model, k.ctypes.data, v.ctypes.data)
+    if rc != FS_OK:
+        raise FsError(rc, "fs_model_set_fp8_scales")
+
+
+def fs_model_unregister(pool, model) -> int:
+    return _L.fs_model_unregister(pool, model)
+
+
+def fs_model_geometry(pool, model) -> fs_geometry_t:
+    g = fs_geometry_t()
+    rc = _L.fs_model_geometry(pool, model, ctypes.byref(g))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_model_geometry")
+    return g
+
+
+def fs_block_alloc(pool, model):
+    """Returns (rc, blk_id)."""
+    out = ctypes.c_int32(-1)
+    rc = _L.fs_block_alloc(pool, model, ctypes.byref(out))
+    return rc, out.value
+
+
+def fs_block_free(pool, model, blk_id) -> int:
+    return _L.fs_block_free(pool, model, blk_id)
+
+
+def fs_pool_stats(pool) -> fs_pool_stats_t:
+    s = fs_pool_stats_t()
+    rc = _L.fs_pool_stats(pool, ctypes.byref(s))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_pool_stats")
+    return s
+
+
+def fs_pool_dump(pool):
+    """Returns (state, key, used, free_stack) int32 arrays."""
+    n = fs_pool_stats(pool).n_slabs
+    state, key, used, fstack = (np.empty(n, np.int32) for _ in range(4))
+    nf = ctypes.c_int64(0)
+    rc = _L.fs_pool_dump(pool, state.ctypes.data, key.ctypes.data, used.ctypes.data, fstack.ctypes.data,
+                         ctypes.byref(nf))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_pool_dump")
+    return state, key, used, fstack[: nf.value].copy()
+
+
+def fs_model_dump_live(pool, model) -> np.ndarray:
+    g = fs_model_geometry(pool, model)
+    live = np.empty(fs_pool_stats(pool).n_slabs * g.blocks_per_slab, np.uint8)
+    rc = _L.fs_model_dump_live(pool, model, live.ctypes.data)
+    if rc != FS_OK:
+        raise FsError(rc, "fs_model_dump_live")
+    return live
+
+
+# ------------------------------------------------------------------ device calls
+def fs_kv_append(pool, model, layer, k_new, v_new, seq_idx, pos, block_tables, stream=None):
+    """k_new/v_new: CUDA fp16 or fp32 [n_tokens][H][D]; seq_idx/pos: CUDA int32 [n_tokens];
+    block_tables: CUDA int32 [n_seq][max_blocks]."""
+    import torch
+    assert k_new.dtype == v_new.dtype and k_new.dtype in (torch.float16, torch.float32)
+    assert k_new.is_contiguous() and v_new.is_contiguous() and block_tables.is_contiguous()
+    assert seq_idx.dtype == torch.int32 and pos.dtype == torch.int32 and block_tables.dtype == torch.int32
+    rc = _L.fs_kv_append(pool, model, layer, _dp(k_new), _dp(v_new),
+                         FS_SRC_FP32 if k_new.dtype == torch.float32 else FS_SRC_FP16, _dp(seq_idx), _dp(pos),
+                         _dp(block_tables), block_tables.shape[1], seq_idx.numel(), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_kv_append")
+
+
+def make_batch(model, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, out, lse=None,
+               seq_lens_host=None) -> fs_batch_t:
+    """Fill an fs_batch_t from torch tensors (which the caller keeps alive)."""
+    import torch
+    assert q.dtype == torch.float16 and out.dtype == torch.float16 and q.is_contiguous() and out.is_contiguous()
+    assert block_tables.dtype == torch.int32 and seq_lens.dtype == torch.int32 and block_tables.is_contiguous()
+    b = fs_batch_t()
+    b.model, b.layer, b.n_q_heads, b.sm_scale = model, layer, n_q_heads, sm_scale
+    b.q, b.block_tables, b.seq_lens = _dp(q), _dp(block_tables), _dp(seq_lens)
+    if seq_lens_host is not None:
+        assert isinstance(seq_lens_host, np.ndarray) and seq_lens_host.dtype == np.int32
+        b.seq_lens_host = seq_lens_host.ctypes.data
+    b.n_seq, b.max_blocks = seq_lens.numel(), block_tables.shape[1]
+    b.out, b.lse = _dp(out), _dp(lse)
+    return b
+
+
+def fs_decode_workspace_bytes(pool, batches) -> int:
+    arr = (fs_batch_t * len(batches))(*batches)
+    return _L.fs_decode_workspace_bytes(pool, arr, len(batches))
+
+
+def fs_decode_attention(pool, model, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, out, lse, workspace,
+                        stream=None):
+    rc = _L.fs_decode_attention(pool, model, layer, n_q_heads, sm_scale, _dp(q), _dp(block_tables), _dp(seq_lens),
+                                seq_lens.numel(), block_tables.shape[1], _dp(out), _dp(lse), _dp(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_decode_attention")
+
+
+def fs_decode_attention_multi(pool, batches, workspace, stream=None):
+    arr = (fs_batch_t * len(batches))(*batches)
+    rc = _L.fs_decode_attention_multi(pool, arr, len(batches), _dp(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_decode_attention_multi")
+
+
+def fs_decode_status(workspace, stream=None) -> int:
+    return _L.fs_decode_status(_dp(workspace), _stream(stream))
+
+
+def fs_set_kernel_mode(mode: int) -> int:
+    return _L.fs_set_kernel_mode(mode)
+
+
+def fs_set_split_bytes(n: int) -> int:
+    return _L.fs_set_split_bytes(n)

@@ -1,0 +1,41 @@
+"""Builds libfineserve.so (hipcc, gfx950) next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(_DIR)
+LIB = os.path.join(_DIR, "libfineserve.so")
+SOURCES = ["fs_pool.hip", "fs_append.hip", "fs_attention.hip", "fs_attention_generic.hip", "fs_attention_mfma.hip"]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# -packed-fp32-ops off: the compiler must not form packed fp32 instructions.
+# -ffp-contract=off: quantizer arithmetic must not be fused (bytes are compared bit for bit).
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def build(verbose: bool = False) -> str:
+    csrc = os.path.join(_DIR, "csrc")
+    objs = []
+    procs = []
+    for src in SOURCES:
+        obj = os.path.join(csrc, src.replace(".hip", ".o"))
+        cmd = [HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", csrc, "-c", os.path.join(csrc, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd))
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for src, pr in procs:
+        out, _ = pr.communicate()
+        out = "\n".join(ln for ln in out.splitlines() if "packed-fp32-ops" not in ln)
+        if pr.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        if verbose and out.strip():
+            print(out)
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", LIB, *objs], check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,62 @@
+// Device-side records of the split-K paged decode-attention launch (internal).
+#pragma once
+
+#include "fs_internal.h"
+
+namespace fs {
+
+// One model's batch as the kernels see it.
+struct DevBatch {
+  DevGeom g;
+  const uint8_t* layer_base;  // pool base + layer * layer_bytes
+  const _Float16* q;
+  const int32_t* tables;
+  const int32_t* seq_lens;
+  _Float16* out;
+  float* lse;
+  const float* k_scale;  // FP8: [H] of this layer; otherwise null
+  const float* v_scale;
+  int32_t n_seq, max_blocks, n_q, G;
+  float sm_scale;
+  int32_t chunk_tokens;  // tokens per split-K work item (multiple of 32)
+  int32_t seq_first;     // index of this batch's first sequence among all batches' sequences
+  int32_t part_stride;   // floats per work item in the partial buffer: G * (D + 2)
+  int32_t qrow_first;    // index of this batch's first (sequence, q head) row among all batches
+  int32_t t_magic_shift; // reserved
+  uint32_t t_magic;      // reserved
+  uint32_t pad;
+};
+
+// Workspace header words (uint32 unless noted), 256 bytes.
+enum : int {
+  kHdrCounter = 0,     // work-queue ticket counter
+  kHdrStatus = 1,      // bit 0: a sequence length was out of range; bit 1: partial buffer too small
+  kHdrTotalItems = 2,  // number of work items
+  kHdrBatchFirst = 8,  // [kMaxBatches] first work item of each batch
+  kHdrPartOff = 32     // [kMaxBatches] uint64: float offset of each batch's partials (word index of a uint64 array)
+};
+constexpr uint32_t kHeaderBytes = 256;
+
+struct MultiArgs {
+  DevBatch b[kMaxBatches];
+  uint32_t* header;
+  uint32_t* item_base;  // [n_seq_total + 1] first work item of each sequence
+  float* partials;
+  uint64_t part_capacity;  // floats
+  int32_t n_batches;
+  int32_t n_seq_total;
+  int32_t n_qrows_total;
+  int32_t pad;
+};
+
+// Work item r of a sequence with n_chunks splits and H KV heads: chunk = r / H, head = r % H,
+// so the heads of one (sequence, chunk) -- which lie in the same slabs -- run side by side.
+
+// Launchers implemented in the kernel translation units.
+hipError_t launch_prep(const MultiArgs& A, hipStream_t s);
+hipError_t launch_generic(const MultiArgs& A, int n_workgroups, hipStream_t s);
+hipError_t launch_combine(const MultiArgs& A, hipStream_t s);
+bool mfma_supports(const DevBatch& b);
+hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s);
+
+}  // namespace fs

@@ -1,0 +1,184 @@
+"""Parity machinery for the GPU tests: drives the HIP library and the CPU oracle on the same
+seeded workload and compares them (allocator state, appended bytes, attention outputs).
+
+The oracle never sees a value produced by the GPU: its KV bytes come from its own quantizer
+applied to source rows regenerated on the host by fs_inputs.gen, placed by its own allocator.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from fs_inputs import gen, workloads
+
+TOL_FP16 = 2e-3   # max-abs, FP16 KV (benchmark definition)
+TOL_QUANT = 4e-3  # max-abs, FP8 / INT8 / INT4 KV
+TOL_LSE = 1e-3
+
+
+class LockstepAdapter:
+    """Feeds every allocator call to the HIP library and to the oracle and insists on identical answers."""
+
+    def __init__(self, fs_adapter, opool, fs_ids, o_ids):
+        self.a, self.o = fs_adapter, opool
+        self.map = dict(zip(fs_ids, o_ids))
+        self.n_ops = 0
+
+    def alloc(self, m):
+        rc, b = self.a.alloc(m)
+        orc, ob = self.o.alloc(self.map[m])
+        assert (rc, b if rc == 0 else -1) == (orc, ob if orc == 0 else -1), f"alloc mismatch at op {self.n_ops}"
+        self.n_ops += 1
+        return rc, b
+
+    def free(self, m, blk):
+        rc = self.a.free(m, blk)
+        assert rc == self.o.free(self.map[m], blk), f"free mismatch at op {self.n_ops}"
+        self.n_ops += 1
+        return rc
+
+
+class Parity:
+    def __init__(self, wl: workloads.Workload, zero_pool=False):
+        import paper_2509_06261_amd as fs
+        from paper_2509_06261_amd import harness
+
+        self.fs = fs
+        self.wl = wl
+        self.gw = harness.GpuWorkload(wl, zero_pool=zero_pool)
+        self.opool = oracle.Pool(wl.slab_bytes, wl.pool_bytes)
+        self.o_ids = [self.opool.model_add(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget)
+                      for s in wl.models]
+        self.ogeom = [self.opool.model_geometry(m) for m in self.o_ids]
+        for m, og in zip(self.gw.model_ids, self.ogeom):
+            assert self.gw.T[m] == og.tokens_per_block
+        adapter = LockstepAdapter(harness.AllocAdapter(self.gw.pool), self.opool, self.gw.model_ids, self.o_ids)
+        self.gw.place(adapter)
+        self.n_alloc_ops = adapter.n_ops
+        self.check_allocator_state()
+
+    def close(self):
+        self.gw.close()
+
+    def check_allocator_state(self):
+        ost, ok, ou, ofs = self.opool.dump()
+        st, key, used, fstack = self.fs.fs_pool_dump(self.gw.pool)
+        key_map = np.full(65, -1, np.int32)
+        for a, o in zip(self.gw.model_ids, self.o_ids):
+            key_map[a] = o
+        assert np.array_equal(st, ost) and np.array_equal(used, ou) and np.array_equal(fstack, ofs)
+        assert np.array_equal(np.where(key >= 0, key_map[np.maximum(key, 0)], -1), ok)
+
+    # ------------------------------------------------------------------ oracle side
+    def oracle_sequences(self, k, layer, seqs):
+        """Oracle KV bytes and attention for sequences ``seqs`` of model k at ``layer`` in a compact host mirror.
+        Returns dict with mirror bytes per block, written mask, out, lse."""
+        s, g = self.wl.models[k], self.ogeom[k]
+        T = g.tokens_per_block
+        lens = self.gw.lens[k][seqs]
+        tab = self.gw.tables_host[k]
+        real_blocks = []
+        for i, n in zip(seqs, lens):
+            real_blocks.extend(tab[i, : workloads.blocks_needed(n, T)].tolist())
+        assert len(set(real_blocks)) == len(real_blocks), "a block is owned by two sequences"
+        remap = {b: j for j, b in enumerate(real_blocks)}
+        ctab = np.zeros((len(seqs), tab.shape[1]), np.int32)
+        for r, (i, n) in enumerate(zip(seqs, lens)):
+            nb = workloads.blocks_needed(n, T)
+            ctab[r, :nb] = [remap[b] for b in tab[i, :nb]]
+        dt = np.float32 if s.src_f32 else np.float16
+        krows = workloads.source_rows(self.wl.seed, s.tag, layer, gen.WHICH_K, lens, s.n_kv_heads, s.head_dim, seqs, dt)
+        vrows = workloads.source_rows(self.wl.seed, s.tag, layer, gen.WHICH_V, lens, s.n_kv_heads, s.head_dim, seqs, dt)
+        ks = vs = None
+        if s.kv_dtype == workloads.FP8:
+            ks, vs = self.gw.scales[self.gw.model_ids[k]]
+        seq_idx, pos = workloads.token_index(lens)
+        mem0 = np.zeros(len(real_blocks) * g.block_budget, np.uint8)
+        oracle.kv_append(mem0, g, layer, krows, vrows, seq_idx, pos, ctab, ks, vs)
+        mem1 = np.full(len(real_blocks) * g.block_budget, 0xFF, np.uint8)
+        oracle.kv_append(mem1, g, layer, krows, vrows, seq_idx, pos, ctab, ks, vs)
+        written = mem0 == mem1  # bytes the append defines (identical whatever was there before)
+        q = gen.normal_q(self.wl.seed, s.tag, layer, seqs, s.n_q_heads, s.head_dim)
+        out, lse = oracle.decode_attention(mem0, g, layer, s.n_q_heads, 1.0 / np.sqrt(s.head_dim), q, ctab, lens, ks,
+                                           vs, n_threads=8)
+        return dict(real_blocks=real_blocks, mem=mem0, written=written, out=out, lse=lse, q=q)
+
+    # ------------------------------------------------------------------ comparisons
+    def check_bytes(self, k, ref):
+        """Every byte the oracle's append defines must be identical in the GPU's slab blocks."""
+        g = self.ogeom[k]
+        m = self.gw.model_ids[k]
+        n_bad = 0
+        for j, b in enumerate(ref["real_blocks"]):
+            gpu = self.gw.read_block(m, b)
+            lo = j * g.block_budget
+            want = ref["mem"][lo: lo + g.block_bytes]
+            mask = ref["written"][lo: lo + g.block_bytes]
+            assert oracle.block_offset(g, b) == b * self.gw.geom[m].block_budget
+            n_bad += int(np.count_nonzero((gpu != want) & mask))
+        assert n_bad == 0, f"model {k}: {n_bad} appended bytes differ from the oracle"
+
+    def check_attention(self, k, seqs, ref, out_gpu, lse_gpu=None):
+        s = self.wl.models[k]
+        tol = TOL_FP16 if s.kv_dtype == workloads.FP16 else TOL_QUANT
+        got = out_gpu[seqs].astype(np.float64)
+        assert np.all(np.isfinite(got))
+        err = float(np.max(np.abs(got - ref["out"])))
+        assert err <= tol, f"model {k} ({s.name}): max abs error {err:.3e} > {tol}"
+        if lse_gpu is not None:
+            lerr = float(np.max(np.abs(lse_gpu[seqs].astype(np.float64) - ref["lse"])))
+            assert lerr <= TOL_LSE, f"model {k} ({s.name}): lse error {lerr:.3e}"
+        return err
+
+    def sample(self, k, n_random, tag=55):
+        """Seeded sample of sequences of model k: n_random random ones plus the shortest and the longest."""
+        lens = self.gw.lens[k]
+        pick = set(gen.permutation(self.wl.seed, tag + k, len(lens))[:n_random].tolist())
+        pick.add(int(np.argmin(lens)))
+        pick.add(int(np.argmax(lens)))
+        return np.array(sorted(pick), dtype=np.int64)
+
+    def run_and_check(self, layers, n_random=None, with_bytes=True, kernel_mode=0):
+        """Populate ``layers[k]`` of every model, decode all models in one multi launch, and compare the sampled
+        (default: all) sequences with the oracle.  Returns max errors per model."""
+        import torch
+
+        gw = self.gw
+        self.fs.fs_set_kernel_mode(kernel_mode)
+        try:
+            gw.populate([[l] for l in layers])
+            batches, keep = gw.make_batches(layers)
+            ws = gw.decode(batches)
+            torch.cuda.synchronize()
+            status = self.fs.fs_decode_status(ws)
+            assert status == 0, f"decode status {status}"
+        finally:
+            self.fs.fs_set_kernel_mode(0)
+        errs = []
+        for k in range(len(self.wl.models)):
+            seqs = np.arange(len(gw.lens[k])) if n_random is None else self.sample(k, n_random)
+            ref = self.oracle_sequences(k, layers[k], seqs)
+            if with_bytes:
+                self.check_bytes(k, ref)
+            errs.append(self.check_attention(k, seqs, ref, keep["out"][k].cpu().numpy(), keep["lse"][k].cpu().numpy()))
+        return errs
+
+
+def smoke():
+    """Tiny end-to-end check used by __graft_entry__.smoke()."""
+    wl = workloads.config(1)
+    par = Parity(wl, zero_pool=True)
+    try:
+        errs = par.run_and_check([0])
+        print(f"config 1 on cuda:0: allocator ops {par.n_alloc_ops} identical, appended bytes identical, "
+              f"attention max abs err {errs[0]:.2e}")
+    finally:
+        par.close()
+    # a small two-model mixed-precision pool through the multi-model launch
+    wl = workloads.scaled_down(workloads.config(3), n_seq=4, max_len=300, pool_bytes=256 * workloads.MiB)
+    par = Parity(wl, zero_pool=True)
+    try:
+        errs = par.run_and_check([1, 2])
+        print(f"mixed fp16+fp8 pool: attention max abs err {errs}")
+    finally:
+        par.close()

@@ -1,0 +1,279 @@
+"""GPU parity tests: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on small seeded workloads that still span several tiles, splits and ragged tails."""
+import numpy as np
+import pytest
+
+from fs_inputs import gen, workloads
+from fs_inputs.workloads import FP16, FP8, INT4, INT8, KiB, MiB, ModelSpec, Workload
+
+pytestmark = pytest.mark.gpu
+
+KERNEL_MODES = [1, 0]  # 1 = generic vector-ALU kernel, 0 = automatic (MFMA where supported)
+
+
+def _parity(wl, zero_pool=True):
+    import gpu_harness
+
+    return gpu_harness.Parity(wl, zero_pool=zero_pool)
+
+
+def test_config1_tiny_fp16_everything_identical():
+    """Config 1 in full: allocator trace, every byte of the 16 MiB pool, all outputs."""
+    import torch
+    import oracle
+
+    wl = workloads.config(1)
+    par = _parity(wl)
+    try:
+        errs = par.run_and_check([0])
+        assert errs[0] <= 2e-3
+        # whole-pool comparison: the GPU wrote nothing but what the oracle's append defines
+        s, g = wl.models[0], par.ogeom[0]
+        mem = np.zeros(wl.pool_bytes, np.uint8)
+        lens = par.gw.lens[0]
+        k = workloads.source_rows(wl.seed, s.tag, 0, gen.WHICH_K, lens, 4, 64)
+        v = workloads.source_rows(wl.seed, s.tag, 0, gen.WHICH_V, lens, 4, 64)
+        si, po = workloads.token_index(lens)
+        oracle.kv_append(mem, g, 0, k, v, si, po, par.gw.tables_host[0])
+        torch.cuda.synchronize()
+        assert np.array_equal(par.gw.pool_mem.cpu().numpy(), mem)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("dtype,src_f32", [(FP16, False), (FP8, False), (INT8, False), (INT4, True), (INT4, False)])
+def test_gqa_8b_shape_all_dtypes(dtype, src_f32, mode):
+    """8B-shaped layer (32 q heads, 8 KV heads, head_dim 128) at reduced depth; lengths straddle block and
+    split boundaries; every sequence compared."""
+    lens = np.array([1, 2, 31, 32, 33, 63, 64, 65, 127, 200, 517, 1100, 2049], np.int32)
+    wl = Workload("gqa", 256 * KiB, 64 * MiB, [ModelSpec("m", dtype, 8, 128, 2, 32, lens, tag=21, src_f32=src_f32)],
+                  "shuffle")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(64 * KiB)  # force several splits per long sequence
+        errs = par.run_and_check([1], kernel_mode=mode)
+        print("max abs err", errs)
+    finally:
+        par.fs.fs_set_split_bytes(512 * KiB)
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("dtype", [FP16, INT4])
+def test_mha_13b_shape(dtype, mode):
+    """MHA (40 q heads = 40 KV heads): one query head per KV head; odd tokens_per_block."""
+    lens = np.array([1, 9, 37, 38, 39, 76, 77, 300, 900], np.int32)
+    wl = Workload("mha", 512 * KiB, 128 * MiB, [ModelSpec("m", dtype, 40, 128, 3, 40, lens, tag=22, src_f32=True)],
+                  "shuffle")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(32 * KiB)
+        errs = par.run_and_check([2], kernel_mode=mode)
+        print("T", par.gw.T, "max abs err", errs)
+    finally:
+        par.fs.fs_set_split_bytes(512 * KiB)
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_mixed_four_model_pool_small(mode):
+    """Config 5 scaled down: four models of four precisions in one churned pool, one multi-model launch."""
+    wl = workloads.scaled_down(workloads.config(5), n_seq=4, max_len=500, pool_bytes=320 * MiB, churn_steps=300)
+    par = _parity(wl)
+    try:
+        errs = par.run_and_check([7, 0, 3, 9], kernel_mode=mode)
+        print("max abs err", errs)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_interleaved_two_model_pool_small(mode):
+    """Config 3 scaled down: FP16 and FP8 models with slabs interleaved block by block."""
+    wl = workloads.scaled_down(workloads.config(3), n_seq=5, max_len=400, pool_bytes=512 * MiB)
+    par = _parity(wl)
+    try:
+        errs = par.run_and_check([31, 5], kernel_mode=mode)
+        print("max abs err", errs)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("group", [1, 2, 4, 8, 16])
+def test_group_sizes_and_head_dim_64(group, mode):
+    lens = np.array([5, 64, 129, 700], np.int32)
+    wl = Workload("g", 64 * KiB, 16 * MiB, [ModelSpec("m", FP16, 2, 64, 1, 2 * group, lens, tag=23)], "shuffle")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(16 * KiB)
+        par.run_and_check([0], kernel_mode=mode)
+    finally:
+        par.fs.fs_set_split_bytes(512 * KiB)
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_several_blocks_per_slab(mode):
+    """fs_model_register_ex: four blocks per slab for one model, two for the other, in one pool."""
+    la = np.array([3, 40, 90], np.int32)
+    wl = Workload("bps", 64 * KiB, 8 * MiB,
+                  [ModelSpec("a", INT8, 2, 64, 1, 4, la, tag=24, block_budget=16 * KiB),
+                   ModelSpec("b", FP8, 2, 64, 1, 4, la, tag=25, block_budget=32 * KiB)], "interleave")
+    par = _parity(wl)
+    try:
+        st = par.fs.fs_pool_stats(par.gw.pool)
+        assert st.slabs_partial > 0
+        par.run_and_check([0, 0], kernel_mode=mode)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_placement_invariance_and_split_independence_on_gpu(mode):
+    """Identity vs shuffled block placement must give bit-identical GPU outputs (splits are defined on the
+    logical token index); one split vs many must agree within 1e-3."""
+    import torch
+
+    lens = gen.uniform_lengths(7, 1, 12, 1, 900)
+    outs = {}
+    for placement in ("identity", "shuffle"):
+        for split in (8 * KiB, 4 * MiB):
+            wl = Workload("pi", 64 * KiB, 32 * MiB, [ModelSpec("m", INT4, 4, 128, 1, 16, lens, tag=26, src_f32=True)],
+                          placement)
+            par = _parity(wl)
+            try:
+                par.fs.fs_set_split_bytes(split)
+                par.fs.fs_set_kernel_mode(mode)
+                par.gw.populate([[0]])
+                batches, keep = par.gw.make_batches([0])
+                par.gw.decode(batches)
+                torch.cuda.synchronize()
+                outs[(placement, split)] = keep["out"][0].cpu().numpy().copy()
+            finally:
+                par.fs.fs_set_split_bytes(512 * KiB)
+                par.fs.fs_set_kernel_mode(0)
+                par.close()
+    for split in (8 * KiB, 4 * MiB):
+        assert np.array_equal(outs[("identity", split)], outs[("shuffle", split)])
+    a = outs[("identity", 8 * KiB)].astype(np.float64)
+    b = outs[("identity", 4 * MiB)].astype(np.float64)
+    assert np.max(np.abs(a - b)) <= 1e-3
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_fp8_every_code_decodes_exactly(mode):
+    """One-token sequences whose V row holds every finite E4M3 value: out must equal V^[0] exactly."""
+    import torch
+    import oracle
+    import paper_2509_06261_amd as fs
+
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    vals = np.array([oracle.e4m3_decode(int(c)) for c in codes], np.float32)
+    rows = np.zeros((2, 1, 128), np.float32)
+    rows.reshape(-1)[: len(vals)] = vals
+    pool_mem = torch.zeros(1 * MiB, dtype=torch.uint8, device="cuda:0")
+    pool = fs.fs_pool_create(64 * KiB, 1 * MiB, pool_mem)
+    T, m = fs.fs_model_register(pool, fs.FS_KV_FP8_E4M3, 1, 128, 1)
+    fs.fs_model_set_fp8_scales(pool, m, np.ones((1, 1), np.float32), np.ones((1, 1), np.float32))
+    ids = [fs.fs_block_alloc(pool, m)[1] for _ in range(2)]
+    tables = torch.tensor([[ids[0]], [ids[1]]], dtype=torch.int32, device="cuda:0")
+    kv = torch.from_numpy(rows).cuda()
+    si = torch.tensor([0, 1], dtype=torch.int32, device="cuda:0")
+    po = torch.zeros(2, dtype=torch.int32, device="cuda:0")
+    fs.fs_kv_append(pool, m, 0, kv, kv, si, po, tables)
+    q = torch.ones((2, 1, 128), dtype=torch.float16, device="cuda:0")
+    out = torch.zeros_like(q)
+    lens = torch.ones(2, dtype=torch.int32, device="cuda:0")
+    b = fs.make_batch(m, 0, 1, 0.1, q, tables, lens, out)
+    ws = torch.empty(fs.fs_decode_workspace_bytes(pool, [b]), dtype=torch.uint8, device="cuda:0")
+    fs.fs_set_kernel_mode(mode)
+    try:
+        fs.fs_decode_attention_multi(pool, [b], ws)
+        torch.cuda.synchronize()
+    finally:
+        fs.fs_set_kernel_mode(0)
+    got = out.cpu().numpy().astype(np.float32).reshape(-1)[: len(vals)]
+    assert np.array_equal(got, vals.astype(np.float16).astype(np.float32))
+    # and the stored bytes are the codes themselves
+    g = fs.fs_model_geometry(pool, m)
+    stored = pool_mem[ids[0] * g.block_budget + g.kv_tile:][:128].cpu().numpy()
+    assert np.array_equal(stored, codes[:128])
+    fs.fs_pool_destroy(pool)
+
+
+def test_weights_sum_to_one_on_gpu():
+    """V == 1 everywhere gives out == 1 and the lse of a zero query is ln(n)."""
+    import torch
+    import paper_2509_06261_amd as fs
+    from paper_2509_06261_amd import harness
+
+    lens = np.array([1, 77, 1000, 3000], np.int32)
+    wl = Workload("ones", 64 * KiB, 32 * MiB, [ModelSpec("m", FP16, 2, 128, 1, 8, lens, tag=27)], "shuffle")
+    gw = harness.GpuWorkload(wl, zero_pool=True)
+    try:
+        gw.place()
+        si, po = workloads.token_index(lens)
+        si, po = torch.from_numpy(si).cuda(), torch.from_numpy(po).cuda()
+        k = torch.randn((len(po), 2, 128), dtype=torch.float16, device="cuda:0")
+        fs.fs_kv_append(gw.pool, gw.model_ids[0], 0, k, torch.ones_like(k), si, po, gw.tables[0])
+        for mode in KERNEL_MODES:
+            fs.fs_set_kernel_mode(mode)
+            batches, keep = gw.make_batches([0])
+            keep["q"][0].zero_()
+            gw.decode(batches)
+            torch.cuda.synchronize()
+            out = keep["out"][0].cpu().numpy().astype(np.float64)
+            lse = keep["lse"][0].cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(out - 1.0)) <= 1e-3
+            assert np.max(np.abs(lse - np.log(lens)[:, None])) <= 1e-3
+    finally:
+        fs.fs_set_kernel_mode(0)
+        gw.close()
+
+
+def test_argument_errors_and_status_flags():
+    import torch
+    import paper_2509_06261_amd as fs
+    from paper_2509_06261_amd import harness
+
+    lens = np.array([10, 20], np.int32)
+    wl = Workload("err", 64 * KiB, 4 * MiB, [ModelSpec("m", FP16, 2, 64, 2, 4, lens, tag=28)], "identity")
+    gw = harness.GpuWorkload(wl, zero_pool=True)
+    try:
+        gw.place()
+        gw.populate()
+        batches, keep = gw.make_batches([0])
+        ws = gw.workspace_for(batches)
+        b = batches[0]
+        for field, bad in (("layer", 2), ("layer", -1), ("n_q_heads", 3), ("n_q_heads", 64), ("n_seq", 0),
+                           ("max_blocks", 0), ("model", 5)):
+            good = getattr(b, field)
+            setattr(b, field, bad)
+            with pytest.raises(fs.binding.FsError) as ei:
+                fs.fs_decode_attention_multi(gw.pool, [b], ws)
+            assert ei.value.code == fs.FS_ERR_INVALID
+            setattr(b, field, good)
+        small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+        with pytest.raises(fs.binding.FsError) as ei:
+            fs.fs_decode_attention_multi(gw.pool, [b], small)
+        assert ei.value.code == fs.FS_ERR_NOMEM
+        # a sequence length beyond max_blocks * T is clamped and reported, never followed out of the table
+        gw.seq_lens[0][1] = 10_000
+        fs.fs_decode_attention_multi(gw.pool, [b], ws)
+        assert fs.fs_decode_status(ws) & 1
+        gw.seq_lens[0][1] = 0
+        fs.fs_decode_attention_multi(gw.pool, [b], ws)
+        assert fs.fs_decode_status(ws) & 1
+        gw.seq_lens[0][1] = 20
+        fs.fs_decode_attention_multi(gw.pool, [b], ws)
+        assert fs.fs_decode_status(ws) == 0
+        # single-model entry point gives the same result as the multi-model one
+        out2 = torch.zeros_like(keep["out"][0])
+        fs.fs_decode_attention(gw.pool, b.model, 0, 4, b.sm_scale, keep["q"][0], gw.tables[0], gw.seq_lens[0], out2,
+                               None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, keep["out"][0])
+    finally:
+        gw.close()

@@ -1,0 +1,155 @@
+"""CPU-only tests of the HIP library's host side: it loads, exports every declared symbol,
+and its geometry and slab allocator agree bit for bit with the oracle's.  No kernel is launched:
+the pool is created over a caller-supplied (never dereferenced) base address."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_06261_amd as fs
+from fs_inputs import gen
+
+FAKE_BASE = 0x10000000
+KiB, MiB = 1 << 10, 1 << 20
+
+
+class FsPoolAdapter:
+    """alloc/free facade over the C ABI with the oracle Pool's interface."""
+
+    def __init__(self, slab, pool_bytes):
+        self.pool = fs.fs_pool_create(slab, pool_bytes, FAKE_BASE)
+
+    def model_add(self, dtype, H, D, L, budget=None):
+        return fs.fs_model_register(self.pool, dtype, H, D, L, budget)[1]
+
+    def alloc(self, m):
+        return fs.fs_block_alloc(self.pool, m)
+
+    def free(self, m, b):
+        return fs.fs_block_free(self.pool, m, b)
+
+    def close(self):
+        fs.fs_pool_destroy(self.pool)
+
+
+def test_every_declared_symbol_is_exported():
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "fineserve.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(fs_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(fs.binding.EXPORTS)
+    for name in declared:
+        assert hasattr(fs.binding._L, name), name
+
+
+@pytest.mark.parametrize("dtype", [0, 1, 2, 3])
+def test_geometry_matches_oracle(dtype):
+    p = fs.fs_pool_create(2 * MiB, 64 * MiB, FAKE_BASE)
+    rng = np.random.default_rng(dtype)
+    shapes = [(8, 128, 32, None), (8, 128, 8, None), (40, 128, 40, None), (40, 128, 10, None), (4, 64, 1, 64 * KiB)]
+    shapes += [(int(rng.integers(1, 41)), int(rng.choice([8, 16, 32, 64, 128, 256, 512])), int(rng.integers(1, 48)),
+                int(rng.choice([64 * KiB, 512 * KiB, 2 * MiB]))) for _ in range(40)]
+    for H, D, L, budget in shapes:
+        try:
+            og = oracle.geometry(dtype, H, D, L, budget or 2 * MiB)
+        except ValueError:
+            with pytest.raises(fs.binding.FsError):
+                fs.fs_model_register(p, dtype, H, D, L, budget)
+            continue
+        T, m = fs.fs_model_register(p, dtype, H, D, L, budget)
+        g = fs.fs_model_geometry(p, m)
+        assert T == og.tokens_per_block == g.tokens_per_block
+        for f in ("row_bytes", "kv_tile", "par_tile", "head_chunk", "layer_bytes", "block_bytes", "block_budget",
+                  "param_bytes"):
+            assert getattr(g, f) == getattr(og, f), f
+        assert g.blocks_per_slab == 2 * MiB // (budget or 2 * MiB)
+        assert fs.fs_model_unregister(p, m) == 0
+    fs.fs_pool_destroy(p)
+
+
+def test_worked_block_id_example_through_the_abi(golden_dir):
+    rows = [list(map(int, ln.split())) for ln in open(os.path.join(golden_dir, "kv_slab_fig_example.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    slab = 64 * KiB
+    a = FsPoolAdapter(slab, 4 * slab)
+    spec = {r[0]: r for r in rows}
+    m2 = a.model_add(fs.FS_KV_FP8_E4M3, 2, 64, 1, slab // spec[2][1])
+    m1 = a.model_add(fs.FS_KV_FP16, 2, 64, 1, slab // spec[1][1])
+    got2 = [a.alloc(m2)[1] for _ in range(4)]
+    got1 = a.alloc(m1)[1]
+    assert got2[3] == spec[2][4] and got1 == spec[1][4]
+    a.close()
+
+
+def _run_trace(slab, n_slabs, model_specs, n_ops, seed):
+    o = oracle.Pool(slab, n_slabs * slab)
+    a = FsPoolAdapter(slab, n_slabs * slab)
+    om = [o.model_add(*s) for s in model_specs]
+    am = [a.model_add(*s) for s in model_specs]
+    assert om == am
+    live = [[] for _ in model_specs]
+    r = gen.uniform_ints(seed, 5, n_ops, 1 << 40)
+    for step in range(n_ops):
+        x = int(r[step])
+        k = x % len(model_specs)
+        if (x >> 8) % 100 < 45 and live[k]:
+            idx = (x >> 16) % len(live[k])
+            b = live[k][idx]
+            live[k][idx] = live[k][-1]
+            live[k].pop()
+            assert o.free(om[k], b) == a.free(am[k], b) == 0
+        else:
+            (rc1, b1), (rc2, b2) = o.alloc(om[k]), a.alloc(am[k])
+            assert rc1 == rc2
+            if rc1 == 0:
+                assert b1 == b2
+                live[k].append(b1)
+        if (x >> 30) % 1000 == 0:  # occasional invalid operations must fail identically
+            bogus = (x >> 12) % (n_slabs * 4)
+            kk = (k + 1) % len(model_specs)
+            if bogus not in live[kk]:
+                assert o.free(om[kk], bogus) == a.free(am[kk], bogus) < 0
+    ost, ok, ou, ofs = o.dump()
+    ast, ak, au, afs = fs.fs_pool_dump(a.pool)
+    assert np.array_equal(ost, ast) and np.array_equal(ok, ak) and np.array_equal(ou, au) and np.array_equal(ofs, afs)
+    for x, y in zip(om, am):
+        assert np.array_equal(o.dump_live(x), fs.fs_model_dump_live(a.pool, y))
+    st = fs.fs_pool_stats(a.pool)
+    assert st.live_blocks == sum(len(v) for v in live) and st.slabs_free == len(afs)
+    assert st.slabs_free + st.slabs_partial + st.slabs_full == n_slabs
+    a.close()
+
+
+def test_allocator_matches_oracle_one_block_per_slab():
+    specs = [(0, 8, 128, 8, None), (1, 8, 128, 8, None), (2, 8, 128, 8, None), (3, 40, 128, 10, None)]
+    _run_trace(2 * MiB, 512, specs, 300_000, seed=11)
+
+
+def test_allocator_matches_oracle_many_blocks_per_slab():
+    slab = 256 * KiB
+    specs = [(0, 4, 64, 1, slab // 2), (1, 4, 64, 1, slab // 4), (3, 2, 64, 2, slab // 16), (2, 4, 64, 1, slab)]
+    _run_trace(slab, 96, specs, 300_000, seed=12)
+
+
+def test_error_codes_without_device():
+    p = fs.fs_pool_create(64 * KiB, 1 * MiB, FAKE_BASE)
+    with pytest.raises(fs.binding.FsError):
+        fs.fs_pool_create(100, 1000, FAKE_BASE)  # slab not a multiple of 256
+    with pytest.raises(fs.binding.FsError):
+        fs.fs_model_register(p, 0, 1024, 512, 64)  # one token does not fit a 64 KiB block
+    with pytest.raises(fs.binding.FsError):
+        fs.fs_model_register(p, 7, 4, 64, 1)  # unknown dtype
+    T, m = fs.fs_model_register(p, fs.FS_KV_FP16, 4, 64, 1)
+    assert T == 64
+    rc, b = fs.fs_block_alloc(p, m)
+    assert (rc, b) == (0, 0)
+    assert fs.fs_model_unregister(p, m) == fs.FS_ERR_STATE
+    assert fs.fs_block_free(p, m, 1) == fs.FS_ERR_STATE
+    assert fs.fs_block_free(p, m, -1) == fs.FS_ERR_INVALID
+    assert fs.fs_block_free(p, m + 1, 0) == fs.FS_ERR_INVALID
+    assert fs.fs_block_free(p, m, 0) == 0
+    assert fs.fs_model_unregister(p, m) == 0
+    fs.fs_pool_destroy(p)
