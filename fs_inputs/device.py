@@ -9,6 +9,7 @@ import ctypes
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- first, so that libfs_inputs.so binds to the HIP runtime torch has already loaded
 
 from . import gen
 

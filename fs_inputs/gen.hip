@@ -70,6 +70,7 @@ int fsi_fill_rows(void* out, int out_is_f32, const float* table, uint64_t seed, 
   uint64_t blocks = (n_words + threads - 1) / threads;
   if (blocks > 65536) blocks = 65536;
   hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
   if (out_is_f32)
     hipLaunchKernelGGL(fill_rows_kernel<float>, dim3((unsigned)blocks), dim3(threads), 0, s, (float*)out, table, a,
                        lw, seq_id, pos, (uint32_t)row_elems, n_words);

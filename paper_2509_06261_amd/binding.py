@@ -11,6 +11,7 @@ import ctypes
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- first, so that libfineserve.so binds to the HIP runtime torch has already loaded
 
 FS_KV_FP16, FS_KV_FP8_E4M3, FS_KV_INT8, FS_KV_INT4 = 0, 1, 2, 3
 FS_SRC_FP16, FS_SRC_FP32 = 0, 1

@@ -234,6 +234,7 @@ extern "C" int fs_kv_append(fs_pool* p, fs_model_t model, int layer, const void*
   const int64_t cap = (int64_t)p->n_cu * 64;
   if (blocks > cap) blocks = cap;
   hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
   if (src_dtype == FS_SRC_FP32)
     hipLaunchKernelGGL(kv_append_kernel<true>, dim3((unsigned)blocks), dim3(kWaves * 64), 0, s, A);
   else

@@ -287,6 +287,7 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
     return FS_ERR_INVALID;
   }
   hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
   hipError_t e = launch_prep(plan.args, s);
   if (e != hipSuccess) return device_error(e, "prep launch");
   // Persistent grid: two workgroups per compute unit drain the queue (never more than the

@@ -84,11 +84,7 @@ int fs_pool_create(uint64_t slab_bytes, uint64_t pool_bytes, void* device_base, 
   // Without a HIP device the pool can still do its bookkeeping (slab table, block ids) when the
   // caller supplies the base address; every device entry point then fails with FS_ERR_DEVICE.
   hipError_t e = hipGetDevice(&p->device);
-  if (e == hipSuccess) {
-    hipDeviceProp_t prop;
-    e = hipGetDeviceProperties(&prop, p->device);
-    if (e == hipSuccess) p->n_cu = prop.multiProcessorCount;
-  }
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&p->n_cu, hipDeviceAttributeMultiprocessorCount, p->device);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     p->n_cu = 0;
