@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-slab decode hot path on one MI355X.
+
+A *step* is one decode step of one layer over the whole batch: ``fs_kv_append`` of every
+sequence's newest token (quantize + scatter into its slab block) followed by one
+``fs_decode_attention_multi`` launch (work-list preparation, split-K paged attention over all
+co-located models, split combine).  Slab allocation is host bookkeeping done while the workload
+is set up (its rate is reported under ``extra``).  KV, block tables, queries and lengths are
+resident in HBM before the timed region starts; the layer index rotates between steps so that no
+step re-reads what the previous one left in cache.
+
+Prints ONE JSON line: metric/value = algorithmic KV GB/s of the whole step, plus ``roofline`` for
+the attention kernel (HIP-event time of that kernel alone) and ``cpu_baseline`` (the CPU oracle
+timed on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(gw, wl, layers, n_per_model, n_threads):
+    """Time the CPU oracle (append of the newest token + decode attention) on a seeded sample of sequences of
+    every model of the workload; returns (GB/s, tokens/s, description)."""
+    import numpy as np
+
+    import oracle
+    from fs_inputs import gen, workloads
+
+    total_bytes = 0
+    total_time = 0.0
+    total_seqs = 0
+    used_threads = 1
+    for k, s in enumerate(wl.models):
+        lens_all = gw.lens[k]
+        order = gen.permutation(wl.seed, 77 + k, len(lens_all))
+        seqs = np.sort(order[:n_per_model])
+        lens = lens_all[seqs]
+        g = oracle.geometry(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget or wl.slab_bytes)
+        T = g.tokens_per_block
+        nblk = [workloads.blocks_needed(n, T) for n in lens]
+        tab = np.zeros((len(seqs), max(nblk)), np.int32)
+        nxt = 0
+        for r, nb in enumerate(nblk):  # compact host mirror: only the sampled sequences' blocks
+            tab[r, :nb] = np.arange(nxt, nxt + nb)
+            nxt += nb
+        mem = np.zeros(nxt * g.block_budget, np.uint8)
+        layer = layers[k]
+        dt = np.float32 if s.src_f32 else np.float16
+        kr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_K, lens, s.n_kv_heads, s.head_dim, seqs, dt)
+        vr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_V, lens, s.n_kv_heads, s.head_dim, seqs, dt)
+        ks = vs = None
+        if s.kv_dtype == workloads.FP8:
+            ks, vs = workloads.fp8_scales_table(s.n_layers, s.n_kv_heads)
+        si, po = workloads.token_index(lens)
+        oracle.kv_append(mem, g, layer, kr, vr, si, po, tab, ks, vs)  # cache fill: not timed
+        q = gen.normal_q(wl.seed, s.tag, layer, seqs, s.n_q_heads, s.head_dim)
+        last = np.cumsum(lens) - 1
+        t0 = time.perf_counter()
+        oracle.kv_append(mem, g, layer, kr[last], vr[last], np.arange(len(seqs), dtype=np.int32),
+                         (lens - 1).astype(np.int32), tab, ks, vs)
+        oracle.decode_attention(mem, g, layer, s.n_q_heads, 1.0 / np.sqrt(s.head_dim), q, tab, lens, ks, vs,
+                                n_threads=n_threads, want_lse=False)
+        total_time += time.perf_counter() - t0
+        total_bytes += int(lens.astype(np.int64).sum()) * workloads.kv_bytes_per_token_layer(s)
+        total_seqs += len(seqs)
+        used_threads = max(used_threads, min(n_threads, len(seqs)))
+    desc = (f"{n_per_model} seeded sequences per model ({total_seqs} of {sum(m.n_seq for m in wl.models)}), "
+            f"one layer each, append of the newest token + decode attention, {total_bytes / 1e6:.1f} MB of KV")
+    return total_bytes / total_time / 1e9, total_seqs / total_time, desc, used_threads
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, help="workload: 2..5 (BASELINE.json configs, 1-based)")
+    ap.add_argument("--kernel-mode", type=int, default=0, help="0 auto, 1 generic kernel, 2 MFMA kernel")
+    ap.add_argument("--split-bytes", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0, help="populate only the first N layers (0 = all)")
+    ap.add_argument("--identity", action="store_true", help="control run: contiguous (identity) block placement")
+    ap.add_argument("--only-model", type=int, default=-1, help="control run: only model k of the workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=6, help="sequences per model for the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build targets one GPU (every box has one); --gpus must be 1. "
+            "The path shards by sequence or by KV head with no exchange step (see DESIGN.md).")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2509_06261_amd as fs
+    from fs_inputs import workloads
+    from paper_2509_06261_amd import harness
+
+    t_setup = time.perf_counter()
+    wl = workloads.config(args.config)
+    if args.identity:
+        wl.placement = "identity"
+    if args.only_model >= 0:
+        wl.models = [wl.models[args.only_model]]
+    log(f"[bench] workload {wl.name}: pool {wl.pool_bytes / 2**30:.0f} GiB, slabs {wl.slab_bytes // 1024} KiB, "
+        f"placement {wl.placement}")
+    gw = harness.GpuWorkload(wl)
+    t0 = time.perf_counter()
+    gw.place()
+    t_place = time.perf_counter() - t0
+    n_alloc_ops = sum(len(b) for m in gw.blocks for b in m)
+    st = fs.fs_pool_stats(gw.pool)
+    log(f"[bench] placed: {st.live_blocks} live blocks of {st.n_slabs} slabs in {t_place:.1f} s")
+    n_layers_of = [s.n_layers if args.layers <= 0 else min(args.layers, s.n_layers) for s in wl.models]
+    t0 = time.perf_counter()
+    gw.populate([list(range(n)) for n in n_layers_of])
+    torch.cuda.synchronize()
+    log(f"[bench] KV populated for layers {n_layers_of} in {time.perf_counter() - t0:.1f} s")
+    if args.kernel_mode:
+        fs.fs_set_kernel_mode(args.kernel_mode)
+    if args.split_bytes:
+        fs.fs_set_split_bytes(args.split_bytes)
+
+    # per-layer batches (queries differ per layer), prepared before timing
+    n_rot = max(n_layers_of)
+    per_layer = []
+    keepalive = []
+    for r in range(n_rot):
+        layers = [r % n for n in n_layers_of]
+        batches, keep = gw.make_batches(layers, with_lse=False)
+        per_layer.append((layers, batches))
+        keepalive.append(keep)
+    ws = gw.workspace_for(per_layer[0][1])
+    # newest-token rows for the per-step append (position n_b - 1 of every sequence), per model
+    new_rows = []
+    for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)):
+        n = s.n_seq
+        si = torch.arange(n, dtype=torch.int32, device=gw.device)
+        po = (gw.seq_lens[k] - 1).to(torch.int32)
+        dt = torch.float32 if s.src_f32 else torch.float16
+        rows = []
+        for layer in range(n_layers_of[k]):
+            kb = torch.empty((n, s.n_kv_heads, s.head_dim), dtype=dt, device=gw.device)
+            vb = torch.empty_like(kb)
+            from fs_inputs import device as gen_device
+            from fs_inputs import gen
+            gen_device.fill_rows(kb, wl.seed, s.tag, layer, gen.WHICH_K, si, po, s.n_kv_heads, s.head_dim)
+            gen_device.fill_rows(vb, wl.seed, s.tag, layer, gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
+            rows.append((kb, vb))
+        new_rows.append((si, po, rows))
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        layers, batches = per_layer[i % n_rot]
+        for k, m in enumerate(gw.model_ids):
+            si, po, rows = new_rows[k]
+            kb, vb = rows[layers[k]]
+            fs.fs_kv_append(gw.pool, m, layers[k], kb, vb, si, po, gw.tables[k], stream)
+        fs.fs_decode_attention_multi(gw.pool, batches, ws, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    status = fs.fs_decode_status(ws)
+    assert status == 0, f"decode status {status}"
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # attention kernel alone, HIP events on the launch stream
+    fs.fs_set_kernel_timing(1)
+    kms = []
+    for i in range(args.steps):
+        step(args.warmup + args.steps + i)
+        kms.append(fs.fs_last_attention_kernel_ms())
+    fs.fs_set_kernel_timing(0)
+    kms = np.array(kms)
+    kernel_ms = float(kms.mean())
+
+    kv_bytes = gw.kv_bytes_per_layer_launch()
+    n_seq_total = sum(s.n_seq for s in wl.models)
+    table_bytes = sum(int(np.sum((gw.lens[k] + gw.T[m] - 1) // gw.T[m])) * 4 + 4 * s.n_seq
+                      for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)))
+    qo_bytes = sum(2 * s.n_seq * s.n_q_heads * s.head_dim * 2 for s in wl.models)
+    algo_bytes = kv_bytes + table_bytes + qo_bytes
+    value = algo_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    full_depth_tok_s = n_seq_total / (ms_per_step * 1e-3) / np.mean([s.full_layers or s.n_layers for s in wl.models])
+
+    result = {
+        "metric": "decode-attention KV GB/s, mixed-precision slab pool",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp16/fp8_e4m3/int8/int4 KV, fp16 q, fp32 accumulate",
+        "data": "synthetic (seeded N(0,1) table deviates; lengths per config)",
+        "config": {
+            "workload": wl.name + ("-identity" if args.identity else ""),
+            "baseline_config_index": args.config,
+            "models": [f"{s.name}:{s.n_q_heads}q/{s.n_kv_heads}kv/d{s.head_dim}/L{n_layers_of[k]}of{s.n_layers}"
+                       f"/T{gw.T[gw.model_ids[k]]}/{s.n_seq}seq" for k, s in enumerate(wl.models)],
+            "pool_GiB": wl.pool_bytes / 2**30,
+            "slab_KiB": wl.slab_bytes // 1024,
+            "placement": wl.placement,
+            "churn_steps": wl.churn_steps if wl.placement == "churn" else 0,
+            "live_slabs": int(st.live_blocks),
+            "step": "fs_kv_append(newest token of every sequence) + fs_decode_attention_multi, one layer",
+            "kernel_mode": args.kernel_mode,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "split-K paged decode attention",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "kernel_ms_mean": round(kernel_ms, 4),
+            "kernel_ms_p10_p50_p90": [round(float(x), 4) for x in np.percentile(kms, [10, 50, 90])],
+            "algorithmic_bytes_per_launch": int(algo_bytes),
+        },
+        "extra": {
+            "tokens_per_s_layer": round(n_seq_total / (ms_per_step * 1e-3), 1),
+            "tokens_per_s_full_depth_equiv": round(float(full_depth_tok_s), 1),
+            "kv_bytes_per_launch": int(kv_bytes),
+            "alloc_block_ops_per_s_host": round(n_alloc_ops / max(t_place, 1e-9), 1),
+            "setup_s": round(time.perf_counter() - t_setup, 1),
+        },
+    }
+    if not args.no_cpu_baseline:
+        n_threads = min(os.cpu_count() or 1, 16)
+        t0 = time.perf_counter()
+        gbs, toks, desc, used = cpu_baseline(gw, wl, per_layer[0][0], args.cpu_sample, n_threads)
+        log(f"[bench] cpu oracle baseline took {time.perf_counter() - t0:.1f} s")
+        result["cpu_baseline"] = {"value": round(gbs, 4), "unit": "GB/s", "cores": used, "kind": "oracle",
+                                  "sample": desc, "tokens_per_s_layer": round(toks, 2)}
+    gw.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

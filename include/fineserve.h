@@ -175,6 +175,12 @@ int fs_set_kernel_mode(int mode);
 /* Target KV bytes per split-K work item (default 512 KiB); tokens per item are rounded to 32. */
 int fs_set_split_bytes(uint64_t bytes);
 
+/* Measurement aid: while enabled, every decode call brackets its attention kernel (not the small
+ * work-list and combine kernels) with HIP events on the call's stream; fs_last_attention_kernel_ms
+ * waits for the latest such pair and returns the elapsed milliseconds (negative if none). */
+int fs_set_kernel_timing(int enable);
+float fs_last_attention_kernel_ms(void);
+
 const char* fs_last_error(void);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_regist
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_set_kernel_mode",
-           "fs_set_split_bytes", "fs_last_error"]
+           "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
 
 
 class fs_geometry_t(ctypes.Structure):
@@ -77,6 +77,8 @@ def _load():
         "fs_decode_status": (i32, [vp, vp]),
         "fs_set_kernel_mode": (i32, [i32]),
         "fs_set_split_bytes": (i32, [u64]),
+        "fs_set_kernel_timing": (i32, [i32]),
+        "fs_last_attention_kernel_ms": (f32, []),
         "fs_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -274,3 +276,11 @@ def fs_set_kernel_mode(mode: int) -> int:
 
 def fs_set_split_bytes(n: int) -> int:
     return _L.fs_set_split_bytes(n)
+
+
+def fs_set_kernel_timing(enable: int) -> int:
+    return _L.fs_set_kernel_timing(int(enable))
+
+
+def fs_last_attention_kernel_ms() -> float:
+    return _L.fs_last_attention_kernel_ms()

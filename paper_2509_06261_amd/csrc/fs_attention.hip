@@ -16,6 +16,8 @@ namespace {
 
 int g_kernel_mode = 0;
 uint64_t g_split_bytes = 512u << 10;
+bool g_timing = false;
+hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
 // ---------------------------------------------------------------------------------------
 // Work-list preparation: one workgroup scans the sequences of all batches and writes, for
@@ -251,6 +253,24 @@ int fs_set_kernel_mode(int mode) {
   return FS_OK;
 }
 
+int fs_set_kernel_timing(int enable) {
+  if (enable && !g_ev0) {
+    hipError_t e = hipEventCreate(&g_ev0);
+    if (e == hipSuccess) e = hipEventCreate(&g_ev1);
+    if (e != hipSuccess) return device_error(e, "hipEventCreate");
+  }
+  g_timing = enable != 0;
+  return FS_OK;
+}
+
+float fs_last_attention_kernel_ms(void) {
+  if (!g_ev0) return -1.0f;
+  if (hipEventSynchronize(g_ev1) != hipSuccess) return -1.0f;
+  float ms = -1.0f;
+  if (hipEventElapsedTime(&ms, g_ev0, g_ev1) != hipSuccess) return -1.0f;
+  return ms;
+}
+
 int fs_set_split_bytes(uint64_t bytes) {
   if (bytes < 4096 || bytes > (1ull << 30)) return FS_ERR_INVALID;
   g_split_bytes = bytes;
@@ -293,7 +313,9 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
   // Persistent grid: two workgroups per compute unit drain the queue (never more than the
   // upper bound on work items, so tiny batches launch tiny grids).
   const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * 2, std::max<uint64_t>(plan.ub_items, 1));
+  if (g_timing) (void)hipEventRecord(g_ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
+  if (g_timing) (void)hipEventRecord(g_ev1, s);
   if (e != hipSuccess) return device_error(e, "attention launch");
   e = launch_combine(plan.args, s);
   if (e != hipSuccess) return device_error(e, "combine launch");
