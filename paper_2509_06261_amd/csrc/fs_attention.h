@@ -23,7 +23,7 @@ struct DevBatch {
   int32_t part_stride;   // floats per work item in the partial buffer: G * (D + 2)
   int32_t qrow_first;    // index of this batch's first (sequence, q head) row among all batches
   int32_t t_magic_shift; // reserved
-  uint32_t t_magic;      // reserved
+  uint32_t t_magic;      // ceil(2^32 / T): token / T == umulhi(token, t_magic) for token <= 2^32 / T
   uint32_t pad;
 };
 

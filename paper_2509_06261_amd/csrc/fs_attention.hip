@@ -203,6 +203,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
     B.qrow_first = (int32_t)qrows;
+    B.t_magic = (uint32_t)(((1ull << 32) + (uint64_t)g.tokens_per_block - 1) / (uint64_t)g.tokens_per_block);
     seq_total += b.n_seq;
     qrows += (int64_t)b.n_seq * b.n_q_heads;
     // upper bound on this batch's work items
