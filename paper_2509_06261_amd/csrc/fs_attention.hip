@@ -8,6 +8,7 @@
 // flattened into one queue of work items (sequence, split, KV head) that a persistent grid
 // drains, in place of the paper's separate per-engine launches.
 #include <algorithm>
+#include <cstdlib>
 
 #include "fs_attention.h"
 
@@ -313,7 +314,12 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
   if (e != hipSuccess) return device_error(e, "prep launch");
   // Persistent grid: two workgroups per compute unit drain the queue (never more than the
   // upper bound on work items, so tiny batches launch tiny grids).
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * 2, std::max<uint64_t>(plan.ub_items, 1));
+  static const int wgs_per_cu = [] {
+    const char* e = getenv("FS_WGS_PER_CU");  // tuning knob for measurements
+    const int v = e ? atoi(e) : 0;
+    return v >= 1 && v <= 8 ? v : 2;
+  }();
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu, std::max<uint64_t>(plan.ub_items, 1));
   if (g_timing) (void)hipEventRecord(g_ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
   if (g_timing) (void)hipEventRecord(g_ev1, s);

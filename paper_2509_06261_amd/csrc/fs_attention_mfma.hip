@@ -24,9 +24,11 @@
 //   and the Q operand is pre-arranged once per item in the same order.
 //
 // Dequantization is folded around the MFMAs: FP8 static scales and INT8/INT4 per-token K scales
-// multiply the logits, per-token V scales multiply P, INT4 codes are centred to n-8 exactly in fp16
-// and the zero-points enter as rank-1 corrections ((8 - z_k) * sum(q) on the logits, sum_t p_t s_t
-// (8 - z_v) on the output).
+// multiply the logits, per-token V scales multiply P; integer codes enter the MFMA unconverted, as fp16
+// subnormals, and their offsets (128 for INT8, the zero-point for INT4) come back as rank-1
+// corrections (z_k * sum(q) on the logits, sum_t p_t s_t z_t on the output).
+#include <utility>
+
 #include "fs_attention.h"
 
 namespace fs {
@@ -70,47 +72,47 @@ __device__ __forceinline__ float f16lo(uint32_t w) { return (float)__builtin_bit
 __device__ __forceinline__ float f16hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
 
 // ---- 8 stored elements -> 4 registers of packed fp16 -----------------------------------------
-// FP16 / FP8 / INT8: register p holds elements (2p, 2p+1).  INT4: register p holds codes (p, p+4).
+// FP16 and FP8 convert to their exact fp16 values, register p holding elements (2p, 2p+1).
+// The integer formats are not converted at all: a small integer n placed in the low mantissa bits of a
+// zero-exponent half IS the fp16 subnormal n * 2^-24, which the MFMA consumes exactly; the common
+// factor 2^24 is applied in fp32 afterwards.
+//   INT8: byte b ^ 0x80 = b + 128 (unsigned) -> halves (u0, u1), (u2, u3) by v_perm_b32; the offset 128
+//         comes back as a rank-1 correction (128 * sum(q) on the logits, 128 * sum(p') on the output).
+//   INT4: w & 0x000F000F = codes (0, 4); w & 0x00F000F0 = 16 * codes (1, 5); the same on w >> 8 for
+//         (2, 6) and 16 * (3, 7).  Register p thus holds codes (p, p + 4), odd p scaled by 16: the query
+//         operand carries 1/16 at those positions, the output columns are rescaled at the end.
 
 // two E4M3 bytes of a dword -> packed fp16 (exact)
 __device__ __forceinline__ uint32_t fp8x2_lo(uint32_t w) { return h2u(__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false)); }
 __device__ __forceinline__ uint32_t fp8x2_hi(uint32_t w) { return h2u(__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true)); }
 
-// four INT8 bytes -> two registers of packed fp16 (exact): x ^ 0x80 = x + 128 as an unsigned byte,
-// 0x6400 | u is the fp16 number 1024 + u, and 1024 + u - 1152 = x.
 __device__ __forceinline__ void int8x4(uint32_t w, uint32_t& r0, uint32_t& r1) {
   const uint32_t u = w ^ 0x80808080u;
-  const half2v off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
-  r0 = h2u(u2h(__builtin_amdgcn_perm(0x64646464u, u, 0x04010400u)) + off);
-  r1 = h2u(u2h(__builtin_amdgcn_perm(0x64646464u, u, 0x04030402u)) + off);
+  r0 = __builtin_amdgcn_perm(0u, u, 0x0C010C00u);  // selector 0x0C yields a zero byte
+  r1 = __builtin_amdgcn_perm(0u, u, 0x0C030C02u);
 }
 
-// eight INT4 codes of a dword -> four registers of packed fp16 holding code - 8 (exact):
-// 0x6400 | n = 1024 + n;  0x6400 | (n << 4) = 1024 + 16 n, and (1024 + 16 n) / 16 - 72 = n - 8.
 __device__ __forceinline__ void int4x8(uint32_t w, uint32_t (&r)[4]) {
-  const half2v c1032 = {(_Float16)-1032.0f, (_Float16)-1032.0f};
-  const half2v s16 = {(_Float16)0.0625f, (_Float16)0.0625f};
-  const half2v c72 = {(_Float16)-72.0f, (_Float16)-72.0f};
   const uint32_t w8 = w >> 8;
-  r[0] = h2u(u2h((w & 0x000F000Fu) | 0x64006400u) + c1032);                            // codes 0, 4
-  r[1] = h2u(__builtin_elementwise_fma(u2h((w & 0x00F000F0u) | 0x64006400u), s16, c72));  // codes 1, 5
-  r[2] = h2u(u2h((w8 & 0x000F000Fu) | 0x64006400u) + c1032);                           // codes 2, 6
-  r[3] = h2u(__builtin_elementwise_fma(u2h((w8 & 0x00F000F0u) | 0x64006400u), s16, c72)); // codes 3, 7
+  r[0] = w & 0x000F000Fu;
+  r[1] = w & 0x00F000F0u;
+  r[2] = w8 & 0x000F000Fu;
+  r[3] = w8 & 0x00F000F0u;
 }
 
-// Address of the rows of one 8-token run: token i of the run lives at (i < cross ? p0 : p1) + i * stride.
-struct Run {
-  const uint8_t* c0;  // head chunk of the block holding the first token of the run
-  const uint8_t* c1;  // head chunk of the next block (or c0 again when there is none)
-  int r0;             // slot of the run's first token inside its block
-  int cross;          // tokens of the run that stay in the first block (>= 8: no crossing)
-};
+constexpr float kTwo24 = 16777216.0f;
+constexpr float kTwo20 = 1048576.0f;
 
 template <int DT>
 struct Tile {
   u32x4 k[2][Fmt<DT>::kKLoads];
   uint32_t v[8][Fmt<DT>::kVBytes / 4];
-  uint32_t kpar[8], vpar[8];
+  uint32_t par;  // INT8/INT4: lanes c < 8 hold the K parameters of token c of the lane's run, lanes c >= 8 the V ones
+};
+
+// Block ids a lane needs for one tile: first and following block of its V-role run and of its K-role run.
+struct Ids {
+  uint32_t v0, v1, k0, k1;
 };
 
 struct ItemCtx {
@@ -122,82 +124,96 @@ struct ItemCtx {
   uint32_t t_magic;          // ceil(2^32 / T)
 };
 
-__device__ __forceinline__ Run make_run(const ItemCtx& X, int tok) {
-  const DevGeom& g = X.B->g;
-  const int bi = (int)__umulhi((uint32_t)tok, X.t_magic);
-  Run r;
-  r.r0 = tok - bi * g.T;
-  r.cross = g.T - r.r0;
-  const int b0 = min(bi, X.nblk - 1);  // tokens past the sequence end alias valid memory of its last block
-  const uint32_t blk0 = (uint32_t)X.table[b0];
-  r.c0 = X.head_base + (uint64_t)blk0 * g.block_budget;
-  r.c1 = r.c0;
-  if (r.cross < 8) {
-    const uint32_t blk1 = bi + 1 < X.nblk ? (uint32_t)X.table[bi + 1] : blk0;
-    r.c1 = X.head_base + (uint64_t)blk1 * g.block_budget;
-  }
-  if (bi >= X.nblk) {  // whole run is past the end: keep every address inside the last block
-    r.r0 = 0;
-    r.cross = 8;
-  }
-  return r;
+__device__ __forceinline__ Ids load_ids(const ItemCtx& X, int tb, int j, int c) {
+  const int last = X.nblk - 1;
+  const int bv = (int)__umulhi((uint32_t)(tb + 8 * j), X.t_magic);
+  const int bk = (int)__umulhi((uint32_t)(tb + 8 * (c >> 2)), X.t_magic);
+  Ids d;  // indices past the sequence's last block alias that block: always valid table entries
+  d.v0 = (uint32_t)X.table[min(bv, last)];
+  d.v1 = (uint32_t)X.table[min(bv + 1, last)];
+  d.k0 = (uint32_t)X.table[min(bk, last)];
+  d.k1 = (uint32_t)X.table[min(bk + 1, last)];
+  return d;
 }
 
-// pointer to slot i of the run inside a tile that starts `tile_off` bytes into the head chunk
-__device__ __forceinline__ const uint8_t* run_ptr(const Run& r, int i, uint32_t tile_off, int stride) {
-  const bool first = i < r.cross;
-  const uint8_t* c = first ? r.c0 : r.c1;
-  const int slot = first ? r.r0 + i : i - r.cross;
-  return c + tile_off + (uint32_t)(slot * stride);
+// Slot of a run's first token in its block and how many of the run's 8 tokens stay in that block.
+// Token i of the run is slot r0 + i of the first block if i < cross, else slot i - cross of the next.
+// A run wholly past the sequence end is mapped to slots 0..7 of the last block (valid memory).
+__device__ __forceinline__ void run_pos(const ItemCtx& X, int tok, int& r0, int& cross) {
+  const int T = X.B->g.T;
+  const int bi = (int)__umulhi((uint32_t)tok, X.t_magic);
+  r0 = tok - bi * T;
+  cross = T - r0;
+  if (bi >= X.nblk) {
+    r0 = 0;
+    cross = 8;
+  }
 }
 
 template <int DT>
-__device__ __forceinline__ void load_tile(const ItemCtx& X, int tb, int j, int c, Tile<DT>& t) {
+__device__ __forceinline__ void issue_k(const ItemCtx& X, const Ids& ids, int tb, int j, int c, Tile<DT>& t) {
   using F = Fmt<DT>;
   const DevGeom& g = X.B->g;
-  // V role: the 8-token run tb + 8j .. +7, 8 elements (d = 8c .. 8c+7) of each row
-  const Run rv = make_run(X, tb + 8 * j);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const uint8_t* p = run_ptr(rv, i, g.kv_tile, F::kRowBytes) + c * F::kVBytes;
-    if constexpr (F::kVBytes == 16) {
-      const u32x4 x = *reinterpret_cast<const u32x4*>(p);
-      t.v[i][0] = x[0];
-      t.v[i][1] = x[1];
-      t.v[i][2] = x[2];
-      t.v[i][3] = x[3];
-    } else if constexpr (F::kVBytes == 8) {
-      const u32x2 x = *reinterpret_cast<const u32x2*>(p);
-      t.v[i][0] = x[0];
-      t.v[i][1] = x[1];
-    } else {
-      t.v[i][0] = *reinterpret_cast<const uint32_t*>(p);
-    }
-    if constexpr (F::kParBytes == 2) {
-      t.kpar[i] = *reinterpret_cast<const uint16_t*>(run_ptr(rv, i, 2u * g.kv_tile, 2));
-      t.vpar[i] = *reinterpret_cast<const uint16_t*>(run_ptr(rv, i, 2u * g.kv_tile + g.par_tile, 2));
-    } else if constexpr (F::kParBytes == 4) {
-      t.kpar[i] = *reinterpret_cast<const uint32_t*>(run_ptr(rv, i, 2u * g.kv_tile, 4));
-      t.vpar[i] = *reinterpret_cast<const uint32_t*>(run_ptr(rv, i, 2u * g.kv_tile + g.par_tile, 4));
-    }
-  }
-  // K role: rows of tokens tb + 8*(c/4) + 4u + (c%4), 16 bytes at 64 s + 16 j of each
-  const Run rk = make_run(X, tb + 8 * (c >> 2));
+  int r0, cross;
+  run_pos(X, tb + 8 * (c >> 2), r0, cross);
+  const uint8_t* c0 = X.head_base + (uint64_t)ids.k0 * g.block_budget;
+  const uint8_t* c1 = X.head_base + (uint64_t)ids.k1 * g.block_budget;
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    // slot index inside the run is 4u + (c & 3): not a compile-time constant, so select by value
     const int i = 4 * u + (c & 3);
-    const bool first = i < rk.cross;
-    const uint8_t* cb = first ? rk.c0 : rk.c1;
-    const int slot = first ? rk.r0 + i : i - rk.cross;
-    const uint8_t* p = cb + (uint32_t)(slot * F::kRowBytes) + 16 * j;
+    const bool first = i < cross;
+    const uint8_t* p = (first ? c0 : c1) + (uint32_t)((first ? r0 + i : i - cross) * F::kRowBytes) + 16 * j;
 #pragma unroll
     for (int s = 0; s < F::kKLoads; ++s) t.k[u][s] = *reinterpret_cast<const u32x4*>(p + 64 * s);
   }
 }
 
+template <int DT>
+__device__ __forceinline__ void load_v_row(const uint8_t* p, uint32_t (&v)[Fmt<DT>::kVBytes / 4]) {
+  if constexpr (Fmt<DT>::kVBytes == 16) {
+    const u32x4 x = *reinterpret_cast<const u32x4*>(p);
+    v[0] = x[0];
+    v[1] = x[1];
+    v[2] = x[2];
+    v[3] = x[3];
+  } else if constexpr (Fmt<DT>::kVBytes == 8) {
+    const u32x2 x = *reinterpret_cast<const u32x2*>(p);
+    v[0] = x[0];
+    v[1] = x[1];
+  } else {
+    v[0] = *reinterpret_cast<const uint32_t*>(p);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void issue_v(const ItemCtx& X, const Ids& ids, int tb, int j, int c, Tile<DT>& t) {
+  using F = Fmt<DT>;
+  const DevGeom& g = X.B->g;
+  int r0, cross;
+  run_pos(X, tb + 8 * j, r0, cross);
+  const uint8_t* c0 = X.head_base + (uint64_t)ids.v0 * g.block_budget;
+  const uint8_t* c1 = X.head_base + (uint64_t)ids.v1 * g.block_budget;
+  if constexpr (F::kParBytes != 0) {  // parameters first: the softmax needs them before the V rows
+    const int i = c & 7;
+    const bool first = i < cross;
+    const uint8_t* p = (first ? c0 : c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
+                       (uint32_t)((first ? r0 + i : i - cross) * F::kParBytes);
+    if constexpr (F::kParBytes == 2) t.par = *reinterpret_cast<const uint16_t*>(p);
+    else t.par = *reinterpret_cast<const uint32_t*>(p);
+  }
+  const uint8_t* p0 = c0 + g.kv_tile + (uint32_t)(r0 * F::kRowBytes) + c * F::kVBytes;
+  if (__all(cross >= 8)) {  // no run of this wave crosses a block boundary: one base, constant offsets
+#pragma unroll
+    for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
+  } else {
+    const uint8_t* p1 = c1 + g.kv_tile + c * F::kVBytes - (int64_t)cross * F::kRowBytes;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) load_v_row<DT>((i < cross ? p0 : p1) + i * F::kRowBytes, t.v[i]);
+  }
+}
+
 // The Q operand (B of S^T = K Q^T) of lane (j, c) for k-step ks: 8 halves of q[head c] in the d order
-// that the format's K unpacking produces.
+// (and with the per-position factors) that the format's K unpacking produces.  qsum = sum_d q[d].
 template <int DT>
 __device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u32x4 (&qb)[4], float& qsum) {
   qsum = 0.f;
@@ -209,17 +225,17 @@ __device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u
     else d0 = 64 * (ks >> 1) + 16 * j + 8 * (ks & 1);
     u32x4 x = {0u, 0u, 0u, 0u};
     if (live) x = *reinterpret_cast<const u32x4*>(qrow + d0);
-    if (DT == FS_KV_INT4) {
-      // K registers hold codes (0,4), (1,5), (2,6), (3,7): bring q into the same order
-      u32x4 y;
-      y[0] = __builtin_amdgcn_perm(x[2], x[0], 0x05040100u);  // q0, q4
-      y[1] = __builtin_amdgcn_perm(x[2], x[0], 0x07060302u);  // q1, q5
-      y[2] = __builtin_amdgcn_perm(x[3], x[1], 0x05040100u);  // q2, q6
-      y[3] = __builtin_amdgcn_perm(x[3], x[1], 0x07060302u);  // q3, q7
-      x = y;
-    }
 #pragma unroll
     for (int p = 0; p < 4; ++p) qsum += f16lo(x[p]) + f16hi(x[p]);
+    if (DT == FS_KV_INT4) {
+      const half2v s16 = {(_Float16)0.0625f, (_Float16)0.0625f};
+      u32x4 y;
+      y[0] = __builtin_amdgcn_perm(x[2], x[0], 0x05040100u);             // q0, q4
+      y[1] = h2u(u2h(__builtin_amdgcn_perm(x[2], x[0], 0x07060302u)) * s16);  // (q1, q5) / 16
+      y[2] = __builtin_amdgcn_perm(x[3], x[1], 0x05040100u);             // q2, q6
+      y[3] = h2u(u2h(__builtin_amdgcn_perm(x[3], x[1], 0x07060302u)) * s16);  // (q3, q7) / 16
+      x = y;
+    }
     qb[ks] = x;
   }
 }
@@ -269,7 +285,7 @@ __device__ __forceinline__ void k_operands(const u32x4 (&k)[Fmt<DT>::kKLoads], u
   }
 }
 
-// 8 elements of one V row -> four packed-fp16 registers (see the layout note above int8x4).
+// 8 elements of one V row -> four packed-fp16 registers (layout note above).
 template <int DT>
 __device__ __forceinline__ void v_unpack(const uint32_t (&v)[Fmt<DT>::kVBytes / 4], uint32_t (&x)[4]) {
   if constexpr (DT == FS_KV_FP16) {
@@ -288,20 +304,29 @@ __device__ __forceinline__ void v_unpack(const uint32_t (&v)[Fmt<DT>::kVBytes / 
   }
 }
 
+// value of lane I of the own 16-lane row, broadcast to the whole row (DPP row_newbcast)
+template <int I>
+__device__ __forceinline__ float row_bcast(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x150 + I, 0xF, 0xF, false));
+}
+
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+
 // Per-wave online-softmax state.  acc[e] is the 16x16 output tile of d columns {8c' + e}: lane (j', c')
 // holds rows (heads) 4j'..4j'+3.  m, l, zc are per head c in the S^T layout (lane (j, c), any j).
 struct State {
   float4v acc[8];
   float m;   // running max of the logits (base-2 domain)
   float l;   // this lane's share of the running sum (its 8-token runs only)
-  float zc;  // INT4: this lane's share of sum_t p_t s_t (8 - z_t)
+  float zc;  // INT8/INT4: this lane's share of the zero-point term  -sum_t p_t s_t z_t
 };
 
+// S^T = K Q^T for the 32 tokens of the tile: s[u][r] = raw logit of head c, token tb + 8j + 4u + r.
 template <int DT>
-__device__ __forceinline__ void compute_tile(const ItemCtx& X, const Tile<DT>& t, int tb, int j, int c,
-                                             const u32x4 (&qb)[4], float qsum, float alpha, State& st) {
-  // ---- S^T = K Q^T ----
-  float4v s[2];
+__device__ __forceinline__ void qk_tile(const Tile<DT>& t, const u32x4 (&qb)[4], float4v (&s)[2]) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     u32x4 a[4];
@@ -311,70 +336,98 @@ __device__ __forceinline__ void compute_tile(const ItemCtx& X, const Tile<DT>& t
     for (int ks = 0; ks < 4; ++ks) acc = mfma(a[ks], qb[ks], acc);
     s[u] = acc;
   }
-  // ---- logits of head c for tokens tb + 8j + i (i = 4u + r), base-2 domain ----
+}
+
+// Online softmax over the tile and out += P V.
+template <int DT>
+__device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const float4v (&s)[2], int tb, int j, int c,
+                                           float qsum, float alpha, State& st) {
   const int n_valid = X.t1 - (tb + 8 * j);  // tokens of this lane's run inside the range
-  float x[8], vs[8];
-  float tmax = -INFINITY;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float v = s[i >> 2][i & 3];
-    float sc = alpha;
-    vs[i] = 1.0f;
-    if (DT == FS_KV_INT8) {
-      sc = alpha * f16lo(t.kpar[i]);
-      vs[i] = f16lo(t.vpar[i]);
-    } else if (DT == FS_KV_INT4) {
-      sc = alpha * f16lo(t.kpar[i]);
-      v = fmaf(8.0f - f16hi(t.kpar[i]), qsum, v);
-      vs[i] = f16lo(t.vpar[i]);
+  const bool partial = tb + kTile > X.t1;    // wave-uniform
+  float x[8];
+  // per-token dequantization factors, prepared by the lane that loaded the token's parameters
+  float pa = 0.f, pb = 0.f;
+  if constexpr (Fmt<DT>::kParBytes != 0) {
+    const float sc = f16lo(t.par);
+    const float zp = DT == FS_KV_INT4 ? f16hi(t.par) : 128.0f;
+    if (c < 8) {  // K: logit = alpha * sc * (2^24 * S_raw - zp * qsum)
+      pa = alpha * kTwo24 * sc;
+      pb = -alpha * sc * zp;
+    } else {      // V: p' = p * sc, zero-point term -p * sc * zp
+      const bool ok = (c & 7) < n_valid;
+      pa = ok ? sc : 0.f;
+      pb = ok ? -sc * zp : 0.f;
     }
-    x[i] = i < n_valid ? v * sc : -INFINITY;
-    tmax = fmaxf(tmax, x[i]);
   }
+  float ka[8], kb[8], va[8], vb[8];
+  static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    const float v = s[i >> 2][i & 3];
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      ka[i] = row_bcast<i>(pa);
+      kb[i] = row_bcast<i>(pb);
+      va[i] = row_bcast<8 + i>(pa);
+      vb[i] = row_bcast<8 + i>(pb);
+      x[i] = fmaf(v, ka[i], kb[i] * qsum);
+    } else {
+      x[i] = v * alpha;
+    }
+  });
+  if (partial) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = i < n_valid ? x[i] : -INFINITY;
+    if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
+      // rows past the range may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int w = 0; w < Fmt<DT>::kVBytes / 4; ++w) t.v[i][w] = i < n_valid ? t.v[i][w] : 0u;
+    }
+  }
+  float tmax = x[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
   tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-  const float m_new = fmaxf(st.m, tmax);  // finite: every tile has at least one valid token (token tb)
-  const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
+  const float m_new = fmaxf(st.m, tmax);  // finite: token tb of every tile is inside the range
   // ---- rescale the running state when some head's max moved ----
   if (__any(m_new > st.m)) {
+    const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
     st.l *= corr;
-    if (DT == FS_KV_INT4) st.zc *= corr;
+    if constexpr (Fmt<DT>::kParBytes != 0) st.zc *= corr;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const float cr = __shfl(corr, 4 * j + r, 64);  // head 4j + r keeps its factor in lane c = 4j + r
 #pragma unroll
       for (int e = 0; e < 8; ++e) st.acc[e][r] *= cr;
     }
+    st.m = m_new;
   }
-  st.m = m_new;
-  // ---- P (and P scaled by the per-token V scale) ----
+  // ---- P (times the per-token V scale) ----
   float p[8];
   float lsum = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const float e = __builtin_amdgcn_exp2f(x[i] - m_new);
     lsum += e;
-    p[i] = e;
-    if (DT == FS_KV_INT8 || DT == FS_KV_INT4) p[i] = i < n_valid ? e * vs[i] : 0.f;
-    if (DT == FS_KV_INT4) st.zc = fmaf(p[i], 8.0f - (i < n_valid ? f16hi(t.vpar[i]) : 8.0f), st.zc);
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      p[i] = e * va[i];
+      st.zc = fmaf(e, vb[i], st.zc);
+    } else {
+      p[i] = e;
+    }
   }
   st.l += lsum;
-  u32x4 pa;
+  u32x4 pk;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
-    pa[q] = h2u(h);
+    pk[q] = h2u(h);
   }
   // ---- V rows of the run -> B operands (8x8 in-register transpose) and out += P V ----
   uint32_t vx[8][4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    v_unpack<DT>(t.v[i], vx[i]);
-    if (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
-      // rows past the range may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
-      if (i >= n_valid) vx[i][0] = vx[i][1] = vx[i][2] = vx[i][3] = 0u;
-    }
-  }
+  for (int i = 0; i < 8; ++i) v_unpack<DT>(t.v[i], vx[i]);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int reg = DT == FS_KV_INT4 ? (e & 3) : (e >> 1);
@@ -382,7 +435,7 @@ __device__ __forceinline__ void compute_tile(const ItemCtx& X, const Tile<DT>& t
     u32x4 b;
 #pragma unroll
     for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
-    st.acc[e] = mfma(pa, b, st.acc[e]);
+    st.acc[e] = mfma(pk, b, st.acc[e]);
   }
 }
 
@@ -417,7 +470,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   u32x4 qb[4];
   float qsum;
   load_q<DT>(B.q + ((int64_t)seq * B.n_q + head * G + c) * kD, c < G, j, qb, qsum);
-  if (DT == FS_KV_INT4) {
+  if constexpr (Fmt<DT>::kParBytes != 0) {
     qsum += __shfl_xor(qsum, 16, 64);
     qsum += __shfl_xor(qsum, 32, 64);
   }
@@ -431,22 +484,37 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   st.l = 0.f;
   st.zc = 0.f;
 
-  // software pipeline: the loads of tile n+1 are in flight while tile n is computed
+  // Software pipeline over this wave's tiles n = wave, wave + 4, ...: one register copy of a tile; the K
+  // rows of the next tile are requested as soon as S^T of the current one is done, its V rows as soon as
+  // P V is done, and the block-table entries of the tile after that just before those V rows, so that a
+  // wait for them never waits for the V rows behind them.
   const int n_tiles = (X.t1 - t0 + kTile - 1) / kTile;
-  int n = wave;
-  Tile<DT> cur, nxt;
-  if (n < n_tiles) load_tile<DT>(X, t0 + n * kTile, j, c, cur);
-  for (; n < n_tiles; n += kWaves) {
+  Tile<DT> t;
+  Ids ids_next;
+  if (wave < n_tiles) {
+    const Ids ids0 = load_ids(X, t0 + wave * kTile, j, c);
+    ids_next = load_ids(X, t0 + min(wave + kWaves, n_tiles - 1) * kTile, j, c);
+    issue_k<DT>(X, ids0, t0 + wave * kTile, j, c, t);
+    issue_v<DT>(X, ids0, t0 + wave * kTile, j, c, t);
+  }
+  for (int n = wave; n < n_tiles; n += kWaves) {
+    const int tb = t0 + n * kTile;
     const bool more = n + kWaves < n_tiles;
-    if (more) load_tile<DT>(X, t0 + (n + kWaves) * kTile, j, c, nxt);
-    compute_tile<DT>(X, cur, t0 + n * kTile, j, c, qb, qsum, alpha, st);
-    if (more) cur = nxt;
+    float4v s[2];
+    qk_tile<DT>(t, qb, s);
+    const Ids ids_cur = ids_next;
+    if (more) issue_k<DT>(X, ids_cur, tb + kWaves * kTile, j, c, t);
+    softmax_pv<DT>(X, t, s, tb, j, c, qsum, alpha, st);
+    if (more) {
+      ids_next = load_ids(X, t0 + min(n + 2 * kWaves, n_tiles - 1) * kTile, j, c);
+      issue_v<DT>(X, ids_cur, tb + kWaves * kTile, j, c, t);
+    }
   }
 
   // ---- merge the four waves through LDS: [wave][head][D] accumulators, [wave][head] m, l, zc ----
   st.l += __shfl_xor(st.l, 16, 64);
   st.l += __shfl_xor(st.l, 32, 64);
-  if (DT == FS_KV_INT4) {
+  if constexpr (Fmt<DT>::kParBytes != 0) {
     st.zc += __shfl_xor(st.zc, 16, 64);
     st.zc += __shfl_xor(st.zc, 32, 64);
   }
@@ -459,7 +527,11 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
     const int h = 4 * j + r;
     if (h < G) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s_acc[(wave * 16 + h) * kD + 8 * c + e] = st.acc[e][r];
+      for (int e = 0; e < 8; ++e) {
+        // integer formats: undo the 2^-24 of the subnormal encoding (and the 16 of INT4's odd code positions)
+        const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+        s_acc[(wave * 16 + h) * kD + 8 * c + e] = st.acc[e][r] * f;
+      }
     }
   }
   if (j == 0 && c < G) {
@@ -481,7 +553,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
       const float wt = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
       L += s_l[w * 16 + h] * wt;
       float o = s_acc[(w * 16 + h) * kD + d];
-      if (DT == FS_KV_INT4) o += s_z[w * 16 + h];
+      if constexpr (Fmt<DT>::kParBytes != 0) o += s_z[w * 16 + h];
       O += o * wt;
     }
     O *= v_static;
