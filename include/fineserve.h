@@ -172,7 +172,7 @@ int fs_decode_status(const void* workspace, void* stream);
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
 int fs_set_kernel_mode(int mode);
-/* Target KV bytes per split-K work item (default 512 KiB); tokens per item are rounded to 32. */
+/* Target KV bytes per split-K work item (default 1 MiB); tokens per item are rounded to 32. */
 int fs_set_split_bytes(uint64_t bytes);
 
 /* Measurement aid: while enabled, every decode call brackets its attention kernel (not the small

@@ -16,7 +16,7 @@ namespace fs {
 namespace {
 
 int g_kernel_mode = 0;
-uint64_t g_split_bytes = 512u << 10;
+uint64_t g_split_bytes = 1u << 20;
 bool g_timing = false;
 hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
@@ -200,6 +200,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.sm_scale = b.sm_scale;
     const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
     int64_t ct = (int64_t)(g_split_bytes / token_bytes) / 32 * 32;
+    ct = std::min<int64_t>(ct, (int64_t)2040 * g.tokens_per_block / 32 * 32);  // at most ~2K blocks per work item
     B.chunk_tokens = (int32_t)std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);

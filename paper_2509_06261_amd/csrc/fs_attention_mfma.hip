@@ -27,6 +27,7 @@
 // multiply the logits, per-token V scales multiply P; integer codes enter the MFMA unconverted, as fp16
 // subnormals, and their offsets (128 for INT8, the zero-point for INT4) come back as rank-1
 // corrections (z_k * sum(q) on the logits, sum_t p_t s_t z_t on the output).
+#include <algorithm>
 #include <utility>
 
 #include "fs_attention.h"
@@ -46,24 +47,25 @@ constexpr int kD = 128;
 constexpr int kTile = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kMergeFloats = kWaves * 16 * kD + 3 * kWaves * 16;  // LDS floats of the cross-wave merge
 
 template <int DT>
 struct Fmt;
 template <>
 struct Fmt<FS_KV_FP16> {
-  static constexpr int kRowBytes = 256, kKLoads = 4, kVBytes = 16, kParBytes = 0;
+  static constexpr int kRowBytes = 256, kKLoads = 4, kVBytes = 16, kParBytes = 0, kRing = 1;
 };
 template <>
 struct Fmt<FS_KV_FP8_E4M3> {
-  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 0;
+  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 0, kRing = 2;
 };
 template <>
 struct Fmt<FS_KV_INT8> {
-  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 2;
+  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 2, kRing = 2;
 };
 template <>
 struct Fmt<FS_KV_INT4> {
-  static constexpr int kRowBytes = 64, kKLoads = 1, kVBytes = 4, kParBytes = 4;
+  static constexpr int kRowBytes = 64, kKLoads = 1, kVBytes = 4, kParBytes = 4, kRing = 3;
 };
 
 __device__ __forceinline__ uint32_t h2u(half2v h) { return __builtin_bit_cast(uint32_t, h); }
@@ -110,59 +112,50 @@ struct Tile {
   uint32_t par;  // INT8/INT4: lanes c < 8 hold the K parameters of token c of the lane's run, lanes c >= 8 the V ones
 };
 
-// Block ids a lane needs for one tile: first and following block of its V-role run and of its K-role run.
-struct Ids {
-  uint32_t v0, v1, k0, k1;
-};
-
 struct ItemCtx {
   const DevBatch* B;
-  const int32_t* table;
-  const uint8_t* head_base;  // layer_base + head * head_chunk
-  int nblk;                  // blocks of this sequence
-  int t1;                    // end of this item's token range
-  uint32_t t_magic;          // ceil(2^32 / T)
+  const uint64_t* chunk_ptr;  // LDS: head-chunk address of blocks b_first .. b_last + 1 of this item's range
+  int b_first, b_last;        // first / last block the item's token range touches
+  int t1;                     // end of this item's token range
+  uint32_t t_magic;           // ceil(2^32 / T)
 };
 
-__device__ __forceinline__ Ids load_ids(const ItemCtx& X, int tb, int j, int c) {
-  const int last = X.nblk - 1;
-  const int bv = (int)__umulhi((uint32_t)(tb + 8 * j), X.t_magic);
-  const int bk = (int)__umulhi((uint32_t)(tb + 8 * (c >> 2)), X.t_magic);
-  Ids d;  // indices past the sequence's last block alias that block: always valid table entries
-  d.v0 = (uint32_t)X.table[min(bv, last)];
-  d.v1 = (uint32_t)X.table[min(bv + 1, last)];
-  d.k0 = (uint32_t)X.table[min(bk, last)];
-  d.k1 = (uint32_t)X.table[min(bk + 1, last)];
-  return d;
-}
+// Where an 8-token run starting at token `tok` lives: head-chunk addresses of its first block (c0) and of
+// the block after it (c1), the slot r0 of its first token, and how many of its tokens stay in the first
+// block (cross >= 8: no crossing).  Token i is slot r0 + i of c0 if i < cross, else slot i - cross of c1.
+// A run wholly past the item's last block is mapped to slots 0..7 of a valid block (its data is masked).
+struct Run {
+  const uint8_t* c0;
+  const uint8_t* c1;
+  int r0, cross;
+};
 
-// Slot of a run's first token in its block and how many of the run's 8 tokens stay in that block.
-// Token i of the run is slot r0 + i of the first block if i < cross, else slot i - cross of the next.
-// A run wholly past the sequence end is mapped to slots 0..7 of the last block (valid memory).
-__device__ __forceinline__ void run_pos(const ItemCtx& X, int tok, int& r0, int& cross) {
+__device__ __forceinline__ Run locate_run(const ItemCtx& X, int tok) {
   const int T = X.B->g.T;
   const int bi = (int)__umulhi((uint32_t)tok, X.t_magic);
-  r0 = tok - bi * T;
-  cross = T - r0;
-  if (bi >= X.nblk) {
-    r0 = 0;
-    cross = 8;
+  Run r;
+  r.r0 = tok - bi * T;
+  r.cross = T - r.r0;
+  int idx = bi - X.b_first;
+  if (bi > X.b_last) {
+    r.r0 = 0;
+    r.cross = 8;
+    idx = X.b_last + 1 - X.b_first;
   }
+  r.c0 = reinterpret_cast<const uint8_t*>(X.chunk_ptr[idx]);
+  r.c1 = reinterpret_cast<const uint8_t*>(X.chunk_ptr[min(idx + 1, X.b_last + 1 - X.b_first)]);
+  return r;
 }
 
 template <int DT>
-__device__ __forceinline__ void issue_k(const ItemCtx& X, const Ids& ids, int tb, int j, int c, Tile<DT>& t) {
+__device__ __forceinline__ void issue_k(const ItemCtx& X, int tb, int j, int c, Tile<DT>& t) {
   using F = Fmt<DT>;
-  const DevGeom& g = X.B->g;
-  int r0, cross;
-  run_pos(X, tb + 8 * (c >> 2), r0, cross);
-  const uint8_t* c0 = X.head_base + (uint64_t)ids.k0 * g.block_budget;
-  const uint8_t* c1 = X.head_base + (uint64_t)ids.k1 * g.block_budget;
+  const Run r = locate_run(X, tb + 8 * (c >> 2));
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int i = 4 * u + (c & 3);
-    const bool first = i < cross;
-    const uint8_t* p = (first ? c0 : c1) + (uint32_t)((first ? r0 + i : i - cross) * F::kRowBytes) + 16 * j;
+    const bool first = i < r.cross;
+    const uint8_t* p = (first ? r.c0 : r.c1) + (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kRowBytes) + 16 * j;
 #pragma unroll
     for (int s = 0; s < F::kKLoads; ++s) t.k[u][s] = *reinterpret_cast<const u32x4*>(p + 64 * s);
   }
@@ -186,29 +179,26 @@ __device__ __forceinline__ void load_v_row(const uint8_t* p, uint32_t (&v)[Fmt<D
 }
 
 template <int DT>
-__device__ __forceinline__ void issue_v(const ItemCtx& X, const Ids& ids, int tb, int j, int c, Tile<DT>& t) {
+__device__ __forceinline__ void issue_v(const ItemCtx& X, int tb, int j, int c, Tile<DT>& t) {
   using F = Fmt<DT>;
   const DevGeom& g = X.B->g;
-  int r0, cross;
-  run_pos(X, tb + 8 * j, r0, cross);
-  const uint8_t* c0 = X.head_base + (uint64_t)ids.v0 * g.block_budget;
-  const uint8_t* c1 = X.head_base + (uint64_t)ids.v1 * g.block_budget;
+  const Run r = locate_run(X, tb + 8 * j);
   if constexpr (F::kParBytes != 0) {  // parameters first: the softmax needs them before the V rows
     const int i = c & 7;
-    const bool first = i < cross;
-    const uint8_t* p = (first ? c0 : c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
-                       (uint32_t)((first ? r0 + i : i - cross) * F::kParBytes);
+    const bool first = i < r.cross;
+    const uint8_t* p = (first ? r.c0 : r.c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
+                       (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kParBytes);
     if constexpr (F::kParBytes == 2) t.par = *reinterpret_cast<const uint16_t*>(p);
     else t.par = *reinterpret_cast<const uint32_t*>(p);
   }
-  const uint8_t* p0 = c0 + g.kv_tile + (uint32_t)(r0 * F::kRowBytes) + c * F::kVBytes;
-  if (__all(cross >= 8)) {  // no run of this wave crosses a block boundary: one base, constant offsets
+  const uint8_t* p0 = r.c0 + g.kv_tile + (uint32_t)(r.r0 * F::kRowBytes) + c * F::kVBytes;
+  if (__all(r.cross >= 8)) {  // no run of this wave crosses a block boundary: one base, constant offsets
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
   } else {
-    const uint8_t* p1 = c1 + g.kv_tile + c * F::kVBytes - (int64_t)cross * F::kRowBytes;
+    const uint8_t* p1 = r.c1 + g.kv_tile + c * F::kVBytes - (int64_t)r.cross * F::kRowBytes;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_v_row<DT>((i < cross ? p0 : p1) + i * F::kRowBytes, t.v[i]);
+    for (int i = 0; i < 8; ++i) load_v_row<DT>((i < r.cross ? p0 : p1) + i * F::kRowBytes, t.v[i]);
   }
 }
 
@@ -451,18 +441,34 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
   const int n_chunks = (len + B.chunk_tokens - 1) / B.chunk_tokens;
   const int t0 = chunk * B.chunk_tokens;
+  const int t1 = min(len, t0 + B.chunk_tokens);
+  const int nblk = (len + g.T - 1) / g.T;
   ItemCtx X;
   X.B = &B;
-  X.table = B.tables + (int64_t)seq * B.max_blocks;
-  X.head_base = B.layer_base + (uint64_t)head * g.head_chunk;
-  X.nblk = (len + g.T - 1) / g.T;
-  X.t1 = min(len, t0 + B.chunk_tokens);
+  X.b_first = t0 / g.T;
+  X.b_last = (t1 - 1) / g.T;
+  X.t1 = t1;
   X.t_magic = B.t_magic;
+  // head-chunk addresses of the blocks this item touches (plus one more), through LDS: every lane of
+  // every tile looks its blocks up here instead of gathering them from the block table in memory
+  uint64_t* s_ptr = reinterpret_cast<uint64_t*>(smem + kMergeFloats);
+  X.chunk_ptr = s_ptr;
+  {
+    const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
+    const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
+    const int nb = X.b_last - X.b_first + 2;
+    for (int i = threadIdx.x; i < nb; i += kThreads) {
+      const int bi = min(X.b_first + i, nblk - 1);  // past the sequence's last block: alias it (valid memory)
+      s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[bi] * g.block_budget);
+    }
+  }
+  __syncthreads();
 
   const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
   const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
   if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {
     if (threadIdx.x == 0) atomicOr(A.header + kHdrStatus, 2u);
+    __syncthreads();
     return;
   }
 
@@ -484,31 +490,37 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   st.l = 0.f;
   st.zc = 0.f;
 
-  // Software pipeline over this wave's tiles n = wave, wave + 4, ...: one register copy of a tile; the K
-  // rows of the next tile are requested as soon as S^T of the current one is done, its V rows as soon as
-  // P V is done, and the block-table entries of the tile after that just before those V rows, so that a
-  // wait for them never waits for the V rows behind them.
-  const int n_tiles = (X.t1 - t0 + kTile - 1) / kTile;
-  Tile<DT> t;
-  Ids ids_next;
-  if (wave < n_tiles) {
-    const Ids ids0 = load_ids(X, t0 + wave * kTile, j, c);
-    ids_next = load_ids(X, t0 + min(wave + kWaves, n_tiles - 1) * kTile, j, c);
-    issue_k<DT>(X, ids0, t0 + wave * kTile, j, c, t);
-    issue_v<DT>(X, ids0, t0 + wave * kTile, j, c, t);
-  }
-  for (int n = wave; n < n_tiles; n += kWaves) {
-    const int tb = t0 + n * kTile;
-    const bool more = n + kWaves < n_tiles;
-    float4v s[2];
-    qk_tile<DT>(t, qb, s);
-    const Ids ids_cur = ids_next;
-    if (more) issue_k<DT>(X, ids_cur, tb + kWaves * kTile, j, c, t);
-    softmax_pv<DT>(X, t, s, tb, j, c, qsum, alpha, st);
-    if (more) {
-      ids_next = load_ids(X, t0 + min(n + 2 * kWaves, n_tiles - 1) * kTile, j, c);
-      issue_v<DT>(X, ids_cur, tb + kWaves * kTile, j, c, t);
+  // Software pipeline over this wave's tiles (tile k of the wave is tile wave + 4k of the item): a ring of
+  // NBUF register copies of a tile.  The K rows of the tile that will next occupy a slot are requested as
+  // soon as S^T of its current occupant is done, the V rows as soon as P V is done, so the narrower the
+  // format the more tiles are in flight (about 16 KiB per wave for every format).
+  constexpr int NBUF = Fmt<DT>::kRing;
+  const int n_tiles = (t1 - t0 + kTile - 1) / kTile;
+  const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
+  Tile<DT> t[NBUF];
+  static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
+    constexpr int bi = decltype(Bi)::value;
+    if (bi < my_tiles) {
+      const int tb = t0 + (wave + bi * kWaves) * kTile;
+      issue_k<DT>(X, tb, j, c, t[bi]);
+      issue_v<DT>(X, tb, j, c, t[bi]);
     }
+  });
+  for (int k0 = 0; k0 < my_tiles; k0 += NBUF) {
+    static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
+      constexpr int bi = decltype(Bi)::value;
+      const int k = k0 + bi;
+      if (k < my_tiles) {
+        const int tb = t0 + (wave + k * kWaves) * kTile;
+        const int tb_next = tb + NBUF * kWaves * kTile;
+        const bool more = k + NBUF < my_tiles;
+        float4v s[2];
+        qk_tile<DT>(t[bi], qb, s);
+        if (more) issue_k<DT>(X, tb_next, j, c, t[bi]);
+        softmax_pv<DT>(X, t[bi], s, tb, j, c, qsum, alpha, st);
+        if (more) issue_v<DT>(X, tb_next, j, c, t[bi]);
+      }
+    });
   }
 
   // ---- merge the four waves through LDS: [wave][head][D] accumulators, [wave][head] m, l, zc ----
@@ -614,7 +626,10 @@ bool mfma_supports(const DevBatch& b) {
 }
 
 hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s) {
-  const size_t smem = (size_t)(kWaves * 16 * kD + 3 * kWaves * 16) * sizeof(float);
+  // LDS: merge buffers, then one 8-byte address per block of the largest split (+ slack)
+  int max_blocks = 0;
+  for (int i = 0; i < A.n_batches; ++i) max_blocks = std::max(max_blocks, A.b[i].chunk_tokens / A.b[i].g.T + 4);
+  const size_t smem = (size_t)kMergeFloats * sizeof(float) + (size_t)max_blocks * sizeof(uint64_t);
   hipLaunchKernelGGL(mfma_attention_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A);
   return hipGetLastError();
 }
