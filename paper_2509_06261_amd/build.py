@@ -13,6 +13,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: quantizer arithmetic must not be fused (bytes are compared bit for bit).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+FLAGS += os.environ.get("FS_EXTRA_HIPCC_FLAGS", "").split()  # experiments only
 
 
 def build(verbose: bool = False) -> str:

@@ -40,6 +40,8 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#define FS_GLOBAL __attribute__((address_space(1)))
+typedef const FS_GLOBAL uint8_t* gptr;  // global (not flat) address
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
@@ -125,8 +127,8 @@ struct ItemCtx {
 // block (cross >= 8: no crossing).  Token i is slot r0 + i of c0 if i < cross, else slot i - cross of c1.
 // A run wholly past the item's last block is mapped to slots 0..7 of a valid block (its data is masked).
 struct Run {
-  const uint8_t* c0;
-  const uint8_t* c1;
+  gptr c0;
+  gptr c1;
   int r0, cross;
 };
 
@@ -142,8 +144,8 @@ __device__ __forceinline__ Run locate_run(const ItemCtx& X, int tok) {
     r.cross = 8;
     idx = X.b_last + 1 - X.b_first;
   }
-  r.c0 = reinterpret_cast<const uint8_t*>(X.chunk_ptr[idx]);
-  r.c1 = reinterpret_cast<const uint8_t*>(X.chunk_ptr[min(idx + 1, X.b_last + 1 - X.b_first)]);
+  r.c0 = (gptr)X.chunk_ptr[idx];
+  r.c1 = (gptr)X.chunk_ptr[min(idx + 1, X.b_last + 1 - X.b_first)];
   return r;
 }
 
@@ -155,26 +157,26 @@ __device__ __forceinline__ void issue_k(const ItemCtx& X, int tb, int j, int c, 
   for (int u = 0; u < 2; ++u) {
     const int i = 4 * u + (c & 3);
     const bool first = i < r.cross;
-    const uint8_t* p = (first ? r.c0 : r.c1) + (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kRowBytes) + 16 * j;
+    const gptr p = (first ? r.c0 : r.c1) + (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kRowBytes) + 16 * j;
 #pragma unroll
-    for (int s = 0; s < F::kKLoads; ++s) t.k[u][s] = *reinterpret_cast<const u32x4*>(p + 64 * s);
+    for (int s = 0; s < F::kKLoads; ++s) t.k[u][s] = *reinterpret_cast<const FS_GLOBAL u32x4*>(p + 64 * s);
   }
 }
 
 template <int DT>
-__device__ __forceinline__ void load_v_row(const uint8_t* p, uint32_t (&v)[Fmt<DT>::kVBytes / 4]) {
+__device__ __forceinline__ void load_v_row(gptr p, uint32_t (&v)[Fmt<DT>::kVBytes / 4]) {
   if constexpr (Fmt<DT>::kVBytes == 16) {
-    const u32x4 x = *reinterpret_cast<const u32x4*>(p);
+    const u32x4 x = *reinterpret_cast<const FS_GLOBAL u32x4*>(p);
     v[0] = x[0];
     v[1] = x[1];
     v[2] = x[2];
     v[3] = x[3];
   } else if constexpr (Fmt<DT>::kVBytes == 8) {
-    const u32x2 x = *reinterpret_cast<const u32x2*>(p);
+    const u32x2 x = *reinterpret_cast<const FS_GLOBAL u32x2*>(p);
     v[0] = x[0];
     v[1] = x[1];
   } else {
-    v[0] = *reinterpret_cast<const uint32_t*>(p);
+    v[0] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
   }
 }
 
@@ -186,17 +188,17 @@ __device__ __forceinline__ void issue_v(const ItemCtx& X, int tb, int j, int c, 
   if constexpr (F::kParBytes != 0) {  // parameters first: the softmax needs them before the V rows
     const int i = c & 7;
     const bool first = i < r.cross;
-    const uint8_t* p = (first ? r.c0 : r.c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
+    const gptr p = (first ? r.c0 : r.c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
                        (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kParBytes);
-    if constexpr (F::kParBytes == 2) t.par = *reinterpret_cast<const uint16_t*>(p);
-    else t.par = *reinterpret_cast<const uint32_t*>(p);
+    if constexpr (F::kParBytes == 2) t.par = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p);
+    else t.par = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
   }
-  const uint8_t* p0 = r.c0 + g.kv_tile + (uint32_t)(r.r0 * F::kRowBytes) + c * F::kVBytes;
+  const gptr p0 = r.c0 + g.kv_tile + (uint32_t)(r.r0 * F::kRowBytes) + c * F::kVBytes;
   if (__all(r.cross >= 8)) {  // no run of this wave crosses a block boundary: one base, constant offsets
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
   } else {
-    const uint8_t* p1 = r.c1 + g.kv_tile + c * F::kVBytes - (int64_t)r.cross * F::kRowBytes;
+    const gptr p1 = r.c1 + g.kv_tile + c * F::kVBytes - (int64_t)r.cross * F::kRowBytes;
 #pragma unroll
     for (int i = 0; i < 8; ++i) load_v_row<DT>((i < r.cross ? p0 : p1) + i * F::kRowBytes, t.v[i]);
   }
@@ -433,7 +435,8 @@ template <int DT>
 __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, float* smem) {
   const DevBatch& B = A.b[b];
   const DevGeom& g = B.g;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps the tile loop scalar
   const int j = lane >> 4, c = lane & 15;
   const int G = B.G;
   const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
