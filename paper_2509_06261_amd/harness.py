@@ -59,6 +59,9 @@ class GpuWorkload:
             fs.fs_pool_destroy(self.pool)
             self.pool = None
             self.pool_mem = None
+            self._ws = None
+            self.tables, self.seq_lens = [], []
+            torch.cuda.empty_cache()  # hand the (possibly >100 GiB) pool back before the next workload
 
     # ------------------------------------------------------------------ allocation
     def place(self, adapter=None):

@@ -1,0 +1,61 @@
+"""GPU parity at the benchmark's full sizes (configs 2-5), in the launch configuration bench.py times:
+the whole workload is placed and decoded in one multi-model launch; the allocator is compared with
+the oracle operation by operation over the complete trace; appended bytes and attention outputs are
+compared on a seeded sample of sequences per model (always including the shortest and the longest)
+that the CPU oracle recomputes one by one; every other sequence is cross-checked between the two
+independently written GPU kernels (MFMA vs generic)."""
+import numpy as np
+import pytest
+
+from fs_inputs import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_size(cfg, layers, n_random):
+    import torch
+    import gpu_harness
+
+    wl = workloads.config(cfg)
+    print(f"[full-size] config {cfg}: placing", flush=True)
+    par = gpu_harness.Parity(wl, zero_pool=False)
+    try:
+        print(f"[full-size] config {cfg}: {par.n_alloc_ops} allocator calls identical; decoding", flush=True)
+        errs = par.run_and_check(layers, n_random=n_random)
+        print(f"[full-size] config {cfg}: sampled max abs err {errs}", flush=True)
+        # all sequences: the MFMA kernel against the generic kernel on the same pool contents
+        gw, fs = par.gw, par.fs
+        outs = {}
+        for mode in (0, 1):
+            fs.fs_set_kernel_mode(mode)
+            try:
+                batches, keep = gw.make_batches(layers, with_lse=False)
+                ws = gw.decode(batches)
+                torch.cuda.synchronize()
+                assert fs.fs_decode_status(ws) == 0
+                outs[mode] = [o.float().cpu().numpy() for o in keep["out"]]
+            finally:
+                fs.fs_set_kernel_mode(0)
+        for k, s in enumerate(wl.models):
+            tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
+            d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
+            assert np.all(np.isfinite(outs[0][k])) and d <= tol, f"model {k}: kernels differ by {d:.3e}"
+        return errs
+    finally:
+        par.close()
+
+
+def test_config2_llama8b_fp16_full():
+    _full_size(2, [17], n_random=6)
+
+
+def test_config3_fp16_fp8_interleaved_full():
+    _full_size(3, [3, 29], n_random=3)
+
+
+def test_config4_int4_full():
+    _full_size(4, [11], n_random=4)
+
+
+def test_config5_four_model_churned_pool_full():
+    _full_size(5, [7, 0, 3, 9], n_random=2)
