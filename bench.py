@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--only-model", type=int, default=-1, help="control run: only model k of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=6, help="sequences per model for the CPU oracle timing")
+    ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
+                    help="after the timed region also run a plain device copy of this size (counter calibration "
+                         "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build targets one GPU (every box has one); --gpus must be 1. "
@@ -118,10 +121,22 @@ def main():
     log(f"[bench] workload {wl.name}: pool {wl.pool_bytes / 2**30:.0f} GiB, slabs {wl.slab_bytes // 1024} KiB, "
         f"placement {wl.placement}")
     gw = harness.GpuWorkload(wl)
+
+    class CountingAdapter(harness.AllocAdapter):
+        calls = 0
+
+        def alloc(self, model):
+            CountingAdapter.calls += 1
+            return super().alloc(model)
+
+        def free(self, model, blk):
+            CountingAdapter.calls += 1
+            return super().free(model, blk)
+
     t0 = time.perf_counter()
-    gw.place()
+    gw.place(CountingAdapter(gw.pool))
     t_place = time.perf_counter() - t0
-    n_alloc_ops = sum(len(b) for m in gw.blocks for b in m)
+    n_alloc_ops = CountingAdapter.calls
     st = fs.fs_pool_stats(gw.pool)
     log(f"[bench] placed: {st.live_blocks} live blocks of {st.n_slabs} slabs in {t_place:.1f} s")
     n_layers_of = [s.n_layers if args.layers <= 0 else min(args.layers, s.n_layers) for s in wl.models]
@@ -195,6 +210,17 @@ def main():
     kms = np.array(kms)
     kernel_ms = float(kms.mean())
 
+    if args.copy_calibration_gib > 0:
+        n = int(args.copy_calibration_gib * 2**30)
+        src = torch.empty(n, dtype=torch.uint8, device=gw.device)
+        src.fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"[bench] calibration: 3 device copies of {n} bytes each (reads {n}, writes {n})")
+        del src, dst
+
     kv_bytes = gw.kv_bytes_per_layer_launch()
     n_seq_total = sum(s.n_seq for s in wl.models)
     table_bytes = sum(int(np.sum((gw.lens[k] + gw.T[m] - 1) // gw.T[m])) * 4 + 4 * s.n_seq
@@ -247,10 +273,19 @@ def main():
             "tokens_per_s_layer": round(n_seq_total / (ms_per_step * 1e-3), 1),
             "tokens_per_s_full_depth_equiv": round(float(full_depth_tok_s), 1),
             "kv_bytes_per_launch": int(kv_bytes),
-            "alloc_block_ops_per_s_host": round(n_alloc_ops / max(t_place, 1e-9), 1),
+            "alloc_free_calls": n_alloc_ops,
+            "alloc_free_calls_per_s_host": round(n_alloc_ops / max(t_place, 1e-9), 1),
             "setup_s": round(time.perf_counter() - t_setup, 1),
         },
     }
+    # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated against a plain
+    # copy) is recorded under profiles/ for the default workload and kernel; quote it when it applies.
+    tpath = os.path.join(ROOT, "profiles", f"attention_traffic_cfg{args.config}.json")
+    if os.path.exists(tpath) and not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers):
+        with open(tpath) as f:
+            tr = json.load(f)
+        result["roofline"]["traffic"] = tr.get("hbm_bytes_per_launch")
+        result["roofline"]["traffic_source"] = tr.get("source")
     if not args.no_cpu_baseline:
         n_threads = min(os.cpu_count() or 1, 16)
         t0 = time.perf_counter()
