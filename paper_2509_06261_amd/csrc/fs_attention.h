@@ -41,8 +41,11 @@ struct MultiArgs {
   DevBatch b[kMaxBatches];
   uint32_t* header;
   uint32_t* item_base;  // [n_seq_total + 1] first work item of each sequence
+  int4* item_list;      // [item_capacity] (batch, sequence, split, KV head) of every work item, queue order
   float* partials;
   uint64_t part_capacity;  // floats
+  uint32_t item_capacity;  // entries of item_list
+  uint32_t pad1;
   int32_t n_batches;
   int32_t n_seq_total;
   int32_t n_qrows_total;

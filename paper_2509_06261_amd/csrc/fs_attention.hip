@@ -70,7 +70,14 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
         __syncthreads();
       }
       const uint32_t running = s_running;
-      if (i < B.n_seq) A.item_base[B.seq_first + i] = running + scan[tid] - v;
+      if (i < B.n_seq) {
+        const uint32_t first = running + scan[tid] - v;
+        A.item_base[B.seq_first + i] = first;
+        // the sequence's items in queue order: split-major, KV heads innermost
+        const uint32_t H = (uint32_t)B.g.H;
+        for (uint32_t r = 0; r < v && first + r < A.item_capacity; ++r)
+          A.item_list[first + r] = make_int4(b, i, (int)(r / H), (int)(r % H));
+      }
       __syncthreads();
       if (tid == kPrepThreads - 1) s_running = running + scan[tid];
       __syncthreads();
@@ -79,7 +86,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
   }
   if (tid == 0) {
     A.item_base[A.n_seq_total] = s_running;
-    A.header[kHdrTotalItems] = s_running;
+    if (s_running > A.item_capacity) atomicOr(A.header + kHdrStatus, 2u);  // lengths exceed what the workspace was sized for
+    A.header[kHdrTotalItems] = min(s_running, A.item_capacity);
     A.header[kHdrCounter] = 0;
   }
 }
@@ -232,12 +240,15 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
   A.n_qrows_total = (int32_t)qrows;
   A.part_capacity = part_floats;
   const uint64_t off_items = kHeaderBytes;
-  const uint64_t off_part = align256(off_items + 4ull * (uint64_t)(seq_total + 1));
+  const uint64_t off_list = align256(off_items + 4ull * (uint64_t)(seq_total + 1));
+  const uint64_t off_part = align256(off_list + 16ull * plan.ub_items);
+  A.item_capacity = (uint32_t)plan.ub_items;
   plan.workspace_bytes = align256(off_part + 4ull * part_floats);
   if (workspace) {
     uint8_t* w = (uint8_t*)workspace;
     A.header = (uint32_t*)w;
     A.item_base = (uint32_t*)(w + off_items);
+    A.item_list = (int4*)(w + off_list);
     A.partials = (float*)(w + off_part);
   }
   return FS_OK;

@@ -229,18 +229,8 @@ __global__ __launch_bounds__(kThreads) void generic_attention_kernel(MultiArgs A
     const uint32_t item = s_item;
     __syncthreads();
     if (item >= total) break;  // every wave of every workgroup reaches this once the queue is empty
-    // sequence that owns the item: last index with item_base[i] <= item
-    int lo = 0, hi = A.n_seq_total;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (A.item_base[mid] <= item) lo = mid; else hi = mid;
-    }
-    int b = 0;
-    while (b + 1 < A.n_batches && lo >= A.b[b + 1].seq_first) ++b;
-    const int seq = lo - A.b[b].seq_first;
-    const uint32_t r = item - A.item_base[lo];
-    const int H = A.b[b].g.H;
-    const int chunk = (int)(r / (uint32_t)H), head = (int)(r % (uint32_t)H);
+    const int4 rec = A.item_list[item];
+    const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
     switch (A.b[b].g.dtype) {
       case FS_KV_FP16: dispatch_gp<FS_KV_FP16>(A, b, seq, chunk, head, item, smem); break;
       case FS_KV_FP8_E4M3: dispatch_gp<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, smem); break;

@@ -106,6 +106,7 @@ __device__ __forceinline__ void int4x8(uint32_t w, uint32_t (&r)[4]) {
 
 constexpr float kTwo24 = 16777216.0f;
 constexpr float kTwo20 = 1048576.0f;
+constexpr float kTau = 3.0f;  // log2 of the largest softmax weight tolerated before the reference is moved
 
 template <int DT>
 struct Tile {
@@ -311,7 +312,7 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
 // holds rows (heads) 4j'..4j'+3.  m, l, zc are per head c in the S^T layout (lane (j, c), any j).
 struct State {
   float4v acc[8];
-  float m;   // running max of the logits (base-2 domain)
+  float m;   // reference subtracted from the logits (base-2 domain): within kTau of the running max
   float l;   // this lane's share of the running sum (its 8-token runs only)
   float zc;  // INT8/INT4: this lane's share of the zero-point term  -sum_t p_t s_t z_t
 };
@@ -376,14 +377,17 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const 
         for (int w = 0; w < Fmt<DT>::kVBytes / 4; ++w) t.v[i][w] = i < n_valid ? t.v[i][w] : 0u;
     }
   }
+  // ---- lazy running reference: the softmax is invariant to the value subtracted from the logits, so the
+  // reference m only has to stay within 2^kTau of the largest logit seen (P stays <= 2^kTau, far inside fp16).
+  // The exact cross-lane maximum and the rescale of the accumulators run only when some logit of the tile
+  // exceeds its head's reference by more than kTau (always on a wave's first tile, where m = -inf).
   float tmax = x[0];
 #pragma unroll
   for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-  const float m_new = fmaxf(st.m, tmax);  // finite: token tb of every tile is inside the range
-  // ---- rescale the running state when some head's max moved ----
-  if (__any(m_new > st.m)) {
+  if (__any(tmax - st.m > kTau)) {
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(st.m, tmax);  // finite: token tb of every tile is inside the range
     const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
     st.l *= corr;
     if constexpr (Fmt<DT>::kParBytes != 0) st.zc *= corr;
@@ -395,6 +399,7 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const 
     }
     st.m = m_new;
   }
+  const float m_new = st.m;
   // ---- P (times the per-token V scale) ----
   float p[8];
   float lsum = 0.f;
@@ -590,25 +595,32 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
 
 __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A) {
   extern __shared__ float smem[];
-  __shared__ uint32_t s_item;
+  __shared__ uint32_t s_ticket;
+  __shared__ int4 s_rec;
   const uint32_t total = A.header[kHdrTotalItems];
+  // Thread 0 draws the ticket (and reads the item record) of the NEXT item before the current one is
+  // processed, so neither the atomic nor the record load is waited for between items.
+  uint32_t next_ticket = 0;
+  int4 next_rec = make_int4(0, 0, 0, 0);
+  if (threadIdx.x == 0) {
+    next_ticket = atomicAdd(A.header + kHdrCounter, 1u);
+    if (next_ticket < total) next_rec = A.item_list[next_ticket];
+  }
   for (;;) {
-    if (threadIdx.x == 0) s_item = atomicAdd(A.header + kHdrCounter, 1u);
+    if (threadIdx.x == 0) {
+      s_ticket = next_ticket;
+      s_rec = next_rec;
+    }
     __syncthreads();
-    const uint32_t item = s_item;
+    const uint32_t item = s_ticket;
+    const int4 rec = s_rec;
     __syncthreads();
     if (item >= total) break;  // every wave of every workgroup leaves here once the queue is empty
-    int lo = 0, hi = A.n_seq_total;
-    while (hi - lo > 1) {  // sequence owning the item: last index with item_base[i] <= item
-      const int mid = (lo + hi) >> 1;
-      if (A.item_base[mid] <= item) lo = mid; else hi = mid;
+    if (threadIdx.x == 0) {
+      next_ticket = atomicAdd(A.header + kHdrCounter, 1u);
+      if (next_ticket < total) next_rec = A.item_list[next_ticket];
     }
-    int b = 0;
-    while (b + 1 < A.n_batches && lo >= A.b[b + 1].seq_first) ++b;
-    const int seq = lo - A.b[b].seq_first;
-    const uint32_t r = item - A.item_base[lo];
-    const int H = A.b[b].g.H;
-    const int chunk = (int)(r / (uint32_t)H), head = (int)(r % (uint32_t)H);
+    const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
     switch (A.b[b].g.dtype) {
       case FS_KV_FP16: process_item<FS_KV_FP16>(A, b, seq, chunk, head, item, smem); break;
       case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, smem); break;
