@@ -133,7 +133,7 @@ int fs_kv_append(fs_pool* pool, fs_model_t model, int layer, const void* k_new, 
  *   seq_lens     : device int32 [n_seq], 1 <= n_b <= max_blocks * tokens_per_block
  *   seq_lens_host: optional host copy of seq_lens, used only to size the workspace tightly
  *   lse          : optional device fp32 [n_seq][n_q_heads], receives max_t s_t + ln sum_t e^(s_t - max)
- * n_q_heads must be a multiple of n_kv_heads with ratio <= 16. */
+ * n_q_heads must be a multiple of n_kv_heads with ratio <= 16; q and out must be 16-byte aligned. */
 typedef struct {
   fs_model_t model;
   int32_t layer;
@@ -172,7 +172,7 @@ int fs_decode_status(const void* workspace, void* stream);
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
 int fs_set_kernel_mode(int mode);
-/* Target KV bytes per split-K work item (default 1 MiB); tokens per item are rounded to 32. */
+/* Target KV bytes per split-K work item (default 192 KiB); tokens per item are rounded to 32. */
 int fs_set_split_bytes(uint64_t bytes);
 
 /* Measurement aid: while enabled, every decode call brackets its attention kernel (not the small

@@ -16,40 +16,35 @@ namespace fs {
 namespace {
 
 int g_kernel_mode = 0;
-uint64_t g_split_bytes = 1u << 20;
+uint64_t g_split_bytes = 192u << 10;
 bool g_timing = false;
 hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
 // ---------------------------------------------------------------------------------------
-// Work-list preparation: one workgroup scans the sequences of all batches and writes, for
-// every sequence, the index of its first work item (items of a sequence = splits x KV heads).
-// It also validates sequence lengths and resets the queue counter.
+// Work-list preparation: scans the sequences of all batches and writes, for every sequence,
+// the index of its first work item (items of a sequence = splits x KV heads) and, for every
+// work item, its (batch, sequence, split, KV head) record in queue order.  Every workgroup
+// repeats the (small) scan and writes its own share of the records; workgroup 0 also writes
+// the per-sequence and per-batch words, validates the sequence lengths and resets the queue.
 // ---------------------------------------------------------------------------------------
 constexpr int kPrepThreads = 1024;
-
-__device__ __forceinline__ int clamp_len(int len, int max_len, uint32_t* status) {
-  if (len < 1 || len > max_len) {
-    atomicOr(status, 1u);
-    len = len < 1 ? 1 : max_len;
-  }
-  return len;
-}
+constexpr int kPrepGroups = 64;
 
 __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
-  __shared__ uint32_t scan[kPrepThreads];
-  __shared__ uint32_t s_running;
-  const int tid = threadIdx.x;
+  __shared__ uint32_t s_incl[kPrepThreads];  // inclusive scan of the item counts of this round's sequences
+  __shared__ uint32_t s_wave[kPrepThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool leader = blockIdx.x == 0;
   uint64_t* part_off = reinterpret_cast<uint64_t*>(A.header + kHdrPartOff);
-  if (tid == 0) {
-    s_running = 0;
-    A.header[kHdrStatus] = 0;
-  }
-  __syncthreads();
+  if (leader && tid == 0) A.header[kHdrStatus] = 0;
+  __syncthreads();  // workgroup 0: the reset precedes every flag its threads may raise below
+  uint32_t running = 0;  // items before the current round (same value in every thread)
   uint64_t part_running = 0;
   for (int b = 0; b < A.n_batches; ++b) {
     const DevBatch& B = A.b[b];
-    const uint32_t batch_first = s_running;
-    if (tid == 0) {
+    const uint32_t H = (uint32_t)B.g.H;
+    const uint32_t batch_first = running;
+    if (leader && tid == 0) {
       A.header[kHdrBatchFirst + b] = batch_first;
       part_off[b] = part_running;
     }
@@ -58,36 +53,51 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
       const int i = base + tid;
       uint32_t v = 0;
       if (i < B.n_seq) {
-        const int len = clamp_len(B.seq_lens[i], max_len, A.header + kHdrStatus);
-        v = (uint32_t)((len + B.chunk_tokens - 1) / B.chunk_tokens) * (uint32_t)B.g.H;
+        int len = B.seq_lens[i];
+        if (len < 1 || len > max_len) {
+          if (leader) atomicOr(A.header + kHdrStatus, 1u);
+          len = len < 1 ? 1 : max_len;
+        }
+        v = (uint32_t)((len + B.chunk_tokens - 1) / B.chunk_tokens) * H;
       }
-      scan[tid] = v;
-      __syncthreads();
-      for (int off = 1; off < kPrepThreads; off <<= 1) {  // inclusive Hillis-Steele scan
-        const uint32_t add = tid >= off ? scan[tid - off] : 0;
-        __syncthreads();
-        scan[tid] += add;
-        __syncthreads();
+      // inclusive scan: within each wave by shuffles, then over the waves' totals
+      uint32_t incl = v;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
       }
-      const uint32_t running = s_running;
-      if (i < B.n_seq) {
-        const uint32_t first = running + scan[tid] - v;
-        A.item_base[B.seq_first + i] = first;
-        // the sequence's items in queue order: split-major, KV heads innermost
-        const uint32_t H = (uint32_t)B.g.H;
-        for (uint32_t r = 0; r < v && first + r < A.item_capacity; ++r)
-          A.item_list[first + r] = make_int4(b, i, (int)(r / H), (int)(r % H));
+      if (lane == 63) s_wave[wave] = incl;
+      __syncthreads();
+      uint32_t before = 0;
+      for (int w = 0; w < wave; ++w) before += s_wave[w];
+      incl += before;
+      s_incl[tid] = incl;
+      __syncthreads();
+      const uint32_t round_items = s_incl[kPrepThreads - 1];
+      if (leader && i < B.n_seq) A.item_base[B.seq_first + i] = running + incl - v;
+      // the round's items in queue order (sequence-major, then split, KV heads innermost): item r of the
+      // round belongs to the first sequence k whose inclusive count exceeds r
+      for (uint32_t r = blockIdx.x * kPrepThreads + tid; r < round_items; r += gridDim.x * kPrepThreads) {
+        int lo = 0, hi = kPrepThreads - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (s_incl[mid] > r) hi = mid;
+          else lo = mid + 1;
+        }
+        const uint32_t rr = r - (lo ? s_incl[lo - 1] : 0u);
+        const uint32_t idx = running + r;
+        if (idx < A.item_capacity) A.item_list[idx] = make_int4(b, base + lo, (int)(rr / H), (int)(rr % H));
       }
-      __syncthreads();
-      if (tid == kPrepThreads - 1) s_running = running + scan[tid];
-      __syncthreads();
+      __syncthreads();  // s_incl and s_wave are rewritten by the next round
+      running += round_items;
     }
-    part_running += (uint64_t)(s_running - batch_first) * (uint64_t)B.part_stride;
+    part_running += (uint64_t)(running - batch_first) * (uint64_t)B.part_stride;
   }
-  if (tid == 0) {
-    A.item_base[A.n_seq_total] = s_running;
-    if (s_running > A.item_capacity) atomicOr(A.header + kHdrStatus, 2u);  // lengths exceed what the workspace was sized for
-    A.header[kHdrTotalItems] = min(s_running, A.item_capacity);
+  if (leader && tid == 0) {
+    A.item_base[A.n_seq_total] = running;
+    if (running > A.item_capacity) atomicOr(A.header + kHdrStatus, 2u);  // lengths exceed what the workspace was sized for
+    A.header[kHdrTotalItems] = min(running, A.item_capacity);
     A.header[kHdrCounter] = 0;
   }
 }
@@ -95,12 +105,79 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
 // ---------------------------------------------------------------------------------------
 // Split combine: m = max m_i, l = sum l_i e^(m_i - m), out = sum acc_i e^(m_i - m) / l for the
 // sequences that were split; sequences with a single split were finished by the attention
-// kernel itself.  One workgroup per (sequence, query head).
+// kernel itself.  One wave per (sequence, query head).
 // ---------------------------------------------------------------------------------------
-constexpr int kCombineThreads = 128;
+constexpr int kCombineWaves = 4;
 
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(MultiArgs A) {
-  const int row = blockIdx.x;
+// NK = number of 64-wide column groups of the head dimension (lane handles d = lane + 64 k).
+template <int NK>
+__device__ __forceinline__ void combine_row(const float* P, uint64_t chunk_stride, int n_chunks, int D, int lane,
+                                            _Float16* out, float* lse) {
+  const int dl = min(lane, D - 1);  // head_dim < 64: the surplus lanes repeat the last column
+  // the splits' references and sums, one split per lane (both loads of the first 64 splits in flight together)
+  float m0 = -INFINITY, l0 = 0.f;
+  if (lane < n_chunks) {
+    m0 = P[lane * chunk_stride + D];
+    l0 = P[lane * chunk_stride + D + 1];
+  }
+  float M = m0;
+  for (int c = lane + 64; c < n_chunks; c += 64) M = fmaxf(M, P[c * chunk_stride + D]);
+#pragma unroll
+  for (int off = 32; off; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+  // out[d] = sum_c w_c acc_c[d] / sum_c w_c l_c with w_c = e^(m_c - M); lane c' of each group of 64 splits
+  // prepares the weight of split c0 + c', the accumulation reads it from there
+  float L = 0.f;
+  float o[NK];
+#pragma unroll
+  for (int k = 0; k < NK; ++k) o[k] = 0.f;
+  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+    float w = 0.f;
+    if (c0 == 0) {
+      w = expf(m0 - M);  // lanes without a split: e^(-inf) = 0
+      L = l0 * w;
+    } else if (c0 + lane < n_chunks) {
+      const float* pc = P + (c0 + lane) * chunk_stride;
+      w = expf(pc[D] - M);
+      L += pc[D + 1] * w;
+    }
+    const int n = min(64, n_chunks - c0);
+    const float* pg = P + c0 * chunk_stride + dl;
+    int c = 0;
+    for (; c + 8 <= n; c += 8) {  // eight splits' loads in flight together
+      float x[8][NK];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int k = 0; k < NK; ++k) x[u][k] = pg[(c + u) * chunk_stride + 64 * k];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), c + u));
+#pragma unroll
+        for (int k = 0; k < NK; ++k) o[k] += x[u][k] * wc;
+      }
+    }
+    for (; c < n; ++c) {
+      const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), c));
+#pragma unroll
+      for (int k = 0; k < NK; ++k) o[k] += pg[c * chunk_stride + 64 * k] * wc;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off; off >>= 1) L += __shfl_xor(L, off, 64);
+  const float inv = 1.0f / L;
+  if (lane < D) {
+#pragma unroll
+    for (int k = 0; k < NK; ++k) out[lane + 64 * k] = (_Float16)(o[k] * inv);
+  }
+  if (lse && lane == 0) *lse = M + logf(L);
+}
+
+__global__ __launch_bounds__(kCombineWaves * 64) void combine_kernel(MultiArgs A) {
+  const int lane = threadIdx.x & 63;
+  // one wave per (sequence, query head); the wave index is made provably uniform so that everything derived
+  // from the row stays in scalar registers
+  const int row = blockIdx.x * kCombineWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (row >= A.n_qrows_total) return;
   int b = 0;
   while (b + 1 < A.n_batches && row >= A.b[b + 1].qrow_first) ++b;
   const DevBatch& B = A.b[b];
@@ -118,37 +195,25 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(MultiArgs A) {
   const uint64_t base = part_off[b] + (uint64_t)(item0 - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
   const uint64_t last = base + (uint64_t)((uint32_t)(n_chunks - 1) * H + kvh) * B.part_stride + (uint64_t)(gq + 1) * (D + 2);
   if (last > A.part_capacity) return;  // the attention kernel flagged this already
-  const float* P = A.partials + base + (uint64_t)gq * (D + 2);
   const uint64_t chunk_stride = (uint64_t)H * B.part_stride;
-  const uint64_t head_off = (uint64_t)kvh * B.part_stride;
-  float M = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, P[c * chunk_stride + head_off + D]);
-  float L = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const float* pc = P + c * chunk_stride + head_off;
-    L += pc[D + 1] * expf(pc[D] - M);
-  }
-  const float inv = 1.0f / L;
-  for (int d = threadIdx.x; d < D; d += kCombineThreads) {
-    float o = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-      const float* pc = P + c * chunk_stride + head_off;
-      o += pc[d] * expf(pc[D] - M);
-    }
-    B.out[((int64_t)seq * B.n_q + h) * D + d] = (_Float16)(o * inv);
-  }
-  if (B.lse && threadIdx.x == 0) B.lse[(int64_t)seq * B.n_q + h] = M + logf(L);
+  const float* P = A.partials + base + (uint64_t)kvh * B.part_stride + (uint64_t)gq * (D + 2);
+  _Float16* out = B.out + ((int64_t)seq * B.n_q + h) * D;
+  float* lse = B.lse ? B.lse + (int64_t)seq * B.n_q + h : nullptr;
+  if (D <= 64) combine_row<1>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else if (D == 128) combine_row<2>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else if (D == 256) combine_row<4>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else combine_row<8>(P, chunk_stride, n_chunks, D, lane, out, lse);
 }
 
 }  // namespace
 
 hipError_t launch_prep(const MultiArgs& A, hipStream_t s) {
-  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(kPrepThreads), 0, s, A);
+  hipLaunchKernelGGL(prep_kernel, dim3(kPrepGroups), dim3(kPrepThreads), 0, s, A);
   return hipGetLastError();
 }
 
 hipError_t launch_combine(const MultiArgs& A, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3(A.n_qrows_total), dim3(kCombineThreads), 0, s, A);
+  hipLaunchKernelGGL(combine_kernel, dim3((A.n_qrows_total + kCombineWaves - 1) / kCombineWaves), dim3(kCombineWaves * 64), 0, s, A);
   return hipGetLastError();
 }
 
@@ -187,6 +252,10 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
       set_error("decode attention: invalid batch argument");
       return FS_ERR_INVALID;
     }
+    if (((uintptr_t)b.q | (uintptr_t)b.out) & 15) {  // rows are moved as 16-byte vectors
+      set_error("decode attention: q and out must be 16-byte aligned");
+      return FS_ERR_INVALID;
+    }
     if (g.kv_dtype == FS_KV_FP8_E4M3 && !M.d_k_scale) {
       set_error("decode attention: FP8 model has no scales (fs_model_set_fp8_scales)");
       return FS_ERR_INVALID;
@@ -208,7 +277,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.sm_scale = b.sm_scale;
     const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
     int64_t ct = (int64_t)(g_split_bytes / token_bytes) / 32 * 32;
-    ct = std::min<int64_t>(ct, (int64_t)2040 * g.tokens_per_block / 32 * 32);  // at most ~2K blocks per work item
+    ct = std::min<int64_t>(ct, (int64_t)500 * g.tokens_per_block / 32 * 32);  // at most ~500 blocks per work item
     B.chunk_tokens = (int32_t)std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
@@ -324,14 +393,17 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
   (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
   hipError_t e = launch_prep(plan.args, s);
   if (e != hipSuccess) return device_error(e, "prep launch");
-  // Persistent grid: two workgroups per compute unit drain the queue (never more than the
+  // Persistent grid: two workgroups (eight waves) per compute unit drain the queue (never more than the
   // upper bound on work items, so tiny batches launch tiny grids).
   static const int wgs_per_cu = [] {
     const char* e = getenv("FS_WGS_PER_CU");  // tuning knob for measurements
     const int v = e ? atoi(e) : 0;
     return v >= 1 && v <= 8 ? v : 2;
   }();
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu, std::max<uint64_t>(plan.ub_items, 1));
+  // (the MFMA kernel's workers are waves, four to a workgroup; the generic kernel's are workgroups)
+  const uint64_t workers_per_wg = use_mfma ? 4 : 1;
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,
+                                           std::max<uint64_t>((plan.ub_items + workers_per_wg - 1) / workers_per_wg, 1));
   if (g_timing) (void)hipEventRecord(g_ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
   if (g_timing) (void)hipEventRecord(g_ev1, s);

@@ -8,9 +8,9 @@
 // (padded to 16) form the second matrix dimension.
 //
 // Work decomposition
-//   persistent workgroups (4 waves) pull work items (sequence, split, KV head) from a ticket counter;
-//   inside an item wave w owns the 32-token tiles w, w+4, ... of the split and keeps a private
-//   online-softmax state; the four waves are merged through LDS at the end of the item.
+//   a persistent grid of independent waves: each wave takes every n-th work item (sequence, split, KV head)
+//   of the queue, streams the split's 32-token tiles with a private online-softmax state and writes the
+//   output (or the split's partial record) straight from its accumulators.  No wave waits for another.
 //
 // One 32-token tile (base token tb), lane l = 16*j + c:
 //   S^T = K Q^T as two 16x16 MFMA tiles u = 0,1 (rows = tokens, columns = query heads).  Row m of tile u
@@ -49,7 +49,6 @@ constexpr int kD = 128;
 constexpr int kTile = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kMergeFloats = kWaves * 16 * kD + 3 * kWaves * 16;  // LDS floats of the cross-wave merge
 
 template <int DT>
 struct Fmt;
@@ -436,12 +435,14 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const 
   }
 }
 
+// One work item, processed by ONE wave: all 32-token tiles of the split, then the output (or the split's
+// partial record) straight from the accumulator registers.  Waves never synchronise with each other.
+// s_ptr: this wave's LDS table of head-chunk addresses.
 template <int DT>
-__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, float* smem) {
+__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, uint64_t* s_ptr) {
   const DevBatch& B = A.b[b];
   const DevGeom& g = B.g;
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps the tile loop scalar
   const int j = lane >> 4, c = lane & 15;
   const int G = B.G;
   const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
@@ -451,6 +452,14 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   const int t0 = chunk * B.chunk_tokens;
   const int t1 = min(len, t0 + B.chunk_tokens);
   const int nblk = (len + g.T - 1) / g.T;
+
+  const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
+  const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
+  if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {  // wave-uniform
+    if (lane == 0) atomicOr(A.header + kHdrStatus, 2u);
+    return;
+  }
+
   ItemCtx X;
   X.B = &B;
   X.b_first = t0 / g.T;
@@ -459,26 +468,21 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   X.t_magic = B.t_magic;
   // head-chunk addresses of the blocks this item touches (plus one more), through LDS: every lane of
   // every tile looks its blocks up here instead of gathering them from the block table in memory
-  uint64_t* s_ptr = reinterpret_cast<uint64_t*>(smem + kMergeFloats);
   X.chunk_ptr = s_ptr;
   {
     const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
     const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
     const int nb = X.b_last - X.b_first + 2;
-    for (int i = threadIdx.x; i < nb; i += kThreads) {
+    for (int i = lane; i < nb; i += 64) {
       const int bi = min(X.b_first + i, nblk - 1);  // past the sequence's last block: alias it (valid memory)
       s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[bi] * g.block_budget);
     }
   }
-  __syncthreads();
-
-  const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
-  const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
-  if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {
-    if (threadIdx.x == 0) atomicOr(A.header + kHdrStatus, 2u);
-    __syncthreads();
-    return;
-  }
+  // the table is private to this wave; LDS operations of a wave complete in order, the fence only keeps the
+  // compiler from moving the look-ups above the writes of other lanes
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
   // Q operand and per-head constants
   u32x4 qb[4];
@@ -498,30 +502,29 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   st.l = 0.f;
   st.zc = 0.f;
 
-  // Software pipeline over this wave's tiles (tile k of the wave is tile wave + 4k of the item): a ring of
-  // NBUF register copies of a tile.  The K rows of the tile that will next occupy a slot are requested as
-  // soon as S^T of its current occupant is done, the V rows as soon as P V is done, so the narrower the
-  // format the more tiles are in flight (about 16 KiB per wave for every format).
+  // Software pipeline over the item's tiles: a ring of NBUF register copies of a tile.  The K rows of the
+  // tile that will next occupy a slot are requested as soon as S^T of its current occupant is done, the V
+  // rows as soon as P V is done, so the narrower the format the more tiles are in flight (about 16 KiB per
+  // wave for every format).
   constexpr int NBUF = Fmt<DT>::kRing;
   const int n_tiles = (t1 - t0 + kTile - 1) / kTile;
-  const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
   Tile<DT> t[NBUF];
   static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
     constexpr int bi = decltype(Bi)::value;
-    if (bi < my_tiles) {
-      const int tb = t0 + (wave + bi * kWaves) * kTile;
+    if (bi < n_tiles) {
+      const int tb = t0 + bi * kTile;
       issue_k<DT>(X, tb, j, c, t[bi]);
       issue_v<DT>(X, tb, j, c, t[bi]);
     }
   });
-  for (int k0 = 0; k0 < my_tiles; k0 += NBUF) {
+  for (int k0 = 0; k0 < n_tiles; k0 += NBUF) {
     static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
       constexpr int bi = decltype(Bi)::value;
       const int k = k0 + bi;
-      if (k < my_tiles) {
-        const int tb = t0 + (wave + k * kWaves) * kTile;
-        const int tb_next = tb + NBUF * kWaves * kTile;
-        const bool more = k + NBUF < my_tiles;
+      if (k < n_tiles) {
+        const int tb = t0 + k * kTile;
+        const int tb_next = tb + NBUF * kTile;
+        const bool more = k + NBUF < n_tiles;
         float4v s[2];
         qk_tile<DT>(t[bi], qb, s);
         if (more) issue_k<DT>(X, tb_next, j, c, t[bi]);
@@ -531,103 +534,75 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
     });
   }
 
-  // ---- merge the four waves through LDS: [wave][head][D] accumulators, [wave][head] m, l, zc ----
+  // ---- output: per-head sums over the four lane groups, then rows h < G straight from the accumulators ----
   st.l += __shfl_xor(st.l, 16, 64);
   st.l += __shfl_xor(st.l, 32, 64);
   if constexpr (Fmt<DT>::kParBytes != 0) {
     st.zc += __shfl_xor(st.zc, 16, 64);
     st.zc += __shfl_xor(st.zc, 32, 64);
   }
-  float* s_acc = smem;                          // [kWaves][16][kD]
-  float* s_m = smem + kWaves * 16 * kD;         // [kWaves][16]
-  float* s_l = s_m + kWaves * 16;
-  float* s_z = s_l + kWaves * 16;
+  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int h = 4 * j + r;
+    const int h = 4 * j + r;  // accumulator row r of this lane; its m, l, zc live in lane c = h
+    const float L = __shfl(st.l, h, 64), M = __shfl(st.m, h, 64), Z = __shfl(st.zc, h, 64);
     if (h < G) {
+      float o[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         // integer formats: undo the 2^-24 of the subnormal encoding (and the 16 of INT4's odd code positions)
         const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
-        s_acc[(wave * 16 + h) * kD + 8 * c + e] = st.acc[e][r] * f;
+        o[e] = st.acc[e][r] * f;
+        if constexpr (Fmt<DT>::kParBytes != 0) o[e] += Z;
+        o[e] *= v_static;
+      }
+      const int qh = head * G + h;
+      if (n_chunks == 1) {
+        const float inv = 1.0f / L;
+        u32x4 w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const half2v hv = {(_Float16)(o[2 * q] * inv), (_Float16)(o[2 * q + 1] * inv)};
+          w[q] = h2u(hv);
+        }
+        *reinterpret_cast<u32x4*>(B.out + ((int64_t)seq * B.n_q + qh) * kD + 8 * c) = w;
+        if (c == 0 && B.lse) B.lse[(int64_t)seq * B.n_q + qh] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+      } else {
+        float* pr = A.partials + part_base + (uint64_t)h * (kD + 2);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pr[8 * c + e] = o[e];
+        if (c == 0) {
+          pr[kD] = M * kLn2;  // partial records keep the reference in natural-log units
+          pr[kD + 1] = L;
+        }
       }
     }
   }
-  if (j == 0 && c < G) {
-    s_m[wave * 16 + c] = st.m;
-    s_l[wave * 16 + c] = st.l;
-    s_z[wave * 16 + c] = st.zc;
-  }
-  __syncthreads();
-  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
-  for (int idx = threadIdx.x; idx < G * kD; idx += kThreads) {
-    const int h = idx >> 7, d = idx & (kD - 1);
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, s_m[w * 16 + h]);
-    float L = 0.f, O = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float mw = s_m[w * 16 + h];
-      const float wt = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      L += s_l[w * 16 + h] * wt;
-      float o = s_acc[(w * 16 + h) * kD + d];
-      if constexpr (Fmt<DT>::kParBytes != 0) o += s_z[w * 16 + h];
-      O += o * wt;
-    }
-    O *= v_static;
-    const int qh = head * G + h;
-    if (n_chunks == 1) {
-      B.out[((int64_t)seq * B.n_q + qh) * kD + d] = (_Float16)(O / L);
-      if (d == 0 && B.lse) B.lse[(int64_t)seq * B.n_q + qh] = (M + __builtin_amdgcn_logf(L)) * kLn2;
-    } else {
-      float* pr = A.partials + part_base + (uint64_t)h * (kD + 2);
-      pr[d] = O;
-      if (d == 0) {
-        pr[kD] = M * kLn2;  // partial records keep the max in natural-log units
-        pr[kD + 1] = L;
-      }
-    }
-  }
-  __syncthreads();
 }
 
-__global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A) {
-  extern __shared__ float smem[];
-  __shared__ uint32_t s_ticket;
-  __shared__ int4 s_rec;
+__device__ __forceinline__ void dispatch_item(const MultiArgs& A, uint32_t item, uint64_t* s_ptr) {
+  const int4 rec = A.item_list[item];
+  const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
+  switch (A.b[b].g.dtype) {
+    case FS_KV_FP16: process_item<FS_KV_FP16>(A, b, seq, chunk, head, item, s_ptr); break;
+    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, s_ptr); break;
+    case FS_KV_INT8: process_item<FS_KV_INT8>(A, b, seq, chunk, head, item, s_ptr); break;
+    default: process_item<FS_KV_INT4>(A, b, seq, chunk, head, item, s_ptr); break;
+  }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A, int table_entries) {
+  extern __shared__ uint64_t smem64[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint64_t* s_ptr = smem64 + (size_t)wave * table_entries;
   const uint32_t total = A.header[kHdrTotalItems];
-  // Thread 0 draws the ticket (and reads the item record) of the NEXT item before the current one is
-  // processed, so neither the atomic nor the record load is waited for between items.
-  uint32_t next_ticket = 0;
-  int4 next_rec = make_int4(0, 0, 0, 0);
-  if (threadIdx.x == 0) {
-    next_ticket = atomicAdd(A.header + kHdrCounter, 1u);
-    if (next_ticket < total) next_rec = A.item_list[next_ticket];
-  }
-  for (;;) {
-    if (threadIdx.x == 0) {
-      s_ticket = next_ticket;
-      s_rec = next_rec;
-    }
-    __syncthreads();
-    const uint32_t item = s_ticket;
-    const int4 rec = s_rec;
-    __syncthreads();
-    if (item >= total) break;  // every wave of every workgroup leaves here once the queue is empty
-    if (threadIdx.x == 0) {
-      next_ticket = atomicAdd(A.header + kHdrCounter, 1u);
-      if (next_ticket < total) next_rec = A.item_list[next_ticket];
-    }
-    const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
-    switch (A.b[b].g.dtype) {
-      case FS_KV_FP16: process_item<FS_KV_FP16>(A, b, seq, chunk, head, item, smem); break;
-      case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, smem); break;
-      case FS_KV_INT8: process_item<FS_KV_INT8>(A, b, seq, chunk, head, item, smem); break;
-      default: process_item<FS_KV_INT4>(A, b, seq, chunk, head, item, smem); break;
-    }
-  }
+  // Every wave is its own worker and takes the items worker, worker + n_workers, ... of the queue.  Items
+  // are splits of (nearly) equal bytes and every worker's stride walks through all batches alike, so this
+  // fixed deal balances to within about one item per batch.  (Drawing the items from a shared ticket
+  // counter instead was measured to bound the kernel: the memory system serves one atomic on a given
+  // address every ~11 ns when idle and several times slower under streaming load.)
+  const uint32_t n_workers = gridDim.x * kWaves, worker = blockIdx.x * kWaves + wave;
+  for (uint32_t item = worker; item < total; item += n_workers) dispatch_item(A, item, s_ptr);
 }
 
 }  // namespace
@@ -641,11 +616,11 @@ bool mfma_supports(const DevBatch& b) {
 }
 
 hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s) {
-  // LDS: merge buffers, then one 8-byte address per block of the largest split (+ slack)
-  int max_blocks = 0;
-  for (int i = 0; i < A.n_batches; ++i) max_blocks = std::max(max_blocks, A.b[i].chunk_tokens / A.b[i].g.T + 4);
-  const size_t smem = (size_t)kMergeFloats * sizeof(float) + (size_t)max_blocks * sizeof(uint64_t);
-  hipLaunchKernelGGL(mfma_attention_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A);
+  // LDS: per wave one 8-byte address per block of the largest split (+ slack)
+  int entries = 0;
+  for (int i = 0; i < A.n_batches; ++i) entries = std::max(entries, A.b[i].chunk_tokens / A.b[i].g.T + 4);
+  const size_t smem = (size_t)kWaves * entries * sizeof(uint64_t);
+  hipLaunchKernelGGL(mfma_attention_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries);
   return hipGetLastError();
 }
 
