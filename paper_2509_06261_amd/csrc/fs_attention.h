@@ -18,12 +18,16 @@ struct DevBatch {
   const float* v_scale;
   int32_t n_seq, max_blocks, n_q, G;
   float sm_scale;
-  int32_t chunk_tokens;  // tokens per split-K work item (multiple of 32)
+  int32_t chunk_tokens;  // generic kernel: tokens per split-K work item (multiple of 32)
   int32_t seq_first;     // index of this batch's first sequence among all batches' sequences
   int32_t part_stride;   // floats per work item in the partial buffer: G * (D + 2)
   int32_t qrow_first;    // index of this batch's first (sequence, q head) row among all batches
-  int32_t t_magic_shift; // reserved
-  uint32_t t_magic;      // ceil(2^32 / T): token / T == umulhi(token, t_magic) for token <= 2^32 / T
+  // MFMA kernel: a sequence is cut into runs of 8 token slots that never cross a block (R = ceil(T / 8) runs
+  // per block, the last one of a block shifted back to end at slot T - 1); a work item is chunk_runs
+  // consecutive runs.  chunk_runs == 0 selects the token-based splits of the generic kernel.
+  int32_t chunk_runs;    // multiple of 4
+  int32_t R;
+  uint32_t r_magic;      // ceil(2^32 / R): run / R == umulhi(run, r_magic) while run * R < 2^32
   uint32_t pad;
 };
 
@@ -54,6 +58,19 @@ struct MultiArgs {
 
 // Work item r of a sequence with n_chunks splits and H KV heads: chunk = r / H, head = r % H,
 // so the heads of one (sequence, chunk) -- which lie in the same slabs -- run side by side.
+
+// Runs of 8 token slots that a sequence of `len` tokens occupies (MFMA kernel's unit of work).
+__device__ __host__ inline int n_runs(int len, int T, int R) {
+  const int nblk = (len + T - 1) / T;
+  const int rem = len - (nblk - 1) * T;
+  return (nblk - 1) * R + ((rem + 7) >> 3);
+}
+
+// Splits of a sequence of `len` (already clamped) tokens.
+__device__ __host__ inline int n_splits(const DevBatch& B, int len) {
+  if (B.chunk_runs) return (n_runs(len, B.g.T, B.R) + B.chunk_runs - 1) / B.chunk_runs;
+  return (len + B.chunk_tokens - 1) / B.chunk_tokens;
+}
 
 // Launchers implemented in the kernel translation units.
 hipError_t launch_prep(const MultiArgs& A, hipStream_t s);

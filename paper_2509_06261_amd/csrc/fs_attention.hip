@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
           if (leader) atomicOr(A.header + kHdrStatus, 1u);
           len = len < 1 ? 1 : max_len;
         }
-        v = (uint32_t)((len + B.chunk_tokens - 1) / B.chunk_tokens) * H;
+        v = (uint32_t)n_splits(B, len) * H;
       }
       // inclusive scan: within each wave by shuffles, then over the waves' totals
       uint32_t incl = v;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kCombineWaves * 64) void combine_kernel(MultiArgs A
   const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
   int len = B.seq_lens[seq];
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
-  const int n_chunks = (len + B.chunk_tokens - 1) / B.chunk_tokens;
+  const int n_chunks = n_splits(B, len);
   if (n_chunks <= 1) return;
   const int D = B.g.D, H = B.g.H;
   const int kvh = h / B.G, gq = h % B.G;
@@ -224,6 +224,7 @@ struct Plan {
   uint64_t workspace_bytes = 0;
   uint64_t ub_items = 0;
   bool all_mfma = true;
+  bool use_mfma = false;
 };
 
 uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
@@ -279,24 +280,30 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     int64_t ct = (int64_t)(g_split_bytes / token_bytes) / 32 * 32;
     ct = std::min<int64_t>(ct, (int64_t)500 * g.tokens_per_block / 32 * 32);  // at most ~500 blocks per work item
     B.chunk_tokens = (int32_t)std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
+    B.R = (g.tokens_per_block + 7) / 8;
+    B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);  // unused for R = 1
+    int64_t cr = (int64_t)(g_split_bytes / (8 * token_bytes)) / 4 * 4;
+    cr = std::min<int64_t>(cr, (int64_t)500 * B.R / 4 * 4);
+    B.chunk_runs = (int32_t)std::min<int64_t>(std::max<int64_t>(cr, 4), 1 << 17);
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
     B.qrow_first = (int32_t)qrows;
-    B.t_magic = (uint32_t)(((1ull << 32) + (uint64_t)g.tokens_per_block - 1) / (uint64_t)g.tokens_per_block);
     seq_total += b.n_seq;
     qrows += (int64_t)b.n_seq * b.n_q_heads;
-    // upper bound on this batch's work items
-    uint64_t items = 0;
+    // upper bound on this batch's work items under either split rule (which kernel runs is decided below)
+    uint64_t items_tok = 0, items_run = 0;
     const int64_t ub_len = std::min<int64_t>((int64_t)b.max_blocks * g.tokens_per_block, 0x7fffffff);
     if (b.seq_lens_host) {
       for (int s = 0; s < b.n_seq; ++s) {
-        int64_t len = std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[s], 1), ub_len);
-        items += (uint64_t)((len + B.chunk_tokens - 1) / B.chunk_tokens);
+        const int64_t len = std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[s], 1), ub_len);
+        items_tok += (uint64_t)((len + B.chunk_tokens - 1) / B.chunk_tokens);
+        items_run += (uint64_t)((n_runs((int)len, g.tokens_per_block, B.R) + B.chunk_runs - 1) / B.chunk_runs);
       }
     } else {
-      items = (uint64_t)b.n_seq * (uint64_t)((ub_len + B.chunk_tokens - 1) / B.chunk_tokens);
+      items_tok = (uint64_t)b.n_seq * (uint64_t)((ub_len + B.chunk_tokens - 1) / B.chunk_tokens);
+      items_run = (uint64_t)b.n_seq * (uint64_t)(((int64_t)b.max_blocks * B.R + B.chunk_runs - 1) / B.chunk_runs);
     }
-    items *= (uint64_t)g.n_kv_heads;
+    const uint64_t items = std::max(items_tok, items_run) * (uint64_t)g.n_kv_heads;
     plan.ub_items += items;
     part_floats += items * (uint64_t)B.part_stride;
     if (!mfma_supports(B)) plan.all_mfma = false;
@@ -305,6 +312,10 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     set_error("decode attention: batch too large");
     return FS_ERR_INVALID;
   }
+  // the generic kernel splits by tokens, the MFMA kernel by runs
+  plan.use_mfma = plan.all_mfma && g_kernel_mode != 1;
+  if (!plan.use_mfma)
+    for (int i = 0; i < n_batches; ++i) A.b[i].chunk_runs = 0;
   A.n_seq_total = (int32_t)seq_total;
   A.n_qrows_total = (int32_t)qrows;
   A.part_capacity = part_floats;
@@ -383,8 +394,7 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
     set_error("decode attention: pool has no HIP device");
     return FS_ERR_DEVICE;
   }
-  bool use_mfma = plan.all_mfma;
-  if (g_kernel_mode == 1) use_mfma = false;
+  const bool use_mfma = plan.use_mfma;
   if (g_kernel_mode == 2 && !plan.all_mfma) {
     set_error("decode attention: MFMA kernel forced but a batch has a shape it does not support");
     return FS_ERR_INVALID;

@@ -46,7 +46,6 @@ typedef const FS_GLOBAL uint8_t* gptr;  // global (not flat) address
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kD = 128;
-constexpr int kTile = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -107,60 +106,65 @@ constexpr float kTwo24 = 16777216.0f;
 constexpr float kTwo20 = 1048576.0f;
 constexpr float kTau = 3.0f;  // log2 of the largest softmax weight tolerated before the reference is moved
 
-template <int DT>
+// GP = padded group size: 4 when the KV head serves at most 4 query heads, else 16.  The MFMAs always work on 16
+// head columns; GP decides how the softmax between them is spread over the lanes (see softmax_pv).
+template <int DT, int GP>
 struct Tile {
   u32x4 k[2][Fmt<DT>::kKLoads];
   uint32_t v[8][Fmt<DT>::kVBytes / 4];
-  uint32_t par;  // INT8/INT4: lanes c < 8 hold the K parameters of token c of the lane's run, lanes c >= 8 the V ones
+  // INT8/INT4 per-token parameters.  GP == 16: one register; lanes c < 8 hold the K parameters of token c of
+  // the lane's run, lanes c >= 8 the V ones.  GP == 4: those of the lane's own two tokens, K K V V.
+  uint32_t par[GP == 16 ? 1 : 4];
 };
 
+// A sequence is walked in runs of 8 token slots that never cross a block: block k holds runs k R .. k R + R - 1
+// (R = ceil(T / 8)); run r of a block covers slots 8 r .. 8 r + 7, except that the last run of a block whose T
+// is no multiple of 8 is shifted back to end at slot T - 1 and its first slots, which repeat tokens of the run
+// before, are masked.  A tile is 4 consecutive runs.
 struct ItemCtx {
-  const DevBatch* B;
-  const uint64_t* chunk_ptr;  // LDS: head-chunk address of blocks b_first .. b_last + 1 of this item's range
-  int b_first, b_last;        // first / last block the item's token range touches
-  int t1;                     // end of this item's token range
-  uint32_t t_magic;           // ceil(2^32 / T)
+  const uint64_t* chunk_ptr;  // LDS: head-chunk address of blocks k0 .. of this item's range
+  int k0;                     // first block the item touches
+  int v_end;                  // one past the item's last run
+  int len;                    // sequence length
+  int T, R;
+  uint32_t r_magic;           // ceil(2^32 / R)
 };
 
-// Where an 8-token run starting at token `tok` lives: head-chunk addresses of its first block (c0) and of
-// the block after it (c1), the slot r0 of its first token, and how many of its tokens stay in the first
-// block (cross >= 8: no crossing).  Token i is slot r0 + i of c0 if i < cross, else slot i - cross of c1.
-// A run wholly past the item's last block is mapped to slots 0..7 of a valid block (its data is masked).
-struct Run {
-  gptr c0;
-  gptr c1;
-  int r0, cross;
+// Run vr: head-chunk address of its block, first slot, and the slots [lo, hi) of it that hold tokens of this
+// item (none for a run past the item's end, which is mapped onto the item's last run: valid memory).
+struct RunLoc {
+  gptr base;
+  int start, lo, hi;
 };
 
-__device__ __forceinline__ Run locate_run(const ItemCtx& X, int tok) {
-  const int T = X.B->g.T;
-  const int bi = (int)__umulhi((uint32_t)tok, X.t_magic);
-  Run r;
-  r.r0 = tok - bi * T;
-  r.cross = T - r.r0;
-  int idx = bi - X.b_first;
-  if (bi > X.b_last) {
-    r.r0 = 0;
-    r.cross = 8;
-    idx = X.b_last + 1 - X.b_first;
-  }
-  r.c0 = (gptr)X.chunk_ptr[idx];
-  r.c1 = (gptr)X.chunk_ptr[min(idx + 1, X.b_last + 1 - X.b_first)];
-  return r;
+// run / R  (r_magic = ceil(2^32 / R) does not fit 32 bits for R = 1)
+__device__ __forceinline__ int div_runs(int vr, int R, uint32_t r_magic) {
+  return R == 1 ? vr : (int)__umulhi((uint32_t)vr, r_magic);
 }
 
-template <int DT>
-__device__ __forceinline__ void issue_k(const ItemCtx& X, int tb, int j, int c, Tile<DT>& t) {
+__device__ __forceinline__ RunLoc locate(const ItemCtx& X, int vr) {
+  const int vc = min(vr, X.v_end - 1);
+  const int k = div_runs(vc, X.R, X.r_magic);
+  const int r8 = 8 * (vc - k * X.R);
+  RunLoc L;
+  L.start = min(r8, X.T - 8);
+  L.lo = r8 - L.start;
+  L.hi = vr < X.v_end ? min(8, X.len - k * X.T - L.start) : 0;
+  L.base = (gptr)X.chunk_ptr[k - X.k0];
+  return L;
+}
+
+template <int DT, int GP>
+__device__ __forceinline__ void issue_k(const ItemCtx& X, int vb, int j, int c, Tile<DT, GP>& t) {
   using F = Fmt<DT>;
-  const Run r = locate_run(X, tb + 8 * (c >> 2));
+  // row m = c of S^T tile u is slot 4u + (c & 3) of run c >> 2
+  const RunLoc L = locate(X, vb + (c >> 2));
+  const gptr p = L.base + (uint32_t)((L.start + (c & 3)) * F::kRowBytes) + 16 * j;
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int i = 4 * u + (c & 3);
-    const bool first = i < r.cross;
-    const gptr p = (first ? r.c0 : r.c1) + (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kRowBytes) + 16 * j;
+  for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int s = 0; s < F::kKLoads; ++s) t.k[u][s] = *reinterpret_cast<const FS_GLOBAL u32x4*>(p + 64 * s);
-  }
+    for (int s = 0; s < F::kKLoads; ++s)
+      t.k[u][s] = *reinterpret_cast<const FS_GLOBAL u32x4*>(p + u * 4 * F::kRowBytes + 64 * s);
 }
 
 template <int DT>
@@ -180,28 +184,35 @@ __device__ __forceinline__ void load_v_row(gptr p, uint32_t (&v)[Fmt<DT>::kVByte
   }
 }
 
-template <int DT>
-__device__ __forceinline__ void issue_v(const ItemCtx& X, int tb, int j, int c, Tile<DT>& t) {
+template <int DT, int GP>
+__device__ __forceinline__ void issue_v(const ItemCtx& X, const DevGeom& g, int vb, int j, int c, Tile<DT, GP>& t) {
   using F = Fmt<DT>;
-  const DevGeom& g = X.B->g;
-  const Run r = locate_run(X, tb + 8 * j);
+  const RunLoc L = locate(X, vb + j);
   if constexpr (F::kParBytes != 0) {  // parameters first: the softmax needs them before the V rows
-    const int i = c & 7;
-    const bool first = i < r.cross;
-    const gptr p = (first ? r.c0 : r.c1) + 2u * g.kv_tile + ((c >> 3) ? g.par_tile : 0u) +
-                       (uint32_t)((first ? r.r0 + i : i - r.cross) * F::kParBytes);
-    if constexpr (F::kParBytes == 2) t.par = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p);
-    else t.par = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
+    const gptr pk = L.base + 2u * g.kv_tile;
+    if constexpr (GP == 16) {
+      const gptr p = pk + ((c >> 3) ? g.par_tile : 0u) + (uint32_t)((L.start + (c & 7)) * F::kParBytes);
+      if constexpr (F::kParBytes == 2) t.par[0] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p);
+      else t.par[0] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
+    } else {
+      const gptr p = pk + (uint32_t)((L.start + 2 * (c >> 2)) * F::kParBytes);  // slots 2 (c >> 2), + 1 of the run
+      const gptr q = p + g.par_tile;
+      if constexpr (F::kParBytes == 2) {
+        t.par[0] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p);
+        t.par[1] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p + 2);
+        t.par[2] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(q);
+        t.par[3] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(q + 2);
+      } else {
+        t.par[0] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
+        t.par[1] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p + 4);
+        t.par[2] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(q);
+        t.par[3] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(q + 4);
+      }
+    }
   }
-  const gptr p0 = r.c0 + g.kv_tile + (uint32_t)(r.r0 * F::kRowBytes) + c * F::kVBytes;
-  if (__all(r.cross >= 8)) {  // no run of this wave crosses a block boundary: one base, constant offsets
+  const gptr p0 = L.base + g.kv_tile + (uint32_t)(L.start * F::kRowBytes) + c * F::kVBytes;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
-  } else {
-    const gptr p1 = r.c1 + g.kv_tile + c * F::kVBytes - (int64_t)r.cross * F::kRowBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) load_v_row<DT>((i < r.cross ? p0 : p1) + i * F::kRowBytes, t.v[i]);
-  }
+  for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
 }
 
 // The Q operand (B of S^T = K Q^T) of lane (j, c) for k-step ks: 8 halves of q[head c] in the d order
@@ -308,17 +319,18 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
 }
 
 // Per-wave online-softmax state.  acc[e] is the 16x16 output tile of d columns {8c' + e}: lane (j', c')
-// holds rows (heads) 4j'..4j'+3.  m, l, zc are per head c in the S^T layout (lane (j, c), any j).
+// holds rows (heads) 4j'..4j'+3.  m, l, zc belong to the head whose logits the lane exponentiates (see
+// softmax_pv): m is the same in all lanes of a head, l and zc are the lane's share.
 struct State {
   float4v acc[8];
   float m;   // reference subtracted from the logits (base-2 domain): within kTau of the running max
-  float l;   // this lane's share of the running sum (its 8-token runs only)
+  float l;   // this lane's share of the running sum
   float zc;  // INT8/INT4: this lane's share of the zero-point term  -sum_t p_t s_t z_t
 };
 
-// S^T = K Q^T for the 32 tokens of the tile: s[u][r] = raw logit of head c, token tb + 8j + 4u + r.
-template <int DT>
-__device__ __forceinline__ void qk_tile(const Tile<DT>& t, const u32x4 (&qb)[4], float4v (&s)[2]) {
+// S^T = K Q^T for the 32 tokens of the tile: s[u][r] = raw logit of head c, slot 4u + r of run j.
+template <int DT, int GP>
+__device__ __forceinline__ void qk_tile(const Tile<DT, GP>& t, const u32x4 (&qb)[4], float4v (&s)[2]) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     u32x4 a[4];
@@ -330,95 +342,185 @@ __device__ __forceinline__ void qk_tile(const Tile<DT>& t, const u32x4 (&qb)[4],
   }
 }
 
-// Online softmax over the tile and out += P V.
-template <int DT>
-__device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const float4v (&s)[2], int tb, int j, int c,
-                                           float qsum, float alpha, State& st) {
-  const int n_valid = X.t1 - (tb + 8 * j);  // tokens of this lane's run inside the range
-  const bool partial = tb + kTile > X.t1;    // wave-uniform
-  float x[8];
-  // per-token dequantization factors, prepared by the lane that loaded the token's parameters
-  float pa = 0.f, pb = 0.f;
-  if constexpr (Fmt<DT>::kParBytes != 0) {
-    const float sc = f16lo(t.par);
-    const float zp = DT == FS_KV_INT4 ? f16hi(t.par) : 128.0f;
-    if (c < 8) {  // K: logit = alpha * sc * (2^24 * S_raw - zp * qsum)
-      pa = alpha * kTwo24 * sc;
-      pb = -alpha * sc * zp;
-    } else {      // V: p' = p * sc, zero-point term -p * sc * zp
-      const bool ok = (c & 7) < n_valid;
-      pa = ok ? sc : 0.f;
-      pb = ok ? -sc * zp : 0.f;
-    }
+// lanes of the banks in BANKS take src from the lane SHIFT places to their right in the 16-lane row
+// (DPP row_shr), the others keep old
+template <int SHIFT, int BANKS>
+__device__ __forceinline__ float take_shr(float old, float src) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(old), __float_as_uint(src), 0x110 + SHIFT, 0xF, BANKS, false));
+}
+// value of the lane SHIFT places to the left in the row (DPP row_shl), 0 where the row ends
+template <int SHIFT>
+__device__ __forceinline__ uint32_t from_shl(uint32_t src) {
+  return __builtin_amdgcn_update_dpp(0u, src, 0x100 + SHIFT, 0xF, 0xF, true);
+}
+
+// Moves the reference of the lazy online softmax: called when some logit of the tile exceeds its head's
+// reference by more than kTau (always on the first tile, where m = -inf).  tmax = largest logit among this
+// lane's tokens; the lanes of a head are those with equal c % GP.
+template <int DT, int GP>
+__device__ __forceinline__ void move_reference(State& st, float tmax, int j) {
+  if constexpr (GP == 4) {
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 4, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 8, 64));
   }
-  float ka[8], kb[8], va[8], vb[8];
-  static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
-    constexpr int i = decltype(I)::value;
-    const float v = s[i >> 2][i & 3];
-    if constexpr (Fmt<DT>::kParBytes != 0) {
-      ka[i] = row_bcast<i>(pa);
-      kb[i] = row_bcast<i>(pb);
-      va[i] = row_bcast<8 + i>(pa);
-      vb[i] = row_bcast<8 + i>(pb);
-      x[i] = fmaf(v, ka[i], kb[i] * qsum);
-    } else {
-      x[i] = v * alpha;
-    }
-  });
-  if (partial) {
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const float m_new = fmaxf(st.m, tmax);  // finite: the tile's first run holds a token of the item
+  const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
+  st.l *= corr;
+  if constexpr (Fmt<DT>::kParBytes != 0) st.zc *= corr;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = i < n_valid ? x[i] : -INFINITY;
+  for (int r = 0; r < 4; ++r) {
+    const float cr = __shfl(corr, (4 * j + r) % GP, 64);  // head h keeps its factor in lane c = h
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[e][r] *= cr;
+  }
+  st.m = m_new;
+}
+
+// Online softmax over the tile and out += P V.
+//
+// The lazy running reference: the softmax is invariant to the value subtracted from the logits, so the
+// reference m only has to stay within 2^kTau of the largest logit seen (P stays <= 2^kTau, far inside fp16).
+//
+// GP == 16: lane (j, c) exponentiates the 8 logits of head c it holds after S^T; its packed P is directly the A
+// operand of P V.  Per-token parameters reach it by DPP broadcast from the lanes that loaded them.
+// GP == 4: only head columns 0..3 are real, so 12 of 16 lanes would exponentiate padding.  Instead lane
+// (j, c) takes head c % 4 and slots 2 (c / 4), + 1 of run j: it fetches those two logits from lane (j, c % 4)
+// (DPP row shifts), loads the parameters of its own two tokens itself, and hands its packed pair of P back to
+// lanes c < 4 (DPP again), which assemble the A operand.  A quarter of the exponentials, no broadcasts.
+template <int DT, int GP>
+__device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, const float4v (&s)[2], int vb, int j, int c,
+                                           float qsum, float alpha, State& st) {
+  using F = Fmt<DT>;
+  const RunLoc L = locate(X, vb + j);
+  const uint32_t n_ok = (uint32_t)max(L.hi - L.lo, 0);   // slot i of the run is live iff (unsigned)(i - lo) < n_ok
+  const bool partial = !__all(L.lo == 0 && L.hi == 8);   // wave-uniform
+  if (partial) {
     if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
-      // rows past the range may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
+      // slots past the sequence's end may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
+      // (slots before lo repeat live tokens: finite, their weight is 0)
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int w = 0; w < Fmt<DT>::kVBytes / 4; ++w) t.v[i][w] = i < n_valid ? t.v[i][w] : 0u;
+        for (int w = 0; w < F::kVBytes / 4; ++w) t.v[i][w] = i < L.hi ? t.v[i][w] : 0u;
     }
   }
-  // ---- lazy running reference: the softmax is invariant to the value subtracted from the logits, so the
-  // reference m only has to stay within 2^kTau of the largest logit seen (P stays <= 2^kTau, far inside fp16).
-  // The exact cross-lane maximum and the rescale of the accumulators run only when some logit of the tile
-  // exceeds its head's reference by more than kTau (always on a wave's first tile, where m = -inf).
-  float tmax = x[0];
-#pragma unroll
-  for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
-  if (__any(tmax - st.m > kTau)) {
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(st.m, tmax);  // finite: token tb of every tile is inside the range
-    const float corr = __builtin_amdgcn_exp2f(st.m - m_new);
-    st.l *= corr;
-    if constexpr (Fmt<DT>::kParBytes != 0) st.zc *= corr;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float cr = __shfl(corr, 4 * j + r, 64);  // head 4j + r keeps its factor in lane c = 4j + r
-#pragma unroll
-      for (int e = 0; e < 8; ++e) st.acc[e][r] *= cr;
+  u32x4 pk;  // A operand of P V: halves (2q, 2q + 1) of pk[q] = weights of slots 2q, 2q + 1 of run j, head c
+  if constexpr (GP == 16) {
+    float x[8];
+    // per-token dequantization factors, prepared by the lane that loaded the token's parameters
+    float pa = 0.f, pb = 0.f;
+    if constexpr (F::kParBytes != 0) {
+      const float sc = f16lo(t.par[0]);
+      const float zp = DT == FS_KV_INT4 ? f16hi(t.par[0]) : 128.0f;
+      if (c < 8) {  // K: logit = alpha * sc * (2^24 * S_raw - zp * qsum)
+        pa = alpha * kTwo24 * sc;
+        pb = -alpha * sc * zp;
+      } else {      // V: p' = p * sc, zero-point term -p * sc * zp
+        const bool ok = (uint32_t)((c & 7) - L.lo) < n_ok;
+        pa = ok ? sc : 0.f;
+        pb = ok ? -sc * zp : 0.f;
+      }
     }
-    st.m = m_new;
-  }
-  const float m_new = st.m;
-  // ---- P (times the per-token V scale) ----
-  float p[8];
-  float lsum = 0.f;
+    float va[8], vb2[8];
+    static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const float v = s[i >> 2][i & 3];
+      if constexpr (F::kParBytes != 0) {
+        const float ka = row_bcast<i>(pa);
+        const float kb = row_bcast<i>(pb);
+        va[i] = row_bcast<8 + i>(pa);
+        vb2[i] = row_bcast<8 + i>(pb);
+        x[i] = fmaf(v, ka, kb * qsum);
+      } else {
+        x[i] = v * alpha;
+      }
+    });
+    if (partial) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float e = __builtin_amdgcn_exp2f(x[i] - m_new);
-    lsum += e;
-    if constexpr (Fmt<DT>::kParBytes != 0) {
-      p[i] = e * va[i];
-      st.zc = fmaf(e, vb[i], st.zc);
+      for (int i = 0; i < 8; ++i) x[i] = (uint32_t)(i - L.lo) < n_ok ? x[i] : -INFINITY;
+    }
+    float tmax = x[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
+    if (__any(tmax - st.m > kTau)) move_reference<DT, GP>(st, tmax, j);
+    const float m = st.m;
+    float p[8];
+    float lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float e = __builtin_amdgcn_exp2f(x[i] - m);
+      lsum += e;
+      if constexpr (F::kParBytes != 0) {
+        p[i] = e * va[i];
+        st.zc = fmaf(e, vb2[i], st.zc);
+      } else {
+        p[i] = e;
+      }
+    }
+    st.l += lsum;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
+      pk[q] = h2u(h);
+    }
+  } else {
+    // the two logits of head c % 4 for slots 2 (c / 4), 2 (c / 4) + 1: registers 2 (c / 4), + 1 of lane (j, c % 4)
+    float y0 = s[0][0], y1 = s[0][1];
+    y0 = take_shr<4, 0x2>(y0, s[0][2]);
+    y1 = take_shr<4, 0x2>(y1, s[0][3]);
+    y0 = take_shr<8, 0x4>(y0, s[1][0]);
+    y1 = take_shr<8, 0x4>(y1, s[1][1]);
+    y0 = take_shr<12, 0x8>(y0, s[1][2]);
+    y1 = take_shr<12, 0x8>(y1, s[1][3]);
+    const int i0 = 2 * (c >> 2);
+    bool ok0 = true, ok1 = true;
+    if (partial) {
+      ok0 = (uint32_t)(i0 - L.lo) < n_ok;
+      ok1 = (uint32_t)(i0 + 1 - L.lo) < n_ok;
+    }
+    float x0, x1;
+    if constexpr (F::kParBytes != 0) {
+      // logit = alpha * sc * (2^24 * S_raw - zp * qsum)     (qsum: of this lane's head)
+      const float a24 = alpha * kTwo24, aq = -alpha * qsum;
+      const float s0 = f16lo(t.par[0]), s1 = f16lo(t.par[1]);
+      const float z0 = DT == FS_KV_INT4 ? f16hi(t.par[0]) : 128.0f, z1 = DT == FS_KV_INT4 ? f16hi(t.par[1]) : 128.0f;
+      x0 = fmaf(y0, s0 * a24, (s0 * z0) * aq);
+      x1 = fmaf(y1, s1 * a24, (s1 * z1) * aq);
     } else {
-      p[i] = e;
+      x0 = y0 * alpha;
+      x1 = y1 * alpha;
     }
-  }
-  st.l += lsum;
-  u32x4 pk;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
-    pk[q] = h2u(h);
+    if (partial) {
+      x0 = ok0 ? x0 : -INFINITY;
+      x1 = ok1 ? x1 : -INFINITY;
+    }
+    const float tmax = fmaxf(x0, x1);
+    if (__any(tmax - st.m > kTau)) move_reference<DT, GP>(st, tmax, j);
+    const float m = st.m;
+    const float e0 = __builtin_amdgcn_exp2f(x0 - m), e1 = __builtin_amdgcn_exp2f(x1 - m);
+    st.l += e0 + e1;
+    float p0 = e0, p1 = e1;
+    if constexpr (F::kParBytes != 0) {
+      // p' = p * sc, zero-point term -p' * zp
+      float s0 = f16lo(t.par[2]), s1 = f16lo(t.par[3]);
+      const float z0 = DT == FS_KV_INT4 ? f16hi(t.par[2]) : 128.0f, z1 = DT == FS_KV_INT4 ? f16hi(t.par[3]) : 128.0f;
+      if (partial) {  // a dead slot's scale may be any bit pattern
+        s0 = ok0 ? s0 : 0.f;
+        s1 = ok1 ? s1 : 0.f;
+      }
+      p0 = e0 * s0;
+      p1 = e1 * s1;
+      st.zc = fmaf(-p0, z0, st.zc);
+      st.zc = fmaf(-p1, z1, st.zc);
+    }
+    const half2v h = {(_Float16)p0, (_Float16)p1};
+    const uint32_t pp = h2u(h);
+    pk[0] = pp;  // rows c >= 4 of the operand are padding heads: whatever lands there is finite and unused
+    pk[1] = from_shl<4>(pp);
+    pk[2] = from_shl<8>(pp);
+    pk[3] = from_shl<12>(pp);
   }
   // ---- V rows of the run -> B operands (8x8 in-register transpose) and out += P V ----
   uint32_t vx[8][4];
@@ -435,23 +537,26 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT>& t, const 
   }
 }
 
-// One work item, processed by ONE wave: all 32-token tiles of the split, then the output (or the split's
-// partial record) straight from the accumulator registers.  Waves never synchronise with each other.
+// One work item, processed by ONE wave: all tiles of the split, then the output (or the split's partial
+// record) straight from the accumulator registers.  Waves never synchronise with each other.
 // s_ptr: this wave's LDS table of head-chunk addresses.
-template <int DT>
+template <int DT, int GP>
 __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, uint64_t* s_ptr) {
   const DevBatch& B = A.b[b];
   const DevGeom& g = B.g;
-  const int lane = threadIdx.x & 63;
+  // The lane index is made opaque per item: otherwise the compiler hoists every variant's lane-dependent
+  // constants out of the kernel's item loop, where they stay live across all other variants and push the
+  // tile loops into spilling.
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
   const int j = lane >> 4, c = lane & 15;
   const int G = B.G;
   const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
   int len = B.seq_lens[seq];
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
-  const int n_chunks = (len + B.chunk_tokens - 1) / B.chunk_tokens;
-  const int t0 = chunk * B.chunk_tokens;
-  const int t1 = min(len, t0 + B.chunk_tokens);
-  const int nblk = (len + g.T - 1) / g.T;
+  const int n_chunks = n_splits(B, len);
+  const int v0 = chunk * B.chunk_runs;
+  const int v1 = min(n_runs(len, g.T, B.R), v0 + B.chunk_runs);
 
   const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
   const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
@@ -461,22 +566,21 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   }
 
   ItemCtx X;
-  X.B = &B;
-  X.b_first = t0 / g.T;
-  X.b_last = (t1 - 1) / g.T;
-  X.t1 = t1;
-  X.t_magic = B.t_magic;
-  // head-chunk addresses of the blocks this item touches (plus one more), through LDS: every lane of
-  // every tile looks its blocks up here instead of gathering them from the block table in memory
+  X.T = g.T;
+  X.R = B.R;
+  X.r_magic = B.r_magic;
+  X.len = len;
+  X.v_end = v1;
+  X.k0 = div_runs(v0, B.R, B.r_magic);
+  // head-chunk addresses of the blocks this item touches, through LDS: every lane of every tile looks its
+  // blocks up here instead of gathering them from the block table in memory
   X.chunk_ptr = s_ptr;
   {
     const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
     const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
-    const int nb = X.b_last - X.b_first + 2;
-    for (int i = lane; i < nb; i += 64) {
-      const int bi = min(X.b_first + i, nblk - 1);  // past the sequence's last block: alias it (valid memory)
-      s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[bi] * g.block_budget);
-    }
+    const int nb = div_runs(v1 - 1, B.R, B.r_magic) - X.k0 + 1;
+    for (int i = lane; i < nb; i += 64)
+      s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
   }
   // the table is private to this wave; LDS operations of a wave complete in order, the fence only keeps the
   // compiler from moving the look-ups above the writes of other lanes
@@ -491,6 +595,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   if constexpr (Fmt<DT>::kParBytes != 0) {
     qsum += __shfl_xor(qsum, 16, 64);
     qsum += __shfl_xor(qsum, 32, 64);
+    if constexpr (GP == 4) qsum = __shfl(qsum, c & 3, 64);  // of the head this lane exponentiates
   }
   float alpha = B.sm_scale * kLog2e;
   if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
@@ -506,38 +611,45 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   // tile that will next occupy a slot are requested as soon as S^T of its current occupant is done, the V
   // rows as soon as P V is done, so the narrower the format the more tiles are in flight (about 16 KiB per
   // wave for every format).
+  // Every step refills its slot unconditionally: past the item's last tile the runs are mapped onto the
+  // item's last run (rows just read, so the refill hits in cache) and the data is never used.  With refills
+  // that depend on a condition the compiler cannot know how many loads are outstanding behind the one it
+  // needs and waits for all of them, the ones just issued included, which exposes the full memory latency on
+  // every tile.  For the same reason the tile count is rounded up to whole rings: the surplus tiles lie past
+  // the item's end, are fully masked and contribute zeros.
   constexpr int NBUF = Fmt<DT>::kRing;
-  const int n_tiles = (t1 - t0 + kTile - 1) / kTile;
-  Tile<DT> t[NBUF];
+  const int n_tiles = (v1 - v0 + 3) >> 2;
+  Tile<DT, GP> t[NBUF];
   static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
     constexpr int bi = decltype(Bi)::value;
-    if (bi < n_tiles) {
-      const int tb = t0 + bi * kTile;
-      issue_k<DT>(X, tb, j, c, t[bi]);
-      issue_v<DT>(X, tb, j, c, t[bi]);
-    }
+    issue_k<DT, GP>(X, v0 + bi * 4, j, c, t[bi]);
+    issue_v<DT, GP>(X, g, v0 + bi * 4, j, c, t[bi]);
   });
   for (int k0 = 0; k0 < n_tiles; k0 += NBUF) {
     static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
       constexpr int bi = decltype(Bi)::value;
-      const int k = k0 + bi;
-      if (k < n_tiles) {
-        const int tb = t0 + k * kTile;
-        const int tb_next = tb + NBUF * kTile;
-        const bool more = k + NBUF < n_tiles;
-        float4v s[2];
-        qk_tile<DT>(t[bi], qb, s);
-        if (more) issue_k<DT>(X, tb_next, j, c, t[bi]);
-        softmax_pv<DT>(X, t[bi], s, tb, j, c, qsum, alpha, st);
-        if (more) issue_v<DT>(X, tb_next, j, c, t[bi]);
-      }
+      const int vb = v0 + (k0 + bi) * 4;
+      const int vb_next = vb + NBUF * 4;
+      float4v s[2];
+      qk_tile<DT, GP>(t[bi], qb, s);
+      issue_k<DT, GP>(X, vb_next, j, c, t[bi]);
+      softmax_pv<DT, GP>(X, t[bi], s, vb, j, c, qsum, alpha, st);
+      issue_v<DT, GP>(X, g, vb_next, j, c, t[bi]);
     });
   }
 
-  // ---- output: per-head sums over the four lane groups, then rows h < G straight from the accumulators ----
+  // ---- output: per-head sums over the lanes of the head, then rows h < G straight from the accumulators ----
+  if constexpr (GP == 4) {
+    st.l += __shfl_xor(st.l, 4, 64);
+    st.l += __shfl_xor(st.l, 8, 64);
+  }
   st.l += __shfl_xor(st.l, 16, 64);
   st.l += __shfl_xor(st.l, 32, 64);
   if constexpr (Fmt<DT>::kParBytes != 0) {
+    if constexpr (GP == 4) {
+      st.zc += __shfl_xor(st.zc, 4, 64);
+      st.zc += __shfl_xor(st.zc, 8, 64);
+    }
     st.zc += __shfl_xor(st.zc, 16, 64);
     st.zc += __shfl_xor(st.zc, 32, 64);
   }
@@ -580,15 +692,21 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   }
 }
 
-__device__ __forceinline__ void dispatch_item(const MultiArgs& A, uint32_t item, uint64_t* s_ptr) {
-  const int4 rec = A.item_list[item];
-  const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
+template <int GP>
+__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, int b, int4 rec, uint32_t item, uint64_t* s_ptr) {
   switch (A.b[b].g.dtype) {
-    case FS_KV_FP16: process_item<FS_KV_FP16>(A, b, seq, chunk, head, item, s_ptr); break;
-    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, s_ptr); break;
-    case FS_KV_INT8: process_item<FS_KV_INT8>(A, b, seq, chunk, head, item, s_ptr); break;
-    default: process_item<FS_KV_INT4>(A, b, seq, chunk, head, item, s_ptr); break;
+    case FS_KV_FP16: process_item<FS_KV_FP16, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
+    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
+    case FS_KV_INT8: process_item<FS_KV_INT8, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
+    default: process_item<FS_KV_INT4, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
   }
+}
+
+__device__ __forceinline__ void dispatch_item(const MultiArgs& A, uint32_t item, uint64_t* s_ptr) {
+  const int4 rec = A.item_list[item];  // (batch, sequence, split, KV head)
+  const int b = rec.x;
+  if (A.b[b].G <= 4) dispatch_dtype<4>(A, b, rec, item, s_ptr);
+  else dispatch_dtype<16>(A, b, rec, item, s_ptr);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A, int table_entries) {
@@ -607,18 +725,19 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A
 
 }  // namespace
 
-// Shapes this kernel covers: head_dim 128, at least 8 tokens per block (an 8-token run then crosses at
-// most one block boundary), and token indices small enough for the multiply-high division by T.
+// Shapes this kernel covers: head_dim 128, at least 8 tokens per block (a run of 8 slots fits a block), and
+// run indices small enough for the multiply-high division by R.
 bool mfma_supports(const DevBatch& b) {
   if (b.g.D != kD || b.g.T < 8 || b.G > 16) return false;
-  const uint64_t max_tok = (uint64_t)b.max_blocks * (uint64_t)b.g.T + 64;
-  return max_tok <= (1ull << 32) / (uint64_t)b.g.T && max_tok < (1ull << 31);
+  const uint64_t max_tok = (uint64_t)b.max_blocks * (uint64_t)b.g.T;
+  const uint64_t max_run = (uint64_t)b.max_blocks * (uint64_t)b.R + 8;
+  return max_tok < (1ull << 31) && max_run * (uint64_t)b.R < (1ull << 32);
 }
 
 hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s) {
   // LDS: per wave one 8-byte address per block of the largest split (+ slack)
   int entries = 0;
-  for (int i = 0; i < A.n_batches; ++i) entries = std::max(entries, A.b[i].chunk_tokens / A.b[i].g.T + 4);
+  for (int i = 0; i < A.n_batches; ++i) entries = std::max(entries, A.b[i].chunk_runs / A.b[i].R + 4);
   const size_t smem = (size_t)kWaves * entries * sizeof(uint64_t);
   hipLaunchKernelGGL(mfma_attention_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries);
   return hipGetLastError();
