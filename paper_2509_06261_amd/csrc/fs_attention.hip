@@ -16,7 +16,8 @@ namespace fs {
 namespace {
 
 int g_kernel_mode = 0;
-uint64_t g_split_bytes = 192u << 10;
+uint64_t g_split_bytes = 0;  // 0: chosen per launch (see launch_split_bytes)
+constexpr uint64_t kSplitMax = 192u << 10, kSplitMin = 64u << 10;
 bool g_timing = false;
 hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
@@ -229,6 +230,61 @@ struct Plan {
 
 uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 
+// Runs of 8 token slots per work item for a target of split_bytes per item (a multiple of 4, at most ~500 blocks).
+int32_t chunk_runs_for(const fs_geometry_t& g, uint64_t split_bytes) {
+  const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
+  const int64_t R = (g.tokens_per_block + 7) / 8;
+  int64_t cr = (int64_t)(split_bytes / (8 * token_bytes)) / 4 * 4;
+  cr = std::min<int64_t>(cr, 500 * R / 4 * 4);
+  return (int32_t)std::min<int64_t>(std::max<int64_t>(cr, 4), 1 << 17);
+}
+
+// KV bytes per split-K work item of this launch.  The work items are dealt to the persistent grid's waves in
+// a fixed round-robin, so the launch takes ceil(items / waves) rounds of one item each: with the lengths
+// known on the host the split between 64 and 192 KiB is chosen that minimises rounds x (item bytes + a
+// per-item set-up worth about 4 KiB); without them 192 KiB, less when even the upper bound of the launch's
+// bytes gives a wave fewer than three such items.  Below 64 KiB the per-item set-up starts to dominate.
+uint64_t launch_split_bytes(const fs_pool* p, const fs_batch_t* batches, int n_batches) {
+  if (g_split_bytes) return g_split_bytes;
+  if (!p || !batches || p->n_cu == 0) return kSplitMax;
+  const uint64_t waves = (uint64_t)p->n_cu * 8;
+  bool host_lens = true;
+  uint64_t total_ub = 0;
+  for (int i = 0; i < n_batches; ++i) {
+    const fs_batch_t& b = batches[i];
+    if (b.model < 0 || b.model >= kMaxModels || !p->models[b.model].in_use || b.n_seq < 1 || b.max_blocks < 1) return kSplitMax;
+    const fs_geometry_t& g = p->models[b.model].g;
+    if (!b.seq_lens_host) host_lens = false;
+    total_ub += (uint64_t)b.n_seq * (uint64_t)b.max_blocks * (uint64_t)g.tokens_per_block * 2 *
+                (g.row_bytes + (uint64_t)g.param_bytes) * (uint64_t)g.n_kv_heads;
+  }
+  if (!host_lens) return std::min(kSplitMax, std::max(kSplitMin, total_ub / (3 * waves) / 4096 * 4096));
+  uint64_t best_split = kSplitMax, best_cost = ~0ull;
+  for (uint64_t split = kSplitMax; split >= kSplitMin; split -= 8192) {
+    uint64_t items = 0;
+    for (int i = 0; i < n_batches; ++i) {
+      const fs_batch_t& b = batches[i];
+      const fs_geometry_t& g = p->models[b.model].g;
+      const int R = (g.tokens_per_block + 7) / 8;
+      const int64_t cr = chunk_runs_for(g, split);
+      const int64_t ub_len = std::min<int64_t>((int64_t)b.max_blocks * g.tokens_per_block, 0x7fffffff);
+      uint64_t n = 0;
+      for (int q = 0; q < b.n_seq; ++q) {
+        const int64_t len = std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[q], 1), ub_len);
+        n += (uint64_t)((n_runs((int)len, g.tokens_per_block, R) + cr - 1) / cr);
+      }
+      items += n * (uint64_t)g.n_kv_heads;
+    }
+    if (split == kSplitMax && items >= 8 * waves) return kSplitMax;  // many rounds: the rounding no longer matters
+    const uint64_t cost = ((items + waves - 1) / waves) * (split + 4096);
+    if (cost < best_cost) {
+      best_cost = cost;
+      best_split = split;
+    }
+  }
+  return best_split;
+}
+
 // Validates the batches and lays the workspace out.  With workspace == nullptr only sizes are computed.
 int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, Plan& plan) {
   if (!p || !batches || n_batches < 1 || n_batches > kMaxBatches) {
@@ -237,6 +293,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
   }
   MultiArgs& A = plan.args;
   A.n_batches = n_batches;
+  const uint64_t split_bytes = launch_split_bytes(p, batches, n_batches);
   int64_t seq_total = 0, qrows = 0;
   uint64_t part_floats = 0;
   for (int i = 0; i < n_batches; ++i) {
@@ -277,14 +334,12 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.G = b.n_q_heads / g.n_kv_heads;
     B.sm_scale = b.sm_scale;
     const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
-    int64_t ct = (int64_t)(g_split_bytes / token_bytes) / 32 * 32;
+    int64_t ct = (int64_t)(split_bytes / token_bytes) / 32 * 32;
     ct = std::min<int64_t>(ct, (int64_t)500 * g.tokens_per_block / 32 * 32);  // at most ~500 blocks per work item
     B.chunk_tokens = (int32_t)std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
     B.R = (g.tokens_per_block + 7) / 8;
     B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);  // unused for R = 1
-    int64_t cr = (int64_t)(g_split_bytes / (8 * token_bytes)) / 4 * 4;
-    cr = std::min<int64_t>(cr, (int64_t)500 * B.R / 4 * 4);
-    B.chunk_runs = (int32_t)std::min<int64_t>(std::max<int64_t>(cr, 4), 1 << 17);
+    B.chunk_runs = chunk_runs_for(g, split_bytes);
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
     B.qrow_first = (int32_t)qrows;
@@ -366,7 +421,7 @@ float fs_last_attention_kernel_ms(void) {
 }
 
 int fs_set_split_bytes(uint64_t bytes) {
-  if (bytes < 4096 || bytes > (1ull << 30)) return FS_ERR_INVALID;
+  if (bytes != 0 && (bytes < 4096 || bytes > (1ull << 30))) return FS_ERR_INVALID;
   g_split_bytes = bytes;
   return FS_OK;
 }

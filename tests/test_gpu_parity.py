@@ -55,7 +55,7 @@ def test_gqa_8b_shape_all_dtypes(dtype, src_f32, mode):
         errs = par.run_and_check([1], kernel_mode=mode)
         print("max abs err", errs)
     finally:
-        par.fs.fs_set_split_bytes(192 * KiB)
+        par.fs.fs_set_split_bytes(0)
         par.close()
 
 
@@ -72,7 +72,7 @@ def test_mha_13b_shape(dtype, mode):
         errs = par.run_and_check([2], kernel_mode=mode)
         print("T", par.gw.T, "max abs err", errs)
     finally:
-        par.fs.fs_set_split_bytes(192 * KiB)
+        par.fs.fs_set_split_bytes(0)
         par.close()
 
 
@@ -110,7 +110,7 @@ def test_group_sizes_and_head_dim_64(group, mode):
         par.fs.fs_set_split_bytes(16 * KiB)
         par.run_and_check([0], kernel_mode=mode)
     finally:
-        par.fs.fs_set_split_bytes(192 * KiB)
+        par.fs.fs_set_split_bytes(0)
         par.close()
 
 
@@ -152,7 +152,7 @@ def test_placement_invariance_and_split_independence_on_gpu(mode):
                 torch.cuda.synchronize()
                 outs[(placement, split)] = keep["out"][0].cpu().numpy().copy()
             finally:
-                par.fs.fs_set_split_bytes(192 * KiB)
+                par.fs.fs_set_split_bytes(0)
                 par.fs.fs_set_kernel_mode(0)
                 par.close()
     for split in (8 * KiB, 4 * MiB):
