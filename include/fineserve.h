@@ -173,8 +173,8 @@ int fs_decode_status(const void* workspace, void* stream);
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
 int fs_set_kernel_mode(int mode);
 /* Target KV bytes per split-K work item, rounded to whole 32-token tiles.  0 (the default) lets every launch
- * choose between 64 and 192 KiB so that the items divide evenly among the waves of the grid (exactly, from
- * seq_lens_host when every batch gives it; otherwise from the upper bound max_blocks * tokens_per_block).
+ * choose: 192 KiB, less (down to 64 KiB) for launches too small to give each wave of the grid three items
+ * (judged from seq_lens_host where given, otherwise from the upper bound max_blocks * tokens_per_block).
  * The workspace size depends on it: query fs_decode_workspace_bytes with the setting the launch will use. */
 int fs_set_split_bytes(uint64_t bytes);
 

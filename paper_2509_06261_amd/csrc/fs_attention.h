@@ -31,21 +31,32 @@ struct DevBatch {
   uint32_t pad;
 };
 
-// Workspace header words (uint32 unless noted), 256 bytes.
+// Workspace header words (uint32 unless noted).
 enum : int {
-  kHdrCounter = 0,     // work-queue ticket counter
+  kHdrCounter = 0,     // generic kernel: work-queue ticket counter
   kHdrStatus = 1,      // bit 0: a sequence length was out of range; bit 1: partial buffer too small
   kHdrTotalItems = 2,  // number of work items
-  kHdrBatchFirst = 8,  // [kMaxBatches] first work item of each batch
-  kHdrPartOff = 32     // [kMaxBatches] uint64: float offset of each batch's partials (word index of a uint64 array)
+  kHdrBatchFirst = 8,  // [kMaxBatches] first work item of each batch (sequence-major numbering)
+  kHdrPartOff = 32,    // [kMaxBatches] uint64: float offset of each batch's partials (word index of a uint64 array)
+  kHdrPools = 64       // [kPools] ticket counters of the MFMA kernel's end-of-launch pools, kPoolStride words apart
 };
-constexpr uint32_t kHeaderBytes = 256;
+constexpr int kPools = 64;
+constexpr int kPoolStride = 16;  // one counter per 64 bytes: neighbours never share a cache line
+constexpr uint32_t kHeaderBytes = 256 + kPools * kPoolStride * 4;
+
+// A work item's record in the queue: x = batch | KV head << 4, y = sequence, z = split, w = the item's index
+// within its batch in sequence-major order (sequence, split, KV head) -- the order of the partial records.
+__device__ __host__ inline int4 make_rec(int batch, int seq, int split, int head, uint32_t local) {
+  return int4{batch | (head << 4), seq, split, (int)local};
+}
+__device__ __host__ inline int rec_batch(const int4& r) { return r.x & 15; }
+__device__ __host__ inline int rec_head(const int4& r) { return r.x >> 4; }
 
 struct MultiArgs {
   DevBatch b[kMaxBatches];
   uint32_t* header;
   uint32_t* item_base;  // [n_seq_total + 1] first work item of each sequence
-  int4* item_list;      // [item_capacity] (batch, sequence, split, KV head) of every work item, queue order
+  int4* item_list;      // [item_capacity] record of every work item, queue order (see make_rec)
   float* partials;
   uint64_t part_capacity;  // floats
   uint32_t item_capacity;  // entries of item_list
@@ -56,8 +67,11 @@ struct MultiArgs {
   int32_t pad;
 };
 
-// Work item r of a sequence with n_chunks splits and H KV heads: chunk = r / H, head = r % H,
-// so the heads of one (sequence, chunk) -- which lie in the same slabs -- run side by side.
+// Work item r of a sequence with n_chunks splits and H KV heads: chunk = r / H, head = r % H, so the heads
+// of one (sequence, chunk) -- which lie in the same slabs -- are neighbours.  The queue merges the batches'
+// sequence-major item lists proportionally (item i of n_b in batch b sorts by i / n_b), so that at any time
+// the grid works on all batches -- all KV formats -- at once: formats bound by the vector ALU and formats
+// bound by memory then share every compute unit instead of taking turns.
 
 // Runs of 8 token slots that a sequence of `len` tokens occupies (MFMA kernel's unit of work).
 __device__ __host__ inline int n_runs(int len, int T, int R) {

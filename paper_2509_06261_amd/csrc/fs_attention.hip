@@ -23,44 +23,72 @@ hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
 // ---------------------------------------------------------------------------------------
 // Work-list preparation: scans the sequences of all batches and writes, for every sequence,
-// the index of its first work item (items of a sequence = splits x KV heads) and, for every
-// work item, its (batch, sequence, split, KV head) record in queue order.  Every workgroup
-// repeats the (small) scan and writes its own share of the records; workgroup 0 also writes
-// the per-sequence and per-batch words, validates the sequence lengths and resets the queue.
+// the index of its first work item in sequence-major numbering (items of a sequence = splits
+// x KV heads) and, for every work item, its record at the item's place in the queue.  Every
+// workgroup repeats the (small) scans and writes its own share of the records; workgroup 0
+// also writes the per-sequence and per-batch words, validates the sequence lengths and resets
+// the counters.
+//
+// Queue order: the batches' item lists merged proportionally -- item i of the n_b items of
+// batch b sorts by (i / n_b, b).  Its place is i + the number of items of the other batches
+// that sort before it, a closed form, so no sort is run.
 // ---------------------------------------------------------------------------------------
 constexpr int kPrepThreads = 1024;
 constexpr int kPrepGroups = 64;
 
+// Items of the sequence a thread looks at (0 past the batch's last sequence); flags lengths out of range.
+__device__ __forceinline__ uint32_t seq_items(const MultiArgs& A, const DevBatch& B, int i, bool report) {
+  if (i >= B.n_seq) return 0;
+  const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
+  int len = B.seq_lens[i];
+  if (len < 1 || len > max_len) {
+    if (report) atomicOr(A.header + kHdrStatus, 1u);
+    len = len < 1 ? 1 : max_len;
+  }
+  return (uint32_t)n_splits(B, len) * (uint32_t)B.g.H;
+}
+
 __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
   __shared__ uint32_t s_incl[kPrepThreads];  // inclusive scan of the item counts of this round's sequences
   __shared__ uint32_t s_wave[kPrepThreads / 64];
+  __shared__ uint32_t s_count[kMaxBatches];  // items of each batch
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bool leader = blockIdx.x == 0;
   uint64_t* part_off = reinterpret_cast<uint64_t*>(A.header + kHdrPartOff);
   if (leader && tid == 0) A.header[kHdrStatus] = 0;
+  if (leader && tid < kPools) A.header[kHdrPools + tid * kPoolStride] = 0;
+  if (tid < kMaxBatches) s_count[tid] = 0;
   __syncthreads();  // workgroup 0: the reset precedes every flag its threads may raise below
-  uint32_t running = 0;  // items before the current round (same value in every thread)
+
+  // pass 1: items per batch
+  for (int b = 0; b < A.n_batches; ++b) {
+    const DevBatch& B = A.b[b];
+    uint32_t v = 0;
+    for (int i = tid; i < B.n_seq; i += kPrepThreads) v += seq_items(A, B, i, leader);
+#pragma unroll
+    for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0 && v) atomicAdd(&s_count[b], v);
+  }
+  __syncthreads();
+  uint32_t count[kMaxBatches];
+#pragma unroll
+  for (int b = 0; b < kMaxBatches; ++b) count[b] = b < A.n_batches ? s_count[b] : 0u;
+
+  // pass 2: per-sequence first items and the records
+  uint32_t running = 0;  // items before the current round, sequence-major (same value in every thread)
   uint64_t part_running = 0;
   for (int b = 0; b < A.n_batches; ++b) {
     const DevBatch& B = A.b[b];
     const uint32_t H = (uint32_t)B.g.H;
     const uint32_t batch_first = running;
+    const uint64_t n_b = count[b];
     if (leader && tid == 0) {
       A.header[kHdrBatchFirst + b] = batch_first;
       part_off[b] = part_running;
     }
-    const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
     for (int base = 0; base < B.n_seq; base += kPrepThreads) {
       const int i = base + tid;
-      uint32_t v = 0;
-      if (i < B.n_seq) {
-        int len = B.seq_lens[i];
-        if (len < 1 || len > max_len) {
-          if (leader) atomicOr(A.header + kHdrStatus, 1u);
-          len = len < 1 ? 1 : max_len;
-        }
-        v = (uint32_t)n_splits(B, len) * H;
-      }
+      const uint32_t v = seq_items(A, B, i, false);
       // inclusive scan: within each wave by shuffles, then over the waves' totals
       uint32_t incl = v;
 #pragma unroll
@@ -77,8 +105,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
       __syncthreads();
       const uint32_t round_items = s_incl[kPrepThreads - 1];
       if (leader && i < B.n_seq) A.item_base[B.seq_first + i] = running + incl - v;
-      // the round's items in queue order (sequence-major, then split, KV heads innermost): item r of the
-      // round belongs to the first sequence k whose inclusive count exceeds r
+      // item r of the round (sequence-major: sequence, then split, KV heads innermost) belongs to the first
+      // sequence k whose inclusive count exceeds r
       for (uint32_t r = blockIdx.x * kPrepThreads + tid; r < round_items; r += gridDim.x * kPrepThreads) {
         int lo = 0, hi = kPrepThreads - 1;
         while (lo < hi) {
@@ -87,8 +115,18 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
           else lo = mid + 1;
         }
         const uint32_t rr = r - (lo ? s_incl[lo - 1] : 0u);
-        const uint32_t idx = running + r;
-        if (idx < A.item_capacity) A.item_list[idx] = make_int4(b, base + lo, (int)(rr / H), (int)(rr % H));
+        const uint64_t local = running - batch_first + r;  // index within the batch
+        // place in the queue: items of batch b' < b with i' / n_b' <= local / n_b, of b' > b with i' / n_b' < local / n_b
+        uint64_t idx = local;
+#pragma unroll
+        for (int o = 0; o < kMaxBatches; ++o) {
+          const uint64_t n_o = count[o];
+          if (o == b || n_o == 0) continue;
+          const uint64_t num = local * n_o;
+          const uint64_t c = o < b ? num / n_b + 1 : (num + n_b - 1) / n_b;
+          idx += c < n_o ? c : n_o;
+        }
+        if (idx < A.item_capacity) A.item_list[idx] = make_rec(b, base + lo, (int)(rr / H), (int)(rr % H), (uint32_t)local);
       }
       __syncthreads();  // s_incl and s_wave are rewritten by the next round
       running += round_items;
@@ -239,50 +277,27 @@ int32_t chunk_runs_for(const fs_geometry_t& g, uint64_t split_bytes) {
   return (int32_t)std::min<int64_t>(std::max<int64_t>(cr, 4), 1 << 17);
 }
 
-// KV bytes per split-K work item of this launch.  The work items are dealt to the persistent grid's waves in
-// a fixed round-robin, so the launch takes ceil(items / waves) rounds of one item each: with the lengths
-// known on the host the split between 64 and 192 KiB is chosen that minimises rounds x (item bytes + a
-// per-item set-up worth about 4 KiB); without them 192 KiB, less when even the upper bound of the launch's
-// bytes gives a wave fewer than three such items.  Below 64 KiB the per-item set-up starts to dominate.
+// KV bytes per split-K work item of this launch: 192 KiB, less (not below 64 KiB, where the per-item set-up
+// starts to dominate) when the launch is too small to give every wave of the grid about three such items to
+// draw.  Lengths not known on the host count at their upper bound.
 uint64_t launch_split_bytes(const fs_pool* p, const fs_batch_t* batches, int n_batches) {
   if (g_split_bytes) return g_split_bytes;
   if (!p || !batches || p->n_cu == 0) return kSplitMax;
-  const uint64_t waves = (uint64_t)p->n_cu * 8;
-  bool host_lens = true;
-  uint64_t total_ub = 0;
+  uint64_t total = 0;
   for (int i = 0; i < n_batches; ++i) {
     const fs_batch_t& b = batches[i];
     if (b.model < 0 || b.model >= kMaxModels || !p->models[b.model].in_use || b.n_seq < 1 || b.max_blocks < 1) return kSplitMax;
     const fs_geometry_t& g = p->models[b.model].g;
-    if (!b.seq_lens_host) host_lens = false;
-    total_ub += (uint64_t)b.n_seq * (uint64_t)b.max_blocks * (uint64_t)g.tokens_per_block * 2 *
-                (g.row_bytes + (uint64_t)g.param_bytes) * (uint64_t)g.n_kv_heads;
+    const uint64_t ub_len = (uint64_t)b.max_blocks * (uint64_t)g.tokens_per_block;
+    uint64_t tokens = 0;
+    if (b.seq_lens_host)
+      for (int s = 0; s < b.n_seq; ++s) tokens += std::min<uint64_t>((uint64_t)std::max(b.seq_lens_host[s], 1), ub_len);
+    else
+      tokens = (uint64_t)b.n_seq * ub_len;
+    total += tokens * 2 * (g.row_bytes + (uint64_t)g.param_bytes) * (uint64_t)g.n_kv_heads;
   }
-  if (!host_lens) return std::min(kSplitMax, std::max(kSplitMin, total_ub / (3 * waves) / 4096 * 4096));
-  uint64_t best_split = kSplitMax, best_cost = ~0ull;
-  for (uint64_t split = kSplitMax; split >= kSplitMin; split -= 8192) {
-    uint64_t items = 0;
-    for (int i = 0; i < n_batches; ++i) {
-      const fs_batch_t& b = batches[i];
-      const fs_geometry_t& g = p->models[b.model].g;
-      const int R = (g.tokens_per_block + 7) / 8;
-      const int64_t cr = chunk_runs_for(g, split);
-      const int64_t ub_len = std::min<int64_t>((int64_t)b.max_blocks * g.tokens_per_block, 0x7fffffff);
-      uint64_t n = 0;
-      for (int q = 0; q < b.n_seq; ++q) {
-        const int64_t len = std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[q], 1), ub_len);
-        n += (uint64_t)((n_runs((int)len, g.tokens_per_block, R) + cr - 1) / cr);
-      }
-      items += n * (uint64_t)g.n_kv_heads;
-    }
-    if (split == kSplitMax && items >= 8 * waves) return kSplitMax;  // many rounds: the rounding no longer matters
-    const uint64_t cost = ((items + waves - 1) / waves) * (split + 4096);
-    if (cost < best_cost) {
-      best_cost = cost;
-      best_split = split;
-    }
-  }
-  return best_split;
+  const uint64_t waves = (uint64_t)p->n_cu * 8;
+  return std::min(kSplitMax, std::max(kSplitMin, total / (3 * waves) / 4096 * 4096));
 }
 
 // Validates the batches and lays the workspace out.  With workspace == nullptr only sizes are computed.

@@ -99,7 +99,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
 
   // where this item's partial record goes (only used when the sequence is split)
   const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
-  const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
+  const uint64_t part_base = part_off[b] + (uint64_t)item * (uint64_t)B.part_stride;  // item: index within the batch
   const bool part_ok = part_base + (uint64_t)B.part_stride <= A.part_capacity;
   if (n_chunks > 1 && !part_ok) {
     if (threadIdx.x == 0) atomicOr(A.header + kHdrStatus, 2u);
@@ -230,12 +230,13 @@ __global__ __launch_bounds__(kThreads) void generic_attention_kernel(MultiArgs A
     __syncthreads();
     if (item >= total) break;  // every wave of every workgroup reaches this once the queue is empty
     const int4 rec = A.item_list[item];
-    const int b = rec.x, seq = rec.y, chunk = rec.z, head = rec.w;
+    const int b = rec_batch(rec), seq = rec.y, chunk = rec.z, head = rec_head(rec);
+    const uint32_t local = (uint32_t)rec.w;  // the item's index within its batch: where its partial record goes
     switch (A.b[b].g.dtype) {
-      case FS_KV_FP16: dispatch_gp<FS_KV_FP16>(A, b, seq, chunk, head, item, smem); break;
-      case FS_KV_FP8_E4M3: dispatch_gp<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, smem); break;
-      case FS_KV_INT8: dispatch_gp<FS_KV_INT8>(A, b, seq, chunk, head, item, smem); break;
-      default: dispatch_gp<FS_KV_INT4>(A, b, seq, chunk, head, item, smem); break;
+      case FS_KV_FP16: dispatch_gp<FS_KV_FP16>(A, b, seq, chunk, head, local, smem); break;
+      case FS_KV_FP8_E4M3: dispatch_gp<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, local, smem); break;
+      case FS_KV_INT8: dispatch_gp<FS_KV_INT8>(A, b, seq, chunk, head, local, smem); break;
+      default: dispatch_gp<FS_KV_INT4>(A, b, seq, chunk, head, local, smem); break;
     }
   }
 }

@@ -541,7 +541,7 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
 // record) straight from the accumulator registers.  Waves never synchronise with each other.
 // s_ptr: this wave's LDS table of head-chunk addresses.
 template <int DT, int GP>
-__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, uint64_t* s_ptr) {
+__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, uint64_t* s_ptr) {  // item: index within the batch
   const DevBatch& B = A.b[b];
   const DevGeom& g = B.g;
   // The lane index is made opaque per item: otherwise the compiler hoists every variant's lane-dependent
@@ -559,7 +559,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   const int v1 = min(n_runs(len, g.T, B.R), v0 + B.chunk_runs);
 
   const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
-  const uint64_t part_base = part_off[b] + (uint64_t)(item - A.header[kHdrBatchFirst + b]) * (uint64_t)B.part_stride;
+  const uint64_t part_base = part_off[b] + (uint64_t)item * (uint64_t)B.part_stride;  // item: index within the batch
   if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {  // wave-uniform
     if (lane == 0) atomicOr(A.header + kHdrStatus, 2u);
     return;
@@ -693,34 +693,54 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
 }
 
 template <int GP>
-__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, int b, int4 rec, uint32_t item, uint64_t* s_ptr) {
+__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, int b, int4 rec, uint64_t* s_ptr) {
+  const int head = rec_head(rec);
+  const uint32_t local = (uint32_t)rec.w;  // the item's index within its batch: where its partial record goes
   switch (A.b[b].g.dtype) {
-    case FS_KV_FP16: process_item<FS_KV_FP16, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
-    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
-    case FS_KV_INT8: process_item<FS_KV_INT8, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
-    default: process_item<FS_KV_INT4, GP>(A, b, rec.y, rec.z, rec.w, item, s_ptr); break;
+    case FS_KV_FP16: process_item<FS_KV_FP16, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
+    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
+    case FS_KV_INT8: process_item<FS_KV_INT8, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
+    default: process_item<FS_KV_INT4, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
   }
 }
 
 __device__ __forceinline__ void dispatch_item(const MultiArgs& A, uint32_t item, uint64_t* s_ptr) {
-  const int4 rec = A.item_list[item];  // (batch, sequence, split, KV head)
-  const int b = rec.x;
-  if (A.b[b].G <= 4) dispatch_dtype<4>(A, b, rec, item, s_ptr);
-  else dispatch_dtype<16>(A, b, rec, item, s_ptr);
+  const int4 rec = A.item_list[item];
+  const int b = rec_batch(rec);
+  if (A.b[b].G <= 4) dispatch_dtype<4>(A, b, rec, s_ptr);
+  else dispatch_dtype<16>(A, b, rec, s_ptr);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A, int table_entries) {
   extern __shared__ uint64_t smem64[];
+  const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint64_t* s_ptr = smem64 + (size_t)wave * table_entries;
   const uint32_t total = A.header[kHdrTotalItems];
-  // Every wave is its own worker and takes the items worker, worker + n_workers, ... of the queue.  Items
-  // are splits of (nearly) equal bytes and every worker's stride walks through all batches alike, so this
-  // fixed deal balances to within about one item per batch.  (Drawing the items from a shared ticket
-  // counter instead was measured to bound the kernel: the memory system serves one atomic on a given
-  // address every ~11 ns when idle and several times slower under streaming load.)
-  const uint32_t n_workers = gridDim.x * kWaves, worker = blockIdx.x * kWaves + wave;
-  for (uint32_t item = worker; item < total; item += n_workers) dispatch_item(A, item, s_ptr);
+  // Every wave is its own worker and draws its items from kPools ticket counters: pool p holds the items
+  // p, p + kPools, ... of the queue.  Waves that get short items, or sit on a faster compute unit, simply
+  // draw more often; with a fixed deal (wave w takes items w, w + n_workers, ...) the slowest wave was
+  // measured to finish a quarter later than the median one.  One counter for all items is no option: an
+  // address serves an atomic every ~11 ns when idle and several times slower under streaming load, which
+  // was measured to bound the kernel; kPools counters with about a thousand draws each do not.
+  // A wave empties its home pool first, so every pool is emptied by its home waves whatever the others do;
+  // after that it tries a few more pools and leaves.  The next ticket is drawn before the current item is
+  // processed, so the atomic's latency is not waited for between items.
+  const uint32_t worker = blockIdx.x * kWaves + wave;
+  uint32_t pool = worker % kPools;
+  uint32_t ticket = 0;
+  if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
+  for (int empty = 0;;) {
+    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    while (item >= total && ++empty < 4) {  // this pool is empty: try another
+      pool = (pool + 17) % kPools;
+      if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
+      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    }
+    if (item >= total) break;  // every wave leaves here after at most four empty pools
+    if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
+    dispatch_item(A, item, s_ptr);
+  }
 }
 
 }  // namespace
