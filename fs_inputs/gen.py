@@ -102,6 +102,17 @@ def normal_q(seed: int, model: int, layer: int, seq_ids, n_q_heads: int, head_di
     return out
 
 
+def normal_q_chunks(seed: int, model: int, layer: int, seq_ids, first_pos, n_new, n_q_heads: int,
+                    head_dim: int) -> np.ndarray:
+    """float16 [sum(n_new)][n_q_heads][head_dim] query rows of prefill chunks: for sequence seq_ids[i] the rows of
+    positions first_pos[i] .. first_pos[i] + n_new[i] - 1, chunks one after the other."""
+    parts = [normal_rows(seed, model, layer, WHICH_Q, int(s), np.arange(int(p), int(p) + int(n)), n_q_heads,
+                         head_dim).astype(np.float16) for s, p, n in zip(seq_ids, first_pos, n_new)]
+    if not parts:
+        return np.empty((0, n_q_heads, head_dim), np.float16)
+    return np.concatenate(parts, axis=0)
+
+
 def _draw64(seed: int, tag: int, n: int) -> np.ndarray:
     key = stream_key(seed, 0xFFFF, 0, 3, tag)
     with np.errstate(over="ignore"):

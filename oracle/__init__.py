@@ -102,6 +102,8 @@ def load():
     L.fso_kv_append.argtypes = [vp, gp, i32, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp]
     L.fso_dequant_sequence.restype = i32
     L.fso_dequant_sequence.argtypes = [vp, gp, i32, vp, i32, vp, vp, vp, vp]
+    L.fso_prefill_attention.restype = i32
+    L.fso_prefill_attention.argtypes = [vp, gp, i32, i32, dbl, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, i32]
     L.fso_decode_attention.restype = i32
     L.fso_decode_attention.argtypes = [vp, gp, i32, i32, dbl, vp, vp, vp, i32, i32, vp, vp, vp, vp, i32]
     _LIB = L
@@ -289,4 +291,28 @@ def decode_attention(pool_mem, g, layer, n_q_heads, sm_scale, q, block_tables, s
                                      block_tables.shape[1], _ptr(ks), _ptr(vs), _ptr(out), _ptr(lse), n_threads)
     if rc != OK:
         raise ValueError(f"fso_decode_attention failed: {rc}")
+    return out, lse
+
+
+def prefill_attention(pool_mem, g, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, q_offsets, k_scale=None,
+                      v_scale=None, n_threads=1, want_lse=True):
+    """Chunked-prefill attention (Sec. 2.1): q [n_rows][n_q][D] fp16, the chunks of the sequences one after the
+    other (q_offsets [n_seq + 1]); row r of sequence b stands at position seq_lens[b] - n_b + r.
+    Returns (out float64 [n_rows][n_q][D], lse float64 [n_rows][n_q] or None)."""
+    q = np.ascontiguousarray(q)
+    assert q.dtype == np.float16 and q.ndim == 3
+    block_tables = _c(block_tables, np.int32)
+    seq_lens = _c(seq_lens, np.int32)
+    q_offsets = _c(q_offsets, np.int32)
+    n_seq = len(seq_lens)
+    assert len(q_offsets) == n_seq + 1 and int(q_offsets[-1]) == q.shape[0]
+    out = np.empty((q.shape[0], n_q_heads, g.head_dim), np.float64)
+    lse = np.empty((q.shape[0], n_q_heads), np.float64) if want_lse else None
+    ks = None if k_scale is None else _c(k_scale, np.float32)
+    vs = None if v_scale is None else _c(v_scale, np.float32)
+    rc = load().fso_prefill_attention(_ptr(pool_mem), ctypes.byref(g), layer, n_q_heads, float(sm_scale),
+                                      _ptr(q.view(np.uint16)), _ptr(block_tables), _ptr(seq_lens), _ptr(q_offsets),
+                                      n_seq, block_tables.shape[1], _ptr(ks), _ptr(vs), _ptr(out), _ptr(lse), n_threads)
+    if rc != OK:
+        raise ValueError(f"fso_prefill_attention failed: {rc}")
     return out, lse

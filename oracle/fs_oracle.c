@@ -16,7 +16,10 @@
  *     with FREE / PARTIAL / FULL states; allocate from a matching slab or carve a
  *     new one; an emptied slab returns to the shared tensor.
  *   - Sec. 2.1 / 2.3: decode attention reads every cached token of a sequence
- *     through its block table as if the KV were contiguous.
+ *     through its block table as if the KV were contiguous; the prefill phase
+ *     processes the prompt's tokens, each attending to the tokens up to itself
+ *     (Sec. 4.2's chunked prefill: a chunk of the prompt at a time, against the
+ *     cache that the earlier chunks and the chunk itself have filled).
  * The paper fixes no byte layout, no quantizer arithmetic and no allocator
  * tie-breaks; the readings used here are listed where each function is defined.
  *
@@ -24,7 +27,10 @@
  * (Fig. "kv_slab_detail"), closed-form geometry, allocator invariants on random
  * traces, exhaustive E4M3 / fp16 tables against independent definitions, the
  * quantizer error bounds and idempotence, dense fp64 softmax(qK^T)V from numpy,
- * placement invariance and the degenerate attention cases.  The allocator
+ * placement invariance and the degenerate attention cases; prefill attention
+ * against decode attention of the truncated sequence, a dense masked numpy
+ * softmax, causality under perturbation of later tokens and chunk invariance.
+ * The allocator
  * tie-break policy itself (which free slab is taken first) is fixed by this
  * repository's own reading, not by the paper: "parity unpinned" beyond the
  * invariants.
@@ -631,6 +637,110 @@ int fso_decode_attention(const uint8_t* pool_mem, const fso_geom* g, int layer, 
   }
   for (int i = 1; i < n_threads; ++i) pthread_create(&th[i], NULL, attn_worker, &jobs[i]);
   if (n_threads > 0) attn_worker(&jobs[0]);
+  for (int i = 1; i < n_threads; ++i) pthread_join(th[i], NULL);
+  return FSO_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Prefill (chunked prefill) attention over the pool: Sec. 2.1.  Sequence b has seq_lens[b] tokens
+ * in the pool, the last n_b = q_offsets[b+1] - q_offsets[b] of which are the chunk being prefilled;
+ * query row r of the chunk stands at position p = seq_lens[b] - n_b + r and attends to the cached
+ * tokens 0..p (itself included), dequantized exactly as decode attention sees them.
+ * q: [n_rows][n_q_heads][D] fp16 bits, sequences' chunks one after the other; out: same shape,
+ * doubles; lse (may be NULL): [n_rows][n_q_heads].  Rows are dealt round-robin to the threads.
+ * --------------------------------------------------------------------------------------------- */
+typedef struct {
+  const uint8_t* pool_mem;
+  const fso_geom* g;
+  int layer, n_q_heads;
+  double sm_scale;
+  const uint16_t* q;
+  const int32_t* block_tables;
+  const int32_t* seq_lens;
+  const int32_t* q_offsets;
+  int n_seq, max_blocks;
+  const float *k_scale, *v_scale;
+  double *out, *lse;
+  int first, stride;
+} prefill_job;
+
+static void prefill_row(const prefill_job* J, int b, int row) {
+  const fso_geom* g = J->g;
+  const int H = g->n_kv_heads, D = g->head_dim, T = g->tokens_per_block, nq = J->n_q_heads;
+  const int group = nq / H;
+  const int n_new = J->q_offsets[b + 1] - J->q_offsets[b];
+  const int pos = J->seq_lens[b] - n_new + (row - J->q_offsets[b]);
+  const int n = pos + 1; /* tokens this row attends to */
+  const int32_t* table = J->block_tables + (int64_t)b * J->max_blocks;
+  double* kv = (double*)malloc((size_t)D * sizeof(double));
+  double* s = (double*)malloc((size_t)n * sizeof(double));
+  double* acc = (double*)malloc((size_t)D * sizeof(double));
+  for (int h = 0; h < nq; ++h) {
+    const int kvh = h / group;
+    const uint16_t* qh = J->q + ((int64_t)row * nq + h) * D;
+    double ks = g->dtype == FSO_FP8 ? (double)J->k_scale[J->layer * H + kvh] : 1.0;
+    double vs = g->dtype == FSO_FP8 ? (double)J->v_scale[J->layer * H + kvh] : 1.0;
+    double m = -INFINITY;
+    for (int t = 0; t < n; ++t) {
+      load_row(J->pool_mem, g, table[t / T], J->layer, kvh, 0, t % T, ks, kv);
+      double dot = 0.0;
+      for (int d = 0; d < D; ++d) dot += (double)fso_f16_to_f32(qh[d]) * kv[d];
+      s[t] = J->sm_scale * dot;
+      if (s[t] > m) m = s[t];
+    }
+    double l = 0.0;
+    for (int d = 0; d < D; ++d) acc[d] = 0.0;
+    for (int t = 0; t < n; ++t) {
+      double p = exp(s[t] - m);
+      l += p;
+      load_row(J->pool_mem, g, table[t / T], J->layer, kvh, 1, t % T, vs, kv);
+      for (int d = 0; d < D; ++d) acc[d] += p * kv[d];
+    }
+    double* o = J->out + ((int64_t)row * nq + h) * D;
+    for (int d = 0; d < D; ++d) o[d] = acc[d] / l;
+    if (J->lse) J->lse[(int64_t)row * nq + h] = m + log(l);
+  }
+  free(kv);
+  free(s);
+  free(acc);
+}
+
+static void* prefill_worker(void* arg) {
+  const prefill_job* J = (const prefill_job*)arg;
+  const int n_rows = J->q_offsets[J->n_seq];
+  int b = 0;
+  for (int row = 0; row < n_rows; ++row) {
+    while (row >= J->q_offsets[b + 1]) ++b;
+    if (row % J->stride == J->first) prefill_row(J, b, row);
+  }
+  return NULL;
+}
+
+int fso_prefill_attention(const uint8_t* pool_mem, const fso_geom* g, int layer, int n_q_heads, double sm_scale,
+                          const uint16_t* q, const int32_t* block_tables, const int32_t* seq_lens,
+                          const int32_t* q_offsets, int n_seq, int max_blocks, const float* k_scale,
+                          const float* v_scale, double* out, double* lse, int n_threads) {
+  if (layer < 0 || layer >= g->n_layers || n_q_heads < g->n_kv_heads || n_q_heads % g->n_kv_heads)
+    return FSO_ERR_INVALID;
+  if (g->dtype == FSO_FP8 && (!k_scale || !v_scale)) return FSO_ERR_INVALID;
+  if (n_seq < 1 || q_offsets[0] != 0) return FSO_ERR_INVALID;
+  for (int b = 0; b < n_seq; ++b) {
+    const int n_new = q_offsets[b + 1] - q_offsets[b];
+    if (n_new < 0 || seq_lens[b] < 1 || n_new > seq_lens[b] ||
+        (seq_lens[b] + g->tokens_per_block - 1) / g->tokens_per_block > max_blocks)
+      return FSO_ERR_INVALID;
+  }
+  if (n_threads < 1) n_threads = 1;
+  if (n_threads > 256) n_threads = 256;
+  prefill_job jobs[256];
+  pthread_t th[256];
+  for (int i = 0; i < n_threads; ++i) {
+    prefill_job J = {pool_mem, g, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, q_offsets, n_seq,
+                     max_blocks, k_scale, v_scale, out, lse, i, n_threads};
+    jobs[i] = J;
+  }
+  for (int i = 1; i < n_threads; ++i) pthread_create(&th[i], NULL, prefill_worker, &jobs[i]);
+  prefill_worker(&jobs[0]);
   for (int i = 1; i < n_threads; ++i) pthread_join(th[i], NULL);
   return FSO_OK;
 }
