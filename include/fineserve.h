@@ -169,6 +169,28 @@ int fs_decode_attention_multi(fs_pool* pool, const fs_batch_t* batches, int n_ba
  * affected sequences left unwritten).  Synchronizes the stream. */
 int fs_decode_status(const void* workspace, void* stream);
 
+/* ---- Prefill (chunked prefill) attention: FineServe Sec. 2.1 (the prefill phase processes the prompt's tokens),
+ * Sec. 4.2 (it is scheduled in chunks), over the same slab pool (Sec. 5.1).
+ * Sequence b holds seq_lens[b] tokens in the pool (device int32), the last n_b = q_offsets[b+1] - q_offsets[b]
+ * of which are the chunk being prefilled -- append their keys and values with fs_kv_append first.  Query row r
+ * of the chunk stands at position seq_lens[b] - n_b + r and attends to the cached tokens 0 .. that position,
+ * dequantized exactly as fs_decode_attention sees them.
+ *   q, out:  device fp16 [n_rows][n_q_heads][head_dim], 16-byte aligned, the sequences' chunks one after the
+ *            other (n_rows = q_offsets[n_seq]); lse: device fp32 [n_rows][n_q_heads] or NULL
+ *   q_offsets: device int32 [n_seq + 1], starting at 0, non-decreasing; q_offsets_host: the same values in
+ *            host memory (sizes the launch; the kernels read the device copy, and clamp every row index into
+ *            n_rows, so a mismatch cannot make them leave the buffers)
+ *   workspace: device memory of fs_prefill_workspace_bytes(n_seq) bytes, 256-byte aligned, owned by the caller,
+ *            in use until the stream has passed the call.  fs_decode_status(workspace, stream) afterwards: bit 0
+ *            set if a length or a chunk size was out of range (clamped).
+ * Covers head_dim 128, at least 8 tokens per block, at most 16 query heads per KV head (FS_ERR_INVALID
+ * otherwise).  Asynchronous on `stream`; no allocation, no host synchronisation. */
+uint64_t fs_prefill_workspace_bytes(int n_seq);
+int fs_prefill_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,
+                         const int32_t* block_tables, const int32_t* seq_lens, const int32_t* q_offsets,
+                         const int32_t* q_offsets_host, int n_seq, int max_blocks, void* out, float* lse,
+                         void* workspace, uint64_t workspace_bytes, void* stream);
+
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
 int fs_set_kernel_mode(int mode);

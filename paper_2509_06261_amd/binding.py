@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(_DIR, "libfineserve.so")
 EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
-           "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_set_kernel_mode",
+           "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
+           "fs_prefill_attention", "fs_set_kernel_mode",
            "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
 
 
@@ -75,6 +76,8 @@ def _load():
         "fs_decode_attention": (i32, [vp, i32, i32, i32, f32, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
         "fs_decode_attention_multi": (i32, [vp, ctypes.POINTER(fs_batch_t), i32, vp, u64, vp]),
         "fs_decode_status": (i32, [vp, vp]),
+        "fs_prefill_workspace_bytes": (u64, [i32]),
+        "fs_prefill_attention": (i32, [vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
         "fs_set_kernel_mode": (i32, [i32]),
         "fs_set_split_bytes": (i32, [u64]),
         "fs_set_kernel_timing": (i32, [i32]),
@@ -268,6 +271,25 @@ def fs_decode_attention_multi(pool, batches, workspace, stream=None):
 
 def fs_decode_status(workspace, stream=None) -> int:
     return _L.fs_decode_status(_dp(workspace), _stream(stream))
+
+
+def fs_prefill_workspace_bytes(n_seq: int) -> int:
+    return _L.fs_prefill_workspace_bytes(n_seq)
+
+
+def fs_prefill_attention(pool, model, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, q_offsets, q_offsets_host,
+                         out, lse, workspace, stream=None):
+    """q, out: fp16 [n_rows][n_q][D] torch tensors; q_offsets: int32 device tensor [n_seq + 1]; q_offsets_host: the
+    same values as a numpy int32 array."""
+    assert isinstance(q_offsets_host, np.ndarray) and q_offsets_host.dtype == np.int32
+    assert q_offsets_host.shape[0] == seq_lens.numel() + 1 and q_offsets.numel() == seq_lens.numel() + 1
+    assert int(q_offsets_host[-1]) == q.shape[0] == out.shape[0] and q.is_contiguous() and out.is_contiguous()
+    rc = _L.fs_prefill_attention(pool, model, layer, n_q_heads, sm_scale, _dp(q), _dp(block_tables), _dp(seq_lens),
+                                 _dp(q_offsets), q_offsets_host.ctypes.data, seq_lens.numel(), block_tables.shape[1],
+                                 _dp(out), _dp(lse), _dp(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_prefill_attention")
 
 
 def fs_set_kernel_mode(mode: int) -> int:

@@ -1,0 +1,328 @@
+// MFMA paged prefill (chunked prefill) attention kernel for gfx950 (head_dim 128, all four KV formats).
+//
+// FineServe Sec. 2.1: the prefill phase processes the prompt's tokens, each attending to the tokens up to
+// itself; Sec. 2.3: it is the compute-intensive phase; Sec. 4.2 schedules it in chunks.  Here a chunk's
+// keys and values are first appended to the slab pool (fs_kv_append), then every query row of the chunk
+// attends to the cached tokens 0..its own position, read from the pool exactly as decode attention reads
+// them (same dequantization), through the sequence's block table (Sec. 5.1).
+//
+// Work decomposition: a work item is (sequence, KV head, tile of 16 / G query tokens); the 16 logit columns
+// of the MFMAs (see fs_mfma_tiles.h) are the tile's (query token, query head of the group) pairs.  One wave
+// streams the cached tokens 0 .. last position of the tile once for all 16 columns; causality is a
+// per-column sequence length, so only the tiles on the diagonal pay for masking.  Items of one (sequence,
+// head) are neighbours in the queue, longest first, so that the waves streaming the same keys and values run
+// side by side and share them through the L2.  Waves draw items from the same pooled ticket counters as the
+// decode kernel.  A long context is streamed in segments, the wave's block-address table being refilled per
+// segment.
+#include "fs_mfma_tiles.h"
+
+namespace fs {
+namespace {
+
+struct PrefillArgs {
+  DevBatch b;                // geometry and the batch's pointers (q, tables, seq_lens, out, lse, FP8 scales)
+  const int32_t* q_offsets;  // [n_seq + 1] first query row of each sequence's chunk
+  uint32_t* header;          // workspace header: status word and the pools' ticket counters (layout of fs_attention.h)
+  uint32_t* tile_first;      // [n_seq + 1] first query tile of each sequence
+  int32_t tpt;               // query tokens per tile: 16 / G
+  int32_t seg_runs;          // runs of 8 token slots streamed per refill of the block-address table (multiple of 4)
+  int32_t table_entries;     // LDS table entries per wave
+  int32_t n_rows;            // query rows in q / out (host value: every row index is clamped into it)
+};
+
+constexpr int kPrepThreads = 1024;
+
+// Query tiles per sequence -> tile_first (exclusive scan), validation flags, counter reset.  One workgroup.
+__global__ __launch_bounds__(kPrepThreads) void prefill_prep_kernel(PrefillArgs P) {
+  __shared__ uint32_t s_wave[kPrepThreads / 64];
+  __shared__ uint32_t s_running;
+  const DevBatch& B = P.b;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) {
+    s_running = 0;
+    P.header[kHdrStatus] = 0;
+  }
+  if (tid < kPools) P.header[kHdrPools + tid * kPoolStride] = 0;
+  __syncthreads();
+  const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
+  for (int base = 0; base < B.n_seq; base += kPrepThreads) {
+    const int i = base + tid;
+    uint32_t v = 0;
+    if (i < B.n_seq) {
+      int len = B.seq_lens[i];
+      int n_new = P.q_offsets[i + 1] - P.q_offsets[i];
+      if (len < 1 || len > max_len || n_new < 0 || n_new > len) {
+        atomicOr(P.header + kHdrStatus, 1u);
+        len = len < 1 ? 1 : min(len, max_len);
+        n_new = n_new < 0 ? 0 : min(n_new, len);
+      }
+      v = (uint32_t)((n_new + P.tpt - 1) / P.tpt);
+    }
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t t = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += t;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = s_running;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    if (i < B.n_seq) P.tile_first[i] = before + incl - v;
+    __syncthreads();
+    if (tid == kPrepThreads - 1) s_running = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) P.tile_first[B.n_seq] = s_running;
+}
+
+template <int DT>
+__device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, uint64_t* s_ptr) {
+  constexpr int GP = 16;  // every logit column is live: one column per lane in the softmax
+  const DevBatch& B = P.b;
+  const DevGeom& g = B.g;
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));  // see the decode kernel: keeps lane constants out of the item loop
+  const int j = lane >> 4, c = lane & 15;
+  const int G = B.G;
+  const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
+  int len = B.seq_lens[seq];
+  len = len < 1 ? 1 : min(len, max_len);
+  int n_new = P.q_offsets[seq + 1] - P.q_offsets[seq];
+  n_new = n_new < 0 ? 0 : min(n_new, len);
+  const int r0 = qt * P.tpt;              // first query token of the tile within the chunk
+  if (r0 >= n_new) return;                // (cannot happen with consistent inputs)
+  const int first_pos = len - n_new + r0;  // its position in the sequence
+  const int n_tok = min(P.tpt, n_new - r0);
+  // column c = (query token c / G of the tile, query head c % G of the group)
+  const int tok_c = c / G, hg_c = c - tok_c * G;
+  const bool live = tok_c < n_tok;
+  const int row_c = min(max(P.q_offsets[seq] + r0 + tok_c, 0), P.n_rows - 1);
+
+  ItemCtx X;
+  X.T = g.T;
+  X.R = B.R;
+  X.r_magic = B.r_magic;
+  X.len_u = first_pos + n_tok;                  // the tile's last query sees this many tokens
+  X.len = live ? first_pos + tok_c + 1 : 1;     // causality: a column sees the tokens up to its own position
+  X.chunk_ptr = s_ptr;
+
+  u32x4 qb[4];
+  float qsum;
+  load_q<DT>(B.q + ((int64_t)row_c * B.n_q + head * G + hg_c) * kD, live, j, qb, qsum);
+  if constexpr (Fmt<DT>::kParBytes != 0) {
+    qsum += __shfl_xor(qsum, 16, 64);
+    qsum += __shfl_xor(qsum, 32, 64);
+  }
+  float alpha = B.sm_scale * kLog2e;
+  if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
+
+  State st;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
+  st.m = -INFINITY;
+  st.l = 0.f;
+  st.zc = 0.f;
+
+  const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
+  const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
+  const int n_run = n_runs(X.len_u, g.T, B.R);
+  for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
+    X.v_end = min(n_run, v0 + P.seg_runs);
+    X.k0 = div_runs(v0, B.R, B.r_magic);
+    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane);
+    stream_tiles<DT, GP>(X, g, v0, qb, qsum, alpha, st, j, c);
+  }
+
+  // ---- output: per-column sums over the four lane groups, then the live rows straight from the accumulators ----
+  st.l += __shfl_xor(st.l, 16, 64);
+  st.l += __shfl_xor(st.l, 32, 64);
+  if constexpr (Fmt<DT>::kParBytes != 0) {
+    st.zc += __shfl_xor(st.zc, 16, 64);
+    st.zc += __shfl_xor(st.zc, 32, 64);
+  }
+  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int h = 4 * j + r;  // accumulator row r of this lane is logit column h; its m, l, zc live in lane c = h
+    const float L = __shfl(st.l, h, 64), M = __shfl(st.m, h, 64), Z = __shfl(st.zc, h, 64);
+    const int row_h = __shfl(row_c, h, 64);
+    const int tok_h = h / G, hg_h = h - tok_h * G;
+    if (tok_h < n_tok) {
+      const float inv = 1.0f / L;
+      u32x4 w;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float o[2];
+#pragma unroll
+        for (int z = 0; z < 2; ++z) {
+          const int e = 2 * q + z;
+          // integer formats: undo the 2^-24 of the subnormal encoding (and the 16 of INT4's odd code positions)
+          const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+          o[z] = st.acc[e][r] * f;
+          if constexpr (Fmt<DT>::kParBytes != 0) o[z] += Z;
+          o[z] *= v_static * inv;
+        }
+        const half2v hv = {(_Float16)o[0], (_Float16)o[1]};
+        w[q] = h2u(hv);
+      }
+      const int64_t qrow = (int64_t)row_h * B.n_q + head * G + hg_h;
+      *reinterpret_cast<u32x4*>(B.out + qrow * kD + 8 * c) = w;
+      if (c == 0 && B.lse) B.lse[qrow] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
+  extern __shared__ uint64_t smem64[];
+  const DevBatch& B = P.b;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
+  const uint32_t H = (uint32_t)B.g.H;
+  const uint32_t total = P.tile_first[B.n_seq] * H;
+  // items are drawn from kPools ticket counters (pool p = items p, p + kPools, ...): a wave empties its home
+  // pool, tries three more and leaves; the next ticket is drawn before the current item is processed
+  const uint32_t worker = blockIdx.x * kWaves + wave;
+  uint32_t pool = worker % kPools;
+  uint32_t ticket = 0;
+  if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+  for (int empty = 0;;) {
+    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    while (item >= total && ++empty < 4) {
+      pool = (pool + 17) % kPools;
+      if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    }
+    if (item >= total) break;  // every wave leaves here after at most four empty pools
+    if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+    // item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
+    int lo = 0, hi = B.n_seq - 1;
+    while (lo < hi) {  // last sequence whose first item is <= item
+      const int mid = (lo + hi + 1) >> 1;
+      if (P.tile_first[mid] * H <= item) lo = mid;
+      else hi = mid - 1;
+    }
+    const uint32_t nt = P.tile_first[lo + 1] - P.tile_first[lo];
+    if (nt == 0) continue;  // (cannot happen: an item lies in a sequence that has tiles)
+    const uint32_t li = item - P.tile_first[lo] * H;
+    const int head = (int)(li / nt), qt = (int)(nt - 1 - li % nt);
+    switch (B.g.dtype) {
+      case FS_KV_FP16: prefill_item<FS_KV_FP16>(P, lo, head, qt, s_ptr); break;
+      case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3>(P, lo, head, qt, s_ptr); break;
+      case FS_KV_INT8: prefill_item<FS_KV_INT8>(P, lo, head, qt, s_ptr); break;
+      default: prefill_item<FS_KV_INT4>(P, lo, head, qt, s_ptr); break;
+    }
+  }
+}
+
+uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
+
+}  // namespace
+}  // namespace fs
+
+using namespace fs;
+
+uint64_t fs_prefill_workspace_bytes(int n_seq) {
+  if (n_seq < 1) return 0;
+  return align256(kHeaderBytes + 4ull * ((uint64_t)n_seq + 1));
+}
+
+int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,
+                         const int32_t* block_tables, const int32_t* seq_lens, const int32_t* q_offsets,
+                         const int32_t* q_offsets_host, int n_seq, int max_blocks, void* out, float* lse, void* workspace,
+                         uint64_t workspace_bytes, void* stream) {
+  if (!p || model < 0 || model >= kMaxModels || !p->models[model].in_use) {
+    set_error("prefill attention: unknown pool or model");
+    return FS_ERR_INVALID;
+  }
+  const Model& M = p->models[model];
+  const fs_geometry_t& g = M.g;
+  if (layer < 0 || layer >= g.n_layers || n_seq < 1 || max_blocks < 1 || !q || !block_tables || !seq_lens || !q_offsets ||
+      !q_offsets_host || !out || n_q_heads < g.n_kv_heads || n_q_heads % g.n_kv_heads || !(sm_scale == sm_scale)) {
+    set_error("prefill attention: invalid argument");
+    return FS_ERR_INVALID;
+  }
+  if (((uintptr_t)q | (uintptr_t)out) & 15) {
+    set_error("prefill attention: q and out must be 16-byte aligned");
+    return FS_ERR_INVALID;
+  }
+  if (q_offsets_host[0] != 0) {
+    set_error("prefill attention: q_offsets must start at 0");
+    return FS_ERR_INVALID;
+  }
+  const int G = n_q_heads / g.n_kv_heads;
+  if (G > 16) {
+    set_error("prefill attention: more than 16 query heads per KV head");
+    return FS_ERR_INVALID;
+  }
+  const int tpt = 16 / G;
+  uint64_t tiles = 0;
+  for (int b = 0; b < n_seq; ++b) {
+    const int64_t n_new = (int64_t)q_offsets_host[b + 1] - q_offsets_host[b];
+    if (n_new < 0) {
+      set_error("prefill attention: q_offsets must not decrease");
+      return FS_ERR_INVALID;
+    }
+    tiles += (uint64_t)((n_new + tpt - 1) / tpt);
+  }
+  const int64_t n_rows = q_offsets_host[n_seq];
+  if (tiles * (uint64_t)g.n_kv_heads > 0xfffffff0ull || n_rows > 0x7fffffff) {
+    set_error("prefill attention: batch too large");
+    return FS_ERR_INVALID;
+  }
+  if (g.kv_dtype == FS_KV_FP8_E4M3 && !M.d_k_scale) {
+    set_error("prefill attention: FP8 model has no scales (fs_model_set_fp8_scales)");
+    return FS_ERR_INVALID;
+  }
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < fs_prefill_workspace_bytes(n_seq)) {
+    set_error("prefill attention: workspace missing, not 256-byte aligned or too small (see fs_prefill_workspace_bytes)");
+    return workspace && !((uintptr_t)workspace & 255) ? FS_ERR_NOMEM : FS_ERR_INVALID;
+  }
+  if (p->n_cu == 0) {
+    set_error("prefill attention: pool has no HIP device");
+    return FS_ERR_DEVICE;
+  }
+  PrefillArgs P{};
+  DevBatch& B = P.b;
+  B.g = dev_geom(g);
+  B.layer_base = p->base + (uint64_t)layer * g.layer_bytes;
+  B.q = (const _Float16*)q;
+  B.tables = block_tables;
+  B.seq_lens = seq_lens;
+  B.out = (_Float16*)out;
+  B.lse = lse;
+  B.k_scale = M.d_k_scale ? M.d_k_scale + (size_t)layer * g.n_kv_heads : nullptr;
+  B.v_scale = M.d_v_scale ? M.d_v_scale + (size_t)layer * g.n_kv_heads : nullptr;
+  B.n_seq = n_seq;
+  B.max_blocks = max_blocks;
+  B.n_q = n_q_heads;
+  B.G = G;
+  B.sm_scale = sm_scale;
+  B.R = (g.tokens_per_block + 7) / 8;
+  B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);
+  if (!mfma_supports(B)) {
+    set_error("prefill attention: needs head_dim 128 and at least 8 tokens per block");
+    return FS_ERR_INVALID;
+  }
+  P.q_offsets = q_offsets;
+  P.header = (uint32_t*)workspace;
+  P.tile_first = (uint32_t*)((uint8_t*)workspace + kHeaderBytes);
+  P.tpt = tpt;
+  P.seg_runs = (int32_t)std::min<int64_t>(1024, std::max<int64_t>(4, (int64_t)500 * B.R / 4 * 4));
+  P.table_entries = P.seg_runs / B.R + 4;
+  P.n_rows = (int32_t)n_rows;
+  if (n_rows == 0) return FS_OK;
+  hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(prefill_prep_kernel, dim3(1), dim3(kPrepThreads), 0, s, P);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return device_error(e, "prefill prep launch");
+  const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * 2, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
+  const size_t smem = (size_t)kWaves * P.table_entries * sizeof(uint64_t);
+  hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
+  e = hipGetLastError();
+  if (e != hipSuccess) return device_error(e, "prefill launch");
+  return FS_OK;
+}

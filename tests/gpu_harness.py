@@ -101,7 +101,54 @@ class Parity:
         q = gen.normal_q(self.wl.seed, s.tag, layer, seqs, s.n_q_heads, s.head_dim)
         out, lse = oracle.decode_attention(mem0, g, layer, s.n_q_heads, 1.0 / np.sqrt(s.head_dim), q, ctab, lens, ks,
                                            vs, n_threads=8)
-        return dict(real_blocks=real_blocks, mem=mem0, written=written, out=out, lse=lse, q=q)
+        return dict(real_blocks=real_blocks, mem=mem0, written=written, out=out, lse=lse, q=q, ctab=ctab, lens=lens, ks=ks,
+                    vs=vs)
+
+    # ------------------------------------------------------------------ prefill
+    def prefill_and_check(self, k, layer, n_new, seqs=None):
+        """fs_prefill_attention for model k (KV of ``layer`` already appended): the last n_new[i] tokens of every
+        sequence are the chunk being prefilled.  All query rows of the sequences ``seqs`` (default: all) are compared
+        with the oracle.  Returns (max abs error, rows compared)."""
+        import torch
+
+        gw, s = self.gw, self.wl.models[k]
+        m = gw.model_ids[k]
+        lens = gw.lens[k]
+        n_new = np.asarray(n_new, np.int32)
+        assert len(n_new) == len(lens) and np.all(n_new <= lens) and np.all(n_new >= 0)
+        q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        q = gen.normal_q_chunks(self.wl.seed, s.tag, layer, np.arange(len(lens)), lens - n_new, n_new, s.n_q_heads,
+                                s.head_dim)
+        dev = gw.device
+        q_d = torch.from_numpy(q).to(dev)
+        out_d = torch.full_like(q_d, float("nan"))
+        lse_d = torch.full((q.shape[0], s.n_q_heads), float("nan"), dtype=torch.float32, device=dev)
+        q_off_d = torch.from_numpy(q_off).to(dev)
+        ws = torch.empty(self.fs.fs_prefill_workspace_bytes(len(lens)), dtype=torch.uint8, device=dev)
+        self.fs.fs_prefill_attention(gw.pool, m, layer, s.n_q_heads, float(1.0 / np.sqrt(s.head_dim)), q_d, gw.tables[k],
+                                     gw.seq_lens[k], q_off_d, q_off, out_d, lse_d, ws)
+        torch.cuda.synchronize()
+        assert self.fs.fs_decode_status(ws) == 0
+        out, lse = out_d.cpu().numpy(), lse_d.cpu().numpy()
+        assert np.all(np.isfinite(out.astype(np.float32))) and np.all(np.isfinite(lse)), "a query row was left unwritten"
+        seqs = np.arange(len(lens)) if seqs is None else np.asarray(seqs)
+        ref = self.oracle_sequences(k, layer, seqs)
+        rows = np.concatenate([np.arange(q_off[i], q_off[i + 1]) for i in seqs]) if len(seqs) else np.zeros(0, np.int64)
+        sub_off = np.concatenate([[0], np.cumsum(n_new[seqs])]).astype(np.int32)
+        o_out, o_lse = oracle.prefill_attention(ref["mem"], self.ogeom[k], layer, s.n_q_heads, 1.0 / np.sqrt(s.head_dim),
+                                                q[rows], ref["ctab"], ref["lens"], sub_off, ref["ks"], ref["vs"],
+                                                n_threads=8)
+        tol = TOL_FP16 if s.kv_dtype == workloads.FP16 else TOL_QUANT
+        # Rows early in a prompt average few values: outputs reach |4| where rounding the result to fp16 alone costs
+        # up to |ref| * 2^-11 (decode outputs, averages over hundreds of tokens, stay below 1).  That share is
+        # allowed on top of the decode tolerance, element by element.
+        diff = np.abs(out[rows].astype(np.float64) - o_out) if len(rows) else np.zeros(1)
+        allowed = tol + np.abs(o_out) * 2.0 ** -11 if len(rows) else np.ones(1)
+        err = float(np.max(diff))
+        lerr = float(np.max(np.abs(lse[rows].astype(np.float64) - o_lse))) if len(rows) else 0.0
+        assert np.all(diff <= allowed), f"prefill model {k} ({s.name}): max abs error {err:.3e}, tolerance {tol} + |ref| 2^-11"
+        assert lerr <= TOL_LSE, f"prefill model {k} ({s.name}): lse error {lerr:.3e}"
+        return err, len(rows)
 
     # ------------------------------------------------------------------ comparisons
     def check_bytes(self, k, ref):
