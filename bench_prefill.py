@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload: 2..5 (BASELINE.json configs, 1-based)")
     ap.add_argument("--chunk", type=int, default=0, help="tokens prefilled per sequence (0 = the whole prompt)")
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
+    ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -53,6 +54,8 @@ def main():
     from paper_2509_06261_amd import harness
 
     wl = workloads.config(args.config)
+    if args.only_model >= 0:
+        wl.models = [wl.models[args.only_model]]
     gw = harness.GpuWorkload(wl)
     gw.place()
     n_layers_of = [min(args.layers, s.n_layers) for s in wl.models]
@@ -146,7 +149,7 @@ def main():
         },
         "roofline": {
             "bound": "mfma",
-            "kernel": "paged prefill attention (16 logit columns per K/V pass)",
+            "kernel": "paged prefill attention (64 / 64 / 32 / 16 logit columns per K/V pass for FP16 / FP8 / INT8 / INT4 KV)",
             "achieved": round(flops / (attn_ms_per_step * 1e-3) / 1e12, 1),
             "peak": MFMA_F16_PEAK_TFLOPS,
             "unit": "TFLOP/s",

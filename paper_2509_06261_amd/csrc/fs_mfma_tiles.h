@@ -136,6 +136,7 @@ struct ItemCtx {
 struct RunLoc {
   gptr base;
   int start, lo, hi, hi_u;
+  int tok0;  // token index of the run's slot 0 (a huge value for a run past the item's end: no column reaches it)
 };
 
 // run / R  (r_magic = ceil(2^32 / R) does not fit 32 bits for R = 1)
@@ -150,8 +151,9 @@ __device__ __forceinline__ RunLoc locate(const ItemCtx& X, int vr) {
   RunLoc L;
   L.start = min(r8, X.T - 8);
   L.lo = r8 - L.start;
-  L.hi = vr < X.v_end ? min(8, X.len - k * X.T - L.start) : 0;
-  L.hi_u = vr < X.v_end ? min(8, X.len_u - k * X.T - L.start) : 0;
+  L.tok0 = vr < X.v_end ? k * X.T + L.start : 0x3fffffff;
+  L.hi = min(8, X.len - L.tok0);
+  L.hi_u = min(8, X.len_u - L.tok0);
   L.base = (gptr)X.chunk_ptr[k - X.k0];
   return L;
 }

@@ -6,14 +6,18 @@
 // attends to the cached tokens 0..its own position, read from the pool exactly as decode attention reads
 // them (same dequantization), through the sequence's block table (Sec. 5.1).
 //
-// Work decomposition: a work item is (sequence, KV head, tile of 16 / G query tokens); the 16 logit columns
-// of the MFMAs (see fs_mfma_tiles.h) are the tile's (query token, query head of the group) pairs.  One wave
-// streams the cached tokens 0 .. last position of the tile once for all 16 columns; causality is a
-// per-column sequence length, so only the tiles on the diagonal pay for masking.  Items of one (sequence,
-// head) are neighbours in the queue, longest first, so that the waves streaming the same keys and values run
-// side by side and share them through the L2.  Waves draw items from the same pooled ticket counters as the
-// decode kernel.  A long context is streamed in segments, the wave's block-address table being refilled per
-// segment.
+// Work decomposition: a work item is (sequence, KV head, tile of query tokens); the 16 logit columns of the
+// MFMAs (see fs_mfma_tiles.h) are (query token, query head of the group) pairs, 16 / G tokens per block of 16
+// columns.  One wave streams the cached tokens 0 .. last position of the tile once for all its columns;
+// causality is a per-column sequence length, so only the tiles on the diagonal pay for masking.  Two kernels:
+// prefill_kernel keeps one block of 16 columns per wave (two waves per SIMD), prefill_wide_kernel 2 or 4
+// blocks (one wave per SIMD, accumulators in AccVGPRs): a tile's K and V rows are then loaded, unpacked and
+// transposed once for 32 or 64 columns.  Items of one (sequence, head) are neighbours in the queue, longest
+// first, so that the waves streaming the same keys and values run side by side and share them through the
+// L2.  Waves draw items from the same pooled ticket counters as the decode kernel.  A long context is
+// streamed in segments, the wave's block-address table being refilled per segment.
+#include <cstdlib>
+
 #include "fs_mfma_tiles.h"
 
 namespace fs {
@@ -24,7 +28,8 @@ struct PrefillArgs {
   const int32_t* q_offsets;  // [n_seq + 1] first query row of each sequence's chunk
   uint32_t* header;          // workspace header: status word and the pools' ticket counters (layout of fs_attention.h)
   uint32_t* tile_first;      // [n_seq + 1] first query tile of each sequence
-  int32_t tpt;               // query tokens per tile: 16 / G
+  int32_t tpt;               // query tokens per block of 16 logit columns: 16 / G
+  int32_t ncb;               // column blocks per work item (1: prefill_kernel; 2, 4: prefill_wide_kernel)
   int32_t seg_runs;          // runs of 8 token slots streamed per refill of the block-address table (multiple of 4)
   int32_t table_entries;     // LDS table entries per wave
   int32_t n_rows;            // query rows in q / out (host value: every row index is clamped into it)
@@ -56,7 +61,7 @@ __global__ __launch_bounds__(kPrepThreads) void prefill_prep_kernel(PrefillArgs 
         len = len < 1 ? 1 : min(len, max_len);
         n_new = n_new < 0 ? 0 : min(n_new, len);
       }
-      v = (uint32_t)((n_new + P.tpt - 1) / P.tpt);
+      v = (uint32_t)((n_new + P.tpt * P.ncb - 1) / (P.tpt * P.ncb));
     }
     uint32_t incl = v;
 #pragma unroll
@@ -173,6 +178,312 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Wide variant: NCB blocks of 16 logit columns per wave.  A tile's K rows are unpacked once and multiplied
+// with NCB query operands, its V rows are unpacked and transposed once and multiplied with NCB weight
+// operands; per-token parameters are broadcast once.  Only the softmax itself is per block.  The accumulators
+// (NCB x 32 registers) take the place of a second resident wave: the kernel runs one wave per SIMD.
+// ---------------------------------------------------------------------------------------------------------
+template <int NCB>
+struct WideState {
+  float4v acc[NCB][8];
+  float m[NCB], l[NCB], zc[NCB];
+};
+
+template <int DT, int NCB>
+__device__ __forceinline__ void wide_tile(const ItemCtx& X, const DevGeom& g, Tile<DT, 16>& t, const u32x4 (&qb)[NCB][4],
+                                          const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int vb, int vb_next,
+                                          int j, int c, WideState<NCB>& st) {
+  using F = Fmt<DT>;
+  // ---- S^T = K Q^T for every column block ----
+  float4v s[NCB][2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    u32x4 a[4];
+    k_operands<DT>(t.k[u], a);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) acc = mfma(a[ks], qb[cb][ks], acc);
+      s[cb][u] = acc;
+    }
+  }
+  issue_k<DT, 16>(X, vb_next, j, c, t);
+
+  const RunLoc L = locate(X, vb + j);  // X.len == X.len_u here: L.hi == L.hi_u
+  if (!__all(L.lo == 0 && L.hi_u == 8)) {
+    if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
+      // slots past the sequence's end may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int w = 0; w < F::kVBytes / 4; ++w) t.v[i][w] = i < L.hi_u ? t.v[i][w] : 0u;
+    }
+  }
+  // per-token dequantization factors, prepared by the lane that loaded the token's parameters, broadcast once
+  float ka[8], kb[8], va[8], vb2[8];
+  if constexpr (F::kParBytes != 0) {
+    float pa, pb;
+    const float sc = f16lo(t.par[0]);
+    const float zp = DT == FS_KV_INT4 ? f16hi(t.par[0]) : 128.0f;
+    if (c < 8) {  // K: logit = alpha * sc * (2^24 * S_raw - zp * qsum)
+      pa = alpha * kTwo24 * sc;
+      pb = -alpha * sc * zp;
+    } else {      // V: p' = p * sc, zero-point term -p * sc * zp
+      const bool ok = (c & 7) >= L.lo && (c & 7) < L.hi_u;  // a slot past the sequence may hold any bit pattern
+      pa = ok ? sc : 0.f;
+      pb = ok ? -sc * zp : 0.f;
+    }
+    static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+      constexpr int i = decltype(I)::value;
+      ka[i] = row_bcast<i>(pa);
+      kb[i] = row_bcast<i>(pb);
+      va[i] = row_bcast<8 + i>(pa);
+      vb2[i] = row_bcast<8 + i>(pb);
+    });
+  }
+  // ---- online softmax per column block (one column per lane, lazily moved reference) ----
+  u32x4 pk[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
+    const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float v = s[cb][i >> 2][i & 3];
+      if constexpr (F::kParBytes != 0) x[i] = fmaf(v, ka[i], kb[i] * qsum[cb]);
+      else x[i] = v * alpha;
+    }
+    if (!__all(L.lo == 0 && hi == 8)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = (uint32_t)(i - L.lo) < n_ok ? x[i] : -INFINITY;
+    }
+    float tmax = x[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
+    if (__any(tmax - st.m[cb] > kTau)) {
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(st.m[cb], tmax);  // finite: token 0 is seen by every column
+      const float corr = __builtin_amdgcn_exp2f(st.m[cb] - m_new);
+      st.l[cb] *= corr;
+      if constexpr (F::kParBytes != 0) st.zc[cb] *= corr;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float cr = __shfl(corr, 4 * j + r, 64);  // column h keeps its factor in lane c = h
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.acc[cb][e][r] *= cr;
+      }
+      st.m[cb] = m_new;
+    }
+    const float m = st.m[cb];
+    float p[8];
+    float lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float e = __builtin_amdgcn_exp2f(x[i] - m);
+      lsum += e;
+      if constexpr (F::kParBytes != 0) {
+        p[i] = e * va[i];
+        st.zc[cb] = fmaf(e, vb2[i], st.zc[cb]);
+      } else {
+        p[i] = e;
+      }
+    }
+    st.l[cb] += lsum;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
+      pk[cb][q] = h2u(h);
+    }
+  }
+  // ---- V rows of the run -> B operands (8x8 in-register transpose), out += P V for every column block ----
+  uint32_t vx[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v_unpack<DT>(t.v[i], vx[i]);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int reg = DT == FS_KV_INT4 ? (e & 3) : (e >> 1);
+    const uint32_t sel = (DT == FS_KV_INT4 ? (e >> 2) : (e & 1)) ? 0x07060302u : 0x05040100u;
+    u32x4 b;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) st.acc[cb][e] = mfma(pk[cb], b, st.acc[cb][e]);
+  }
+  issue_v<DT, 16>(X, g, vb_next, j, c, t);
+}
+
+// One work item of the wide variant: (sequence, KV head, NCB consecutive 16-column query tiles).
+template <int DT, int NCB>
+__device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int qt, uint64_t* s_ptr) {
+  const DevBatch& B = P.b;
+  const DevGeom& g = B.g;
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  const int j = lane >> 4, c = lane & 15;
+  const int G = B.G;
+  const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
+  int len = B.seq_lens[seq];
+  len = len < 1 ? 1 : min(len, max_len);
+  int n_new = P.q_offsets[seq + 1] - P.q_offsets[seq];
+  n_new = n_new < 0 ? 0 : min(n_new, len);
+  const int r0 = qt * P.tpt * NCB;  // first query token of the item within the chunk
+  if (r0 >= n_new) return;
+  const int first_pos = len - n_new + r0;
+  const int n_tok = min(P.tpt * NCB, n_new - r0);
+  const int tok_c = c / G, hg_c = c - tok_c * G;  // within a column block
+
+  ItemCtx X;
+  X.T = g.T;
+  X.R = B.R;
+  X.r_magic = B.r_magic;
+  X.len_u = first_pos + n_tok;
+  X.len = X.len_u;
+  X.chunk_ptr = s_ptr;
+
+  u32x4 qb[NCB][4];
+  float qsum[NCB];
+  int len_cb[NCB], row_cb[NCB];
+  float alpha = B.sm_scale * kLog2e;
+  if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
+  WideState<NCB> st;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int tok = cb * P.tpt + tok_c;  // query token of this lane's column in block cb
+    const bool live = tok_c < P.tpt && tok < n_tok;
+    len_cb[cb] = live ? first_pos + tok + 1 : 1;
+    row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
+    load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
+      qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[cb][e] = float4v{0.f, 0.f, 0.f, 0.f};
+    st.m[cb] = -INFINITY;
+    st.l[cb] = 0.f;
+    st.zc[cb] = 0.f;
+  }
+
+  const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
+  const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
+  const int n_run = n_runs(X.len_u, g.T, B.R);
+  constexpr int NBUF = Fmt<DT>::kRing;
+  for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
+    X.v_end = min(n_run, v0 + P.seg_runs);
+    X.k0 = div_runs(v0, B.R, B.r_magic);
+    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane);
+    // the ring of stream_tiles (fs_mfma_tiles.h), with the wide tile step
+    const int n_tiles = (X.v_end - v0 + 3) >> 2;
+    Tile<DT, 16> t[NBUF];
+    static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
+      constexpr int bi = decltype(Bi)::value;
+      issue_k<DT, 16>(X, v0 + bi * 4, j, c, t[bi]);
+      issue_v<DT, 16>(X, g, v0 + bi * 4, j, c, t[bi]);
+    });
+    for (int k0 = 0; k0 < n_tiles; k0 += NBUF) {
+      static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
+        constexpr int bi = decltype(Bi)::value;
+        const int vb = v0 + (k0 + bi) * 4;
+        wide_tile<DT, NCB>(X, g, t[bi], qb, qsum, len_cb, alpha, vb, vb + NBUF * 4, j, c, st);
+      });
+    }
+  }
+
+  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float l = st.l[cb], zc = st.zc[cb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      zc += __shfl_xor(zc, 16, 64);
+      zc += __shfl_xor(zc, 32, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int h = 4 * j + r;  // accumulator row r of this lane is logit column h of block cb
+      const float L = __shfl(l, h, 64), M = __shfl(st.m[cb], h, 64), Z = __shfl(zc, h, 64);
+      const int row_h = __shfl(row_cb[cb], h, 64);
+      const int tok_h = h / G, hg_h = h - tok_h * G;
+      if (tok_h < P.tpt && cb * P.tpt + tok_h < n_tok) {
+        const float inv = 1.0f / L;
+        u32x4 w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float o[2];
+#pragma unroll
+          for (int z = 0; z < 2; ++z) {
+            const int e = 2 * q + z;
+            const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+            o[z] = st.acc[cb][e][r] * f;
+            if constexpr (Fmt<DT>::kParBytes != 0) o[z] += Z;
+            o[z] *= v_static * inv;
+          }
+          const half2v hv = {(_Float16)o[0], (_Float16)o[1]};
+          w[q] = h2u(hv);
+        }
+        const int64_t qrow = (int64_t)row_h * B.n_q + head * G + hg_h;
+        *reinterpret_cast<u32x4*>(B.out + qrow * kD + 8 * c) = w;
+        if (c == 0 && B.lse) B.lse[qrow] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+      }
+    }
+  }
+}
+
+// item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
+__device__ __forceinline__ bool decode_item(const PrefillArgs& P, uint32_t item, uint32_t H, int& seq, int& head, int& qt) {
+  int lo = 0, hi = P.b.n_seq - 1;
+  while (lo < hi) {  // last sequence whose first item is <= item
+    const int mid = (lo + hi + 1) >> 1;
+    if (P.tile_first[mid] * H <= item) lo = mid;
+    else hi = mid - 1;
+  }
+  const uint32_t nt = P.tile_first[lo + 1] - P.tile_first[lo];
+  if (nt == 0) return false;  // (cannot happen: an item lies in a sequence that has tiles)
+  const uint32_t li = item - P.tile_first[lo] * H;
+  seq = lo;
+  head = (int)(li / nt);
+  qt = (int)(nt - 1 - li % nt);
+  return true;
+}
+
+template <int NCB>
+__global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs P) {
+  extern __shared__ uint64_t smem64[];
+  const DevBatch& B = P.b;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
+  const uint32_t H = (uint32_t)B.g.H;
+  const uint32_t total = P.tile_first[B.n_seq] * H;
+  const uint32_t worker = blockIdx.x * kWaves + wave;
+  uint32_t pool = worker % kPools;
+  uint32_t ticket = 0;
+  if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+  for (int empty = 0;;) {
+    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    while (item >= total && ++empty < 4) {
+      pool = (pool + 17) % kPools;
+      if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+    }
+    if (item >= total) break;  // every wave leaves here after at most four empty pools
+    if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+    int seq, head, qt;
+    if (!decode_item(P, item, H, seq, head, qt)) continue;
+    switch (B.g.dtype) {
+      case FS_KV_FP16: prefill_item_wide<FS_KV_FP16, NCB>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_FP8_E4M3: prefill_item_wide<FS_KV_FP8_E4M3, NCB>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_INT8: prefill_item_wide<FS_KV_INT8, NCB>(P, seq, head, qt, s_ptr); break;
+      default: prefill_item_wide<FS_KV_INT4, NCB>(P, seq, head, qt, s_ptr); break;
+    }
+  }
+}
+
 __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   const DevBatch& B = P.b;
@@ -257,6 +568,16 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     return FS_ERR_INVALID;
   }
   const int tpt = 16 / G;
+  // column blocks per work item (measurement knob FS_PREFILL_NCB = 1, 2, 4)
+  static const int ncb_env = [] {
+    const char* e = getenv("FS_PREFILL_NCB");
+    const int v = e ? atoi(e) : 0;
+    return v == 1 || v == 2 || v == 4 ? v : 0;
+  }();
+  // measured: the wider the better while the format's unpacking leaves the vector ALU room (FP16, FP8); the
+  // integer formats, whose per-token parameters and code unpacking keep the ALU busy, gain little or lose
+  const int ncb_default = g.kv_dtype == FS_KV_INT4 ? 1 : (g.kv_dtype == FS_KV_INT8 ? 2 : 4);
+  const int ncb = ncb_env ? ncb_env : ncb_default;
   uint64_t tiles = 0;
   for (int b = 0; b < n_seq; ++b) {
     const int64_t n_new = (int64_t)q_offsets_host[b + 1] - q_offsets_host[b];
@@ -264,7 +585,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
       set_error("prefill attention: q_offsets must not decrease");
       return FS_ERR_INVALID;
     }
-    tiles += (uint64_t)((n_new + tpt - 1) / tpt);
+    tiles += (uint64_t)((n_new + tpt * ncb - 1) / (tpt * ncb));
   }
   const int64_t n_rows = q_offsets_host[n_seq];
   if (tiles * (uint64_t)g.n_kv_heads > 0xfffffff0ull || n_rows > 0x7fffffff) {
@@ -309,6 +630,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   P.header = (uint32_t*)workspace;
   P.tile_first = (uint32_t*)((uint8_t*)workspace + kHeaderBytes);
   P.tpt = tpt;
+  P.ncb = ncb;
   P.seg_runs = (int32_t)std::min<int64_t>(1024, std::max<int64_t>(4, (int64_t)500 * B.R / 4 * 4));
   P.table_entries = P.seg_runs / B.R + 4;
   P.n_rows = (int32_t)n_rows;
@@ -319,9 +641,12 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill prep launch");
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * 2, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
+  const uint64_t wgs_per_cu = ncb == 1 ? 2 : 1;  // the wide kernel's accumulators leave room for one wave per SIMD
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
   const size_t smem = (size_t)kWaves * P.table_entries * sizeof(uint64_t);
-  hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
+  if (ncb == 1) hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
+  else if (ncb == 2) hipLaunchKernelGGL(prefill_wide_kernel<2>, dim3(n_wg), dim3(kThreads), smem, s, P);
+  else hipLaunchKernelGGL(prefill_wide_kernel<4>, dim3(n_wg), dim3(kThreads), smem, s, P);
   e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill launch");
   return FS_OK;

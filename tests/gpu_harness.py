@@ -227,5 +227,7 @@ def smoke():
     try:
         errs = par.run_and_check([1, 2])
         print(f"mixed fp16+fp8 pool: attention max abs err {errs}")
+        perr = [par.prefill_and_check(k, layer, par.gw.lens[k])[0] for k, layer in ((0, 1), (1, 2))]
+        print(f"whole-prompt prefill over the same pool: max abs err {perr}")
     finally:
         par.close()
