@@ -190,10 +190,53 @@ struct WideState {
   float m[NCB], l[NCB], zc[NCB];
 };
 
+// The accumulators live in AccVGPRs for the whole item: the MFMAs read and write them there, and nothing on the
+// per-tile path touches them with the vector ALU (which cannot address AccVGPRs: a plain C++ multiply in the
+// rarely taken rescale branch makes the register allocator shuttle all of them to VGPRs and back on every
+// tile).  The rescale therefore goes through explicit accvgpr moves.  The wait states that the hardware does
+// not interlock are spelled out: an MFMA result may be read by v_accvgpr_read only after the MFMA has
+// drained (acc_settle, issued once at the head of the branch -- every MFMA that writes the accumulators
+// precedes the branch), and a v_accvgpr_write needs two states before an MFMA reads the register as C.
+__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
+__device__ __forceinline__ void acc_scale(float& a, float f) {
+  float tmp;
+  asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1\n\ts_nop 1"
+               : "+a"(a), "=&v"(tmp)
+               : "v"(f));
+}
+
+// Moves the reference of column block cb (see the lazy online softmax of fs_mfma_tiles.h): tmax = this lane's
+// largest logit of the tile for its column.
+template <int DT, int NCB>
+__device__ __forceinline__ void wide_move_reference(WideState<NCB>& st, int cb, float tmax, int j) {
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const float m_new = fmaxf(st.m[cb], tmax);  // finite: token 0 is seen by every column
+  const float corr = __builtin_amdgcn_exp2f(st.m[cb] - m_new);
+  st.l[cb] *= corr;
+  if constexpr (Fmt<DT>::kParBytes != 0) st.zc[cb] *= corr;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float cr = __shfl(corr, 4 * j + r, 64);  // column h keeps its factor in lane c = h
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float a = st.acc[cb][e][r];
+      acc_scale(a, cr);
+      st.acc[cb][e][r] = a;
+    }
+  }
+  st.m[cb] = m_new;
+}
+
+// One 32-token tile for NCB column blocks.  Order of work: all S^T MFMAs; the logits and, on the tiles that
+// need it, their masks; the column maxima and one (rare) reference check for all column blocks; per column
+// block the exponentials; the P V MFMAs.  A tile is interior when its four runs are whole (8 slots each, none
+// repeated) and every column of the item sees all 32 tokens (the tile ends at or before the item's first query
+// token): nothing is masked there, and the mask code is one skipped branch that touches no accumulator.
 template <int DT, int NCB>
 __device__ __forceinline__ void wide_tile(const ItemCtx& X, const DevGeom& g, Tile<DT, 16>& t, const u32x4 (&qb)[NCB][4],
-                                          const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int vb, int vb_next,
-                                          int j, int c, WideState<NCB>& st) {
+                                          const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
+                                          int vb, int vb_next, int j, int c, WideState<NCB>& st) {
   using F = Fmt<DT>;
   // ---- S^T = K Q^T for every column block ----
   float4v s[NCB][2];
@@ -212,15 +255,7 @@ __device__ __forceinline__ void wide_tile(const ItemCtx& X, const DevGeom& g, Ti
   issue_k<DT, 16>(X, vb_next, j, c, t);
 
   const RunLoc L = locate(X, vb + j);  // X.len == X.len_u here: L.hi == L.hi_u
-  if (!__all(L.lo == 0 && L.hi_u == 8)) {
-    if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
-      // slots past the sequence's end may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int w = 0; w < F::kVBytes / 4; ++w) t.v[i][w] = i < L.hi_u ? t.v[i][w] : 0u;
-    }
-  }
+  const bool interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);  // wave-uniform
   // per-token dequantization factors, prepared by the lane that loaded the token's parameters, broadcast once
   float ka[8], kb[8], va[8], vb2[8];
   if constexpr (F::kParBytes != 0) {
@@ -243,60 +278,84 @@ __device__ __forceinline__ void wide_tile(const ItemCtx& X, const DevGeom& g, Ti
       vb2[i] = row_bcast<8 + i>(pb);
     });
   }
-  // ---- online softmax per column block (one column per lane, lazily moved reference) ----
-  u32x4 pk[NCB];
+  // logits in the base-2 domain (parameter formats) or raw products (FP16, FP8: their one common factor
+  // alpha > 0 is applied inside the exponential's argument)
+  float x[NCB][8];
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
-    const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
-    float x[8];
+  for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float v = s[cb][i >> 2][i & 3];
-      if constexpr (F::kParBytes != 0) x[i] = fmaf(v, ka[i], kb[i] * qsum[cb]);
-      else x[i] = v * alpha;
+      if constexpr (F::kParBytes != 0) x[cb][i] = fmaf(v, ka[i], kb[i] * qsum[cb]);
+      else x[cb][i] = v;
     }
-    if (!__all(L.lo == 0 && hi == 8)) {
+  if (!interior) {
+    if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
+      // slots past the sequence's end may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
 #pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = (uint32_t)(i - L.lo) < n_ok ? x[i] : -INFINITY;
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int w = 0; w < F::kVBytes / 4; ++w) t.v[i][w] = i < L.hi_u ? t.v[i][w] : 0u;
     }
-    float tmax = x[0];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
-    if (__any(tmax - st.m[cb] > kTau)) {
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(st.m[cb], tmax);  // finite: token 0 is seen by every column
-      const float corr = __builtin_amdgcn_exp2f(st.m[cb] - m_new);
-      st.l[cb] *= corr;
-      if constexpr (F::kParBytes != 0) st.zc[cb] *= corr;
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
+      const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float cr = __shfl(corr, 4 * j + r, 64);  // column h keeps its factor in lane c = h
-#pragma unroll
-        for (int e = 0; e < 8; ++e) st.acc[cb][e][r] *= cr;
-      }
-      st.m[cb] = m_new;
+      for (int i = 0; i < 8; ++i) x[cb][i] = (uint32_t)(i - L.lo) < n_ok ? x[cb][i] : -INFINITY;
     }
+  }
+  // ---- column maxima; the lazily moved reference (see fs_mfma_tiles.h) is checked once for all blocks ----
+  float tmax[NCB];
+  bool need = false;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float mx = fmaxf(fmaxf(x[cb][0], x[cb][1]), x[cb][2]);
+    mx = fmaxf(fmaxf(mx, x[cb][3]), x[cb][4]);
+    mx = fmaxf(fmaxf(mx, x[cb][5]), x[cb][6]);
+    mx = fmaxf(mx, x[cb][7]);
+    if constexpr (F::kParBytes == 0) mx *= alpha;
+    tmax[cb] = mx;
+    need |= mx - st.m[cb] > kTau;
+  }
+  if (__any(need)) {
+    acc_settle();
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, tmax[cb], j);
+  }
+  // ---- weights ----
+  u32x4 pk[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
     const float m = st.m[cb];
-    float p[8];
-    float lsum = 0.f;
+    if constexpr (F::kParBytes != 0) {
+      float p[8], lsum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float e = __builtin_amdgcn_exp2f(x[i] - m);
-      lsum += e;
-      if constexpr (F::kParBytes != 0) {
+      for (int i = 0; i < 8; ++i) {
+        const float e = __builtin_amdgcn_exp2f(x[cb][i] - m);
+        lsum += e;
         p[i] = e * va[i];
         st.zc[cb] = fmaf(e, vb2[i], st.zc[cb]);
-      } else {
-        p[i] = e;
       }
-    }
-    st.l[cb] += lsum;
+      st.l[cb] += lsum;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
-      pk[cb][q] = h2u(h);
+      for (int q = 0; q < 4; ++q) {
+        const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
+        pk[cb][q] = h2u(h);
+      }
+    } else {
+      // the running sum is taken over the weights as the MFMA sees them (rounded to fp16)
+      const half2v one = {(_Float16)1.0f, (_Float16)1.0f};
+      float l = st.l[cb];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(x[cb][2 * q], alpha, -m));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(x[cb][2 * q + 1], alpha, -m));
+        const half2v h = {(_Float16)e0, (_Float16)e1};
+        pk[cb][q] = h2u(h);
+        l = __builtin_amdgcn_fdot2(h, one, l, false);
+      }
+      st.l[cb] = l;
     }
   }
   // ---- V rows of the run -> B operands (8x8 in-register transpose), out += P V for every column block ----
@@ -354,7 +413,7 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
   for (int cb = 0; cb < NCB; ++cb) {
     const int tok = cb * P.tpt + tok_c;  // query token of this lane's column in block cb
     const bool live = tok_c < P.tpt && tok < n_tok;
-    len_cb[cb] = live ? first_pos + tok + 1 : 1;
+    len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
     load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
     if constexpr (Fmt<DT>::kParBytes != 0) {
@@ -388,7 +447,7 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
       static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
         constexpr int bi = decltype(Bi)::value;
         const int vb = v0 + (k0 + bi) * 4;
-        wide_tile<DT, NCB>(X, g, t[bi], qb, qsum, len_cb, alpha, vb, vb + NBUF * 4, j, c, st);
+        wide_tile<DT, NCB>(X, g, t[bi], qb, qsum, len_cb, alpha, first_pos, vb, vb + NBUF * 4, j, c, st);
       });
     }
   }
@@ -434,6 +493,26 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
   }
 }
 
+// Which items a ticket pool holds.  The query tiles of one (sequence, KV head) stream the same keys and values,
+// and each of the chip's eight XCDs has an L2 of its own: a pair's tiles must run on ONE XCD, side by side, for
+// its K/V to be fetched from memory once instead of once per XCD (measured on a 0.58 GB cache: 18 GB fetched
+// per launch with the tiles dealt round-robin over all XCDs).  The item list (sequence-major, then head, then
+// tile) is therefore cut into chunks of kXcdChunk consecutive items, chunk k belongs to XCD k % 8, and the 8
+// pools of an XCD (pool = 8 s + xcd) take that XCD's items s, s + 8, ... in order.  A wave's home pool is one
+// of its own XCD's (the XCC_ID hardware register says which); pools of other XCDs are only visited when the
+// home pool has run dry, at the end of the launch.
+static_assert(kPools == 64, "pool = 8 * sub-pool + XCD");
+constexpr uint32_t kXcdChunk = 128;  // = waves resident per XCD with one workgroup of four per compute unit
+__device__ __forceinline__ uint32_t pool_item(uint32_t pool, uint32_t ticket) {
+  const uint32_t xcd = pool & 7, u = (pool >> 3) + 8 * ticket;  // u: index among the XCD's items
+  return ((u / kXcdChunk) * 8 + xcd) * kXcdChunk + (u % kXcdChunk);
+}
+__device__ __forceinline__ uint32_t home_pool(int wave) {
+  const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7;  // hwreg(HW_REG_XCC_ID, 0, 4)
+  const uint32_t sub = ((blockIdx.x >> 3) * kWaves + wave) & 7;
+  return sub * 8 + xcd;
+}
+
 // item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
 __device__ __forceinline__ bool decode_item(const PrefillArgs& P, uint32_t item, uint32_t H, int& seq, int& head, int& qt) {
   int lo = 0, hi = P.b.n_seq - 1;
@@ -451,8 +530,43 @@ __device__ __forceinline__ bool decode_item(const PrefillArgs& P, uint32_t item,
   return true;
 }
 
-template <int NCB>
-__global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs P) {
+// Drawing work items until none is left.  A wave first empties its home pool; after that it looks at all 64
+// counters at once (lane p reads pool p's), moves to a pool that still holds items -- one of its own XCD's if
+// there is one -- and goes on.  It leaves only when every pool is past its last item, so every item is taken
+// whatever the grid size and wherever the workgroups landed.  The next ticket is drawn before the current item
+// is processed.
+struct ItemDraw {
+  uint32_t pool, ticket;
+};
+__device__ __forceinline__ ItemDraw first_draw(uint32_t* header, int wave, int lane) {
+  ItemDraw d{home_pool(wave), 0u};
+  if (lane == 0) d.ticket = atomicAdd(header + kHdrPools + d.pool * kPoolStride, 1u);
+  return d;
+}
+// The drawn item (and the next ticket drawn), or false when every pool is empty.
+__device__ __forceinline__ bool next_item(ItemDraw& d, uint32_t* header, uint32_t total, int lane, uint32_t& item) {
+  for (;;) {
+    item = pool_item(d.pool, __builtin_amdgcn_readfirstlane(d.ticket));
+    if (item < total) break;
+    const uint32_t cnt = __hip_atomic_load(header + kHdrPools + lane * kPoolStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint64_t left = __ballot(pool_item((uint32_t)lane, cnt) < total);  // wave-uniform; counters only grow
+    if (left == 0) return false;
+    const uint64_t own = left & (0x0101010101010101ull << (d.pool & 7));
+    if (own) left = own;
+    const uint32_t r = (d.pool + 1) & 63;  // the first such pool after the current one, cyclically
+    const uint64_t rot = r ? (left >> r) | (left << (64 - r)) : left;
+    d.pool = (r + (uint32_t)__builtin_ctzll(rot)) & 63;
+    if (lane == 0) d.ticket = atomicAdd(header + kHdrPools + d.pool * kPoolStride, 1u);
+  }
+  if (lane == 0) d.ticket = atomicAdd(header + kHdrPools + d.pool * kPoolStride, 1u);
+  return true;
+}
+
+// One kernel per KV format: the model's format is known at launch, and a kernel that holds a single format's
+// tile code leaves the register allocator a far smaller problem than a run-time switch over all four.
+// WPS = waves per SIMD the kernel is built for (its register budget: 512 / WPS).
+template <int DT, int NCB, int WPS>
+__global__ __launch_bounds__(kThreads, WPS) void prefill_wide_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   const DevBatch& B = P.b;
   const int lane = threadIdx.x & 63;
@@ -460,27 +574,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_wide_kernel(PrefillArgs P
   uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
   const uint32_t H = (uint32_t)B.g.H;
   const uint32_t total = P.tile_first[B.n_seq] * H;
-  const uint32_t worker = blockIdx.x * kWaves + wave;
-  uint32_t pool = worker % kPools;
-  uint32_t ticket = 0;
-  if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
-  for (int empty = 0;;) {
-    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    while (item >= total && ++empty < 4) {
-      pool = (pool + 17) % kPools;
-      if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
-      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    }
-    if (item >= total) break;  // every wave leaves here after at most four empty pools
-    if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
+  ItemDraw d = first_draw(P.header, wave, lane);
+  for (uint32_t item; next_item(d, P.header, total, lane, item);) {
     int seq, head, qt;
     if (!decode_item(P, item, H, seq, head, qt)) continue;
-    switch (B.g.dtype) {
-      case FS_KV_FP16: prefill_item_wide<FS_KV_FP16, NCB>(P, seq, head, qt, s_ptr); break;
-      case FS_KV_FP8_E4M3: prefill_item_wide<FS_KV_FP8_E4M3, NCB>(P, seq, head, qt, s_ptr); break;
-      case FS_KV_INT8: prefill_item_wide<FS_KV_INT8, NCB>(P, seq, head, qt, s_ptr); break;
-      default: prefill_item_wide<FS_KV_INT4, NCB>(P, seq, head, qt, s_ptr); break;
-    }
+    prefill_item_wide<DT, NCB>(P, seq, head, qt, s_ptr);
   }
 }
 
@@ -492,37 +590,15 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
   uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
   const uint32_t H = (uint32_t)B.g.H;
   const uint32_t total = P.tile_first[B.n_seq] * H;
-  // items are drawn from kPools ticket counters (pool p = items p, p + kPools, ...): a wave empties its home
-  // pool, tries three more and leaves; the next ticket is drawn before the current item is processed
-  const uint32_t worker = blockIdx.x * kWaves + wave;
-  uint32_t pool = worker % kPools;
-  uint32_t ticket = 0;
-  if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
-  for (int empty = 0;;) {
-    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    while (item >= total && ++empty < 4) {
-      pool = (pool + 17) % kPools;
-      if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
-      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    }
-    if (item >= total) break;  // every wave leaves here after at most four empty pools
-    if (lane == 0) ticket = atomicAdd(P.header + kHdrPools + pool * kPoolStride, 1u);
-    // item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
-    int lo = 0, hi = B.n_seq - 1;
-    while (lo < hi) {  // last sequence whose first item is <= item
-      const int mid = (lo + hi + 1) >> 1;
-      if (P.tile_first[mid] * H <= item) lo = mid;
-      else hi = mid - 1;
-    }
-    const uint32_t nt = P.tile_first[lo + 1] - P.tile_first[lo];
-    if (nt == 0) continue;  // (cannot happen: an item lies in a sequence that has tiles)
-    const uint32_t li = item - P.tile_first[lo] * H;
-    const int head = (int)(li / nt), qt = (int)(nt - 1 - li % nt);
+  ItemDraw d = first_draw(P.header, wave, lane);
+  for (uint32_t item; next_item(d, P.header, total, lane, item);) {
+    int seq, head, qt;
+    if (!decode_item(P, item, H, seq, head, qt)) continue;
     switch (B.g.dtype) {
-      case FS_KV_FP16: prefill_item<FS_KV_FP16>(P, lo, head, qt, s_ptr); break;
-      case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3>(P, lo, head, qt, s_ptr); break;
-      case FS_KV_INT8: prefill_item<FS_KV_INT8>(P, lo, head, qt, s_ptr); break;
-      default: prefill_item<FS_KV_INT4>(P, lo, head, qt, s_ptr); break;
+      case FS_KV_FP16: prefill_item<FS_KV_FP16>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_INT8: prefill_item<FS_KV_INT8>(P, seq, head, qt, s_ptr); break;
+      default: prefill_item<FS_KV_INT4>(P, seq, head, qt, s_ptr); break;
     }
   }
 }
@@ -577,7 +653,10 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   // measured: the wider the better while the format's unpacking leaves the vector ALU room (FP16, FP8); the
   // integer formats, whose per-token parameters and code unpacking keep the ALU busy, gain little or lose
   const int ncb_default = g.kv_dtype == FS_KV_INT4 ? 1 : (g.kv_dtype == FS_KV_INT8 ? 2 : 4);
-  const int ncb = ncb_env ? ncb_env : ncb_default;
+  // the wide kernels fold the (positive) softmax scale into the exponential's argument; any other scale takes
+  // the 16-column kernel, which does not
+  const bool scale_ok = sm_scale > 0.f && sm_scale < INFINITY;
+  const int ncb = !scale_ok ? 1 : (ncb_env ? ncb_env : ncb_default);
   uint64_t tiles = 0;
   for (int b = 0; b < n_seq; ++b) {
     const int64_t n_new = (int64_t)q_offsets_host[b + 1] - q_offsets_host[b];
@@ -641,12 +720,30 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill prep launch");
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
-  const uint64_t wgs_per_cu = ncb == 1 ? 2 : 1;  // the wide kernel's accumulators leave room for one wave per SIMD
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
+  // waves per SIMD: the 16-column kernel runs two, the wider ones one (measured: a second wave of the
+  // 32-column kernel gains nothing, its loads already saturate the compute unit's vector memory pipeline)
+  static const int wps_env = [] {
+    const char* e = getenv("FS_PREFILL_WPS");
+    const int v = e ? atoi(e) : 0;
+    return v == 1 || v == 2 ? v : 0;
+  }();
+  const int wps = ncb == 1 ? 2 : (ncb == 4 ? 1 : (wps_env ? wps_env : 1));
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
   const size_t smem = (size_t)kWaves * P.table_entries * sizeof(uint64_t);
-  if (ncb == 1) hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
-  else if (ncb == 2) hipLaunchKernelGGL(prefill_wide_kernel<2>, dim3(n_wg), dim3(kThreads), smem, s, P);
-  else hipLaunchKernelGGL(prefill_wide_kernel<4>, dim3(n_wg), dim3(kThreads), smem, s, P);
+  if (ncb == 1) {
+    hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
+  } else {
+    void (*kern)(PrefillArgs) = nullptr;
+#define FS_WIDE(DT) (ncb == 4 ? prefill_wide_kernel<DT, 4, 1> : (wps == 2 ? prefill_wide_kernel<DT, 2, 2> : prefill_wide_kernel<DT, 2, 1>))
+    switch (g.kv_dtype) {
+      case FS_KV_FP16: kern = FS_WIDE(FS_KV_FP16); break;
+      case FS_KV_FP8_E4M3: kern = FS_WIDE(FS_KV_FP8_E4M3); break;
+      case FS_KV_INT8: kern = FS_WIDE(FS_KV_INT8); break;
+      default: kern = FS_WIDE(FS_KV_INT4); break;
+    }
+#undef FS_WIDE
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), smem, s, P);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill launch");
   return FS_OK;
