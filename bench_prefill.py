@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="tokens prefilled per sequence (0 = the whole prompt)")
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
+    ap.add_argument("--kernel", default="0,0", help="column blocks,waves for fs_set_prefill_kernel (0,0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -53,6 +54,9 @@ def main():
     from fs_inputs import device as gen_device
     from paper_2509_06261_amd import harness
 
+    ker_blocks, ker_waves = (int(x) for x in args.kernel.split(","))
+    if fs.fs_set_prefill_kernel(ker_blocks, ker_waves) != 0:
+        raise SystemExit("bench_prefill.py: --kernel must be blocks in {0,1,2,4,16} and waves in {0,4,8}")
     wl = workloads.config(args.config)
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
@@ -149,7 +153,7 @@ def main():
         },
         "roofline": {
             "bound": "mfma",
-            "kernel": "paged prefill attention (64 / 64 / 32 / 16 logit columns per K/V pass for FP16 / FP8 / INT8 / INT4 KV)",
+            "kernel": "paged prefill attention, workgroup kernel (8 waves x 32 logit columns share each K/V tile through LDS)" if (ker_blocks, ker_waves) == (0, 0) else f"paged prefill attention, variant {args.kernel}",
             "achieved": round(flops / (attn_ms_per_step * 1e-3) / 1e12, 1),
             "peak": MFMA_F16_PEAK_TFLOPS,
             "unit": "TFLOP/s",

@@ -184,12 +184,19 @@ int fs_decode_status(const void* workspace, void* stream);
  *            in use until the stream has passed the call.  fs_decode_status(workspace, stream) afterwards: bit 0
  *            set if a length or a chunk size was out of range (clamped).
  * Covers head_dim 128, at least 8 tokens per block, at most 16 query heads per KV head (FS_ERR_INVALID
- * otherwise).  Asynchronous on `stream`; no allocation, no host synchronisation. */
+ * otherwise).  A softmax scale that is not positive and finite is served by the slowest kernel variant.
+ * Asynchronous on `stream`; no allocation, no host synchronisation. */
 uint64_t fs_prefill_workspace_bytes(int n_seq);
 int fs_prefill_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,
                          const int32_t* block_tables, const int32_t* seq_lens, const int32_t* q_offsets,
                          const int32_t* q_offsets_host, int n_seq, int max_blocks, void* out, float* lse,
                          void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Prefill kernel selection for tests and measurements.  column_blocks: 0 = automatic (default: the workgroup
+ * kernel, or the 16-column kernel for launches with fewer work items than compute units), 1 / 2 / 4 = the
+ * wave-level kernels with 16 / 32 / 64 logit columns per wave, 16 = the workgroup kernel; waves: waves of the
+ * workgroup kernel, 4 or 8 (0 = default, 8).  FS_ERR_INVALID for other values. */
+int fs_set_prefill_kernel(int column_blocks, int waves);
 
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */

@@ -25,7 +25,7 @@ EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_regist
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
-           "fs_prefill_attention", "fs_set_kernel_mode",
+           "fs_prefill_attention", "fs_set_prefill_kernel", "fs_set_kernel_mode",
            "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
 
 
@@ -78,6 +78,7 @@ def _load():
         "fs_decode_status": (i32, [vp, vp]),
         "fs_prefill_workspace_bytes": (u64, [i32]),
         "fs_prefill_attention": (i32, [vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
+        "fs_set_prefill_kernel": (i32, [i32, i32]),
         "fs_set_kernel_mode": (i32, [i32]),
         "fs_set_split_bytes": (i32, [u64]),
         "fs_set_kernel_timing": (i32, [i32]),
@@ -290,6 +291,10 @@ def fs_prefill_attention(pool, model, layer, n_q_heads, sm_scale, q, block_table
                                  _stream(stream))
     if rc != FS_OK:
         raise FsError(rc, "fs_prefill_attention")
+
+
+def fs_set_prefill_kernel(column_blocks: int, waves: int = 0) -> int:
+    return _L.fs_set_prefill_kernel(int(column_blocks), int(waves))
 
 
 def fs_set_kernel_mode(mode: int) -> int:

@@ -184,6 +184,17 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
 // operands; per-token parameters are broadcast once.  Only the softmax itself is per block.  The accumulators
 // (NCB x 32 registers) take the place of a second resident wave: the kernel runs one wave per SIMD.
 // ---------------------------------------------------------------------------------------------------------
+// Makes the query operand's loads complete here, once per item.  Their first real use is an MFMA inside the
+// tile loop; left pending until there, the compiler's wait-count bookkeeping must assume at the loop head that
+// they may still be in flight, and its wait for them also waits for the K/V loads issued just before -- the
+// very loads the loop is arranged to keep in flight across a whole step.
+__device__ __forceinline__ void settle_q(u32x4 (&q)[4]) {
+  uint32_t any = 0;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) any |= q[ks][0] | q[ks][1] | q[ks][2] | q[ks][3];
+  asm volatile("" ::"v"(any));
+}
+
 template <int NCB>
 struct WideState {
   float4v acc[NCB][8];
@@ -416,6 +427,7 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
     len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
     load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
+    settle_q(qb[cb]);
     if constexpr (Fmt<DT>::kParBytes != 0) {
       qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
       qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
@@ -497,20 +509,20 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
 // and each of the chip's eight XCDs has an L2 of its own: a pair's tiles must run on ONE XCD, side by side, for
 // its K/V to be fetched from memory once instead of once per XCD (measured on a 0.58 GB cache: 18 GB fetched
 // per launch with the tiles dealt round-robin over all XCDs).  The item list (sequence-major, then head, then
-// tile) is therefore cut into chunks of kXcdChunk consecutive items, chunk k belongs to XCD k % 8, and the 8
+// tile) is therefore cut into chunks of consecutive items, chunk k belongs to XCD k % 8, and the 8
 // pools of an XCD (pool = 8 s + xcd) take that XCD's items s, s + 8, ... in order.  A wave's home pool is one
 // of its own XCD's (the XCC_ID hardware register says which); pools of other XCDs are only visited when the
 // home pool has run dry, at the end of the launch.
 static_assert(kPools == 64, "pool = 8 * sub-pool + XCD");
-constexpr uint32_t kXcdChunk = 128;  // = waves resident per XCD with one workgroup of four per compute unit
-__device__ __forceinline__ uint32_t pool_item(uint32_t pool, uint32_t ticket) {
+// chunk = 2^shift items = the workers resident per XCD (wave-level items: 128 waves, workgroup-level items: 32)
+constexpr uint32_t kWaveChunkShift = 7, kWgChunkShift = 5;
+__device__ __forceinline__ uint32_t pool_item(uint32_t pool, uint32_t ticket, uint32_t shift) {
   const uint32_t xcd = pool & 7, u = (pool >> 3) + 8 * ticket;  // u: index among the XCD's items
-  return ((u / kXcdChunk) * 8 + xcd) * kXcdChunk + (u % kXcdChunk);
+  return ((((u >> shift) << 3) + xcd) << shift) + (u & ((1u << shift) - 1));
 }
-__device__ __forceinline__ uint32_t home_pool(int wave) {
+__device__ __forceinline__ uint32_t home_pool(uint32_t worker) {  // worker: index among the workers of its XCD
   const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7;  // hwreg(HW_REG_XCC_ID, 0, 4)
-  const uint32_t sub = ((blockIdx.x >> 3) * kWaves + wave) & 7;
-  return sub * 8 + xcd;
+  return (worker & 7) * 8 + xcd;
 }
 
 // item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
@@ -538,18 +550,19 @@ __device__ __forceinline__ bool decode_item(const PrefillArgs& P, uint32_t item,
 struct ItemDraw {
   uint32_t pool, ticket;
 };
-__device__ __forceinline__ ItemDraw first_draw(uint32_t* header, int wave, int lane) {
-  ItemDraw d{home_pool(wave), 0u};
+__device__ __forceinline__ ItemDraw first_draw(uint32_t* header, uint32_t worker, int lane) {
+  ItemDraw d{home_pool(worker), 0u};
   if (lane == 0) d.ticket = atomicAdd(header + kHdrPools + d.pool * kPoolStride, 1u);
   return d;
 }
 // The drawn item (and the next ticket drawn), or false when every pool is empty.
-__device__ __forceinline__ bool next_item(ItemDraw& d, uint32_t* header, uint32_t total, int lane, uint32_t& item) {
+__device__ __forceinline__ bool next_item(ItemDraw& d, uint32_t* header, uint32_t total, uint32_t shift, int lane,
+                                          uint32_t& item) {
   for (;;) {
-    item = pool_item(d.pool, __builtin_amdgcn_readfirstlane(d.ticket));
+    item = pool_item(d.pool, __builtin_amdgcn_readfirstlane(d.ticket), shift);
     if (item < total) break;
     const uint32_t cnt = __hip_atomic_load(header + kHdrPools + lane * kPoolStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint64_t left = __ballot(pool_item((uint32_t)lane, cnt) < total);  // wave-uniform; counters only grow
+    uint64_t left = __ballot(pool_item((uint32_t)lane, cnt, shift) < total);  // wave-uniform; counters only grow
     if (left == 0) return false;
     const uint64_t own = left & (0x0101010101010101ull << (d.pool & 7));
     if (own) left = own;
@@ -564,7 +577,8 @@ __device__ __forceinline__ bool next_item(ItemDraw& d, uint32_t* header, uint32_
 
 // One kernel per KV format: the model's format is known at launch, and a kernel that holds a single format's
 // tile code leaves the register allocator a far smaller problem than a run-time switch over all four.
-// WPS = waves per SIMD the kernel is built for (its register budget: 512 / WPS).
+// WPS = waves per SIMD the kernel is built for (its register budget: 512 / WPS).  (Measured: a second wave of the
+// 32-column kernel gains nothing; its loads already saturate the compute unit's vector memory pipeline.)
 template <int DT, int NCB, int WPS>
 __global__ __launch_bounds__(kThreads, WPS) void prefill_wide_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
@@ -574,11 +588,364 @@ __global__ __launch_bounds__(kThreads, WPS) void prefill_wide_kernel(PrefillArgs
   uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
   const uint32_t H = (uint32_t)B.g.H;
   const uint32_t total = P.tile_first[B.n_seq] * H;
-  ItemDraw d = first_draw(P.header, wave, lane);
-  for (uint32_t item; next_item(d, P.header, total, lane, item);) {
+  ItemDraw d = first_draw(P.header, (blockIdx.x >> 3) * kWaves + wave, lane);
+  for (uint32_t item; next_item(d, P.header, total, kWaveChunkShift, lane, item);) {
     int seq, head, qt;
     if (!decode_item(P, item, H, seq, head, qt)) continue;
     prefill_item_wide<DT, NCB>(P, seq, head, qt, s_ptr);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Workgroup variant.  Counters of the wave-level kernels show the compute unit's vector memory pipeline busy
+// 92 % of the time: every wave fetches every K/V byte of its item itself, four times per compute unit.  Here
+// the four waves of a workgroup take four neighbouring query tiles (64 logit columns each) of one (sequence,
+// KV head) and walk the keys and values together, 128 tokens per step: wave w fetches sub-tile w (32 tokens) of
+// the step, unpacks it, transposes its V rows, and leaves the finished MFMA operand fragments -- exactly what
+// it would have fed its own MFMAs -- in LDS; after a barrier every wave multiplies all four sub-tiles from
+// LDS.  Global loads, unpacking and transposes per wave drop to a quarter; the fragments are written and read
+// lane-contiguously (16 bytes per lane), free of bank conflicts.  Two stages alternate, so one barrier per
+// step suffices: a stage is rewritten only after the barrier that follows its last readers.
+// Stage layout: K fragments [sub-tile][u][k-step][lane] 16 B, V fragments [sub-tile][e][lane] 16 B, per-token
+// parameters [sub-tile][lane] 4 B.
+constexpr int kWgCols = 16;  // column blocks per work item: NW waves x (16 / NW) blocks
+constexpr uint32_t kFrag = 64 * 16;                            // one operand fragment of a wave
+constexpr uint32_t kStageK = 0, kStageV = kWaves * 8 * kFrag;  // 32 KiB each
+constexpr uint32_t kStagePar = 2 * kWaves * 8 * kFrag;
+constexpr uint32_t kStageBytes = kStagePar + kWaves * 256;
+constexpr uint32_t kWgCtlBytes = 16;
+
+template <int DT>
+__device__ __forceinline__ void stage_k(uint8_t* stage, int sub, int lane, Tile<DT, 16>& t) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    u32x4 a[4];
+    k_operands<DT>(t.k[u], a);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      *reinterpret_cast<u32x4*>(stage + kStageK + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a[ks];
+  }
+}
+template <int DT>
+__device__ __forceinline__ void stage_v(uint8_t* stage, int sub, int lane, int j, Tile<DT, 16>& t, const ItemCtx& X, int vb) {
+  using F = Fmt<DT>;
+  if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
+    // slots past the sequence's end may hold NaN/Inf bit patterns; 0 * NaN would poison the MFMA
+    const RunLoc L = locate(X, vb + j);
+    if (!__all(L.hi_u >= 8)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < F::kVBytes / 4; ++q) t.v[i][q] = i < L.hi_u ? t.v[i][q] : 0u;
+    }
+  }
+  uint32_t vx[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v_unpack<DT>(t.v[i], vx[i]);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int reg = DT == FS_KV_INT4 ? (e & 3) : (e >> 1);
+    const uint32_t sel = (DT == FS_KV_INT4 ? (e >> 2) : (e & 1)) ? 0x07060302u : 0x05040100u;
+    u32x4 b;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
+    *reinterpret_cast<u32x4*>(stage + kStageV + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16) = b;
+  }
+  if constexpr (F::kParBytes != 0) *reinterpret_cast<uint32_t*>(stage + kStagePar + sub * 256 + lane * 4) = t.par[0];
+}
+
+// One staged 32-token sub-tile for the wave's column blocks: wide_tile with the operands read from LDS.
+template <int DT, int NCB>
+__device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const ItemCtx& X, const u32x4 (&qb)[NCB][4],
+                                        const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
+                                        int vb, int lane, int j, int c, WideState<NCB>& st) {
+  using F = Fmt<DT>;
+  float4v s[NCB][2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    u32x4 a[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      a[ks] = *reinterpret_cast<const u32x4*>(stage + kStageK + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) acc = mfma(a[ks], qb[cb][ks], acc);
+      s[cb][u] = acc;
+    }
+  }
+  const RunLoc L = locate(X, vb + j);
+  const bool interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);  // wave-uniform
+  float ka[8], kb[8], va[8], vb2[8];
+  if constexpr (F::kParBytes != 0) {
+    const uint32_t par = *reinterpret_cast<const uint32_t*>(stage + kStagePar + sub * 256 + lane * 4);
+    float pa, pb;
+    const float sc = f16lo(par);
+    const float zp = DT == FS_KV_INT4 ? f16hi(par) : 128.0f;
+    if (c < 8) {  // K: logit = alpha * sc * (2^24 * S_raw - zp * qsum)
+      pa = alpha * kTwo24 * sc;
+      pb = -alpha * sc * zp;
+    } else {      // V: p' = p * sc, zero-point term -p * sc * zp
+      const bool ok = (c & 7) >= L.lo && (c & 7) < L.hi_u;  // a slot past the sequence may hold any bit pattern
+      pa = ok ? sc : 0.f;
+      pb = ok ? -sc * zp : 0.f;
+    }
+    static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+      constexpr int i = decltype(I)::value;
+      ka[i] = row_bcast<i>(pa);
+      kb[i] = row_bcast<i>(pb);
+      va[i] = row_bcast<8 + i>(pa);
+      vb2[i] = row_bcast<8 + i>(pb);
+    });
+  }
+  float x[NCB][8];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float v = s[cb][i >> 2][i & 3];
+      if constexpr (F::kParBytes != 0) x[cb][i] = fmaf(v, ka[i], kb[i] * qsum[cb]);
+      else x[cb][i] = v;
+    }
+  if (!interior) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
+      const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[cb][i] = (uint32_t)(i - L.lo) < n_ok ? x[cb][i] : -INFINITY;
+    }
+  }
+  float tmax[NCB];
+  bool need = false;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float mx = fmaxf(fmaxf(x[cb][0], x[cb][1]), x[cb][2]);
+    mx = fmaxf(fmaxf(mx, x[cb][3]), x[cb][4]);
+    mx = fmaxf(fmaxf(mx, x[cb][5]), x[cb][6]);
+    mx = fmaxf(mx, x[cb][7]);
+    if constexpr (F::kParBytes == 0) mx *= alpha;
+    tmax[cb] = mx;
+    need |= mx - st.m[cb] > kTau;
+  }
+  if (__any(need)) {
+    acc_settle();
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, tmax[cb], j);
+  }
+  u32x4 pk[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const float m = st.m[cb];
+    if constexpr (F::kParBytes != 0) {
+      float p[8], lsum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float e = __builtin_amdgcn_exp2f(x[cb][i] - m);
+        lsum += e;
+        p[i] = e * va[i];
+        st.zc[cb] = fmaf(e, vb2[i], st.zc[cb]);
+      }
+      st.l[cb] += lsum;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const half2v h = {(_Float16)p[2 * q], (_Float16)p[2 * q + 1]};
+        pk[cb][q] = h2u(h);
+      }
+    } else {
+      const half2v one = {(_Float16)1.0f, (_Float16)1.0f};
+      float l = st.l[cb];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(x[cb][2 * q], alpha, -m));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(x[cb][2 * q + 1], alpha, -m));
+        const half2v h = {(_Float16)e0, (_Float16)e1};
+        pk[cb][q] = h2u(h);
+        l = __builtin_amdgcn_fdot2(h, one, l, false);
+      }
+      st.l[cb] = l;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const u32x4 b = *reinterpret_cast<const u32x4*>(stage + kStageV + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) st.acc[cb][e] = mfma(pk[cb], b, st.acc[cb][e]);
+  }
+}
+
+// One work item of the workgroup variant: (sequence, KV head, kWgCols consecutive 16-column query tiles), NW waves
+// of kWgCols / NW column blocks each.  With 4 waves every wave fetches and stages K and V of sub-tile w; with 8
+// (two per SIMD, so that one's softmax runs under the other's MFMAs) waves 0..3 stage the K fragments of
+// sub-tile w and waves 4..7 the V fragments and parameters of sub-tile w - 4.
+// smem: two stages, then the workgroup's block-address table.
+template <int DT, int NW>
+__device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt, uint8_t* smem, uint64_t* s_tab, int w) {
+  constexpr int NCB = kWgCols / NW;
+  const bool does_k = NW == 4 || w < 4, does_v = NW == 4 || w >= 4;  // wave-uniform staging roles
+  const int sw = w & 3;                                             // the sub-tile this wave stages
+  const DevBatch& B = P.b;
+  const DevGeom& g = B.g;
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  const int j = lane >> 4, c = lane & 15;
+  const int G = B.G;
+  const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
+  int len = B.seq_lens[seq];
+  len = len < 1 ? 1 : min(len, max_len);
+  int n_new = P.q_offsets[seq + 1] - P.q_offsets[seq];
+  n_new = n_new < 0 ? 0 : min(n_new, len);
+  const int qw = P.tpt * NCB;                 // query tokens per wave
+  const int r0_wg = qt * qw * NW;             // first query token of the item within the chunk
+  if (r0_wg >= n_new) return;                 // (cannot happen with consistent inputs; uniform over the workgroup)
+  const int n_tok_wg = min(qw * NW, n_new - r0_wg);
+  const int r0 = r0_wg + w * qw;              // this wave's share
+  const int n_tok = max(0, min(qw, n_tok_wg - w * qw));
+  const int first_pos = len - n_new + r0;
+  const int tok_c = c / G, hg_c = c - tok_c * G;
+
+  ItemCtx X;  // of the workgroup: everything its last query token sees
+  X.T = g.T;
+  X.R = B.R;
+  X.r_magic = B.r_magic;
+  X.len_u = len - n_new + r0_wg + n_tok_wg;
+  X.len = X.len_u;
+  X.chunk_ptr = s_tab;
+
+  u32x4 qb[NCB][4];
+  float qsum[NCB];
+  int len_cb[NCB], row_cb[NCB];
+  float alpha = B.sm_scale * kLog2e;
+  if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
+  WideState<NCB> st;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int tok = cb * P.tpt + tok_c;  // query token of this lane's column in block cb
+    const bool live = tok_c < P.tpt && tok < n_tok;
+    len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
+    row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
+    load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
+    settle_q(qb[cb]);
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
+      qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[cb][e] = float4v{0.f, 0.f, 0.f, 0.f};
+    st.m[cb] = -INFINITY;
+    st.l[cb] = 0.f;
+    st.zc[cb] = 0.f;
+  }
+
+  const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
+  const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
+  const int n_run = n_runs(X.len_u, g.T, B.R);
+  for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
+    X.v_end = min(n_run, v0 + P.seg_runs);
+    X.k0 = div_runs(v0, B.R, B.r_magic);
+    {
+      // the previous segment's (or item's) last barrier lies behind every use of the old table
+      const int nb = div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1;
+      for (int i = threadIdx.x; i < nb; i += NW * 64)
+        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
+      __syncthreads();
+    }
+    const int n_super = (X.v_end - v0 + 15) >> 4;
+    Tile<DT, 16> t;
+    if (does_k) issue_k<DT, 16>(X, v0 + 4 * sw, j, c, t);
+    if (does_v) issue_v<DT, 16>(X, g, v0 + 4 * sw, j, c, t);
+    if (does_k) stage_k<DT>(smem, sw, lane, t);
+    if (does_v) stage_v<DT>(smem, sw, lane, j, t, X, v0 + 4 * sw);
+    __syncthreads();
+    for (int i = 0; i < n_super; ++i) {
+      // next step's sub-tile of this wave (past the segment's end: mapped onto its last run, never used)
+      const int vb_next = v0 + (i + 1) * 16 + 4 * sw;
+      if (does_k) issue_k<DT, 16>(X, vb_next, j, c, t);
+      if (does_v) issue_v<DT, 16>(X, g, vb_next, j, c, t);
+      const uint8_t* stage = smem + (uint32_t)(i & 1) * kStageBytes;
+#pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
+      for (int sub = 0; sub < 4; ++sub) {
+        // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
+        // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
+        // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
+        wg_tile<DT, NCB>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + i * 16 + sub * 4, lane, j, c, st);
+      }
+      uint8_t* next = smem + (uint32_t)((i + 1) & 1) * kStageBytes;
+      if (does_k) stage_k<DT>(next, sw, lane, t);
+      if (does_v) stage_v<DT>(next, sw, lane, j, t, X, vb_next);
+      __syncthreads();
+    }
+  }
+  if (n_tok == 0) return;
+
+  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float l = st.l[cb], zc = st.zc[cb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if constexpr (Fmt<DT>::kParBytes != 0) {
+      zc += __shfl_xor(zc, 16, 64);
+      zc += __shfl_xor(zc, 32, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int h = 4 * j + r;  // accumulator row r of this lane is logit column h of block cb
+      const float L = __shfl(l, h, 64), M = __shfl(st.m[cb], h, 64), Z = __shfl(zc, h, 64);
+      const int row_h = __shfl(row_cb[cb], h, 64);
+      const int tok_h = h / G, hg_h = h - tok_h * G;
+      if (tok_h < P.tpt && cb * P.tpt + tok_h < n_tok) {
+        const float inv = 1.0f / L;
+        u32x4 wv;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float o[2];
+#pragma unroll
+          for (int z = 0; z < 2; ++z) {
+            const int e = 2 * q + z;
+            const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+            o[z] = st.acc[cb][e][r] * f;
+            if constexpr (Fmt<DT>::kParBytes != 0) o[z] += Z;
+            o[z] *= v_static * inv;
+          }
+          const half2v hv = {(_Float16)o[0], (_Float16)o[1]};
+          wv[q] = h2u(hv);
+        }
+        const int64_t qrow = (int64_t)row_h * B.n_q + head * G + hg_h;
+        *reinterpret_cast<u32x4*>(B.out + qrow * kD + 8 * c) = wv;
+        if (c == 0 && B.lse) B.lse[qrow] = (M + __builtin_amdgcn_logf(L)) * kLn2;
+      }
+    }
+  }
+}
+
+template <int DT, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void prefill_wg_kernel(PrefillArgs P) {
+  extern __shared__ uint64_t smem64[];
+  uint8_t* smem = reinterpret_cast<uint8_t*>(smem64);
+  uint64_t* s_tab = reinterpret_cast<uint64_t*>(smem + 2 * kStageBytes);
+  volatile uint32_t* s_ctl = reinterpret_cast<volatile uint32_t*>(smem + 2 * kStageBytes + (size_t)P.table_entries * 8);
+  const DevBatch& B = P.b;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t H = (uint32_t)B.g.H;
+  const uint32_t total = P.tile_first[B.n_seq] * H;
+  ItemDraw d{0u, 0u};
+  if (wave == 0) d = first_draw(P.header, blockIdx.x >> 3, lane);
+  for (;;) {
+    if (wave == 0) {  // one wave draws for the workgroup
+      uint32_t item;
+      const bool ok = next_item(d, P.header, total, kWgChunkShift, lane, item);
+      if (lane == 0) s_ctl[0] = ok ? item : 0xffffffffu;
+    }
+    __syncthreads();
+    const uint32_t item = __builtin_amdgcn_readfirstlane(s_ctl[0]);  // (an LDS load is not uniform to the compiler)
+    __syncthreads();  // everyone holds the item before the next draw may overwrite it
+    if (item == 0xffffffffu) break;
+    int seq, head, qt;
+    if (!decode_item(P, item, H, seq, head, qt)) continue;
+    prefill_item_wg<DT, NW>(P, seq, head, qt, smem, s_tab, wave);
   }
 }
 
@@ -590,8 +957,8 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
   uint64_t* s_ptr = smem64 + (size_t)wave * P.table_entries;
   const uint32_t H = (uint32_t)B.g.H;
   const uint32_t total = P.tile_first[B.n_seq] * H;
-  ItemDraw d = first_draw(P.header, wave, lane);
-  for (uint32_t item; next_item(d, P.header, total, lane, item);) {
+  ItemDraw d = first_draw(P.header, (blockIdx.x >> 3) * kWaves + wave, lane);
+  for (uint32_t item; next_item(d, P.header, total, kWaveChunkShift, lane, item);) {
     int seq, head, qt;
     if (!decode_item(P, item, H, seq, head, qt)) continue;
     switch (B.g.dtype) {
@@ -609,6 +976,18 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 }  // namespace fs
 
 using namespace fs;
+
+namespace {
+int g_prefill_ncb = 0, g_prefill_nw = 0;
+}
+
+int fs_set_prefill_kernel(int column_blocks, int waves) {
+  const bool ok_c = column_blocks == 0 || column_blocks == 1 || column_blocks == 2 || column_blocks == 4 || column_blocks == 16;
+  if (!ok_c || (waves != 0 && waves != 4 && waves != 8)) return FS_ERR_INVALID;
+  g_prefill_ncb = column_blocks;
+  g_prefill_nw = waves;
+  return FS_OK;
+}
 
 uint64_t fs_prefill_workspace_bytes(int n_seq) {
   if (n_seq < 1) return 0;
@@ -644,27 +1023,28 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     return FS_ERR_INVALID;
   }
   const int tpt = 16 / G;
-  // column blocks per work item (measurement knob FS_PREFILL_NCB = 1, 2, 4)
-  static const int ncb_env = [] {
-    const char* e = getenv("FS_PREFILL_NCB");
-    const int v = e ? atoi(e) : 0;
-    return v == 1 || v == 2 || v == 4 ? v : 0;
-  }();
-  // measured: the wider the better while the format's unpacking leaves the vector ALU room (FP16, FP8); the
-  // integer formats, whose per-token parameters and code unpacking keep the ALU busy, gain little or lose
-  const int ncb_default = g.kv_dtype == FS_KV_INT4 ? 1 : (g.kv_dtype == FS_KV_INT8 ? 2 : 4);
+  const int ncb_env = g_prefill_ncb;  // fs_set_prefill_kernel
+  // Default: the workgroup kernel (measured fastest for every format once a launch has a work item per
+  // compute unit); the 16-column wave-level kernel, whose items are sixteen times finer, for smaller launches.
+  const int ncb_default = 16;
   // the wide kernels fold the (positive) softmax scale into the exponential's argument; any other scale takes
   // the 16-column kernel, which does not
   const bool scale_ok = sm_scale > 0.f && sm_scale < INFINITY;
-  const int ncb = !scale_ok ? 1 : (ncb_env ? ncb_env : ncb_default);
+  int ncb = !scale_ok ? 1 : (ncb_env ? ncb_env : ncb_default);
   uint64_t tiles = 0;
-  for (int b = 0; b < n_seq; ++b) {
-    const int64_t n_new = (int64_t)q_offsets_host[b + 1] - q_offsets_host[b];
-    if (n_new < 0) {
-      set_error("prefill attention: q_offsets must not decrease");
-      return FS_ERR_INVALID;
+  for (int pass = 0; pass < 2; ++pass) {
+    tiles = 0;
+    for (int b = 0; b < n_seq; ++b) {
+      const int64_t n_new = (int64_t)q_offsets_host[b + 1] - q_offsets_host[b];
+      if (n_new < 0) {
+        set_error("prefill attention: q_offsets must not decrease");
+        return FS_ERR_INVALID;
+      }
+      tiles += (uint64_t)((n_new + tpt * ncb - 1) / (tpt * ncb));
     }
-    tiles += (uint64_t)((n_new + tpt * ncb - 1) / (tpt * ncb));
+    // a launch with fewer workgroup-level items than compute units: the finest items instead
+    if (pass == 0 && ncb == 16 && !ncb_env && tiles * (uint64_t)g.n_kv_heads < (uint64_t)p->n_cu) ncb = 1;
+    else break;
   }
   const int64_t n_rows = q_offsets_host[n_seq];
   if (tiles * (uint64_t)g.n_kv_heads > 0xfffffff0ull || n_rows > 0x7fffffff) {
@@ -720,21 +1100,31 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill prep launch");
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
-  // waves per SIMD: the 16-column kernel runs two, the wider ones one (measured: a second wave of the
-  // 32-column kernel gains nothing, its loads already saturate the compute unit's vector memory pipeline)
-  static const int wps_env = [] {
-    const char* e = getenv("FS_PREFILL_WPS");
-    const int v = e ? atoi(e) : 0;
-    return v == 1 || v == 2 ? v : 0;
-  }();
-  const int wps = ncb == 1 ? 2 : (ncb == 4 ? 1 : (wps_env ? wps_env : 1));
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
-  const size_t smem = (size_t)kWaves * P.table_entries * sizeof(uint64_t);
-  if (ncb == 1) {
+  // waves per SIMD: the 16-column kernel runs two, the wider wave-level ones one
+  const int wps = ncb == 1 ? 2 : 1;
+  const int nw = g_prefill_nw == 4 ? 4 : 8;
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>(ncb == 16 ? items : (items + kWaves - 1) / kWaves, 1));
+  const size_t smem = ncb == 16 ? 2 * (size_t)kStageBytes + (size_t)P.table_entries * 8 + kWgCtlBytes
+                                : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
+  if (ncb == 16) {
+    void (*kern)(PrefillArgs) = nullptr;
+#define FS_WG(DT) (nw == 8 ? prefill_wg_kernel<DT, 8> : prefill_wg_kernel<DT, 4>)
+    switch (g.kv_dtype) {
+      case FS_KV_FP16: kern = FS_WG(FS_KV_FP16); break;
+      case FS_KV_FP8_E4M3: kern = FS_WG(FS_KV_FP8_E4M3); break;
+      case FS_KV_INT8: kern = FS_WG(FS_KV_INT8); break;
+      default: kern = FS_WG(FS_KV_INT4); break;
+    }
+#undef FS_WG
+    // more than 64 KiB of dynamic LDS has to be granted per kernel
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return device_error(e, "prefill LDS attribute");
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(nw * 64), smem, s, P);
+  } else if (ncb == 1) {
     hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
   } else {
     void (*kern)(PrefillArgs) = nullptr;
-#define FS_WIDE(DT) (ncb == 4 ? prefill_wide_kernel<DT, 4, 1> : (wps == 2 ? prefill_wide_kernel<DT, 2, 2> : prefill_wide_kernel<DT, 2, 1>))
+#define FS_WIDE(DT) (ncb == 4 ? prefill_wide_kernel<DT, 4, 1> : prefill_wide_kernel<DT, 2, 1>)
     switch (g.kv_dtype) {
       case FS_KV_FP16: kern = FS_WIDE(FS_KV_FP16); break;
       case FS_KV_FP8_E4M3: kern = FS_WIDE(FS_KV_FP8_E4M3); break;
