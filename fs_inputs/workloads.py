@@ -37,6 +37,7 @@ class ModelSpec:
     src_f32: bool = False                 # K/V source rows handed to append as fp32 (else fp16)
     full_layers: Optional[int] = None     # depth of the real model this one is shaped after
     block_budget: Optional[int] = None    # None: one block per slab
+    tokens_per_block: Optional[int] = None  # the paper's direction: tokens fixed, block bytes derived (Sec. 3.2 / 5.2)
 
     @property
     def n_seq(self) -> int:

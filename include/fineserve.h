@@ -83,6 +83,20 @@ void* fs_pool_base(fs_pool* pool);
 int fs_model_register(fs_pool* pool, int kv_dtype, int n_kv_heads, int head_dim, int n_layers, fs_model_t* out);
 int fs_model_register_ex(fs_pool* pool, int kv_dtype, int n_kv_heads, int head_dim, int n_layers,
                          uint64_t block_budget_bytes, fs_model_t* out);
+/* The paper's own direction of the same equations (Sec. 3.2: block size = TokensPerBlock x TokenSize +
+ * Quant.Params; Sec. 5.2: all slabs of a GPU have one size, a multiple of the least common multiple of the
+ * co-located models' block sizes, and a slab holds slab/block blocks of its key).  Host only.
+ *   fs_block_bytes: bytes of the laid-out block that holds tokens_per_block tokens (a multiple of 256); 0 for
+ *     an unsupported shape or tokens_per_block < 1.
+ *   fs_slab_bytes_for_blocks: the smallest multiple of lcm(block_bytes[0..n-1]) that is >= min_slab_bytes; 0 if
+ *     an entry is 0 or the result would exceed 2^40 (host pointer to n values).
+ *   fs_model_register_tokens: registers a model whose blocks hold exactly tokens_per_block tokens (block budget =
+ *     fs_block_bytes of it, which must divide the pool's slab_bytes); returns tokens_per_block or a negative
+ *     fs_status, like fs_model_register_ex. */
+uint64_t fs_block_bytes(int kv_dtype, int n_kv_heads, int head_dim, int n_layers, int tokens_per_block);
+uint64_t fs_slab_bytes_for_blocks(const uint64_t* block_bytes, int n, uint64_t min_slab_bytes);
+int fs_model_register_tokens(fs_pool* pool, int kv_dtype, int n_kv_heads, int head_dim, int n_layers,
+                             int tokens_per_block, fs_model_t* out);
 /* FP8 models: static fp32 scales per (layer, KV head), separate for K and V; host pointers to
  * [n_layers][n_kv_heads] floats, all > 0.  Copied to the device synchronously.  Must be called
  * before the first append/attention of an FP8 model. */

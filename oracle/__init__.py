@@ -58,6 +58,10 @@ def load():
         f = getattr(L, name)
         f.restype = u64
         f.argtypes = [gp, ctypes.c_int32, i32, i32, i32, i32]
+    L.fso_block_bytes.restype = u64
+    L.fso_block_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.fso_lcm_slab_bytes.restype = u64
+    L.fso_lcm_slab_bytes.argtypes = [vp, i32, u64]
     L.fso_block_offset.restype = u64
     L.fso_block_offset.argtypes = [gp, ctypes.c_int32]
     L.fso_pool_new.restype = vp
@@ -66,6 +70,8 @@ def load():
     L.fso_pool_delete.argtypes = [vp]
     L.fso_model_add.restype = i32
     L.fso_model_add.argtypes = [vp, i32, i32, i32, i32, u64]
+    L.fso_model_add_tokens.restype = i32
+    L.fso_model_add_tokens.argtypes = [vp, i32, i32, i32, i32, i32]
     L.fso_model_remove.restype = i32
     L.fso_model_remove.argtypes = [vp, i32]
     L.fso_model_geometry.restype = i32
@@ -128,6 +134,17 @@ def geometry(dtype, n_kv_heads, head_dim, n_layers, block_budget) -> Geom:
     return g
 
 
+def block_bytes(dtype, n_kv_heads, head_dim, n_layers, tokens_per_block) -> int:
+    """Sec. 3.2, forward: bytes of the laid-out block holding tokens_per_block tokens (0: invalid)."""
+    return load().fso_block_bytes(dtype, n_kv_heads, head_dim, n_layers, tokens_per_block)
+
+
+def lcm_slab_bytes(block_sizes, min_slab=0) -> int:
+    """Sec. 5.2: smallest multiple of the lcm of the block sizes that is >= min_slab (0: invalid or > 2^40)."""
+    a = np.ascontiguousarray(block_sizes, dtype=np.uint64)
+    return load().fso_lcm_slab_bytes(a.ctypes.data_as(ctypes.c_void_p), len(a), int(min_slab))
+
+
 def row_offset(g, blk, layer, head, which, tok) -> int:
     return load().fso_row_offset(ctypes.byref(g), blk, layer, head, which, tok)
 
@@ -159,6 +176,10 @@ class Pool:
     def model_add(self, dtype, n_kv_heads, head_dim, n_layers, block_budget=None) -> int:
         return self._L.fso_model_add(self._p, dtype, n_kv_heads, head_dim, n_layers,
                                      self.slab_bytes if block_budget is None else block_budget)
+
+    def model_add_tokens(self, dtype, n_kv_heads, head_dim, n_layers, tokens_per_block) -> int:
+        """The paper's direction (Sec. 3.2 / 5.2): exactly tokens_per_block tokens per block."""
+        return self._L.fso_model_add_tokens(self._p, dtype, n_kv_heads, head_dim, n_layers, tokens_per_block)
 
     def model_remove(self, model) -> int:
         return self._L.fso_model_remove(self._p, model)

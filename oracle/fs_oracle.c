@@ -119,6 +119,43 @@ int fso_geometry(int dtype, int n_kv_heads, int head_dim, int n_layers, uint64_t
   return FSO_OK;
 }
 
+/* Sec. 3.2, forward: bytes of the laid-out block that holds T tokens (0: invalid arguments). */
+uint64_t fso_block_bytes(int dtype, int n_kv_heads, int head_dim, int n_layers, int T) {
+  if (dtype_bits(dtype) == 0 || n_kv_heads < 1 || head_dim < 2 || (head_dim & 1) || n_layers < 1 || T < 1) return 0;
+  fso_geom g;
+  memset(&g, 0, sizeof g);
+  g.dtype = dtype;
+  g.n_kv_heads = n_kv_heads;
+  g.head_dim = head_dim;
+  g.n_layers = n_layers;
+  geom_for_tokens(&g, T);
+  return g.block_bytes;
+}
+
+/* Sec. 5.2: the slab size is a multiple of the least common multiple of the co-located block sizes; here the
+ * smallest such multiple that is at least min_slab (0: an entry is 0, or the result exceeds 2^40).  The lcm is
+ * found as the first multiple of the largest block size that every block size divides. */
+uint64_t fso_lcm_slab_bytes(const uint64_t* block_bytes, int n, uint64_t min_slab) {
+  if (!block_bytes || n < 1) return 0;
+  uint64_t big = 0;
+  for (int i = 0; i < n; ++i) {
+    if (block_bytes[i] == 0) return 0;
+    if (block_bytes[i] > big) big = block_bytes[i];
+  }
+  const uint64_t limit = 1ull << 40;
+  for (uint64_t cand = big; cand <= limit; cand += big) {
+    int all = 1;
+    for (int i = 0; i < n; ++i)
+      if (cand % block_bytes[i]) all = 0;
+    if (all) {
+      uint64_t slab = cand;
+      while (slab < min_slab) slab += cand;
+      return slab <= limit ? slab : 0;
+    }
+  }
+  return 0;
+}
+
 /* View mapping of Sec. 5.1: block blk_id of a model starts at blk_id * block_budget
  * from the pool base (= slab * slab_bytes + local * block_budget). */
 uint64_t fso_block_offset(const fso_geom* g, int32_t blk_id) { return (uint64_t)blk_id * g->block_budget; }
@@ -212,6 +249,31 @@ int fso_model_add(fso_pool* p, int dtype, int n_kv_heads, int head_dim, int n_la
       M->in_use = 1;
       M->geom = g;
       M->bps = (int64_t)(p->slab_bytes / block_budget);
+      M->live = (uint8_t*)calloc((size_t)(p->n_slabs * M->bps), 1);
+      return m;
+    }
+  }
+  return FSO_ERR_NOMEM;
+}
+
+/* Sec. 3.2 / 5.2, the paper's direction: a model whose blocks hold exactly T tokens; the block's own size is its
+ * budget and must divide slab_bytes. */
+int fso_model_add_tokens(fso_pool* p, int dtype, int n_kv_heads, int head_dim, int n_layers, int T) {
+  uint64_t b = fso_block_bytes(dtype, n_kv_heads, head_dim, n_layers, T);
+  if (!p || b == 0 || p->slab_bytes % b) return FSO_ERR_INVALID;
+  if (p->pool_bytes / b >= (1ull << 31)) return FSO_ERR_INVALID;
+  for (int m = 0; m < FSO_MAX_MODELS; ++m) {
+    if (!p->models[m].in_use) {
+      fso_model* M = &p->models[m];
+      memset(M, 0, sizeof *M);
+      M->in_use = 1;
+      M->geom.dtype = dtype;
+      M->geom.n_kv_heads = n_kv_heads;
+      M->geom.head_dim = head_dim;
+      M->geom.n_layers = n_layers;
+      M->geom.block_budget = b;
+      geom_for_tokens(&M->geom, T);
+      M->bps = (int64_t)(p->slab_bytes / b);
       M->live = (uint8_t*)calloc((size_t)(p->n_slabs * M->bps), 1);
       return m;
     }

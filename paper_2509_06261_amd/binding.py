@@ -22,6 +22,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_DIR, "libfineserve.so")
 
 EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
+           "fs_block_bytes", "fs_slab_bytes_for_blocks", "fs_model_register_tokens",
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
@@ -63,6 +64,9 @@ def _load():
         "fs_pool_base": (vp, [vp]),
         "fs_model_register": (i32, [vp, i32, i32, i32, i32, pi32]),
         "fs_model_register_ex": (i32, [vp, i32, i32, i32, i32, u64, pi32]),
+        "fs_block_bytes": (u64, [i32, i32, i32, i32, i32]),
+        "fs_slab_bytes_for_blocks": (u64, [vp, i32, u64]),
+        "fs_model_register_tokens": (i32, [vp, i32, i32, i32, i32, i32, pi32]),
         "fs_model_set_fp8_scales": (i32, [vp, i32, vp, vp]),
         "fs_model_unregister": (i32, [vp, i32]),
         "fs_model_geometry": (i32, [vp, i32, ctypes.POINTER(fs_geometry_t)]),
@@ -153,6 +157,24 @@ def fs_model_register(pool, kv_dtype, n_kv_heads, head_dim, n_layers, block_budg
                                      ctypes.byref(m))
     if rc < 0:
         raise FsError(rc, "fs_model_register")
+    return rc, m.value
+
+
+def fs_block_bytes(kv_dtype, n_kv_heads, head_dim, n_layers, tokens_per_block) -> int:
+    return _L.fs_block_bytes(kv_dtype, n_kv_heads, head_dim, n_layers, tokens_per_block)
+
+
+def fs_slab_bytes_for_blocks(block_bytes, min_slab_bytes=0) -> int:
+    a = np.ascontiguousarray(block_bytes, dtype=np.uint64)
+    return _L.fs_slab_bytes_for_blocks(a.ctypes.data, len(a), int(min_slab_bytes))
+
+
+def fs_model_register_tokens(pool, kv_dtype, n_kv_heads, head_dim, n_layers, tokens_per_block):
+    """Returns (tokens_per_block, model)."""
+    m = ctypes.c_int32(-1)
+    rc = _L.fs_model_register_tokens(pool, kv_dtype, n_kv_heads, head_dim, n_layers, tokens_per_block, ctypes.byref(m))
+    if rc < 0:
+        raise FsError(rc, "fs_model_register_tokens")
     return rc, m.value
 
 

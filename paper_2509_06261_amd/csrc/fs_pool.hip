@@ -127,8 +127,9 @@ int fs_pool_destroy(fs_pool* p) {
 
 void* fs_pool_base(fs_pool* p) { return p ? p->base : nullptr; }
 
-int fs_model_register_ex(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim, int n_layers,
-                         uint64_t block_budget_bytes, fs_model_t* out) {
+// forced_tokens > 0: exactly that many tokens per block (they must fit the budget); 0: as many as fit
+static int register_model(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim, int n_layers, uint64_t block_budget_bytes,
+                          int forced_tokens, fs_model_t* out) {
   if (!p || !out) return FS_ERR_INVALID;
   if (kv_dtype < FS_KV_FP16 || kv_dtype > FS_KV_INT4 || n_kv_heads < 1 || n_kv_heads > 1024 || n_layers < 1 ||
       n_layers > 4096 || head_dim < 8 || head_dim > 512 || (head_dim & (head_dim - 1))) {
@@ -147,7 +148,12 @@ int fs_model_register_ex(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim,
   g.n_layers = n_layers;
   g.block_budget = block_budget_bytes;
   g.blocks_per_slab = (int32_t)(p->slab_bytes / block_budget_bytes);
-  if (solve_tokens(g) != FS_OK) {
+  if (forced_tokens > 0) {
+    if (layout(g, forced_tokens) > g.block_budget) {
+      set_error("fs_model_register: the requested tokens do not fit the block budget");
+      return FS_ERR_INVALID;
+    }
+  } else if (solve_tokens(g) != FS_OK) {
     set_error("fs_model_register: not even one token fits the block budget");
     return FS_ERR_INVALID;
   }
@@ -163,6 +169,60 @@ int fs_model_register_ex(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim,
   }
   set_error("fs_model_register: too many models");
   return FS_ERR_NOMEM;
+}
+
+int fs_model_register_ex(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim, int n_layers,
+                         uint64_t block_budget_bytes, fs_model_t* out) {
+  return register_model(p, kv_dtype, n_kv_heads, head_dim, n_layers, block_budget_bytes, 0, out);
+}
+
+static bool shape_ok(int kv_dtype, int n_kv_heads, int head_dim, int n_layers) {
+  return kv_dtype >= FS_KV_FP16 && kv_dtype <= FS_KV_INT4 && n_kv_heads >= 1 && n_kv_heads <= 1024 && n_layers >= 1 &&
+         n_layers <= 4096 && head_dim >= 8 && head_dim <= 512 && !(head_dim & (head_dim - 1));
+}
+
+uint64_t fs_block_bytes(int kv_dtype, int n_kv_heads, int head_dim, int n_layers, int tokens_per_block) {
+  if (!shape_ok(kv_dtype, n_kv_heads, head_dim, n_layers) || tokens_per_block < 1) return 0;
+  fs_geometry_t g{};
+  g.kv_dtype = kv_dtype;
+  g.n_kv_heads = n_kv_heads;
+  g.head_dim = head_dim;
+  g.n_layers = n_layers;
+  return layout(g, tokens_per_block);
+}
+
+uint64_t fs_slab_bytes_for_blocks(const uint64_t* block_bytes, int n, uint64_t min_slab_bytes) {
+  if (!block_bytes || n < 1) return 0;
+  const uint64_t limit = 1ull << 40;  // a slab beyond 1 TiB is no slab
+  uint64_t l = 1;
+  for (int i = 0; i < n; ++i) {
+    const uint64_t b = block_bytes[i];
+    if (b == 0 || b > limit) return 0;
+    uint64_t x = l, y = b;
+    while (y) {  // gcd
+      const uint64_t t = x % y;
+      x = y;
+      y = t;
+    }
+    const uint64_t f = b / x;
+    if (l > limit / f) return 0;
+    l *= f;
+  }
+  const uint64_t k = min_slab_bytes <= l ? 1 : (min_slab_bytes + l - 1) / l;
+  if (k > limit / l) return 0;
+  return k * l;
+}
+
+int fs_model_register_tokens(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim, int n_layers, int tokens_per_block,
+                             fs_model_t* out) {
+  if (!p || !out) return FS_ERR_INVALID;
+  const uint64_t b = fs_block_bytes(kv_dtype, n_kv_heads, head_dim, n_layers, tokens_per_block);
+  if (b == 0) {
+    set_error("fs_model_register_tokens: unsupported model shape or token count");
+    return FS_ERR_INVALID;
+  }
+  // the block's own size is its budget; the token count is imposed (alignment padding may leave room for more)
+  return register_model(p, kv_dtype, n_kv_heads, head_dim, n_layers, b, tokens_per_block, out);
 }
 
 int fs_model_register(fs_pool* p, int kv_dtype, int n_kv_heads, int head_dim, int n_layers, fs_model_t* out) {

@@ -40,7 +40,11 @@ class GpuWorkload:
         self.pool = fs.fs_pool_create(wl.slab_bytes, wl.pool_bytes, self.pool_mem)
         self.model_ids, self.T, self.geom, self.scales = [], {}, {}, {}
         for s in wl.models:
-            T, m = fs.fs_model_register(self.pool, s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget)
+            if s.tokens_per_block:
+                T, m = fs.fs_model_register_tokens(self.pool, s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers,
+                                                   s.tokens_per_block)
+            else:
+                T, m = fs.fs_model_register(self.pool, s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget)
             self.model_ids.append(m)
             self.T[m] = T
             self.geom[m] = fs.fs_model_geometry(self.pool, m)

@@ -47,7 +47,9 @@ class Parity:
         self.wl = wl
         self.gw = harness.GpuWorkload(wl, zero_pool=zero_pool)
         self.opool = oracle.Pool(wl.slab_bytes, wl.pool_bytes)
-        self.o_ids = [self.opool.model_add(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget)
+        self.o_ids = [self.opool.model_add_tokens(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.tokens_per_block)
+                      if s.tokens_per_block else
+                      self.opool.model_add(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget)
                       for s in wl.models]
         self.ogeom = [self.opool.model_geometry(m) for m in self.o_ids]
         for m, og in zip(self.gw.model_ids, self.ogeom):

@@ -114,6 +114,34 @@ def test_group_sizes_and_head_dim_64(group, mode):
         par.close()
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+def test_tokens_fixed_blocks_in_lcm_sized_slabs(mode):
+    """The paper's own direction (Sec. 3.2 / 5.2): every model has 16 tokens per block, block bytes follow from
+    the precision, the slab is a multiple of the lcm of the block sizes and each model sees it as a different
+    number of blocks (17 / 34 / 64 here).  Decode and prefill parity over that pool."""
+    import oracle as orc
+
+    la = np.array([1, 16, 17, 200, 333], np.int32)
+    shapes = [(FP16, 2, 128, 2), (FP8, 2, 128, 2), (INT4, 2, 128, 2)]
+    blocks = [orc.block_bytes(d, h, dd, l, 16) for d, h, dd, l in shapes]
+    slab = orc.lcm_slab_bytes(blocks, 2 * blocks[0])
+    if slab == 0 or slab > 4 * MiB:
+        pytest.skip("no common slab for these block sizes")
+    wl = Workload("lcm", slab, 64 * slab,
+                  [ModelSpec("a", FP16, 2, 128, 2, 8, la, tag=41, tokens_per_block=16),
+                   ModelSpec("b", FP8, 2, 128, 2, 8, la, tag=42, tokens_per_block=16),
+                   ModelSpec("c", INT4, 2, 128, 2, 8, la, tag=43, src_f32=True, tokens_per_block=16)], "interleave")
+    par = _parity(wl)
+    try:
+        assert [par.gw.T[m] for m in par.gw.model_ids] == [16, 16, 16]
+        assert [par.gw.geom[m].blocks_per_slab for m in par.gw.model_ids] == [slab // b for b in blocks]
+        par.run_and_check([1, 0, 1], kernel_mode=mode)
+        for k, layer in ((0, 1), (1, 0), (2, 1)):
+            par.prefill_and_check(k, layer, par.gw.lens[k])
+    finally:
+        par.close()
+
+
 @pytest.mark.parametrize("mode", KERNEL_MODES)
 def test_several_blocks_per_slab(mode):
     """fs_model_register_ex: four blocks per slab for one model, two for the other, in one pool."""

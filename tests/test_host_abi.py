@@ -24,6 +24,9 @@ class FsPoolAdapter:
     def model_add(self, dtype, H, D, L, budget=None):
         return fs.fs_model_register(self.pool, dtype, H, D, L, budget)[1]
 
+    def model_add_tokens(self, dtype, H, D, L, T):
+        return fs.fs_model_register_tokens(self.pool, dtype, H, D, L, T)[1]
+
     def alloc(self, m):
         return fs.fs_block_alloc(self.pool, m)
 
@@ -87,8 +90,9 @@ def test_worked_block_id_example_through_the_abi(golden_dir):
 def _run_trace(slab, n_slabs, model_specs, n_ops, seed):
     o = oracle.Pool(slab, n_slabs * slab)
     a = FsPoolAdapter(slab, n_slabs * slab)
-    om = [o.model_add(*s) for s in model_specs]
-    am = [a.model_add(*s) for s in model_specs]
+    add = lambda pool, s: pool.model_add_tokens(*s[1:]) if s[0] == "tokens" else pool.model_add(*s)
+    om = [add(o, s) for s in model_specs]
+    am = [add(a, s) for s in model_specs]
     assert om == am
     live = [[] for _ in model_specs]
     r = gen.uniform_ints(seed, 5, n_ops, 1 << 40)
@@ -132,6 +136,35 @@ def test_allocator_matches_oracle_many_blocks_per_slab():
     slab = 256 * KiB
     specs = [(0, 4, 64, 1, slab // 2), (1, 4, 64, 1, slab // 4), (3, 2, 64, 2, slab // 16), (2, 4, 64, 1, slab)]
     _run_trace(slab, 96, specs, 300_000, seed=12)
+
+
+def test_paper_direction_sizing_matches_oracle():
+    """fs_block_bytes / fs_slab_bytes_for_blocks / fs_model_register_tokens (Sec. 3.2 forward, Sec. 5.2 lcm slab)."""
+    rng = np.random.default_rng(21)
+    for _ in range(300):
+        dt = int(rng.integers(0, 4))
+        H, D, L, T = int(rng.integers(1, 41)), int(rng.choice([32, 64, 128, 256])), int(rng.integers(1, 41)), int(rng.integers(1, 300))
+        assert fs.fs_block_bytes(dt, H, D, L, T) == oracle.block_bytes(dt, H, D, L, T)
+    for _ in range(200):
+        sizes = [int(rng.integers(1, 64)) * 256 * int(rng.choice([1, 2, 3, 5, 8])) for _ in range(int(rng.integers(1, 5)))]
+        lo = int(rng.integers(0, 1 << 24))
+        assert fs.fs_slab_bytes_for_blocks(sizes, lo) == oracle.lcm_slab_bytes(sizes, lo)
+    assert fs.fs_block_bytes(0, 8, 128, 32, 0) == 0 and fs.fs_slab_bytes_for_blocks([0, 256]) == 0
+    assert fs.fs_slab_bytes_for_blocks([(1 << 39) + 256, (1 << 39) + 512]) == 0
+    # token-fixed registration in an lcm-sized slab pool; allocator traces identical to the oracle's
+    shapes = [(0, 4, 64, 2, 16), (1, 4, 64, 2, 16), (2, 3, 64, 1, 5)]
+    blocks = [fs.fs_block_bytes(*s) for s in shapes]
+    slab = fs.fs_slab_bytes_for_blocks(blocks, 100 * KiB)
+    assert slab == oracle.lcm_slab_bytes(blocks, 100 * KiB) and all(slab % b == 0 for b in blocks)
+    pool = fs.fs_pool_create(slab, 64 * slab, FAKE_BASE)
+    for s, b in zip(shapes, blocks):
+        T, m = fs.fs_model_register_tokens(pool, *s)
+        g = fs.fs_model_geometry(pool, m)
+        assert T == s[4] == g.tokens_per_block and g.block_budget == g.block_bytes == b and g.blocks_per_slab == slab // b
+    with pytest.raises(fs.FsError):
+        fs.fs_model_register_tokens(pool, 0, 4, 64, 2, 17)  # its block size does not divide the slab
+    fs.fs_pool_destroy(pool)
+    _run_trace(slab, 64, [("tokens",) + s for s in shapes], 100_000, seed=13)
 
 
 def test_error_codes_without_device():

@@ -228,3 +228,60 @@ def test_any_free_slab_serves_any_model():
     assert pool.free(a, ida[4]) == 0
     rc, blk = pool.alloc(b)  # the slab freed by model a is immediately usable by model b
     assert rc == 0 and blk == 4
+
+
+# --------------------------------------------------------------------------- Sec. 3.2 forward / Sec. 5.2 slab size
+def test_block_bytes_forward_is_the_block_size_equation():
+    """block size = TokensPerBlock x TokenSize + Quant.Params (Sec. 3.2), recomputed independently; where the layout
+    pads nothing it is exactly T x L x 2 x H x (D x bytes + param bytes); and it inverts fso_geometry."""
+    import math
+
+    bits = {oracle.FP16: 16, oracle.FP8: 8, oracle.INT8: 8, oracle.INT4: 4}
+    par = {oracle.FP16: 0, oracle.FP8: 0, oracle.INT8: 2, oracle.INT4: 4}
+    rng = np.random.default_rng(9)
+    for _ in range(300):
+        dt = int(rng.integers(0, 4))
+        H, D, L, T = int(rng.integers(1, 41)), int(rng.choice([32, 64, 128, 256])), int(rng.integers(1, 41)), int(rng.integers(1, 200))
+        kv = _a(T * D * bits[dt] // 8, 16)
+        p = _a(T * par[dt], 16) if par[dt] else 0
+        want = L * _a(H * (2 * kv + 2 * p), 256)
+        got = oracle.block_bytes(dt, H, D, L, T)
+        assert got == want
+        g = oracle.geometry(dt, H, D, L, got)  # budget = the block's own size: T tokens fit (alignment may admit more)
+        assert g.tokens_per_block >= T and g.block_bytes == got
+        if T > 1:
+            assert oracle.geometry(dt, H, D, L, got - 256).tokens_per_block < T
+    # no padding anywhere: T multiple of 8, H x chunk multiple of 256
+    assert oracle.block_bytes(oracle.FP16, 8, 128, 32, 16) == 16 * 32 * (2 * 8 * 128 * 2)
+    assert oracle.block_bytes(oracle.INT8, 8, 128, 32, 16) == 16 * 32 * (2 * 8 * (128 + 2))
+    assert oracle.block_bytes(oracle.INT4, 8, 128, 32, 16) == 16 * 32 * (2 * 8 * (64 + 4))
+    assert oracle.block_bytes(oracle.FP16, 8, 128, 32, 0) == 0 and oracle.block_bytes(7, 8, 128, 32, 16) == 0
+    # a token count the padding would let grow stays as imposed
+    pool = oracle.Pool(oracle.block_bytes(oracle.INT8, 3, 64, 1, 5) * 4, oracle.block_bytes(oracle.INT8, 3, 64, 1, 5) * 64)
+    m = pool.model_add_tokens(oracle.INT8, 3, 64, 1, 5)
+    assert pool.model_geometry(m).tokens_per_block == 5 and pool.blocks_per_slab(m) == 4
+
+
+def test_lcm_slab_size_against_math_lcm_and_the_figure():
+    """Sec. 5.2: slab = multiple of the lcm of the co-located block sizes.  Checked against Python's math.lcm;
+    the pair FP16 / FP8 at 16 tokens per block gives the picture of the slab figure: one slab seen as 1 block by
+    one model and as 2 blocks by the other; with per-token parameters the lcm explodes (INT8, INT4)."""
+    import math
+
+    rng = np.random.default_rng(10)
+    for _ in range(200):
+        n = int(rng.integers(1, 5))
+        sizes = [int(rng.integers(1, 64)) * 256 * int(rng.choice([1, 2, 3, 5, 8])) for _ in range(n)]
+        lo = int(rng.integers(0, 1 << 24))
+        l = math.lcm(*sizes)
+        want = l * max(1, -(-lo // l))
+        assert oracle.lcm_slab_bytes(sizes, lo) == want
+    b16, b8 = (oracle.block_bytes(d, 8, 128, 32, 16) for d in (oracle.FP16, oracle.FP8))
+    assert (b16, b8) == (2 * MiB, 1 * MiB) and oracle.lcm_slab_bytes([b16, b8]) == 2 * MiB
+    pool = oracle.Pool(2 * MiB, 64 * MiB)
+    a, b = pool.model_add_tokens(oracle.FP16, 8, 128, 32, 16), pool.model_add_tokens(oracle.FP8, 8, 128, 32, 16)
+    assert pool.blocks_per_slab(a) == 1 and pool.blocks_per_slab(b) == 2
+    assert pool.model_geometry(a).tokens_per_block == pool.model_geometry(b).tokens_per_block == 16
+    all4 = [oracle.block_bytes(d, 8, 128, 32, 16) for d in (oracle.FP16, oracle.FP8, oracle.INT8, oracle.INT4)]
+    assert oracle.lcm_slab_bytes(all4) == math.lcm(*all4) == 2 * MiB * 5 * 13 * 17  # 2.2 GiB: no usable slab
+    assert oracle.lcm_slab_bytes([0, 256]) == 0 and oracle.lcm_slab_bytes([(1 << 39) + 256, (1 << 39) + 512]) == 0
