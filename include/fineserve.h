@@ -206,6 +206,41 @@ int fs_prefill_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_hea
                          const int32_t* q_offsets_host, int n_seq, int max_blocks, void* out, float* lse,
                          void* workspace, uint64_t workspace_bytes, void* stream);
 
+/* ---- Two-level scheduler, host side (Sec. 6): no device work ---------------------------------------------------
+ * fs_sched_select_batch: Algorithm 2 (Sec. 6.3), SLO-aware adaptive batching of ONE model's waiting queue at time
+ * `now`.  Every request gets the deadline arrival_time + slo.  A request that would miss it even if prefilled
+ * alone right away is dropped; the others are ordered earliest deadline first (queue order among equals); while
+ * the predicted prefill time of the whole tentative batch ends after the FRONT request's deadline, the longest
+ * request is removed (among equally long ones the latest in deadline order); the result is cut, in deadline order,
+ * to at most n_max requests and t_max prompt tokens.  The chunked-prefill latency of a set R of requests is
+ * predicted as  c0 + c1 * sum_R tokens + c2 * sum_R tokens^2  seconds (the algorithm takes TTFT(R) as a profiled
+ * input; this three-coefficient form -- launch cost, linear layers, attention -- is the library's reading, fitted
+ * from fs_prefill_attention timings).
+ *   waiting[n_waiting]: host; selected / dropped: host int32 [n_waiting] each, receive indices into `waiting`
+ *   (selected in deadline order, dropped in queue order); *n_selected, *n_dropped their counts.  Requests in neither
+ *   list stay queued.
+ * fs_sched_place_models: Algorithm 1 (Sec. 6.2).  Models are taken in descending order of their base footprint
+ * F_M (input order among equals); each goes to the GPU G that maximises
+ *   score(G | M) = (1 / |G'|) * sum_{m in G'} mu_m * K_rem(G'),   K_rem(G') = capacity_G - sum_{m in G'} F_m,
+ * G' = G's residents plus M (the paper's approximation of the contested-memory score; GPUs with K_rem < 0 are no
+ * candidates, equal scores go to the lowest index).  placement[i] receives model i's GPU, or -1 if none fits.
+ *   footprint, mu: host double [n_models] (bytes, tokens per byte); capacity: host double [n_gpus]. */
+typedef struct {
+  double arrival_time; /* seconds */
+  int32_t prompt_tokens;
+  int32_t reserved;
+} fs_request_t;
+typedef struct {
+  double slo;        /* TTFT SLO of the model, seconds */
+  double c0, c1, c2; /* latency model of a prefill batch, see above */
+  int32_t n_max;     /* cap on concurrent requests */
+  int32_t t_max;     /* cap on batched prompt tokens */
+} fs_sched_params_t;
+int fs_sched_select_batch(const fs_request_t* waiting, int n_waiting, const fs_sched_params_t* params, double now,
+                          int32_t* selected, int32_t* n_selected, int32_t* dropped, int32_t* n_dropped);
+int fs_sched_place_models(const double* footprint, const double* mu, int n_models, const double* capacity, int n_gpus,
+                          int32_t* placement);
+
 /* Prefill kernel selection for tests and measurements.  column_blocks: 0 = automatic (default: the workgroup
  * kernel, or the 16-column kernel for launches with fewer work items than compute units), 1 / 2 / 4 = the
  * wave-level kernels with 16 / 32 / 64 logit columns per wave, 16 = the workgroup kernel; waves: waves of the

@@ -26,7 +26,7 @@ EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_regist
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
-           "fs_prefill_attention", "fs_set_prefill_kernel", "fs_set_kernel_mode",
+           "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_set_prefill_kernel", "fs_set_kernel_mode",
            "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
 
 
@@ -82,6 +82,8 @@ def _load():
         "fs_decode_status": (i32, [vp, vp]),
         "fs_prefill_workspace_bytes": (u64, [i32]),
         "fs_prefill_attention": (i32, [vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
+        "fs_sched_select_batch": (i32, [vp, i32, vp, ctypes.c_double, vp, vp, vp, vp]),
+        "fs_sched_place_models": (i32, [vp, vp, i32, vp, i32, vp]),
         "fs_set_prefill_kernel": (i32, [i32, i32]),
         "fs_set_kernel_mode": (i32, [i32]),
         "fs_set_split_bytes": (i32, [u64]),
@@ -313,6 +315,44 @@ def fs_prefill_attention(pool, model, layer, n_q_heads, sm_scale, q, block_table
                                  _stream(stream))
     if rc != FS_OK:
         raise FsError(rc, "fs_prefill_attention")
+
+
+class fs_request_t(ctypes.Structure):
+    _fields_ = [("arrival_time", ctypes.c_double), ("prompt_tokens", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class fs_sched_params_t(ctypes.Structure):
+    _fields_ = [("slo", ctypes.c_double), ("c0", ctypes.c_double), ("c1", ctypes.c_double), ("c2", ctypes.c_double),
+                ("n_max", ctypes.c_int32), ("t_max", ctypes.c_int32)]
+
+
+REQUEST_DTYPE = np.dtype([("arrival_time", np.float64), ("prompt_tokens", np.int32), ("reserved", np.int32)])
+
+
+def fs_sched_select_batch(arrival, tokens, slo, n_max, t_max, c0, c1, c2, now):
+    """Returns (selected, dropped): index arrays into the waiting queue."""
+    n = len(arrival)
+    w = np.zeros(n, dtype=REQUEST_DTYPE)
+    w["arrival_time"], w["prompt_tokens"] = arrival, tokens
+    par = fs_sched_params_t(slo, c0, c1, c2, n_max, t_max)
+    sel, drp = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
+    ns, nd = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = _L.fs_sched_select_batch(w.ctypes.data, n, ctypes.byref(par), float(now), sel.ctypes.data, ctypes.byref(ns),
+                                  drp.ctypes.data, ctypes.byref(nd))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_sched_select_batch")
+    return sel[:ns.value].copy(), drp[:nd.value].copy()
+
+
+def fs_sched_place_models(footprint, mu, capacity):
+    f = np.ascontiguousarray(footprint, np.float64)
+    m = np.ascontiguousarray(mu, np.float64)
+    c = np.ascontiguousarray(capacity, np.float64)
+    out = np.empty(max(len(f), 1), np.int32)
+    rc = _L.fs_sched_place_models(f.ctypes.data, m.ctypes.data, len(f), c.ctypes.data, len(c), out.ctypes.data)
+    if rc != FS_OK:
+        raise FsError(rc, "fs_sched_place_models")
+    return out[:len(f)].copy()
 
 
 def fs_set_prefill_kernel(column_blocks: int, waves: int = 0) -> int:

@@ -8,7 +8,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_DIR)
 LIB = os.path.join(_DIR, "libfineserve.so")
 SOURCES = ["fs_pool.hip", "fs_append.hip", "fs_attention.hip", "fs_attention_generic.hip", "fs_attention_mfma.hip",
-           "fs_prefill.hip"]
+           "fs_prefill.hip", "fs_sched.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions.
 # -ffp-contract=off: quantizer arithmetic must not be fused (bytes are compared bit for bit).
