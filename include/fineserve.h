@@ -243,8 +243,9 @@ int fs_sched_place_models(const double* footprint, const double* mu, int n_model
 
 /* Prefill kernel selection for tests and measurements.  column_blocks: 0 = automatic (default: the workgroup
  * kernel, or the 16-column kernel for launches with fewer work items than compute units), 1 / 2 / 4 = the
- * wave-level kernels with 16 / 32 / 64 logit columns per wave, 16 = the workgroup kernel; waves: waves of the
- * workgroup kernel, 4 or 8 (0 = default, 8).  FS_ERR_INVALID for other values. */
+ * wave-level kernels with 16 / 32 / 64 logit columns per wave, 16 = the workgroup kernel (waves: 8 x 32 columns,
+ * the default, or 4 x 64).  FS_ERR_INVALID for other values (8, a variant with two workgroups per compute unit,
+ * is switched off). */
 int fs_set_prefill_kernel(int column_blocks, int waves);
 
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic

@@ -223,6 +223,10 @@ __device__ __forceinline__ void wide_move_reference(WideState<NCB>& st, int cb, 
   tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
   const float m_new = fmaxf(st.m[cb], tmax);  // finite: token 0 is seen by every column
+  if (__all(st.m[cb] == -INFINITY)) {         // the item's first tile: nothing accumulated yet, nothing to rescale
+    st.m[cb] = m_new;
+    return;
+  }
   const float corr = __builtin_amdgcn_exp2f(st.m[cb] - m_new);
   st.l[cb] *= corr;
   if constexpr (Fmt<DT>::kParBytes != 0) st.zc[cb] *= corr;
@@ -608,25 +612,25 @@ __global__ __launch_bounds__(kThreads, WPS) void prefill_wide_kernel(PrefillArgs
 // step suffices: a stage is rewritten only after the barrier that follows its last readers.
 // Stage layout: K fragments [sub-tile][u][k-step][lane] 16 B, V fragments [sub-tile][e][lane] 16 B, per-token
 // parameters [sub-tile][lane] 4 B.
-constexpr int kWgCols = 16;  // column blocks per work item: NW waves x (16 / NW) blocks
-constexpr uint32_t kFrag = 64 * 16;                            // one operand fragment of a wave
-constexpr uint32_t kStageK = 0, kStageV = kWaves * 8 * kFrag;  // 32 KiB each
-constexpr uint32_t kStagePar = 2 * kWaves * 8 * kFrag;
-constexpr uint32_t kStageBytes = kStagePar + kWaves * 256;
+constexpr uint32_t kFrag = 64 * 16;  // one operand fragment of a wave
+// a stage of SUBS sub-tiles: K fragments, V fragments (8 KiB per sub-tile each), parameters
+constexpr uint32_t stage_v(int subs) { return (uint32_t)subs * 8 * kFrag; }
+constexpr uint32_t stage_par(int subs) { return 2 * (uint32_t)subs * 8 * kFrag; }
+constexpr uint32_t stage_bytes(int subs) { return stage_par(subs) + (uint32_t)subs * 256; }
 constexpr uint32_t kWgCtlBytes = 16;
 
 template <int DT>
-__device__ __forceinline__ void stage_k(uint8_t* stage, int sub, int lane, Tile<DT, 16>& t) {
+__device__ __forceinline__ void stage_k(uint8_t* stage, int sub, int lane, Tile<DT, 16>& t) {  // (K fragments lead the stage)
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     u32x4 a[4];
     k_operands<DT>(t.k[u], a);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      *reinterpret_cast<u32x4*>(stage + kStageK + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a[ks];
+      *reinterpret_cast<u32x4*>(stage + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a[ks];
   }
 }
-template <int DT>
+template <int DT, int SUBS>
 __device__ __forceinline__ void stage_v(uint8_t* stage, int sub, int lane, int j, Tile<DT, 16>& t, const ItemCtx& X, int vb) {
   using F = Fmt<DT>;
   if constexpr (DT == FS_KV_FP16 || DT == FS_KV_FP8_E4M3) {
@@ -649,13 +653,13 @@ __device__ __forceinline__ void stage_v(uint8_t* stage, int sub, int lane, int j
     u32x4 b;
 #pragma unroll
     for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
-    *reinterpret_cast<u32x4*>(stage + kStageV + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16) = b;
+    *reinterpret_cast<u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16) = b;
   }
-  if constexpr (F::kParBytes != 0) *reinterpret_cast<uint32_t*>(stage + kStagePar + sub * 256 + lane * 4) = t.par[0];
+  if constexpr (F::kParBytes != 0) *reinterpret_cast<uint32_t*>(stage + stage_par(SUBS) + sub * 256 + lane * 4) = t.par[0];
 }
 
 // One staged 32-token sub-tile for the wave's column blocks: wide_tile with the operands read from LDS.
-template <int DT, int NCB>
+template <int DT, int NCB, int SUBS>
 __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const ItemCtx& X, const u32x4 (&qb)[NCB][4],
                                         const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
                                         int vb, int lane, int j, int c, WideState<NCB>& st) {
@@ -666,7 +670,7 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
     u32x4 a[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      a[ks] = *reinterpret_cast<const u32x4*>(stage + kStageK + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16);
+      a[ks] = *reinterpret_cast<const u32x4*>(stage + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       float4v acc = {0.f, 0.f, 0.f, 0.f};
@@ -679,7 +683,7 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
   const bool interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);  // wave-uniform
   float ka[8], kb[8], va[8], vb2[8];
   if constexpr (F::kParBytes != 0) {
-    const uint32_t par = *reinterpret_cast<const uint32_t*>(stage + kStagePar + sub * 256 + lane * 4);
+    const uint32_t par = *reinterpret_cast<const uint32_t*>(stage + stage_par(SUBS) + sub * 256 + lane * 4);
     float pa, pb;
     const float sc = f16lo(par);
     const float zp = DT == FS_KV_INT4 ? f16hi(par) : 128.0f;
@@ -769,22 +773,25 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const u32x4 b = *reinterpret_cast<const u32x4*>(stage + kStageV + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) st.acc[cb][e] = mfma(pk[cb], b, st.acc[cb][e]);
   }
 }
 
-// One work item of the workgroup variant: (sequence, KV head, kWgCols consecutive 16-column query tiles), NW waves
-// of kWgCols / NW column blocks each.  With 4 waves every wave fetches and stages K and V of sub-tile w; with 8
-// (two per SIMD, so that one's softmax runs under the other's MFMAs) waves 0..3 stage the K fragments of
-// sub-tile w and waves 4..7 the V fragments and parameters of sub-tile w - 4.
+// One work item of the workgroup variant: (sequence, KV head, NW x NCB consecutive 16-column query tiles): NW waves
+// of NCB column blocks each walk K/V in steps of SUBS sub-tiles (32 tokens each).  With NW == SUBS every wave fetches
+// and stages K and V of sub-tile w; with NW == 2 SUBS waves 0..SUBS-1 stage the K fragments of sub-tile w and the
+// others the V fragments and parameters of sub-tile w - SUBS.  Built variants: 8 waves x 2 blocks, 4 sub-tiles per
+// step, one workgroup per compute unit (two waves per SIMD, so that one's softmax runs under the other's MFMAs);
+// 4 x 4, 4 sub-tiles (one wave per SIMD); 4 x 2 with 2 sub-tiles per step, whose stages are small enough for TWO
+// workgroups per compute unit: the two waves of a SIMD then belong to different items and do not march in step.
 // smem: two stages, then the workgroup's block-address table.
-template <int DT, int NW>
+template <int DT, int NW, int NCB, int SUBS>
 __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt, uint8_t* smem, uint64_t* s_tab, int w) {
-  constexpr int NCB = kWgCols / NW;
-  const bool does_k = NW == 4 || w < 4, does_v = NW == 4 || w >= 4;  // wave-uniform staging roles
-  const int sw = w & 3;                                             // the sub-tile this wave stages
+  static_assert(NW == SUBS || NW == 2 * SUBS, "staging roles");
+  const bool does_k = NW == SUBS || w < SUBS, does_v = NW == SUBS || w >= SUBS;  // wave-uniform staging roles
+  const int sw = w % SUBS;                                                       // the sub-tile this wave stages
   const DevBatch& B = P.b;
   const DevGeom& g = B.g;
   int lane = threadIdx.x & 63;
@@ -851,29 +858,29 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
         s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
       __syncthreads();
     }
-    const int n_super = (X.v_end - v0 + 15) >> 4;
+    const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
     Tile<DT, 16> t;
     if (does_k) issue_k<DT, 16>(X, v0 + 4 * sw, j, c, t);
     if (does_v) issue_v<DT, 16>(X, g, v0 + 4 * sw, j, c, t);
     if (does_k) stage_k<DT>(smem, sw, lane, t);
-    if (does_v) stage_v<DT>(smem, sw, lane, j, t, X, v0 + 4 * sw);
+    if (does_v) stage_v<DT, SUBS>(smem, sw, lane, j, t, X, v0 + 4 * sw);
     __syncthreads();
     for (int i = 0; i < n_super; ++i) {
       // next step's sub-tile of this wave (past the segment's end: mapped onto its last run, never used)
-      const int vb_next = v0 + (i + 1) * 16 + 4 * sw;
+      const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
       if (does_k) issue_k<DT, 16>(X, vb_next, j, c, t);
       if (does_v) issue_v<DT, 16>(X, g, vb_next, j, c, t);
-      const uint8_t* stage = smem + (uint32_t)(i & 1) * kStageBytes;
+      const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
 #pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
-      for (int sub = 0; sub < 4; ++sub) {
+      for (int sub = 0; sub < SUBS; ++sub) {
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
         // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
-        wg_tile<DT, NCB>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + i * 16 + sub * 4, lane, j, c, st);
+        wg_tile<DT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st);
       }
-      uint8_t* next = smem + (uint32_t)((i + 1) & 1) * kStageBytes;
+      uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
       if (does_k) stage_k<DT>(next, sw, lane, t);
-      if (does_v) stage_v<DT>(next, sw, lane, j, t, X, vb_next);
+      if (does_v) stage_v<DT, SUBS>(next, sw, lane, j, t, X, vb_next);
       __syncthreads();
     }
   }
@@ -920,12 +927,13 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
   }
 }
 
-template <int DT, int NW>
-__global__ __launch_bounds__(NW * 64, 1) void prefill_wg_kernel(PrefillArgs P) {
+// WPC = workgroups per compute unit the kernel is built for
+template <int DT, int NW, int NCB, int SUBS, int WPC>
+__global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   uint8_t* smem = reinterpret_cast<uint8_t*>(smem64);
-  uint64_t* s_tab = reinterpret_cast<uint64_t*>(smem + 2 * kStageBytes);
-  volatile uint32_t* s_ctl = reinterpret_cast<volatile uint32_t*>(smem + 2 * kStageBytes + (size_t)P.table_entries * 8);
+  uint64_t* s_tab = reinterpret_cast<uint64_t*>(smem + 2 * stage_bytes(SUBS));
+  volatile uint32_t* s_ctl = reinterpret_cast<volatile uint32_t*>(smem + 2 * stage_bytes(SUBS) + (size_t)P.table_entries * 8);
   const DevBatch& B = P.b;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -936,7 +944,7 @@ __global__ __launch_bounds__(NW * 64, 1) void prefill_wg_kernel(PrefillArgs P) {
   for (;;) {
     if (wave == 0) {  // one wave draws for the workgroup
       uint32_t item;
-      const bool ok = next_item(d, P.header, total, kWgChunkShift, lane, item);
+      const bool ok = next_item(d, P.header, total, kWgChunkShift + (WPC == 2 ? 1 : 0), lane, item);
       if (lane == 0) s_ctl[0] = ok ? item : 0xffffffffu;
     }
     __syncthreads();
@@ -945,7 +953,7 @@ __global__ __launch_bounds__(NW * 64, 1) void prefill_wg_kernel(PrefillArgs P) {
     if (item == 0xffffffffu) break;
     int seq, head, qt;
     if (!decode_item(P, item, H, seq, head, qt)) continue;
-    prefill_item_wg<DT, NW>(P, seq, head, qt, smem, s_tab, wave);
+    prefill_item_wg<DT, NW, NCB, SUBS>(P, seq, head, qt, smem, s_tab, wave);
   }
 }
 
@@ -983,6 +991,9 @@ int g_prefill_ncb = 0, g_prefill_nw = 0;
 
 int fs_set_prefill_kernel(int column_blocks, int waves) {
   const bool ok_c = column_blocks == 0 || column_blocks == 1 || column_blocks == 2 || column_blocks == 4 || column_blocks == 16;
+  // column_blocks == 8 (two workgroups of 4 waves x 32 columns per compute unit, 64-token steps) is switched off:
+  // small cases pass, but a run over the two-model 128 GiB workload ended with the GPU faulted or hung and the cause
+  // has not been found; the variant stays unreachable until it has.
   if (!ok_c || (waves != 0 && waves != 4 && waves != 8)) return FS_ERR_INVALID;
   g_prefill_ncb = column_blocks;
   g_prefill_nw = waves;
@@ -1043,7 +1054,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
       tiles += (uint64_t)((n_new + tpt * ncb - 1) / (tpt * ncb));
     }
     // a launch with fewer workgroup-level items than compute units: the finest items instead
-    if (pass == 0 && ncb == 16 && !ncb_env && tiles * (uint64_t)g.n_kv_heads < (uint64_t)p->n_cu) ncb = 1;
+    if (pass == 0 && ncb >= 8 && !ncb_env && tiles * (uint64_t)g.n_kv_heads < (uint64_t)p->n_cu) ncb = 1;
     else break;
   }
   const int64_t n_rows = q_offsets_host[n_seq];
@@ -1102,13 +1113,18 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
   // waves per SIMD: the 16-column kernel runs two, the wider wave-level ones one
   const int wps = ncb == 1 ? 2 : 1;
-  const int nw = g_prefill_nw == 4 ? 4 : 8;
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>(ncb == 16 ? items : (items + kWaves - 1) / kWaves, 1));
-  const size_t smem = ncb == 16 ? 2 * (size_t)kStageBytes + (size_t)P.table_entries * 8 + kWgCtlBytes
-                                : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
-  if (ncb == 16) {
+  // workgroup kernels: 16 blocks = 8 waves x 2 (default) or 4 x 4, 4 sub-tiles per step, one workgroup per compute
+  // unit; 8 blocks = 4 waves x 2, 2 sub-tiles per step, two workgroups per compute unit
+  const bool wg = ncb >= 8;
+  const int nw = ncb == 8 ? 4 : (g_prefill_nw == 4 ? 4 : 8);
+  const int subs = ncb == 8 ? 2 : 4, wpc = ncb == 8 ? 2 : 1;
+  const int n_wg = wg ? (int)std::min<uint64_t>((uint64_t)p->n_cu * wpc, std::max<uint64_t>(items, 1))
+                      : (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
+  const size_t smem = wg ? 2 * (size_t)stage_bytes(subs) + (size_t)P.table_entries * 8 + kWgCtlBytes
+                         : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
+  if (wg) {
     void (*kern)(PrefillArgs) = nullptr;
-#define FS_WG(DT) (nw == 8 ? prefill_wg_kernel<DT, 8> : prefill_wg_kernel<DT, 4>)
+#define FS_WG(DT) (ncb == 8 ? prefill_wg_kernel<DT, 4, 2, 2, 2> : (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1> : prefill_wg_kernel<DT, 4, 4, 4, 1>))
     switch (g.kv_dtype) {
       case FS_KV_FP16: kern = FS_WG(FS_KV_FP16); break;
       case FS_KV_FP8_E4M3: kern = FS_WG(FS_KV_FP8_E4M3); break;
