@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
     ap.add_argument("--kernel", default="0,0", help="column blocks,waves for fs_set_prefill_kernel (0,0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
+                    help="after the timed region also run a plain device copy of this size (counter calibration "
+                         "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench_prefill.py: this build targets one GPU; --gpus must be 1.")
@@ -129,7 +132,21 @@ def main():
     for i in range(args.steps):
         step(args.warmup + args.steps + i, timed=True)
     attn_ms_per_step = float(np.sum(attn_ms)) / args.steps
+    if args.copy_calibration_gib > 0:
+        n = int(args.copy_calibration_gib * 2**30)
+        src = torch.empty(n, dtype=torch.uint8, device=dev)
+        src.fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
+    # measured HBM-side bytes per launch (counter runs summarised under profiles/), for the workload they were taken on
+    traffic = None
+    tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "prefill_traffic_cfg2.json")
+    if os.path.exists(tpath) and args.config == 2 and args.chunk <= 0 and args.only_model < 0 and (ker_blocks, ker_waves) == (0, 0):
+        traffic = json.load(open(tpath))["hbm_bytes_per_launch"]
     result = {
         "metric": "prefill-attention TFLOP/s over the KV slab pool",
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 1),
@@ -158,7 +175,7 @@ def main():
             "peak": MFMA_F16_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(flops / (attn_ms_per_step * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
-            "traffic": None,
+            "traffic": traffic,
             "attention_ms_per_step": round(attn_ms_per_step, 3),
             "flops_per_step": flops,
             "kv_bytes_in_pool_per_layer": kv_bytes,

@@ -511,7 +511,7 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
 
 // Which items a ticket pool holds.  The query tiles of one (sequence, KV head) stream the same keys and values,
 // and each of the chip's eight XCDs has an L2 of its own: a pair's tiles must run on ONE XCD, side by side, for
-// its K/V to be fetched from memory once instead of once per XCD (measured on a 0.58 GB cache: 18 GB fetched
+// its K/V to be fetched from memory once instead of once per XCD (measured on a 0.58 GB cache: 36 GB fetched
 // per launch with the tiles dealt round-robin over all XCDs).  The item list (sequence-major, then head, then
 // tile) is therefore cut into chunks of consecutive items, chunk k belongs to XCD k % 8, and the 8
 // pools of an XCD (pool = 8 s + xcd) take that XCD's items s, s + 8, ... in order.  A wave's home pool is one
