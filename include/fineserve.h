@@ -123,7 +123,7 @@ int fs_model_dump_live(fs_pool* pool, fs_model_t model, uint8_t* live);
 /* ---- fs_kv_append (Sec. 2.1: every new token appends its keys and values) -------------------
  * Quantizes the new K/V rows of n_tokens tokens of one layer and scatters them, with their
  * per-token parameters, into the slab blocks named by the block tables.
- *   k_new, v_new : device, [n_tokens][n_kv_heads][head_dim], fp16 or fp32 (src_dtype)
+ *   k_new, v_new : device, [n_tokens][n_kv_heads][head_dim], fp16 or fp32 (src_dtype), 16-byte aligned
  *   seq_idx, pos : device int32 [n_tokens]; token i is position pos[i] of sequence seq_idx[i]
  *   block_tables : device int32 [n_seq][max_blocks]; entry [s][p / tokens_per_block] is the Blk ID
  * Quantizers (fp32, round-to-nearest-even, true division; finite inputs):
@@ -247,6 +247,9 @@ int fs_sched_place_models(const double* footprint, const double* mu, int n_model
  * the default, or 4 x 64).  FS_ERR_INVALID for other values (8, a variant with two workgroups per compute unit,
  * is switched off). */
 int fs_set_prefill_kernel(int column_blocks, int waves);
+/* The 4-wave workgroup kernel (column_blocks 16, waves 4) in its software-pipelined form: one wave interleaves the
+ * MFMAs of the next sub-tile's S^T with the current sub-tile's exponentials.  0 = off (default). */
+int fs_set_prefill_pipelined(int enable);
 
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */

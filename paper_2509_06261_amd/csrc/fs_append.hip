@@ -5,9 +5,10 @@
 // quantization parameters stored inside the block.  The paper gives no quantizer
 // arithmetic; the definitions implemented here are the ones stated in fineserve.h.
 //
-// One wavefront handles one (token, KV head, K|V) row: lanes hold element pairs, the row's
-// extrema are reduced across the wave with DPP shuffles, and each lane stores its own bytes
-// (INT4: one byte = the lane's two codes, so no byte is shared between lanes or tokens).
+// A (token, KV head, K|V) row is handled by head_dim / 8 neighbouring lanes, eight elements each (a wave covers
+// 4 rows at head_dim 128): 16-byte source loads, 16 / 8 / 8 / 4-byte stores for FP16 / FP8 / INT8 / INT4.  The
+// row's extrema are reduced over its lanes with xor shuffles (max and min are exact in any order), and each lane
+// stores its own bytes (INT4: a byte holds two codes of one lane, so no byte is shared between lanes or tokens).
 // All arithmetic is IEEE fp32, round-to-nearest-even, correctly rounded division, and this
 // file is compiled with floating-point contraction off so that the stored bytes are
 // reproducible bit for bit.
@@ -16,8 +17,11 @@
 namespace fs {
 namespace {
 
-constexpr int kWaves = 4;        // waves per workgroup
-constexpr int kMaxPairIters = 4; // head_dim <= 512 -> at most 4 element pairs per lane
+constexpr int kWaves = 4;  // waves per workgroup
+constexpr int kEpl = 8;    // elements per lane
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct AppendArgs {
   DevGeom g;
@@ -30,18 +34,18 @@ struct AppendArgs {
   const float* k_scale;  // FP8: device [H] for this layer
   const float* v_scale;
   int64_t n_rows;        // n_tokens * H * 2
+  int32_t lpr_shift;     // log2 of the lanes per row (head_dim / 8)
   int64_t n_blocks;      // valid block ids are [0, n_blocks)
   int32_t layer, max_blocks;
 };
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+// max / min over the lanes of a row (lpr neighbouring lanes, lpr a power of two)
+__device__ __forceinline__ float row_max(float v, int lpr) {
+  for (int o = lpr >> 1; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
   return v;
 }
-__device__ __forceinline__ float wave_min(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+__device__ __forceinline__ float row_min(float v, int lpr) {
+  for (int o = lpr >> 1; o >= 1; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
   return v;
 }
 
@@ -80,16 +84,21 @@ __device__ __forceinline__ uint32_t e4m3_bits(float y) {
   return sign | code;
 }
 
+// the lane's eight source elements, widened exactly
 template <bool kSrcF32>
-__device__ __forceinline__ void load_pair(const void* src, int64_t idx, float& a, float& b) {
+__device__ __forceinline__ void load8(const void* src, int64_t idx, float (&x)[kEpl]) {
   if (kSrcF32) {
-    const float2 v = *reinterpret_cast<const float2*>(reinterpret_cast<const float*>(src) + idx);
-    a = v.x;
-    b = v.y;
+    const float4 a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(src) + idx);
+    const float4 b = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(src) + idx + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
   } else {
-    const uint32_t v = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(src) + idx);
-    a = f16_value((uint16_t)(v & 0xFFFF));
-    b = f16_value((uint16_t)(v >> 16));
+    const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(src) + idx);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      x[2 * q] = f16_value((uint16_t)(v[q] & 0xFFFF));
+      x[2 * q + 1] = f16_value((uint16_t)(v[q] >> 16));
+    }
   }
 }
 
@@ -99,92 +108,90 @@ __global__ __launch_bounds__(kWaves * 64) void kv_append_kernel(AppendArgs A) {
   const int wave = threadIdx.x >> 6;
   const DevGeom& g = A.g;
   const int D = g.D;
-  const int n_iter = (D + 127) >> 7;
-  for (int64_t r = (int64_t)blockIdx.x * kWaves + wave; r < A.n_rows; r += (int64_t)gridDim.x * kWaves) {
+  const int lpr = 1 << A.lpr_shift;           // lanes per row
+  const int rpw = 64 >> A.lpr_shift;          // rows per wave
+  const int lir = lane & (lpr - 1);           // lane within its row
+  const int riw = lane >> A.lpr_shift;        // row within the wave
+  const int64_t n_groups = (A.n_rows + rpw - 1) / rpw;
+  for (int64_t grp = (int64_t)blockIdx.x * kWaves + wave; grp < n_groups; grp += (int64_t)gridDim.x * kWaves) {
+    const int64_t r = grp * rpw + riw;
+    // Lanes of a row agree on every test below; a row that is skipped computes on zeros and stores nothing, so
+    // the shuffles stay unconditional.
+    bool ok = r < A.n_rows;
     const int which = (int)(r & 1);
     const int64_t th = r >> 1;
     const int head = (int)(th % g.H);
-    const int64_t tok = th / g.H;
-    const int p = A.pos[tok];
-    const int s = A.seq_idx[tok];
-    if (p < 0 || s < 0) continue;
-    const int bi = p / g.T;
-    if (bi >= A.max_blocks) continue;
+    const int64_t tok = ok ? th / g.H : 0;
+    const int p = ok ? A.pos[tok] : -1;
+    const int s = ok ? A.seq_idx[tok] : -1;
+    ok = ok && p >= 0 && s >= 0;
+    const int bi = ok ? p / g.T : 0;
+    ok = ok && bi < A.max_blocks;
     const int tib = p - bi * g.T;
-    const int32_t blk = A.tables[(int64_t)s * A.max_blocks + bi];
-    if (blk < 0 || blk >= A.n_blocks) continue;  // never write outside the pool
-    uint8_t* chunk = A.pool + (uint64_t)blk * g.block_budget + (uint64_t)A.layer * g.layer_bytes +
+    const int32_t blk = ok ? A.tables[(int64_t)s * A.max_blocks + bi] : -1;
+    ok = ok && blk >= 0 && blk < A.n_blocks;  // never write outside the pool
+    uint8_t* chunk = A.pool + (uint64_t)(ok ? blk : 0) * g.block_budget + (uint64_t)A.layer * g.layer_bytes +
                      (uint64_t)head * g.head_chunk;
-    uint8_t* row = chunk + (which ? g.kv_tile : 0u) + (uint64_t)tib * g.row_bytes;
-    uint8_t* par = chunk + 2u * g.kv_tile + (which ? g.par_tile : 0u) + (uint64_t)tib * (uint32_t)g.param_bytes;
+    uint8_t* row = chunk + (which ? g.kv_tile : 0u) + (uint64_t)(ok ? tib : 0) * g.row_bytes;
+    uint8_t* par = chunk + 2u * g.kv_tile + (which ? g.par_tile : 0u) + (uint64_t)(ok ? tib : 0) * (uint32_t)g.param_bytes;
     const void* src = which ? A.v_new : A.k_new;
-    const int64_t src_row = (tok * g.H + head) * (int64_t)D;
+    const int d0 = lir * kEpl;                // this lane's first element (head_dim >= 8: always inside the row)
 
-    float xa[kMaxPairIters], xb[kMaxPairIters];
+    float x[kEpl];
 #pragma unroll
-    for (int it = 0; it < kMaxPairIters; ++it) {
-      xa[it] = 0.f;
-      xb[it] = 0.f;
-      const int d = it * 128 + lane * 2;
-      if (it < n_iter && d < D) load_pair<kSrcF32>(src, src_row + d, xa[it], xb[it]);
-    }
+    for (int q = 0; q < kEpl; ++q) x[q] = 0.f;
+    if (ok) load8<kSrcF32>(src, (tok * g.H + head) * (int64_t)D + d0, x);
 
     if (g.dtype == FS_KV_FP16) {
+      u32x4 w;
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) {
-        const int d = it * 128 + lane * 2;
-        if (it < n_iter && d < D)
-          *reinterpret_cast<uint32_t*>(row + 2 * d) = (uint32_t)f16_bits(xa[it]) | ((uint32_t)f16_bits(xb[it]) << 16);
-      }
+      for (int q = 0; q < 4; ++q) w[q] = (uint32_t)f16_bits(x[2 * q]) | ((uint32_t)f16_bits(x[2 * q + 1]) << 16);
+      if (ok) *reinterpret_cast<u32x4*>(row + 2 * d0) = w;
     } else if (g.dtype == FS_KV_FP8_E4M3) {
       const float sc = (which ? A.v_scale : A.k_scale)[head];
+      u32x2 w = {0u, 0u};
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) {
-        const int d = it * 128 + lane * 2;
-        if (it < n_iter && d < D) {
-          const uint32_t c0 = e4m3_bits(__fdiv_rn(xa[it], sc)), c1 = e4m3_bits(__fdiv_rn(xb[it], sc));
-          *reinterpret_cast<uint16_t*>(row + d) = (uint16_t)(c0 | (c1 << 8));
-        }
-      }
+      for (int q = 0; q < kEpl; ++q) w[q >> 2] |= e4m3_bits(__fdiv_rn(x[q], sc)) << (8 * (q & 3));
+      if (ok) *reinterpret_cast<u32x2*>(row + d0) = w;
     } else if (g.dtype == FS_KV_INT8) {
       float amax = 0.f;
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) amax = fmaxf(amax, fmaxf(fabsf(xa[it]), fabsf(xb[it])));
-      amax = wave_max(amax);
+      for (int q = 0; q < kEpl; ++q) amax = fmaxf(amax, fabsf(x[q]));
+      amax = row_max(amax, lpr);
       const uint16_t sb = scale_bits(__fdiv_rn(amax, 127.0f));
       const float sf = f16_value(sb);
+      u32x2 w = {0u, 0u};
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) {
-        const int d = it * 128 + lane * 2;
-        if (it < n_iter && d < D) {
-          const float q0 = fminf(fmaxf(rintf(__fdiv_rn(xa[it], sf)), -127.f), 127.f);
-          const float q1 = fminf(fmaxf(rintf(__fdiv_rn(xb[it], sf)), -127.f), 127.f);
-          *reinterpret_cast<uint16_t*>(row + d) = (uint16_t)(((uint32_t)(int)q0 & 0xFF) | (((uint32_t)(int)q1 & 0xFF) << 8));
-        }
+      for (int q = 0; q < kEpl; ++q) {
+        const float c = fminf(fmaxf(rintf(__fdiv_rn(x[q], sf)), -127.f), 127.f);
+        w[q >> 2] |= ((uint32_t)(int)c & 0xFF) << (8 * (q & 3));
       }
-      if (lane == 0) *reinterpret_cast<uint16_t*>(par) = sb;
+      if (ok) {
+        *reinterpret_cast<u32x2*>(row + d0) = w;
+        if (lir == 0) *reinterpret_cast<uint16_t*>(par) = sb;
+      }
     } else {  // FS_KV_INT4
       float lo = 0.f, hi = 0.f;
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) {
-        lo = fminf(lo, fminf(xa[it], xb[it]));
-        hi = fmaxf(hi, fmaxf(xa[it], xb[it]));
+      for (int q = 0; q < kEpl; ++q) {
+        lo = fminf(lo, x[q]);
+        hi = fmaxf(hi, x[q]);
       }
-      lo = wave_min(lo);
-      hi = wave_max(hi);
+      lo = row_min(lo, lpr);
+      hi = row_max(hi, lpr);
       const uint16_t sb = scale_bits(__fdiv_rn(hi - lo, 15.0f));
       const float sf = f16_value(sb);
       const float z = fminf(fmaxf(rintf(__fdiv_rn(-lo, sf)), 0.f), 15.f);
+      uint32_t w = 0;
 #pragma unroll
-      for (int it = 0; it < kMaxPairIters; ++it) {
-        const int d = it * 128 + lane * 2;
-        if (it < n_iter && d < D) {
-          const float q0 = fminf(fmaxf(rintf(__fdiv_rn(xa[it], sf)) + z, 0.f), 15.f);
-          const float q1 = fminf(fmaxf(rintf(__fdiv_rn(xb[it], sf)) + z, 0.f), 15.f);
-          row[d >> 1] = (uint8_t)((uint32_t)q0 | ((uint32_t)q1 << 4));
-        }
+      for (int q = 0; q < kEpl; ++q) {
+        const float c = fminf(fmaxf(rintf(__fdiv_rn(x[q], sf)) + z, 0.f), 15.f);
+        w |= (uint32_t)c << (4 * q);  // element 2j in the low nibble of byte j
       }
-      if (lane == 0) *reinterpret_cast<uint32_t*>(par) = (uint32_t)sb | ((uint32_t)f16_bits(z) << 16);
+      if (ok) {
+        *reinterpret_cast<uint32_t*>(row + (d0 >> 1)) = w;
+        if (lir == 0) *reinterpret_cast<uint32_t*>(par) = (uint32_t)sb | ((uint32_t)f16_bits(z) << 16);
+      }
     }
   }
 }
@@ -206,6 +213,10 @@ extern "C" int fs_kv_append(fs_pool* p, fs_model_t model, int layer, const void*
   if (n_tokens < 0 || layer < 0 || layer >= M.g.n_layers || !k_new || !v_new || !seq_idx || !pos || !block_tables ||
       max_blocks < 1 || (src_dtype != FS_SRC_FP16 && src_dtype != FS_SRC_FP32)) {
     set_error("fs_kv_append: invalid argument");
+    return FS_ERR_INVALID;
+  }
+  if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) {
+    set_error("fs_kv_append: k_new and v_new must be 16-byte aligned");
     return FS_ERR_INVALID;
   }
   if (M.g.kv_dtype == FS_KV_FP8_E4M3 && !M.d_k_scale) {
@@ -230,7 +241,11 @@ extern "C" int fs_kv_append(fs_pool* p, fs_model_t model, int layer, const void*
   A.n_blocks = (int64_t)(p->pool_bytes / M.g.block_budget);
   A.layer = layer;
   A.max_blocks = max_blocks;
-  int64_t blocks = (A.n_rows + kWaves - 1) / kWaves;
+  int lpr_shift = 0;
+  while ((kEpl << lpr_shift) < M.g.head_dim) ++lpr_shift;  // head_dim is a power of two >= 8
+  A.lpr_shift = lpr_shift;
+  const int64_t rows_per_wg = (int64_t)kWaves * (64 >> lpr_shift);
+  int64_t blocks = (A.n_rows + rows_per_wg - 1) / rows_per_wg;
   const int64_t cap = (int64_t)p->n_cu * 64;
   if (blocks > cap) blocks = cap;
   hipStream_t s = (hipStream_t)stream;

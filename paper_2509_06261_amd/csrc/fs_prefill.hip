@@ -927,8 +927,326 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Software-pipelined workgroup variant (4 waves x 64 columns, one wave per SIMD).  The compiler emits a tile's
+// MFMAs and its softmax as separate bursts, and the step barrier keeps the waves of a SIMD in phase, so in the
+// variants above the matrix cores idle during every softmax.  Here one wave overlaps the two itself: while the
+// vector ALU exponentiates sub-tile s, the MFMAs of S^T for sub-tile s + 1 are issued between its instructions
+// (block 1); while the MFMAs of P V for sub-tile s run, the vector ALU turns the new S^T into logits and column
+// maxima (block 2); scheduling-group barriers pin the interleave (one MFMA, then a few vector instructions).
+// The pipeline is restarted at every step (S^T of the step's first sub-tile runs alone; block 1 of the last
+// sub-tile multiplies the step's first sub-tile again and discards it): carrying it across the step barrier
+// would let a fast wave overwrite a stage that a slow wave still reads.
+// ---------------------------------------------------------------------------------------------------------
+template <int DT, int NCB>
+struct Logits {
+  float x[NCB][8];   // logits (parameter formats) or raw products (FP16, FP8)
+  float tmax[NCB];   // column maxima, base-2 domain
+  float va[8], vb2[8];  // parameter formats: per-token V factors for the weights of this sub-tile
+};
+
+// S^T accumulators -> logits, masks, column maxima.  Returns whether some column's reference must move.
+template <int DT, int NCB, int SUBS>
+__device__ __forceinline__ bool make_logits(const float4v (&s)[NCB][2], const uint8_t* stage, int sub, const ItemCtx& X,
+                                            const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
+                                            int vb, int lane, int c, const WideState<NCB>& st, Logits<DT, NCB>& out) {
+  using F = Fmt<DT>;
+  const RunLoc L = locate(X, vb + (lane >> 4));
+  const bool interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);  // wave-uniform
+  float ka[8], kb[8];
+  if constexpr (F::kParBytes != 0) {
+    const uint32_t par = *reinterpret_cast<const uint32_t*>(stage + stage_par(SUBS) + sub * 256 + lane * 4);
+    float pa, pb;
+    const float sc = f16lo(par);
+    const float zp = DT == FS_KV_INT4 ? f16hi(par) : 128.0f;
+    if (c < 8) {
+      pa = alpha * kTwo24 * sc;
+      pb = -alpha * sc * zp;
+    } else {
+      const bool ok = (c & 7) >= L.lo && (c & 7) < L.hi_u;
+      pa = ok ? sc : 0.f;
+      pb = ok ? -sc * zp : 0.f;
+    }
+    static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+      constexpr int i = decltype(I)::value;
+      ka[i] = row_bcast<i>(pa);
+      kb[i] = row_bcast<i>(pb);
+      out.va[i] = row_bcast<8 + i>(pa);
+      out.vb2[i] = row_bcast<8 + i>(pb);
+    });
+  }
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float v = s[cb][i >> 2][i & 3];
+      if constexpr (F::kParBytes != 0) out.x[cb][i] = fmaf(v, ka[i], kb[i] * qsum[cb]);
+      else out.x[cb][i] = v;
+    }
+  auto maxima = [&]() {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      float mx = fmaxf(fmaxf(out.x[cb][0], out.x[cb][1]), out.x[cb][2]);
+      mx = fmaxf(fmaxf(mx, out.x[cb][3]), out.x[cb][4]);
+      mx = fmaxf(fmaxf(mx, out.x[cb][5]), out.x[cb][6]);
+      mx = fmaxf(mx, out.x[cb][7]);
+      if constexpr (F::kParBytes == 0) mx *= alpha;
+      out.tmax[cb] = mx;
+    }
+  };
+  maxima();  // in the straight-line part, beside the caller's MFMAs; redone below on the rare masked tiles
+  __builtin_amdgcn_sched_barrier(0);
+  if (!interior) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int hi = min(L.hi_u, len_cb[cb] - L.tok0);
+      const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out.x[cb][i] = (uint32_t)(i - L.lo) < n_ok ? out.x[cb][i] : -INFINITY;
+    }
+    maxima();
+  }
+  bool need = false;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) need |= out.tmax[cb] - st.m[cb] > kTau;
+  return need;
+}
+
+template <int DT>
+__device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt, uint8_t* smem, uint64_t* s_tab, int w) {
+  constexpr int NW = 4, NCB = 4, SUBS = 4;
+  using F = Fmt<DT>;
+  const DevBatch& B = P.b;
+  const DevGeom& g = B.g;
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  const int j = lane >> 4, c = lane & 15;
+  const int G = B.G;
+  const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
+  int len = B.seq_lens[seq];
+  len = len < 1 ? 1 : min(len, max_len);
+  int n_new = P.q_offsets[seq + 1] - P.q_offsets[seq];
+  n_new = n_new < 0 ? 0 : min(n_new, len);
+  const int qw = P.tpt * NCB;
+  const int r0_wg = qt * qw * NW;
+  if (r0_wg >= n_new) return;
+  const int n_tok_wg = min(qw * NW, n_new - r0_wg);
+  const int r0 = r0_wg + w * qw;
+  const int n_tok = max(0, min(qw, n_tok_wg - w * qw));
+  const int first_pos = len - n_new + r0;
+  const int tok_c = c / G, hg_c = c - tok_c * G;
+
+  ItemCtx X;
+  X.T = g.T;
+  X.R = B.R;
+  X.r_magic = B.r_magic;
+  X.len_u = len - n_new + r0_wg + n_tok_wg;
+  X.len = X.len_u;
+  X.chunk_ptr = s_tab;
+
+  u32x4 qb[NCB][4];
+  float qsum[NCB];
+  int len_cb[NCB], row_cb[NCB];
+  float alpha = B.sm_scale * kLog2e;
+  if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
+  WideState<NCB> st;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int tok = cb * P.tpt + tok_c;
+    const bool live = tok_c < P.tpt && tok < n_tok;
+    len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;
+    row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
+    load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
+    settle_q(qb[cb]);
+    if constexpr (F::kParBytes != 0) {
+      qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
+      qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[cb][e] = float4v{0.f, 0.f, 0.f, 0.f};
+    st.m[cb] = -INFINITY;
+    st.l[cb] = 0.f;
+    st.zc[cb] = 0.f;
+  }
+
+  const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
+  const uint8_t* head_base = B.layer_base + (uint64_t)head * g.head_chunk;
+  const int n_run = n_runs(X.len_u, g.T, B.R);
+  for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
+    X.v_end = min(n_run, v0 + P.seg_runs);
+    X.k0 = div_runs(v0, B.R, B.r_magic);
+    {
+      const int nb = div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1;
+      for (int i = threadIdx.x; i < nb; i += NW * 64)
+        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
+      __syncthreads();
+    }
+    const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
+    Tile<DT, 16> t;
+    issue_k<DT, 16>(X, v0 + 4 * w, j, c, t);
+    issue_v<DT, 16>(X, g, v0 + 4 * w, j, c, t);
+    stage_k<DT>(smem, w, lane, t);
+    stage_v<DT, SUBS>(smem, w, lane, j, t, X, v0 + 4 * w);
+    __syncthreads();
+    for (int i = 0; i < n_super; ++i) {
+      const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * w;
+      issue_k<DT, 16>(X, vb_next, j, c, t);
+      issue_v<DT, 16>(X, g, vb_next, j, c, t);
+      const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
+      const uint8_t* lane_base = stage + lane * 16;
+      // ---- pipeline start: S^T and logits of the step's first sub-tile ----
+      u32x4 kf[2][4];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kf[u][ks] = *reinterpret_cast<const u32x4*>(lane_base + (uint32_t)((u * 4 + ks) * kFrag));
+      float4v sn[NCB][2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          float4v a4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) a4 = mfma(kf[u][ks], qb[cb][ks], a4);
+          sn[cb][u] = a4;
+        }
+      Logits<DT, NCB> cur;
+      if (__any(make_logits<DT, NCB, SUBS>(sn, stage, 0, X, qsum, len_cb, alpha, first_pos, v0 + i * 4 * SUBS, lane, c, st, cur))) {
+        acc_settle();
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, cur.tmax[cb], j);
+      }
+#pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
+      for (int sub = 0; sub < SUBS; ++sub) {
+        const int nsub = (sub + 1) & (SUBS - 1);  // after the last sub-tile: the first again, its result unused
+        // ---- block 1: S^T of sub-tile nsub (MFMA) beside the exponentials of sub-tile sub (vector ALU) ----
+        u32x4 vf[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vf[e] = *reinterpret_cast<const u32x4*>(lane_base + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag));
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks)
+            kf[u][ks] = *reinterpret_cast<const u32x4*>(lane_base + (uint32_t)((nsub * 8 + u * 4 + ks) * kFrag));
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) {
+            float4v a4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) a4 = mfma(kf[u][ks], qb[cb][ks], a4);
+            sn[cb][u] = a4;
+          }
+        u32x4 pk[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          const float m = st.m[cb];
+          if constexpr (F::kParBytes != 0) {
+            float pw[8], lsum = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const float ex = __builtin_amdgcn_exp2f(cur.x[cb][q] - m);
+              lsum += ex;
+              pw[q] = ex * cur.va[q];
+              st.zc[cb] = fmaf(ex, cur.vb2[q], st.zc[cb]);
+            }
+            st.l[cb] += lsum;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const half2v h = {(_Float16)pw[2 * q], (_Float16)pw[2 * q + 1]};
+              pk[cb][q] = h2u(h);
+            }
+          } else {
+            const half2v one = {(_Float16)1.0f, (_Float16)1.0f};
+            float l = st.l[cb];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float e0 = __builtin_amdgcn_exp2f(fmaf(cur.x[cb][2 * q], alpha, -m));
+              const float e1 = __builtin_amdgcn_exp2f(fmaf(cur.x[cb][2 * q + 1], alpha, -m));
+              const half2v h = {(_Float16)e0, (_Float16)e1};
+              pk[cb][q] = h2u(h);
+              l = __builtin_amdgcn_fdot2(h, one, l, false);
+            }
+            st.l[cb] = l;
+          }
+        }
+        // one MFMA, then a few vector instructions, 32 times
+#pragma unroll
+        for (int r = 0; r < 2 * NCB * 4; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // VALU
+          __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);  // transcendental
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- block 2: P V of sub-tile sub (MFMA) beside the logits of sub-tile nsub (vector ALU) ----
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) st.acc[cb][e] = mfma(pk[cb], vf[e], st.acc[cb][e]);
+#pragma unroll
+        for (int r = 0; r < 8 * NCB; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 2, 1);  // VALU
+        }
+        const bool need = make_logits<DT, NCB, SUBS>(sn, stage, nsub, X, qsum, len_cb, alpha, first_pos,
+                                                     v0 + (i * SUBS + nsub) * 4, lane, c, st, cur);
+        if (sub + 1 < SUBS && __any(need)) {  // (the wrapped-around sub-tile's logits are discarded)
+          acc_settle();
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, cur.tmax[cb], j);
+        }
+      }
+      uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
+      stage_k<DT>(next, w, lane, t);
+      stage_v<DT, SUBS>(next, w, lane, j, t, X, vb_next);
+      __syncthreads();
+    }
+  }
+  if (n_tok == 0) return;
+
+  const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    float l = st.l[cb], zc = st.zc[cb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if constexpr (F::kParBytes != 0) {
+      zc += __shfl_xor(zc, 16, 64);
+      zc += __shfl_xor(zc, 32, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int h = 4 * j + r;
+      const float Lh = __shfl(l, h, 64), M = __shfl(st.m[cb], h, 64), Z = __shfl(zc, h, 64);
+      const int row_h = __shfl(row_cb[cb], h, 64);
+      const int tok_h = h / G, hg_h = h - tok_h * G;
+      if (tok_h < P.tpt && cb * P.tpt + tok_h < n_tok) {
+        const float inv = 1.0f / Lh;
+        u32x4 wv;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float o[2];
+#pragma unroll
+          for (int z = 0; z < 2; ++z) {
+            const int e = 2 * q + z;
+            const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+            o[z] = st.acc[cb][e][r] * f;
+            if constexpr (F::kParBytes != 0) o[z] += Z;
+            o[z] *= v_static * inv;
+          }
+          const half2v hv = {(_Float16)o[0], (_Float16)o[1]};
+          wv[q] = h2u(hv);
+        }
+        const int64_t qrow = (int64_t)row_h * B.n_q + head * G + hg_h;
+        *reinterpret_cast<u32x4*>(B.out + qrow * kD + 8 * c) = wv;
+        if (c == 0 && B.lse) B.lse[qrow] = (M + __builtin_amdgcn_logf(Lh)) * kLn2;
+      }
+    }
+  }
+}
+
 // WPC = workgroups per compute unit the kernel is built for
-template <int DT, int NW, int NCB, int SUBS, int WPC>
+template <int DT, int NW, int NCB, int SUBS, int WPC, bool PIPE = false>
 __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   uint8_t* smem = reinterpret_cast<uint8_t*>(smem64);
@@ -953,7 +1271,8 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
     if (item == 0xffffffffu) break;
     int seq, head, qt;
     if (!decode_item(P, item, H, seq, head, qt)) continue;
-    prefill_item_wg<DT, NW, NCB, SUBS>(P, seq, head, qt, smem, s_tab, wave);
+    if constexpr (PIPE) prefill_item_wgp<DT>(P, seq, head, qt, smem, s_tab, wave);
+    else prefill_item_wg<DT, NW, NCB, SUBS>(P, seq, head, qt, smem, s_tab, wave);
   }
 }
 
@@ -986,7 +1305,7 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 using namespace fs;
 
 namespace {
-int g_prefill_ncb = 0, g_prefill_nw = 0;
+int g_prefill_ncb = 0, g_prefill_nw = 0, g_prefill_pipe = 0;
 }
 
 int fs_set_prefill_kernel(int column_blocks, int waves) {
@@ -997,6 +1316,11 @@ int fs_set_prefill_kernel(int column_blocks, int waves) {
   if (!ok_c || (waves != 0 && waves != 4 && waves != 8)) return FS_ERR_INVALID;
   g_prefill_ncb = column_blocks;
   g_prefill_nw = waves;
+  return FS_OK;
+}
+
+int fs_set_prefill_pipelined(int enable) {
+  g_prefill_pipe = enable != 0;
   return FS_OK;
 }
 
@@ -1124,7 +1448,10 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
                          : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
   if (wg) {
     void (*kern)(PrefillArgs) = nullptr;
-#define FS_WG(DT) (ncb == 8 ? prefill_wg_kernel<DT, 4, 2, 2, 2> : (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1> : prefill_wg_kernel<DT, 4, 4, 4, 1>))
+#define FS_WG(DT)                                                                                          \
+  (ncb == 8 ? prefill_wg_kernel<DT, 4, 2, 2, 2>                                                            \
+            : (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1>                                                 \
+                       : (g_prefill_pipe ? prefill_wg_kernel<DT, 4, 4, 4, 1, true> : prefill_wg_kernel<DT, 4, 4, 4, 1>)))
     switch (g.kv_dtype) {
       case FS_KV_FP16: kern = FS_WG(FS_KV_FP16); break;
       case FS_KV_FP8_E4M3: kern = FS_WG(FS_KV_FP8_E4M3); break;

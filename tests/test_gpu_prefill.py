@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 # (name, column blocks, waves) for fs_set_prefill_kernel.  The workgroup kernel with 8 waves (what large launches
 # run) takes every test; the automatic choice (the 16-column kernel on launches this small) the four-format and
 # the two-model tests; the other variants the four-format test on FP16 and INT4 (without and with parameters).
-VARIANTS = [("wg8", 16, 8), ("auto", 0, 0), ("wg4", 16, 4), ("wg4x2", 8, 4), ("cols32", 2, 0), ("cols64", 4, 0)]
+VARIANTS = [("wg8", 16, 8), ("auto", 0, 0), ("wg4", 16, 4), ("wg4p", 16, 4), ("wg4x2", 8, 4), ("cols32", 2, 0), ("cols64", 4, 0)]
 
 
 @pytest.fixture(params=VARIANTS, ids=[v[0] for v in VARIANTS], autouse=True)
@@ -22,14 +22,18 @@ def kernel_variant(request):
     test = request.node.name
     if name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
         pytest.skip("the automatic choice is covered by the four-format and two-model tests")
-    if name not in ("wg8", "auto") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
+    if name == "wg4p" and not test.startswith(("test_gqa_8b_shape", "test_mha_13b", "test_long_context")):
+        pytest.skip("the pipelined variant takes the four-format, odd-block and long-context tests")
+    if name not in ("wg8", "auto", "wg4p") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
         pytest.skip("variant covered by the four-format test on FP16 and INT4")
     if name == "wg4x2":
         assert fs.fs_set_prefill_kernel(blocks, waves) != 0  # refused by the library
         pytest.skip("variant switched off in the library: a full-size run faulted or hung the GPU, cause not found")
     assert fs.fs_set_prefill_kernel(blocks, waves) == 0
+    fs.fs_set_prefill_pipelined(name == "wg4p")  # the software-pipelined form of the 4-wave workgroup kernel
     yield name
     fs.fs_set_prefill_kernel(0, 0)
+    fs.fs_set_prefill_pipelined(0)
 
 
 def _parity(wl):
