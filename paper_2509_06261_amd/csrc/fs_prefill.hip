@@ -33,6 +33,7 @@ struct PrefillArgs {
   int32_t seg_runs;          // runs of 8 token slots streamed per refill of the block-address table (multiple of 4)
   int32_t table_entries;     // LDS table entries per wave
   int32_t n_rows;            // query rows in q / out (host value: every row index is clamped into it)
+  int32_t tf_cache;          // workgroup kernels: 1 = tile_first is copied into LDS at kernel start
 };
 
 constexpr int kPrepThreads = 1024;
@@ -530,16 +531,18 @@ __device__ __forceinline__ uint32_t home_pool(uint32_t worker) {  // worker: ind
 }
 
 // item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
-__device__ __forceinline__ bool decode_item(const PrefillArgs& P, uint32_t item, uint32_t H, int& seq, int& head, int& qt) {
+// tf: tile_first, in global memory or its copy in LDS (ten dependent look-ups: a round trip to memory each otherwise)
+__device__ __forceinline__ bool decode_item(const PrefillArgs& P, const uint32_t* tf, uint32_t item, uint32_t H, int& seq,
+                                            int& head, int& qt) {
   int lo = 0, hi = P.b.n_seq - 1;
   while (lo < hi) {  // last sequence whose first item is <= item
     const int mid = (lo + hi + 1) >> 1;
-    if (P.tile_first[mid] * H <= item) lo = mid;
+    if (tf[mid] * H <= item) lo = mid;
     else hi = mid - 1;
   }
-  const uint32_t nt = P.tile_first[lo + 1] - P.tile_first[lo];
+  const uint32_t nt = tf[lo + 1] - tf[lo];
   if (nt == 0) return false;  // (cannot happen: an item lies in a sequence that has tiles)
-  const uint32_t li = item - P.tile_first[lo] * H;
+  const uint32_t li = item - tf[lo] * H;
   seq = lo;
   head = (int)(li / nt);
   qt = (int)(nt - 1 - li % nt);
@@ -595,7 +598,7 @@ __global__ __launch_bounds__(kThreads, WPS) void prefill_wide_kernel(PrefillArgs
   ItemDraw d = first_draw(P.header, (blockIdx.x >> 3) * kWaves + wave, lane);
   for (uint32_t item; next_item(d, P.header, total, kWaveChunkShift, lane, item);) {
     int seq, head, qt;
-    if (!decode_item(P, item, H, seq, head, qt)) continue;
+    if (!decode_item(P, P.tile_first, item, H, seq, head, qt)) continue;
     prefill_item_wide<DT, NCB>(P, seq, head, qt, s_ptr);
   }
 }
@@ -1257,6 +1260,13 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t H = (uint32_t)B.g.H;
   const uint32_t total = P.tile_first[B.n_seq] * H;
+  const uint32_t* tf = P.tile_first;
+  if (P.tf_cache) {  // (uniform)
+    uint32_t* s_tf = reinterpret_cast<uint32_t*>(smem + 2 * stage_bytes(SUBS) + (size_t)P.table_entries * 8 + kWgCtlBytes);
+    for (int i = threadIdx.x; i <= B.n_seq; i += NW * 64) s_tf[i] = P.tile_first[i];
+    __syncthreads();
+    tf = s_tf;
+  }
   ItemDraw d{0u, 0u};
   if (wave == 0) d = first_draw(P.header, blockIdx.x >> 3, lane);
   for (;;) {
@@ -1270,7 +1280,7 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
     __syncthreads();  // everyone holds the item before the next draw may overwrite it
     if (item == 0xffffffffu) break;
     int seq, head, qt;
-    if (!decode_item(P, item, H, seq, head, qt)) continue;
+    if (!decode_item(P, tf, item, H, seq, head, qt)) continue;
     if constexpr (PIPE) prefill_item_wgp<DT>(P, seq, head, qt, smem, s_tab, wave);
     else prefill_item_wg<DT, NW, NCB, SUBS>(P, seq, head, qt, smem, s_tab, wave);
   }
@@ -1287,7 +1297,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
   ItemDraw d = first_draw(P.header, (blockIdx.x >> 3) * kWaves + wave, lane);
   for (uint32_t item; next_item(d, P.header, total, kWaveChunkShift, lane, item);) {
     int seq, head, qt;
-    if (!decode_item(P, item, H, seq, head, qt)) continue;
+    if (!decode_item(P, P.tile_first, item, H, seq, head, qt)) continue;
     switch (B.g.dtype) {
       case FS_KV_FP16: prefill_item<FS_KV_FP16>(P, seq, head, qt, s_ptr); break;
       case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3>(P, seq, head, qt, s_ptr); break;
@@ -1444,7 +1454,10 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   const int subs = ncb == 8 ? 2 : 4, wpc = ncb == 8 ? 2 : 1;
   const int n_wg = wg ? (int)std::min<uint64_t>((uint64_t)p->n_cu * wpc, std::max<uint64_t>(items, 1))
                       : (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
-  const size_t smem = wg ? 2 * (size_t)stage_bytes(subs) + (size_t)P.table_entries * 8 + kWgCtlBytes
+  // the per-sequence tile counts go to LDS while they fit beside the stages (16 KiB: 4095 sequences)
+  P.tf_cache = wg && (uint64_t)n_seq + 1 <= 4096;
+  const size_t smem = wg ? 2 * (size_t)stage_bytes(subs) + (size_t)P.table_entries * 8 + kWgCtlBytes +
+                               (P.tf_cache ? (((size_t)n_seq + 1) * 4 + 15) / 16 * 16 : 0)
                          : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
   if (wg) {
     void (*kern)(PrefillArgs) = nullptr;
