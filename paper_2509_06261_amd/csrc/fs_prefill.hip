@@ -836,7 +836,6 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
     load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
-    settle_q(qb[cb]);
     if constexpr (Fmt<DT>::kParBytes != 0) {
       qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
       qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
@@ -868,6 +867,9 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     if (does_k) stage_k<DT>(smem, sw, lane, t);
     if (does_v) stage_v<DT, SUBS>(smem, sw, lane, j, t, X, v0 + 4 * sw);
     __syncthreads();
+    // the query operands' loads, issued before the table and the first K/V fetch, are collected here
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) settle_q(qb[cb]);
     for (int i = 0; i < n_super; ++i) {
       // next step's sub-tile of this wave (past the segment's end: mapped onto its last run, never used)
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
@@ -1060,7 +1062,6 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
     len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
     load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
-    settle_q(qb[cb]);
     if constexpr (F::kParBytes != 0) {
       qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
       qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
@@ -1091,6 +1092,8 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
     stage_k<DT>(smem, w, lane, t);
     stage_v<DT, SUBS>(smem, w, lane, j, t, X, v0 + 4 * w);
     __syncthreads();
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) settle_q(qb[cb]);  // (issued before the table and the first K/V fetch)
     for (int i = 0; i < n_super; ++i) {
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * w;
       issue_k<DT, 16>(X, vb_next, j, c, t);
