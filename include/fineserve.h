@@ -197,8 +197,10 @@ int fs_decode_status(const void* workspace, void* stream);
  *   workspace: device memory of fs_prefill_workspace_bytes(n_seq) bytes, 256-byte aligned, owned by the caller,
  *            in use until the stream has passed the call.  fs_decode_status(workspace, stream) afterwards: bit 0
  *            set if a length or a chunk size was out of range (clamped).
- * Covers head_dim 128, at least 8 tokens per block, at most 16 query heads per KV head (FS_ERR_INVALID
- * otherwise).  A softmax scale that is not positive and finite is served by the slowest kernel variant.
+ * At most 16 query heads per KV head (FS_ERR_INVALID otherwise).  head_dim 128 with at least 8 tokens per block
+ * runs on the MFMA kernels; every other shape the pool accepts on a vector-ALU kernel (one workgroup per query
+ * row and KV head: correct, far slower).  A softmax scale that is not positive and finite is served by the
+ * slowest MFMA kernel variant.
  * Asynchronous on `stream`; no allocation, no host synchronisation. */
 uint64_t fs_prefill_workspace_bytes(int n_seq);
 int fs_prefill_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,

@@ -89,6 +89,7 @@ __device__ __host__ inline int n_splits(const DevBatch& B, int len) {
 // Launchers implemented in the kernel translation units.
 hipError_t launch_prep(const MultiArgs& A, hipStream_t s);
 hipError_t launch_generic(const MultiArgs& A, int n_workgroups, hipStream_t s);
+hipError_t launch_generic_prefill(const MultiArgs& A, const int32_t* q_offsets, int n_rows, int n_workgroups, hipStream_t s);
 hipError_t launch_combine(const MultiArgs& A, hipStream_t s);
 bool mfma_supports(const DevBatch& b);
 hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s);

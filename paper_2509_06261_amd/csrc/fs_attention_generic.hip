@@ -75,9 +75,12 @@ struct Bits {
 
 __device__ __forceinline__ float half_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 
-// One work item for KV format DT, GP query heads at a time.
+// One work item for KV format DT, GP query heads at a time.  Decode: qrow == seq and len_override == 0.  Prefill
+// (one query row of a chunk per item): q / out / lse are indexed by qrow, and the row attends to the first
+// len_override tokens of sequence seq in one piece (no split).
 template <int DT, int GP>
-__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, float* smem) {
+__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, float* smem,
+                             int64_t qrow, int len_override) {
   const DevBatch& B = A.b[b];
   const DevGeom& g = B.g;
   const int D = g.D, T = g.T, G = B.G;
@@ -88,9 +91,10 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   const int max_len = (int)min((int64_t)B.max_blocks * T, (int64_t)0x7fffffff);
   int len = B.seq_lens[seq];
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
-  const int n_chunks = (len + B.chunk_tokens - 1) / B.chunk_tokens;
-  const int t0 = chunk * B.chunk_tokens;
-  const int t1 = min(len, t0 + B.chunk_tokens);
+  if (len_override > 0) len = min(len, len_override);
+  const int n_chunks = len_override > 0 ? 1 : (len + B.chunk_tokens - 1) / B.chunk_tokens;
+  const int t0 = len_override > 0 ? 0 : chunk * B.chunk_tokens;
+  const int t1 = len_override > 0 ? len : min(len, t0 + B.chunk_tokens);
   const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
   constexpr int kElemBytes8 = Bits<DT>::value;  // bytes of 8 elements
   const float k_static = DT == FS_KV_FP8_E4M3 ? B.k_scale[head] : 1.0f;
@@ -99,7 +103,8 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
 
   // where this item's partial record goes (only used when the sequence is split)
   const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
-  const uint64_t part_base = part_off[b] + (uint64_t)item * (uint64_t)B.part_stride;  // item: index within the batch
+  const uint64_t part_base =
+      len_override > 0 ? 0 : part_off[b] + (uint64_t)item * (uint64_t)B.part_stride;  // item: index within the batch
   const bool part_ok = part_base + (uint64_t)B.part_stride <= A.part_capacity;
   if (n_chunks > 1 && !part_ok) {
     if (threadIdx.x == 0) atomicOr(A.header + kHdrStatus, 2u);
@@ -118,7 +123,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
         qf[j][i] = 0.f;
       }
       if (g0 + j < G) {
-        const _Float16* qp = B.q + ((int64_t)seq * B.n_q + head * G + g0 + j) * D + lig * 8;
+        const _Float16* qp = B.q + (qrow * B.n_q + head * G + g0 + j) * D + lig * 8;
 #pragma unroll
         for (int i = 0; i < 8; ++i) qf[j][i] = (float)qp[i];
       }
@@ -192,8 +197,8 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
       }
       const int h = head * G + g0 + j;
       if (n_chunks == 1) {
-        B.out[((int64_t)seq * B.n_q + h) * D + d] = (_Float16)(O / L);
-        if (d == 0 && B.lse) B.lse[(int64_t)seq * B.n_q + h] = M + logf(L);
+        B.out[(qrow * B.n_q + h) * D + d] = (_Float16)(O / L);
+        if (d == 0 && B.lse) B.lse[qrow * B.n_q + h] = M + logf(L);
       } else {
         float* pr = A.partials + part_base + (uint64_t)(g0 + j) * red_stride;
         pr[d] = O;
@@ -209,14 +214,24 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
 
 template <int DT>
 __device__ __forceinline__ void dispatch_gp(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item,
-                                            float* smem) {
+                                            float* smem, int64_t qrow, int len_override) {
   const int G = A.b[b].G;
   if (G == 1)
-    process_item<DT, 1>(A, b, seq, chunk, head, item, smem);
+    process_item<DT, 1>(A, b, seq, chunk, head, item, smem, qrow, len_override);
   else if (G == 2)
-    process_item<DT, 2>(A, b, seq, chunk, head, item, smem);
+    process_item<DT, 2>(A, b, seq, chunk, head, item, smem, qrow, len_override);
   else
-    process_item<DT, 4>(A, b, seq, chunk, head, item, smem);
+    process_item<DT, 4>(A, b, seq, chunk, head, item, smem, qrow, len_override);
+}
+
+__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item,
+                                               float* smem, int64_t qrow, int len_override) {
+  switch (A.b[b].g.dtype) {
+    case FS_KV_FP16: dispatch_gp<FS_KV_FP16>(A, b, seq, chunk, head, item, smem, qrow, len_override); break;
+    case FS_KV_FP8_E4M3: dispatch_gp<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, item, smem, qrow, len_override); break;
+    case FS_KV_INT8: dispatch_gp<FS_KV_INT8>(A, b, seq, chunk, head, item, smem, qrow, len_override); break;
+    default: dispatch_gp<FS_KV_INT4>(A, b, seq, chunk, head, item, smem, qrow, len_override); break;
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void generic_attention_kernel(MultiArgs A) {
@@ -232,16 +247,46 @@ __global__ __launch_bounds__(kThreads) void generic_attention_kernel(MultiArgs A
     const int4 rec = A.item_list[item];
     const int b = rec_batch(rec), seq = rec.y, chunk = rec.z, head = rec_head(rec);
     const uint32_t local = (uint32_t)rec.w;  // the item's index within its batch: where its partial record goes
-    switch (A.b[b].g.dtype) {
-      case FS_KV_FP16: dispatch_gp<FS_KV_FP16>(A, b, seq, chunk, head, local, smem); break;
-      case FS_KV_FP8_E4M3: dispatch_gp<FS_KV_FP8_E4M3>(A, b, seq, chunk, head, local, smem); break;
-      case FS_KV_INT8: dispatch_gp<FS_KV_INT8>(A, b, seq, chunk, head, local, smem); break;
-      default: dispatch_gp<FS_KV_INT4>(A, b, seq, chunk, head, local, smem); break;
+    dispatch_dtype(A, b, seq, chunk, head, local, smem, seq, 0);
+  }
+}
+
+// Prefill over any shape the library accepts (the MFMA prefill kernels cover head_dim 128 with at least 8 tokens
+// per block): one workgroup per (query row, KV head), the decode work item with the row's causal length.  A.b[0]
+// is the model's batch (q / out / lse hold the chunk rows), q_offsets the chunks' first rows.
+__global__ __launch_bounds__(kThreads) void generic_prefill_kernel(MultiArgs A, const int32_t* q_offsets, int n_rows) {
+  extern __shared__ float smem[];
+  const DevBatch& B = A.b[0];
+  const int H = B.g.H;
+  const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
+  for (int64_t work = blockIdx.x; work < (int64_t)n_rows * H; work += gridDim.x) {  // uniform over the workgroup
+    const int row = (int)(work / H), head = (int)(work - (int64_t)row * H);
+    int lo = 0, hi = B.n_seq - 1;
+    while (lo < hi) {  // last sequence whose first row is <= row (sequences with empty chunks are passed over)
+      const int mid = (lo + hi + 1) >> 1;
+      if (q_offsets[mid] <= row) lo = mid;
+      else hi = mid - 1;
     }
+    int len = B.seq_lens[lo];
+    len = len < 1 ? 1 : min(len, max_len);
+    int n_new = q_offsets[lo + 1] - q_offsets[lo];
+    n_new = n_new < 0 ? 0 : min(n_new, len);
+    const int rr = row - q_offsets[lo];
+    if (rr < 0 || rr >= n_new) continue;  // (inconsistent device offsets: the row is left unwritten, flagged by the prep kernel)
+    dispatch_dtype(A, 0, lo, 0, head, 0u, smem, row, len - n_new + rr + 1);
   }
 }
 
 }  // namespace
+
+hipError_t launch_generic_prefill(const MultiArgs& A, const int32_t* q_offsets, int n_rows, int n_workgroups, hipStream_t s) {
+  const int D = A.b[0].g.D;
+  if (D & (D - 1)) return hipErrorInvalidValue;
+  const int gp = A.b[0].G == 1 ? 1 : (A.b[0].G == 2 ? 2 : 4);
+  const size_t smem = (size_t)(kThreads / (D >> 3)) * gp * (D + 2) * sizeof(float);
+  hipLaunchKernelGGL(generic_prefill_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A, q_offsets, n_rows);
+  return hipGetLastError();
+}
 
 hipError_t launch_generic(const MultiArgs& A, int n_workgroups, hipStream_t s) {
   size_t smem = 0;

@@ -1429,8 +1429,9 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.sm_scale = sm_scale;
   B.R = (g.tokens_per_block + 7) / 8;
   B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);
-  if (!mfma_supports(B)) {
-    set_error("prefill attention: needs head_dim 128 and at least 8 tokens per block");
+  const bool generic = !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
+  if (generic && (g.head_dim & (g.head_dim - 1))) {
+    set_error("prefill attention: head_dim must be a power of two");
     return FS_ERR_INVALID;
   }
   P.q_offsets = q_offsets;
@@ -1447,6 +1448,17 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   hipLaunchKernelGGL(prefill_prep_kernel, dim3(1), dim3(kPrepThreads), 0, s, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "prefill prep launch");
+  if (generic) {
+    // one workgroup per (query row, KV head) on the vector ALU: every shape the pool can hold
+    MultiArgs A{};
+    A.b[0] = B;
+    A.header = P.header;
+    A.n_batches = 1;
+    const uint64_t work = (uint64_t)n_rows * (uint64_t)g.n_kv_heads;
+    e = launch_generic_prefill(A, q_offsets, (int)n_rows, (int)std::min<uint64_t>(work, (uint64_t)p->n_cu * 8), s);
+    if (e != hipSuccess) return device_error(e, "prefill launch (generic kernel)");
+    return FS_OK;
+  }
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
   // waves per SIMD: the 16-column kernel runs two, the wider wave-level ones one
   const int wps = ncb == 1 ? 2 : 1;

@@ -20,7 +20,10 @@ def kernel_variant(request):
 
     name, blocks, waves = request.param
     test = request.node.name
-    if name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
+    if test.startswith("test_other_shapes"):
+        if name != "auto":
+            pytest.skip("shapes outside the MFMA kernels take the vector-ALU kernel whatever variant is set")
+    elif name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
         pytest.skip("the automatic choice is covered by the four-format and two-model tests")
     if name == "wg4p" and not test.startswith(("test_gqa_8b_shape", "test_mha_13b", "test_long_context")):
         pytest.skip("the pipelined variant takes the four-format, odd-block and long-context tests")
@@ -86,6 +89,28 @@ def test_group_sizes(group):
         par.gw.populate([[0]])
         print(par.prefill_and_check(0, 0, lens))
         print(par.prefill_and_check(0, 0, np.array([5, 3, 129, 40], np.int32)))
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("dtype,head_dim,kv_heads,q_heads,slab_kib,src_f32", [
+    (FP16, 64, 4, 4, 64, False),     # the tiny configuration's layer: head_dim 64, MHA
+    (INT8, 64, 2, 8, 64, False),     # head_dim 64, four query heads per KV head
+    (INT4, 256, 2, 4, 128, True),    # head_dim 256
+    (FP8, 32, 2, 6, 16, False),      # head_dim 32, three query heads per KV head (a ragged last group of the kernel)
+    (FP16, 128, 8, 8, 16, False),    # head_dim 128 in 16 KiB slabs: 2 tokens per block, fewer than an MFMA run
+])
+def test_other_shapes_take_the_vector_kernel(dtype, head_dim, kv_heads, q_heads, slab_kib, src_f32):
+    """Shapes the MFMA prefill kernels do not cover (head_dim other than 128, blocks of fewer than 8 tokens)."""
+    lens = np.array([1, 2, 7, 33, 100, 257], np.int32)
+    wl = Workload("pfgen", slab_kib * KiB, 32 * MiB,
+                  [ModelSpec("m", dtype, kv_heads, head_dim, 2, q_heads, lens, tag=37, src_f32=src_f32)], "shuffle")
+    par = _parity(wl)
+    try:
+        par.gw.populate([[1]])
+        print("T", par.gw.T)
+        print(par.prefill_and_check(0, 1, lens))
+        print(par.prefill_and_check(0, 1, np.array([1, 0, 3, 33, 17, 200], np.int32)))
     finally:
         par.close()
 
