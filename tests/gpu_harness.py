@@ -152,6 +152,76 @@ class Parity:
         assert lerr <= TOL_LSE, f"prefill model {k} ({s.name}): lse error {lerr:.3e}"
         return err, len(rows)
 
+    def prefill_whole_prompts_and_check_windows(self, k, layer, n_random, window=40):
+        """Whole-prompt fs_prefill_attention over ALL sequences of model k (KV of ``layer`` already appended), as the
+        prefill benchmark launches it.  For a seeded sample of sequences (with the shortest and the longest) the
+        query rows come from the seeded host generator; every other row is filler drawn on the device.  The oracle
+        recomputes three windows of ``window`` rows per sampled sequence (the first rows, rows around the middle, the
+        last rows; a row of a whole prompt at position r sees tokens 0..r, so a window [a, b) is the chunk of the
+        last b - a tokens of the sequence cut at b) and, for the shortest sequence, every row.
+        Returns (max abs error, rows compared)."""
+        import torch
+
+        gw, s = self.gw, self.wl.models[k]
+        m = gw.model_ids[k]
+        lens = gw.lens[k].astype(np.int64)
+        q_off = np.concatenate([[0], np.cumsum(lens)])
+        assert q_off[-1] < 2 ** 31
+        dev = gw.device
+        gen_t = torch.Generator(device=dev)
+        gen_t.manual_seed(int(self.wl.seed) + 977 * s.tag + layer)
+        q_d = torch.empty((int(q_off[-1]), s.n_q_heads, s.head_dim), dtype=torch.float16, device=dev)
+        q_d.normal_(generator=gen_t)
+        seqs = self.sample(k, n_random, tag=77)
+        q_host = {}
+        for i in seqs:
+            qi = gen.normal_q_chunks(self.wl.seed, s.tag, layer, [i], [0], [lens[i]], s.n_q_heads, s.head_dim)
+            q_host[int(i)] = qi
+            q_d[q_off[i]: q_off[i + 1]] = torch.from_numpy(qi).to(dev)
+        out_d = torch.full_like(q_d, float("nan"))
+        lse_d = torch.full((q_d.shape[0], s.n_q_heads), float("nan"), dtype=torch.float32, device=dev)
+        q_off32 = q_off.astype(np.int32)
+        q_off_d = torch.from_numpy(q_off32).to(dev)
+        ws = torch.empty(self.fs.fs_prefill_workspace_bytes(len(lens)), dtype=torch.uint8, device=dev)
+        scale = 1.0 / np.sqrt(s.head_dim)
+        self.fs.fs_prefill_attention(gw.pool, m, layer, s.n_q_heads, float(scale), q_d, gw.tables[k], gw.seq_lens[k],
+                                     q_off_d, q_off32, out_d, lse_d, ws)
+        torch.cuda.synchronize()
+        assert self.fs.fs_decode_status(ws) == 0
+        assert bool(torch.isfinite(out_d).all()) and bool(torch.isfinite(lse_d).all()), "a query row was left unwritten"
+        ref = self.oracle_sequences(k, layer, seqs)
+        shortest = int(seqs[np.argmin(lens[seqs])])
+        ctab, o_lens, n_new, q_rows, where = [], [], [], [], []
+        for r, i in enumerate(seqs):
+            n = int(lens[i])
+            if int(i) == shortest and n <= 1200:
+                wins = [(0, n)]
+            else:
+                w = min(window, n)
+                mid = max(w, min(n, n // 2 + w // 2))
+                wins = sorted({(0, w), (mid - w, mid), (n - w, n)})
+            for a, b in wins:
+                ctab.append(ref["ctab"][r])
+                o_lens.append(b)
+                n_new.append(b - a)
+                q_rows.append(q_host[int(i)][a:b])
+                where.append(np.arange(q_off[i] + a, q_off[i] + b))
+        sub_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        o_out, o_lse = oracle.prefill_attention(ref["mem"], self.ogeom[k], layer, s.n_q_heads, scale,
+                                                np.concatenate(q_rows), np.stack(ctab), np.asarray(o_lens, np.int32),
+                                                sub_off, ref["ks"], ref["vs"], n_threads=8)
+        rows = torch.from_numpy(np.concatenate(where)).to(dev)
+        out = out_d[rows].cpu().numpy().astype(np.float64)
+        lse = lse_d[rows].cpu().numpy().astype(np.float64)
+        tol = TOL_FP16 if s.kv_dtype == workloads.FP16 else TOL_QUANT
+        diff = np.abs(out - o_out)
+        err = float(np.max(diff))
+        assert np.all(diff <= tol + np.abs(o_out) * 2.0 ** -11), \
+            f"prefill model {k} ({s.name}): max abs error {err:.3e}, tolerance {tol} + |ref| 2^-11"
+        lerr = float(np.max(np.abs(lse - o_lse)))
+        assert lerr <= TOL_LSE, f"prefill model {k} ({s.name}): lse error {lerr:.3e}"
+        return err, len(rows)
+
     # ------------------------------------------------------------------ comparisons
     def check_bytes(self, k, ref):
         """Every byte the oracle's append defines must be identical in the GPU's slab blocks."""

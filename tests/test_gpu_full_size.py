@@ -3,7 +3,9 @@ the whole workload is placed and decoded in one multi-model launch; the allocato
 the oracle operation by operation over the complete trace; appended bytes and attention outputs are
 compared on a seeded sample of sequences per model (always including the shortest and the longest)
 that the CPU oracle recomputes one by one; every other sequence is cross-checked between the two
-independently written GPU kernels (MFMA vs generic)."""
+independently written GPU kernels (MFMA vs generic).  Whole-prompt prefill over the same full-size pools, as
+bench_prefill.py launches it (default kernel choice), is compared with the oracle on windows of query rows of
+sampled sequences."""
 import numpy as np
 import pytest
 
@@ -12,7 +14,7 @@ from fs_inputs import workloads
 pytestmark = pytest.mark.gpu
 
 
-def _full_size(cfg, layers, n_random):
+def _full_size(cfg, layers, n_random, prefill_random=None):
     import torch
     import gpu_harness
 
@@ -40,22 +42,27 @@ def _full_size(cfg, layers, n_random):
             tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
             d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
             assert np.all(np.isfinite(outs[0][k])) and d <= tol, f"model {k}: kernels differ by {d:.3e}"
+        if prefill_random is not None:
+            for k in range(len(wl.models)):
+                print(f"[full-size] config {cfg}: whole-prompt prefill of model {k}", flush=True)
+                perr = par.prefill_whole_prompts_and_check_windows(k, layers[k], prefill_random)
+                print(f"[full-size] config {cfg}: prefill model {k}: max abs err {perr[0]:.2e} on {perr[1]} rows", flush=True)
         return errs
     finally:
         par.close()
 
 
 def test_config2_llama8b_fp16_full():
-    _full_size(2, [17], n_random=6)
+    _full_size(2, [17], n_random=6, prefill_random=3)
 
 
 def test_config3_fp16_fp8_interleaved_full():
-    _full_size(3, [3, 29], n_random=3)
+    _full_size(3, [3, 29], n_random=3, prefill_random=1)
 
 
 def test_config4_int4_full():
-    _full_size(4, [11], n_random=4)
+    _full_size(4, [11], n_random=4, prefill_random=1)
 
 
 def test_config5_four_model_churned_pool_full():
-    _full_size(5, [7, 0, 3, 9], n_random=2)
+    _full_size(5, [7, 0, 3, 9], n_random=2, prefill_random=1)
