@@ -262,6 +262,29 @@ def test_block_bytes_forward_is_the_block_size_equation():
     assert pool.model_geometry(m).tokens_per_block == 5 and pool.blocks_per_slab(m) == 4
 
 
+def test_token_size_divides_by_the_tensor_parallel_degree():
+    """TokenSize = #Heads / TP x HeadDim x 2 x bytes(precision) (Sec. 3.2): a GPU of a TP group registers its own
+    share of the KV heads.  Where nothing is padded the block shrinks by exactly TP, and a fixed slab holds TP times
+    the tokens; the quantized formats keep their per-token parameters per head, so they scale the same way."""
+    bytes_x2 = {oracle.FP16: 4, oracle.FP8: 2, oracle.INT8: 2, oracle.INT4: 1}  # 2 x bytes(precision)
+    par = {oracle.FP16: 0, oracle.FP8: 0, oracle.INT8: 2, oracle.INT4: 4}
+    for heads, layers in ((8, 32), (40, 40), (32, 32)):  # 8B GQA, 13B MHA, 7B MHA shapes, head_dim 128
+        for dt in (oracle.FP16, oracle.FP8, oracle.INT8, oracle.INT4):
+            full = oracle.block_bytes(dt, heads, 128, layers, 16)
+            for tp in (1, 2, 4, 8):
+                if heads % tp:
+                    continue
+                h = heads // tp
+                token_size = h * 128 * bytes_x2[dt]            # the equation, per layer
+                want = 16 * layers * (token_size + 2 * h * par[dt])
+                if (h * 16 * (128 * bytes_x2[dt] // 2 + par[dt]) * 2) % 256 == 0:  # the layer's heads end on a 256-byte boundary
+                    assert oracle.block_bytes(dt, h, 128, layers, 16) == want == full // tp
+                else:
+                    assert want <= oracle.block_bytes(dt, h, 128, layers, 16) < want + 256 * layers
+    # a 2 MiB slab of the FP16 8B shape: 16 tokens on one GPU, 32 / 64 / 128 on a TP group of 2 / 4 / 8
+    assert [oracle.geometry(oracle.FP16, 8 // tp, 128, 32, 2 * MiB).tokens_per_block for tp in (1, 2, 4, 8)] == [16, 32, 64, 128]
+
+
 def test_lcm_slab_size_against_math_lcm_and_the_figure():
     """Sec. 5.2: slab = multiple of the lcm of the co-located block sizes.  Checked against Python's math.lcm;
     the pair FP16 / FP8 at 16 tokens per block gives the picture of the slab figure: one slab seen as 1 block by
