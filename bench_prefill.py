@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
     ap.add_argument("--kernel", default="0,0", help="column blocks,waves for fs_set_prefill_kernel (0,0 = automatic)")
+    ap.add_argument("--staged-dequant", type=int, default=1, help="fs_set_prefill_staged_dequant (INT8 / INT4 models)")
     ap.add_argument("--pipelined", action="store_true", help="fs_set_prefill_pipelined(1) (with --kernel 16,4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
@@ -62,6 +63,7 @@ def main():
     if fs.fs_set_prefill_kernel(ker_blocks, ker_waves) != 0:
         raise SystemExit("bench_prefill.py: --kernel must be blocks in {0,1,2,4,16} and waves in {0,4,8}")
     fs.fs_set_prefill_pipelined(int(args.pipelined))
+    fs.fs_set_prefill_staged_dequant(int(args.staged_dequant))
     wl = workloads.config(args.config)
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]

@@ -252,6 +252,12 @@ int fs_set_prefill_kernel(int column_blocks, int waves);
 /* The 4-wave workgroup kernel (column_blocks 16, waves 4) in its software-pipelined form: one wave interleaves the
  * MFMAs of the next sub-tile's S^T with the current sub-tile's exponentials.  0 = off (default). */
 int fs_set_prefill_pipelined(int enable);
+/* INT8 / INT4 models on the 8-wave workgroup kernel: the waves that stage K and V in LDS leave dequantized fp16
+ * operands there, (code - zero point) * scale rounded to fp16, and every wave runs the FP16 tile code (no per-logit
+ * scales or zero-point terms): 15-26 % faster, and the default (non-zero or negative `enable`).  With 0 the integer
+ * codes reach the MFMAs exactly and scales and zero points are applied in fp32 around them, as in decode.  Both stay
+ * inside the prefill tolerance. */
+int fs_set_prefill_staged_dequant(int enable);
 
 /* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
  * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */

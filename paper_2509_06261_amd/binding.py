@@ -26,7 +26,8 @@ EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_regist
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
-           "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_set_prefill_kernel", "fs_set_prefill_pipelined", "fs_set_kernel_mode",
+           "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_set_prefill_kernel", "fs_set_prefill_pipelined", "fs_set_prefill_staged_dequant",
+           "fs_set_kernel_mode",
            "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
 
 
@@ -86,6 +87,7 @@ def _load():
         "fs_sched_place_models": (i32, [vp, vp, i32, vp, i32, vp]),
         "fs_set_prefill_kernel": (i32, [i32, i32]),
         "fs_set_prefill_pipelined": (i32, [i32]),
+        "fs_set_prefill_staged_dequant": (i32, [i32]),
         "fs_set_kernel_mode": (i32, [i32]),
         "fs_set_split_bytes": (i32, [u64]),
         "fs_set_kernel_timing": (i32, [i32]),
@@ -362,6 +364,10 @@ def fs_set_prefill_kernel(column_blocks: int, waves: int = 0) -> int:
 
 def fs_set_prefill_pipelined(enable: int) -> int:
     return _L.fs_set_prefill_pipelined(int(enable))
+
+
+def fs_set_prefill_staged_dequant(enable: int) -> int:
+    return _L.fs_set_prefill_staged_dequant(int(enable))
 
 
 def fs_set_kernel_mode(mode: int) -> int:

@@ -661,6 +661,126 @@ __device__ __forceinline__ void stage_v(uint8_t* stage, int sub, int lane, int j
   if constexpr (F::kParBytes != 0) *reinterpret_cast<uint32_t*>(stage + stage_par(SUBS) + sub * 256 + lane * 4) = t.par[0];
 }
 
+// ---- Staged dequantization (INT8 / INT4) ----------------------------------------------------------------------
+// The staging wave may as well leave *dequantized* fp16 operands in LDS: (code - zero point) * scale, rounded to
+// fp16 -- what an engine that dequantizes in front of its matrix cores feeds them.  Every consumer wave then runs
+// the FP16 tile code (no per-logit scale, no zero-point terms: less than half the vector instructions per logit),
+// and the conversion is paid once per workgroup instead of once per wave.  The codes are made exact fp16
+// integers first (0x6400 | n = 1024 + n, minus 1024); the subtraction of the zero point and the multiplication
+// by the scale each round once (relative 2^-12).
+__device__ __forceinline__ half2v splat_lo(uint32_t w) { return u2h(__builtin_amdgcn_perm(w, w, 0x01000100u)); }
+__device__ __forceinline__ half2v splat_hi(uint32_t w) { return u2h(__builtin_amdgcn_perm(w, w, 0x03020302u)); }
+
+// per-token constants of the dequantization: par = {scale, zero point} (INT4) or {scale} (INT8)
+template <int DT>
+struct Deq {
+  half2v sc, sc16, zp, zp16;
+  __device__ __forceinline__ explicit Deq(uint32_t par) {
+    const half2v c16 = {(_Float16)16.0f, (_Float16)16.0f}, r16 = {(_Float16)0.0625f, (_Float16)0.0625f};
+    sc = splat_lo(par);
+    sc16 = sc * r16;
+    zp = DT == FS_KV_INT4 ? splat_hi(par) : half2v{(_Float16)0.0f, (_Float16)0.0f};
+    zp16 = zp * c16;
+  }
+};
+
+// Four registers of 8 stored codes -> (code - zp) * scale as packed fp16.  INT8: register p holds elements
+// (2p, 2p + 1).  INT4: register p holds codes (p, p + 4), and the odd registers hold them 16-fold (the nibble
+// stays where it is stored): `odd16` leaves that factor in (K: the query operand carries 1/16 there) or takes
+// it out (V).
+template <int DT>
+__device__ __forceinline__ void dequant8(const uint32_t* w, const Deq<DT>& q, bool odd16, uint32_t (&x)[4]) {
+  const half2v k1024 = {(_Float16)1024.0f, (_Float16)1024.0f}, k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
+  if constexpr (DT == FS_KV_INT8) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t u = w[h] ^ 0x80808080u;  // code + 128, unsigned
+      const uint32_t r0 = __builtin_amdgcn_perm(0x64646464u, u, 0x04010400u);  // halves 1024 + 128 + code
+      const uint32_t r1 = __builtin_amdgcn_perm(0x64646464u, u, 0x04030402u);
+      x[2 * h] = h2u((u2h(r0) - k1152) * q.sc);
+      x[2 * h + 1] = h2u((u2h(r1) - k1152) * q.sc);
+    }
+  } else {
+    const uint32_t w0 = w[0], w8 = w0 >> 8;
+    const uint32_t r0 = (w0 & 0x000F000Fu) | 0x64006400u, r1 = (w0 & 0x00F000F0u) | 0x64006400u;
+    const uint32_t r2 = (w8 & 0x000F000Fu) | 0x64006400u, r3 = (w8 & 0x00F000F0u) | 0x64006400u;
+    const half2v so = odd16 ? q.sc : q.sc16;
+    x[0] = h2u(((u2h(r0) - k1024) - q.zp) * q.sc);
+    x[1] = h2u(((u2h(r1) - k1024) - q.zp16) * so);
+    x[2] = h2u(((u2h(r2) - k1024) - q.zp) * q.sc);
+    x[3] = h2u(((u2h(r3) - k1024) - q.zp16) * so);
+  }
+}
+
+// K parameters of the rows this lane stages: row c of half-tile u is slot 4u + (c & 3) of run c >> 2 (as issue_k)
+template <int DT>
+__device__ __forceinline__ void issue_kpar(const ItemCtx& X, const DevGeom& g, int vb, int c, uint32_t (&kpar)[2]) {
+  using F = Fmt<DT>;
+  const RunLoc L = locate(X, vb + (c >> 2));
+  const gptr p = L.base + 2u * g.kv_tile + (uint32_t)((L.start + (c & 3)) * F::kParBytes);
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    if constexpr (F::kParBytes == 2) kpar[u] = *reinterpret_cast<const FS_GLOBAL uint16_t*>(p + u * 4 * F::kParBytes);
+    else kpar[u] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p + u * 4 * F::kParBytes);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void stage_k_deq(uint8_t* stage, int sub, int lane, Tile<DT, 16>& t, const uint32_t (&kpar)[2]) {
+  using F = Fmt<DT>;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const Deq<DT> q(kpar[u]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      // the 8 codes of k-step ks: INT8 two dwords of load ks >> 1, INT4 dword ks of the one load
+      uint32_t w[2];
+      if constexpr (DT == FS_KV_INT8) {
+        w[0] = t.k[u][ks >> 1][2 * (ks & 1)];
+        w[1] = t.k[u][ks >> 1][2 * (ks & 1) + 1];
+      } else {
+        w[0] = t.k[u][0][ks];
+        w[1] = 0u;
+      }
+      uint32_t x[4];
+      dequant8<DT>(w, q, true, x);
+      const u32x4 a = {x[0], x[1], x[2], x[3]};
+      *reinterpret_cast<u32x4*>(stage + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a;
+    }
+  }
+  (void)sizeof(F);
+}
+
+template <int DT, int SUBS>
+__device__ __forceinline__ void stage_v_deq(uint8_t* stage, int sub, int lane, int j, Tile<DT, 16>& t, const ItemCtx& X, int vb) {
+  uint32_t vx[8][4];
+  static_for(std::make_integer_sequence<int, 8>{}, [&](auto I) {
+    constexpr int i = decltype(I)::value;
+    // V parameters of slot i of the lane's run: held by lane 8 + i of the row
+    const uint32_t par = __builtin_amdgcn_update_dpp(0u, t.par[0], 0x150 + 8 + i, 0xF, 0xF, false);
+    const Deq<DT> q(par);
+    dequant8<DT>(t.v[i], q, false, vx[i]);
+  });
+  // slots past the sequence's end may hold any codes and parameters (NaN / Inf after the conversion); 0 * NaN
+  // would poison the MFMA
+  const RunLoc L = locate(X, vb + j);
+  if (!__all(L.hi_u >= 8)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) vx[i][q] = i < L.hi_u ? vx[i][q] : 0u;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int reg = DT == FS_KV_INT4 ? (e & 3) : (e >> 1);
+    const uint32_t sel = (DT == FS_KV_INT4 ? (e >> 2) : (e & 1)) ? 0x07060302u : 0x05040100u;
+    u32x4 b;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
+    *reinterpret_cast<u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16) = b;
+  }
+}
+
 // One staged 32-token sub-tile for the wave's column blocks: wide_tile with the operands read from LDS.
 template <int DT, int NCB, int SUBS>
 __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const ItemCtx& X, const u32x4 (&qb)[NCB][4],
@@ -790,9 +910,12 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
 // 4 x 4, 4 sub-tiles (one wave per SIMD); 4 x 2 with 2 sub-tiles per step, whose stages are small enough for TWO
 // workgroups per compute unit: the two waves of a SIMD then belong to different items and do not march in step.
 // smem: two stages, then the workgroup's block-address table.
-template <int DT, int NW, int NCB, int SUBS>
+// DEQ (INT8 / INT4 only): the staging waves dequantize, the tile code is the FP16 one.
+template <int DT, int NW, int NCB, int SUBS, bool DEQ = false>
 __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt, uint8_t* smem, uint64_t* s_tab, int w) {
   static_assert(NW == SUBS || NW == 2 * SUBS, "staging roles");
+  static_assert(!DEQ || Fmt<DT>::kParBytes != 0, "staged dequantization is for the formats with per-token parameters");
+  constexpr int CDT = DEQ ? FS_KV_FP16 : DT;  // the format the consumer code sees
   const bool does_k = NW == SUBS || w < SUBS, does_v = NW == SUBS || w >= SUBS;  // wave-uniform staging roles
   const int sw = w % SUBS;                                                       // the sub-tile this wave stages
   const DevBatch& B = P.b;
@@ -836,7 +959,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
     load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
-    if constexpr (Fmt<DT>::kParBytes != 0) {
+    if constexpr (Fmt<CDT>::kParBytes != 0) {
       qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
       qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
     }
@@ -862,10 +985,26 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     }
     const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
     Tile<DT, 16> t;
-    if (does_k) issue_k<DT, 16>(X, v0 + 4 * sw, j, c, t);
-    if (does_v) issue_v<DT, 16>(X, g, v0 + 4 * sw, j, c, t);
-    if (does_k) stage_k<DT>(smem, sw, lane, t);
-    if (does_v) stage_v<DT, SUBS>(smem, sw, lane, j, t, X, v0 + 4 * sw);
+    uint32_t kpar[2] = {0u, 0u};  // (DEQ) K parameters of the rows this lane stages
+    // fetch / stage this wave's share of the sub-tile that starts at run vb
+    auto fetch = [&](int vb) {
+      if (does_k) {
+        issue_k<DT, 16>(X, vb, j, c, t);
+        if constexpr (DEQ) issue_kpar<DT>(X, g, vb, c, kpar);
+      }
+      if (does_v) issue_v<DT, 16>(X, g, vb, j, c, t);
+    };
+    auto stage_to = [&](uint8_t* stage, int vb) {
+      if constexpr (DEQ) {
+        if (does_k) stage_k_deq<DT>(stage, sw, lane, t, kpar);
+        if (does_v) stage_v_deq<DT, SUBS>(stage, sw, lane, j, t, X, vb);
+      } else {
+        if (does_k) stage_k<DT>(stage, sw, lane, t);
+        if (does_v) stage_v<DT, SUBS>(stage, sw, lane, j, t, X, vb);
+      }
+    };
+    fetch(v0 + 4 * sw);
+    stage_to(smem, v0 + 4 * sw);
     __syncthreads();
     // the query operands' loads, issued before the table and the first K/V fetch, are collected here
 #pragma unroll
@@ -873,19 +1012,17 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     for (int i = 0; i < n_super; ++i) {
       // next step's sub-tile of this wave (past the segment's end: mapped onto its last run, never used)
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
-      if (does_k) issue_k<DT, 16>(X, vb_next, j, c, t);
-      if (does_v) issue_v<DT, 16>(X, g, vb_next, j, c, t);
+      fetch(vb_next);
       const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
 #pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
       for (int sub = 0; sub < SUBS; ++sub) {
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
         // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
-        wg_tile<DT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st);
+        wg_tile<CDT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st);
       }
       uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
-      if (does_k) stage_k<DT>(next, sw, lane, t);
-      if (does_v) stage_v<DT, SUBS>(next, sw, lane, j, t, X, vb_next);
+      stage_to(next, vb_next);
       __syncthreads();
     }
   }
@@ -897,7 +1034,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     float l = st.l[cb], zc = st.zc[cb];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    if constexpr (Fmt<DT>::kParBytes != 0) {
+    if constexpr (Fmt<CDT>::kParBytes != 0) {
       zc += __shfl_xor(zc, 16, 64);
       zc += __shfl_xor(zc, 32, 64);
     }
@@ -916,9 +1053,9 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
 #pragma unroll
           for (int z = 0; z < 2; ++z) {
             const int e = 2 * q + z;
-            const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
+            const float f = CDT == FS_KV_INT8 ? kTwo24 : (CDT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
             o[z] = st.acc[cb][e][r] * f;
-            if constexpr (Fmt<DT>::kParBytes != 0) o[z] += Z;
+            if constexpr (Fmt<CDT>::kParBytes != 0) o[z] += Z;
             o[z] *= v_static * inv;
           }
           const half2v hv = {(_Float16)o[0], (_Float16)o[1]};
@@ -1252,7 +1389,7 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
 }
 
 // WPC = workgroups per compute unit the kernel is built for
-template <int DT, int NW, int NCB, int SUBS, int WPC, bool PIPE = false>
+template <int DT, int NW, int NCB, int SUBS, int WPC, bool PIPE = false, bool DEQ = false>
 __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   uint8_t* smem = reinterpret_cast<uint8_t*>(smem64);
@@ -1285,7 +1422,7 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
     int seq, head, qt;
     if (!decode_item(P, tf, item, H, seq, head, qt)) continue;
     if constexpr (PIPE) prefill_item_wgp<DT>(P, seq, head, qt, smem, s_tab, wave);
-    else prefill_item_wg<DT, NW, NCB, SUBS>(P, seq, head, qt, smem, s_tab, wave);
+    else prefill_item_wg<DT, NW, NCB, SUBS, DEQ>(P, seq, head, qt, smem, s_tab, wave);
   }
 }
 
@@ -1318,7 +1455,7 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 using namespace fs;
 
 namespace {
-int g_prefill_ncb = 0, g_prefill_nw = 0, g_prefill_pipe = 0;
+int g_prefill_ncb = 0, g_prefill_nw = 0, g_prefill_pipe = 0, g_prefill_deq = 1;
 }
 
 int fs_set_prefill_kernel(int column_blocks, int waves) {
@@ -1334,6 +1471,11 @@ int fs_set_prefill_kernel(int column_blocks, int waves) {
 
 int fs_set_prefill_pipelined(int enable) {
   g_prefill_pipe = enable != 0;
+  return FS_OK;
+}
+
+int fs_set_prefill_staged_dequant(int enable) {
+  g_prefill_deq = enable != 0;  // (a negative value: the default, on)
   return FS_OK;
 }
 
@@ -1480,11 +1622,12 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   (ncb == 8 ? prefill_wg_kernel<DT, 4, 2, 2, 2>                                                            \
             : (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1>                                                 \
                        : (g_prefill_pipe ? prefill_wg_kernel<DT, 4, 4, 4, 1, true> : prefill_wg_kernel<DT, 4, 4, 4, 1>)))
+    const bool deq = g_prefill_deq && ncb == 16 && nw == 8;  // (the 8-wave kernel only)
     switch (g.kv_dtype) {
       case FS_KV_FP16: kern = FS_WG(FS_KV_FP16); break;
       case FS_KV_FP8_E4M3: kern = FS_WG(FS_KV_FP8_E4M3); break;
-      case FS_KV_INT8: kern = FS_WG(FS_KV_INT8); break;
-      default: kern = FS_WG(FS_KV_INT4); break;
+      case FS_KV_INT8: kern = deq ? prefill_wg_kernel<FS_KV_INT8, 8, 2, 4, 1, false, true> : FS_WG(FS_KV_INT8); break;
+      default: kern = deq ? prefill_wg_kernel<FS_KV_INT4, 8, 2, 4, 1, false, true> : FS_WG(FS_KV_INT4); break;
     }
 #undef FS_WG
     // more than 64 KiB of dynamic LDS has to be granted per kernel

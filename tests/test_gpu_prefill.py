@@ -11,7 +11,9 @@ pytestmark = pytest.mark.gpu
 # (name, column blocks, waves) for fs_set_prefill_kernel.  The workgroup kernel with 8 waves (what large launches
 # run) takes every test; the automatic choice (the 16-column kernel on launches this small) the four-format and
 # the two-model tests; the other variants the four-format test on FP16 and INT4 (without and with parameters).
-VARIANTS = [("wg8", 16, 8), ("auto", 0, 0), ("wg4", 16, 4), ("wg4p", 16, 4), ("wg4x2", 8, 4), ("cols32", 2, 0), ("cols64", 4, 0)]
+# wg8dq = the same kernel with staged dequantization (INT8 / INT4 only; the library's default, switched off for the
+# other variants): every test with such a model.
+VARIANTS = [("wg8", 16, 8), ("wg8dq", 16, 8), ("auto", 0, 0), ("wg4", 16, 4), ("wg4p", 16, 4), ("wg4x2", 8, 4), ("cols32", 2, 0), ("cols64", 4, 0)]
 
 
 @pytest.fixture(params=VARIANTS, ids=[v[0] for v in VARIANTS], autouse=True)
@@ -23,20 +25,26 @@ def kernel_variant(request):
     if test.startswith("test_other_shapes"):
         if name != "auto":
             pytest.skip("shapes outside the MFMA kernels take the vector-ALU kernel whatever variant is set")
+    elif name == "wg8dq":
+        fp = test.startswith(("test_gqa_8b_shape", "test_mha_13b")) and ("[wg8dq-0" in test or "[wg8dq-1" in test)
+        if test.startswith("test_long_context") or fp:
+            pytest.skip("staged dequantization concerns INT8 and INT4 models only")
     elif name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
         pytest.skip("the automatic choice is covered by the four-format and two-model tests")
     if name == "wg4p" and not test.startswith(("test_gqa_8b_shape", "test_mha_13b", "test_long_context")):
         pytest.skip("the pipelined variant takes the four-format, odd-block and long-context tests")
-    if name not in ("wg8", "auto", "wg4p") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
+    if name not in ("wg8", "wg8dq", "auto", "wg4p") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
         pytest.skip("variant covered by the four-format test on FP16 and INT4")
     if name == "wg4x2":
         assert fs.fs_set_prefill_kernel(blocks, waves) != 0  # refused by the library
         pytest.skip("variant switched off in the library: a full-size run faulted or hung the GPU, cause not found")
     assert fs.fs_set_prefill_kernel(blocks, waves) == 0
     fs.fs_set_prefill_pipelined(name == "wg4p")  # the software-pipelined form of the 4-wave workgroup kernel
+    fs.fs_set_prefill_staged_dequant(name == "wg8dq")
     yield name
     fs.fs_set_prefill_kernel(0, 0)
     fs.fs_set_prefill_pipelined(0)
+    fs.fs_set_prefill_staged_dequant(-1)  # the default (on)
 
 
 def _parity(wl):
