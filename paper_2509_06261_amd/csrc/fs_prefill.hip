@@ -727,7 +727,6 @@ __device__ __forceinline__ void issue_kpar(const ItemCtx& X, const DevGeom& g, i
 
 template <int DT>
 __device__ __forceinline__ void stage_k_deq(uint8_t* stage, int sub, int lane, Tile<DT, 16>& t, const uint32_t (&kpar)[2]) {
-  using F = Fmt<DT>;
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const Deq<DT> q(kpar[u]);
@@ -748,7 +747,6 @@ __device__ __forceinline__ void stage_k_deq(uint8_t* stage, int sub, int lane, T
       *reinterpret_cast<u32x4*>(stage + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a;
     }
   }
-  (void)sizeof(F);
 }
 
 template <int DT, int SUBS>
