@@ -33,7 +33,8 @@ struct AppendArgs {
   const int32_t* tables;
   const float* k_scale;  // FP8: device [H] for this layer
   const float* v_scale;
-  int64_t n_rows;        // n_tokens * H * 2
+  int64_t n_rows;        // rows of the launch: n_tokens rounded up to a multiple of 4, * H * 2
+  int64_t n_tokens;
   int32_t lpr_shift;     // log2 of the lanes per row (head_dim / 8)
   int64_t n_blocks;      // valid block ids are [0, n_blocks)
   int32_t layer, max_blocks;
@@ -117,11 +118,17 @@ __global__ __launch_bounds__(kWaves * 64) void kv_append_kernel(AppendArgs A) {
     const int64_t r = grp * rpw + riw;
     // Lanes of a row agree on every test below; a row that is skipped computes on zeros and stores nothing, so
     // the shuffles stay unconditional.
-    bool ok = r < A.n_rows;
-    const int which = (int)(r & 1);
-    const int64_t th = r >> 1;
+    // Row order: four consecutive tokens of one (head, K|V) are neighbours, then K|V, the heads, the next four
+    // tokens.  The rows a wave writes then lie side by side in the block whenever the tokens are consecutive
+    // positions of one sequence (a prefill chunk): 256 contiguous bytes even for INT4's 64-byte rows, and the
+    // source rows of a group of waves stay within four tokens.
+    const int64_t rest = r >> 2;
+    const int which = (int)(rest & 1);
+    const int64_t th = rest >> 1;
     const int head = (int)(th % g.H);
-    const int64_t tok = ok ? th / g.H : 0;
+    int64_t tok = (th / g.H) * 4 + (r & 3);
+    bool ok = r < A.n_rows && tok < A.n_tokens;
+    tok = ok ? tok : 0;
     const int p = ok ? A.pos[tok] : -1;
     const int s = ok ? A.seq_idx[tok] : -1;
     ok = ok && p >= 0 && s >= 0;
@@ -237,7 +244,8 @@ extern "C" int fs_kv_append(fs_pool* p, fs_model_t model, int layer, const void*
   A.tables = block_tables;
   A.k_scale = M.d_k_scale ? M.d_k_scale + (size_t)layer * M.g.n_kv_heads : nullptr;
   A.v_scale = M.d_v_scale ? M.d_v_scale + (size_t)layer * M.g.n_kv_heads : nullptr;
-  A.n_rows = n_tokens * M.g.n_kv_heads * 2;
+  A.n_tokens = n_tokens;
+  A.n_rows = (n_tokens + 3) / 4 * 4 * M.g.n_kv_heads * 2;
   A.n_blocks = (int64_t)(p->pool_bytes / M.g.block_budget);
   A.layer = layer;
   A.max_blocks = max_blocks;
