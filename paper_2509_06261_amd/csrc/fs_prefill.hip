@@ -666,49 +666,57 @@ __device__ __forceinline__ void stage_v(uint8_t* stage, int sub, int lane, int j
 // fp16 -- what an engine that dequantizes in front of its matrix cores feeds them.  Every consumer wave then runs
 // the FP16 tile code (no per-logit scale, no zero-point terms: less than half the vector instructions per logit),
 // and the conversion is paid once per workgroup instead of once per wave.  The codes are made exact fp16
-// integers first (0x6400 | n = 1024 + n, minus 1024); the subtraction of the zero point and the multiplication
-// by the scale each round once (relative 2^-12).
+// integers first (0x6400 | n = 1024 + n); the offset and the (integer) zero point are subtracted exactly, the
+// multiplication by the scale rounds once (relative 2^-12).
 __device__ __forceinline__ half2v splat_lo(uint32_t w) { return u2h(__builtin_amdgcn_perm(w, w, 0x01000100u)); }
 __device__ __forceinline__ half2v splat_hi(uint32_t w) { return u2h(__builtin_amdgcn_perm(w, w, 0x03020302u)); }
 
-// per-token constants of the dequantization: par = {scale, zero point} (INT4) or {scale} (INT8)
+// per-token constants of the dequantization: par = {scale, zero point} (INT4) or {scale} (INT8).  The INT4 zero
+// point is an integer 0..15 (the quantizer rounds it), so 1024 + zp and 1024 + 16 zp are exact in fp16 and the
+// offset of the integer encoding and the zero point leave in ONE exact subtraction.
 template <int DT>
 struct Deq {
-  half2v sc, sc16, zp, zp16;
+  half2v sc, sc16, off, off16;
   __device__ __forceinline__ explicit Deq(uint32_t par) {
     const half2v c16 = {(_Float16)16.0f, (_Float16)16.0f}, r16 = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const half2v k1024 = {(_Float16)1024.0f, (_Float16)1024.0f}, k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
     sc = splat_lo(par);
     sc16 = sc * r16;
-    zp = DT == FS_KV_INT4 ? splat_hi(par) : half2v{(_Float16)0.0f, (_Float16)0.0f};
-    zp16 = zp * c16;
+    if constexpr (DT == FS_KV_INT4) {
+      const half2v zp = splat_hi(par);
+      off = zp + k1024;
+      off16 = zp * c16 + k1024;
+    } else {
+      off = k1152;  // 1024 + 128: the stored byte is the code + 128 after the sign flip
+      off16 = k1152;
+    }
   }
 };
 
-// Four registers of 8 stored codes -> (code - zp) * scale as packed fp16.  INT8: register p holds elements
-// (2p, 2p + 1).  INT4: register p holds codes (p, p + 4), and the odd registers hold them 16-fold (the nibble
-// stays where it is stored): `odd16` leaves that factor in (K: the query operand carries 1/16 there) or takes
-// it out (V).
+// Four registers of 8 stored codes -> (code - zp) * scale as packed fp16 (the subtraction exact, the product
+// rounded once).  INT8: register p holds elements (2p, 2p + 1).  INT4: register p holds codes (p, p + 4), and the
+// odd registers hold them 16-fold (the nibble stays where it is stored): `odd16` leaves that factor in (K: the
+// query operand carries 1/16 there) or takes it out (V).
 template <int DT>
 __device__ __forceinline__ void dequant8(const uint32_t* w, const Deq<DT>& q, bool odd16, uint32_t (&x)[4]) {
-  const half2v k1024 = {(_Float16)1024.0f, (_Float16)1024.0f}, k1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
   if constexpr (DT == FS_KV_INT8) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const uint32_t u = w[h] ^ 0x80808080u;  // code + 128, unsigned
       const uint32_t r0 = __builtin_amdgcn_perm(0x64646464u, u, 0x04010400u);  // halves 1024 + 128 + code
       const uint32_t r1 = __builtin_amdgcn_perm(0x64646464u, u, 0x04030402u);
-      x[2 * h] = h2u((u2h(r0) - k1152) * q.sc);
-      x[2 * h + 1] = h2u((u2h(r1) - k1152) * q.sc);
+      x[2 * h] = h2u((u2h(r0) - q.off) * q.sc);
+      x[2 * h + 1] = h2u((u2h(r1) - q.off) * q.sc);
     }
   } else {
     const uint32_t w0 = w[0], w8 = w0 >> 8;
-    const uint32_t r0 = (w0 & 0x000F000Fu) | 0x64006400u, r1 = (w0 & 0x00F000F0u) | 0x64006400u;
+    const uint32_t r0 = (w0 & 0x000F000Fu) | 0x64006400u, r1 = (w0 & 0x00F000F0u) | 0x64006400u;  // 1024 + n, 1024 + 16 n
     const uint32_t r2 = (w8 & 0x000F000Fu) | 0x64006400u, r3 = (w8 & 0x00F000F0u) | 0x64006400u;
     const half2v so = odd16 ? q.sc : q.sc16;
-    x[0] = h2u(((u2h(r0) - k1024) - q.zp) * q.sc);
-    x[1] = h2u(((u2h(r1) - k1024) - q.zp16) * so);
-    x[2] = h2u(((u2h(r2) - k1024) - q.zp) * q.sc);
-    x[3] = h2u(((u2h(r3) - k1024) - q.zp16) * so);
+    x[0] = h2u((u2h(r0) - q.off) * q.sc);
+    x[1] = h2u((u2h(r1) - q.off16) * so);
+    x[2] = h2u((u2h(r2) - q.off) * q.sc);
+    x[3] = h2u((u2h(r3) - q.off16) * so);
   }
 }
 
