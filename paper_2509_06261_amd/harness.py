@@ -112,8 +112,9 @@ class GpuWorkload:
         q = gen.normal_q(self.wl.seed, s.tag, layer, np.arange(s.n_seq), s.n_q_heads, s.head_dim)
         return q
 
-    def make_batches(self, layers, with_lse=True, host_lens=True, models=None):
-        """One fs_batch_t per model (``layers[k]`` = layer index).  Returns (batches, keepalive dict)."""
+    def make_batches(self, layers, with_lse=True, host_lens=True, models=None, sm_scale=None):
+        """One fs_batch_t per model (``layers[k]`` = layer index; softmax scale 1/sqrt(head_dim) unless given).
+        Returns (batches, keepalive dict)."""
         batches, keep = [], {"q": [], "out": [], "lse": [], "q_host": []}
         for k, (s, m) in enumerate(zip(self.wl.models, self.model_ids)):
             if models is not None and k not in models:
@@ -122,7 +123,8 @@ class GpuWorkload:
             q = torch.from_numpy(qh).to(self.device)
             out = torch.zeros((s.n_seq, s.n_q_heads, s.head_dim), dtype=torch.float16, device=self.device)
             lse = torch.zeros((s.n_seq, s.n_q_heads), dtype=torch.float32, device=self.device) if with_lse else None
-            b = fs.make_batch(m, layers[k], s.n_q_heads, float(1.0 / np.sqrt(s.head_dim)), q, self.tables[k],
+            scale = float(1.0 / np.sqrt(s.head_dim)) if sm_scale is None else float(sm_scale)
+            b = fs.make_batch(m, layers[k], s.n_q_heads, scale, q, self.tables[k],
                               self.seq_lens[k], out, lse, self.lens[k] if host_lens else None)
             batches.append(b)
             keep["q"].append(q)

@@ -89,6 +89,19 @@ def test_mixed_four_model_pool_small(mode):
 
 
 @pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("sm_scale", [-0.07, 0.0, 0.3])
+def test_softmax_scales_other_than_the_usual(sm_scale, mode):
+    """A negative, a zero (uniform weights: the mean of V) and a large softmax scale, four precisions in one launch."""
+    wl = workloads.scaled_down(workloads.config(5), n_seq=3, max_len=700, pool_bytes=320 * MiB, churn_steps=100)
+    par = _parity(wl)
+    try:
+        errs = par.run_and_check([1, 0, 2, 3], kernel_mode=mode, with_bytes=False, sm_scale=sm_scale)
+        print("scale", sm_scale, "max abs err", errs)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
 def test_interleaved_two_model_pool_small(mode):
     """Config 3 scaled down: FP16 and FP8 models with slabs interleaved block by block."""
     wl = workloads.scaled_down(workloads.config(3), n_seq=5, max_len=400, pool_bytes=512 * MiB)

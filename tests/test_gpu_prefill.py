@@ -29,6 +29,9 @@ def kernel_variant(request):
         fp = test.startswith(("test_gqa_8b_shape", "test_mha_13b")) and ("[wg8dq-0" in test or "[wg8dq-1" in test)
         if test.startswith("test_long_context") or fp:
             pytest.skip("staged dequantization concerns INT8 and INT4 models only")
+    elif test.startswith("test_softmax_scales"):
+        if name not in ("wg8", "wg8dq", "auto"):
+            pytest.skip("the scale's sign decides the kernel inside the library; three settings suffice")
     elif name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
         pytest.skip("the automatic choice is covered by the four-format and two-model tests")
     if name == "wg4p" and not test.startswith(("test_gqa_8b_shape", "test_mha_13b", "test_long_context")):
@@ -119,6 +122,23 @@ def test_other_shapes_take_the_vector_kernel(dtype, head_dim, kv_heads, q_heads,
         print("T", par.gw.T)
         print(par.prefill_and_check(0, 1, lens))
         print(par.prefill_and_check(0, 1, np.array([1, 0, 3, 33, 17, 200], np.int32)))
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("sm_scale", [-0.07, 0.0, 0.3])
+def test_softmax_scales_other_than_the_usual(sm_scale):
+    """A negative and a zero softmax scale (the wide kernels fold a positive scale into the exponential: the library
+    has to take the 16-column kernel) and a large positive one, on an FP16 and an INT4 model."""
+    lens = np.array([3, 70, 300], np.int32)
+    wl = Workload("pfs", 256 * KiB, 64 * MiB,
+                  [ModelSpec("a", FP16, 2, 128, 1, 8, lens, tag=38), ModelSpec("b", INT4, 2, 128, 1, 8, lens, tag=39, src_f32=True)],
+                  "interleave")
+    par = _parity(wl)
+    try:
+        par.gw.populate([[0], [0]])
+        for k in (0, 1):
+            print("scale", sm_scale, "model", k, par.prefill_and_check(k, 0, lens, sm_scale=sm_scale))
     finally:
         par.close()
 
