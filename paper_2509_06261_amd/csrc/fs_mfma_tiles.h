@@ -221,7 +221,9 @@ __device__ __forceinline__ void issue_v(const ItemCtx& X, const DevGeom& g, int 
 
 // The Q operand (B of S^T = K Q^T) of lane (j, c) for k-step ks: 8 halves of q[head c] in the d order
 // (and with the per-position factors) that the format's K unpacking produces.  qsum = sum_d q[d].
-template <int DT>
+// ODD16 (INT4): the K operand holds its odd code positions 16-fold, the query carries 1/16 there.  Without it the
+// query keeps its values (a K operand that was dequantized on the way holds plain values at every position).
+template <int DT, bool ODD16 = true>
 __device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u32x4 (&qb)[4], float& qsum) {
   qsum = 0.f;
 #pragma unroll
@@ -237,10 +239,14 @@ __device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u
     if (DT == FS_KV_INT4) {
       const half2v s16 = {(_Float16)0.0625f, (_Float16)0.0625f};
       u32x4 y;
-      y[0] = __builtin_amdgcn_perm(x[2], x[0], 0x05040100u);             // q0, q4
-      y[1] = h2u(u2h(__builtin_amdgcn_perm(x[2], x[0], 0x07060302u)) * s16);  // (q1, q5) / 16
-      y[2] = __builtin_amdgcn_perm(x[3], x[1], 0x05040100u);             // q2, q6
-      y[3] = h2u(u2h(__builtin_amdgcn_perm(x[3], x[1], 0x07060302u)) * s16);  // (q3, q7) / 16
+      y[0] = __builtin_amdgcn_perm(x[2], x[0], 0x05040100u);  // q0, q4
+      y[1] = __builtin_amdgcn_perm(x[2], x[0], 0x07060302u);  // q1, q5
+      y[2] = __builtin_amdgcn_perm(x[3], x[1], 0x05040100u);  // q2, q6
+      y[3] = __builtin_amdgcn_perm(x[3], x[1], 0x07060302u);  // q3, q7
+      if (ODD16) {  // (q1, q5) / 16, (q3, q7) / 16
+        y[1] = h2u(u2h(y[1]) * s16);
+        y[3] = h2u(u2h(y[3]) * s16);
+      }
       x = y;
     }
     qb[ks] = x;

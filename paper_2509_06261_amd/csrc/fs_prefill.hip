@@ -694,11 +694,11 @@ struct Deq {
 };
 
 // Four registers of 8 stored codes -> (code - zp) * scale as packed fp16 (the subtraction exact, the product
-// rounded once).  INT8: register p holds elements (2p, 2p + 1).  INT4: register p holds codes (p, p + 4), and the
-// odd registers hold them 16-fold (the nibble stays where it is stored): `odd16` leaves that factor in (K: the
-// query operand carries 1/16 there) or takes it out (V).
+// rounded once).  INT8: register p holds elements (2p, 2p + 1).  INT4: register p holds codes (p, p + 4); the odd
+// registers hold them 16-fold (the nibble stays where it is stored), which the scale / 16 takes out again: every
+// position ends up a plain value, with fp16's whole range.
 template <int DT>
-__device__ __forceinline__ void dequant8(const uint32_t* w, const Deq<DT>& q, bool odd16, uint32_t (&x)[4]) {
+__device__ __forceinline__ void dequant8(const uint32_t* w, const Deq<DT>& q, uint32_t (&x)[4]) {
   if constexpr (DT == FS_KV_INT8) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -712,11 +712,10 @@ __device__ __forceinline__ void dequant8(const uint32_t* w, const Deq<DT>& q, bo
     const uint32_t w0 = w[0], w8 = w0 >> 8;
     const uint32_t r0 = (w0 & 0x000F000Fu) | 0x64006400u, r1 = (w0 & 0x00F000F0u) | 0x64006400u;  // 1024 + n, 1024 + 16 n
     const uint32_t r2 = (w8 & 0x000F000Fu) | 0x64006400u, r3 = (w8 & 0x00F000F0u) | 0x64006400u;
-    const half2v so = odd16 ? q.sc : q.sc16;
     x[0] = h2u((u2h(r0) - q.off) * q.sc);
-    x[1] = h2u((u2h(r1) - q.off16) * so);
+    x[1] = h2u((u2h(r1) - q.off16) * q.sc16);
     x[2] = h2u((u2h(r2) - q.off) * q.sc);
-    x[3] = h2u((u2h(r3) - q.off16) * so);
+    x[3] = h2u((u2h(r3) - q.off16) * q.sc16);
   }
 }
 
@@ -750,7 +749,7 @@ __device__ __forceinline__ void stage_k_deq(uint8_t* stage, int sub, int lane, T
         w[1] = 0u;
       }
       uint32_t x[4];
-      dequant8<DT>(w, q, true, x);
+      dequant8<DT>(w, q, x);
       const u32x4 a = {x[0], x[1], x[2], x[3]};
       *reinterpret_cast<u32x4*>(stage + (uint32_t)((sub * 8 + u * 4 + ks) * kFrag) + lane * 16) = a;
     }
@@ -765,7 +764,7 @@ __device__ __forceinline__ void stage_v_deq(uint8_t* stage, int sub, int lane, i
     // V parameters of slot i of the lane's run: held by lane 8 + i of the row
     const uint32_t par = __builtin_amdgcn_update_dpp(0u, t.par[0], 0x150 + 8 + i, 0xF, 0xF, false);
     const Deq<DT> q(par);
-    dequant8<DT>(t.v[i], q, false, vx[i]);
+    dequant8<DT>(t.v[i], q, vx[i]);
   });
   // slots past the sequence's end may hold any codes and parameters (NaN / Inf after the conversion); 0 * NaN
   // would poison the MFMA
@@ -964,7 +963,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     const bool live = tok_c < P.tpt && tok < n_tok;
     len_cb[cb] = live ? first_pos + tok + 1 : X.len_u;  // a dead column (q = 0, never written) sees everything
     row_cb[cb] = min(max(P.q_offsets[seq] + r0 + tok, 0), P.n_rows - 1);
-    load_q<DT>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
+    load_q<DT, !DEQ>(B.q + ((int64_t)row_cb[cb] * B.n_q + head * G + hg_c) * kD, live, j, qb[cb], qsum[cb]);
     if constexpr (Fmt<CDT>::kParBytes != 0) {
       qsum[cb] += __shfl_xor(qsum[cb], 16, 64);
       qsum[cb] += __shfl_xor(qsum[cb], 32, 64);
