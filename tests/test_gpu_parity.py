@@ -244,6 +244,69 @@ def test_fp8_every_code_decodes_exactly(mode):
     fs.fs_pool_destroy(pool)
 
 
+@pytest.mark.parametrize("dtype", [FP16, FP8, INT8, INT4])
+@pytest.mark.parametrize("src_f32", [True, False])
+def test_append_bytes_on_extreme_rows(dtype, src_f32):
+    """The quantizers at the edges of their ranges: rows of zeros, signed zeros, huge values (fp16 overflow, E4M3
+    saturation, scales that saturate), tiny and subnormal values, one outlier among small values, constant rows,
+    exact rounding ties.  Stored bytes must equal the oracle's, for both source types."""
+    import torch
+    import oracle
+    import paper_2509_06261_amd as fs
+
+    H, D, n = 2, 64, 24
+    rng = np.random.default_rng(20250906 + 31 * dtype + src_f32)
+    rows = rng.standard_normal((2, n, H, D)).astype(np.float32)  # [K|V][token][head][dim]
+    amp = np.array([0.0, 1e-8, 6e-8, 1e-5, 1e-3, 0.05, 1.0, 3.0, 30.0, 447.0, 448.0, 449.0, 500.0, 6e4, 65504.0, 65520.0,
+                    7e4, 1e6, 1e30, 5e37, 2.0 ** -14, 2.0 ** -24, 0.5, 127.0], np.float32)
+    rows *= amp[None, :, None, None]
+    rows[0, 6] = 1.0                      # a constant row
+    rows[1, 6] = -0.0                     # signed zeros
+    rows[0, 7, :, :] = np.linspace(-7.5, 7.5, D, dtype=np.float32)   # INT4 / INT8 ties after scaling
+    rows[1, 7, :, ::2] = 0.0
+    rows[0, 8, :, 1:] *= 1e-4             # one outlier among small values
+    rows[1, 5, :, :] = (np.arange(D, dtype=np.float32) - 31.5) / 64.0  # exact halves in E4M3's subnormal range
+    if not src_f32:
+        with np.errstate(over="ignore"):
+            rows = rows.astype(np.float16).astype(np.float32)  # what an fp16 source can hold (inf where it overflows)
+        rows[~np.isfinite(rows)] = 65504.0                    # finite inputs only (the pinned domain)
+    src = rows if src_f32 else rows.astype(np.float16)
+    ks = vs = None
+    slab, pool_bytes = 64 * KiB, 4 * MiB
+    pool_mem = torch.zeros(pool_bytes, dtype=torch.uint8, device="cuda:0")
+    pool = fs.fs_pool_create(slab, pool_bytes, pool_mem)
+    opool = oracle.Pool(slab, pool_bytes)
+    try:
+        T, m = fs.fs_model_register(pool, dtype, H, D, 1)
+        om = opool.model_add(dtype, H, D, 1)
+        g = opool.model_geometry(om)
+        assert g.tokens_per_block == T
+        if dtype == FP8:
+            ks = np.array([[0.5, 37.0]], np.float32)
+            vs = np.array([[1.0, 0.01]], np.float32)
+            fs.fs_model_set_fp8_scales(pool, m, ks, vs)
+        nb = (n + T - 1) // T
+        ids = [fs.fs_block_alloc(pool, m)[1] for _ in range(nb)]
+        assert ids == [opool.alloc(om)[1] for _ in range(nb)]
+        tab = np.array([ids], np.int32)
+        si, po = np.zeros(n, np.int32), np.arange(n, dtype=np.int32)
+        dev = "cuda:0"
+        fs.fs_kv_append(pool, m, 0, torch.from_numpy(src[0]).to(dev), torch.from_numpy(src[1]).to(dev),
+                        torch.from_numpy(si).to(dev), torch.from_numpy(po).to(dev), torch.from_numpy(tab).to(dev))
+        torch.cuda.synchronize()
+        want0 = np.zeros(pool_bytes, np.uint8)
+        want1 = np.full(pool_bytes, 0xFF, np.uint8)
+        for w in (want0, want1):
+            oracle.kv_append(w, g, 0, src[0], src[1], si, po, tab, ks, vs)
+        defined = want0 == want1
+        got = pool_mem.cpu().numpy()
+        bad = np.flatnonzero((got != want0) & defined)
+        assert bad.size == 0, f"{bad.size} bytes differ, first at {bad[:8]}"
+        assert int(defined.sum()) >= 2 * n * H * (D * [16, 8, 8, 4][dtype] // 8)
+    finally:
+        fs.fs_pool_destroy(pool)
+
+
 def test_weights_sum_to_one_on_gpu():
     """V == 1 everywhere gives out == 1 and the lse of a zero query is ln(n)."""
     import torch
