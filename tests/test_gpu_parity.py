@@ -127,6 +127,24 @@ def test_group_sizes_and_head_dim_64(group, mode):
         par.close()
 
 
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("group", [2, 3, 5, 8, 12, 16])
+@pytest.mark.parametrize("dtype", [FP16, INT4])
+def test_group_sizes_head_dim_128(dtype, group, mode):
+    """Query heads per KV head that fill the MFMA's 16 head columns differently (<= 4: four softmax lanes per head,
+    3 with a padded one; > 4: one lane per head, 5 and 12 with padded columns), head_dim 128, splits forced."""
+    lens = np.array([7, 64, 130, 900], np.int32)
+    wl = Workload("g128", 128 * KiB, 32 * MiB,
+                  [ModelSpec("m", dtype, 2, 128, 1, 2 * group, lens, tag=43, src_f32=dtype == INT4)], "shuffle")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(32 * KiB)
+        print(par.run_and_check([0], kernel_mode=mode))
+    finally:
+        par.fs.fs_set_split_bytes(0)
+        par.close()
+
+
 @pytest.mark.parametrize("mode", [1, 2])
 def test_tokens_fixed_blocks_in_lcm_sized_slabs(mode):
     """The paper's own direction (Sec. 3.2 / 5.2): every model has 16 tokens per block, block bytes follow from
