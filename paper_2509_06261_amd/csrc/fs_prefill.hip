@@ -34,6 +34,7 @@ struct PrefillArgs {
   int32_t table_entries;     // LDS table entries per wave
   int32_t n_rows;            // query rows in q / out (host value: every row index is clamped into it)
   int32_t tf_cache;          // workgroup kernels: 1 = tile_first is copied into LDS at kernel start
+  int32_t whole_runs;        // 1 = tokens per block is a multiple of 8: run r starts at token 8 r, no run is shifted
 };
 
 constexpr int kPrepThreads = 1024;
@@ -790,7 +791,7 @@ __device__ __forceinline__ void stage_v_deq(uint8_t* stage, int sub, int lane, i
 template <int DT, int NCB, int SUBS>
 __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const ItemCtx& X, const u32x4 (&qb)[NCB][4],
                                         const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
-                                        int vb, int lane, int j, int c, WideState<NCB>& st) {
+                                        int vb, int lane, int j, int c, WideState<NCB>& st, bool whole_runs = false) {
   using F = Fmt<DT>;
   float4v s[NCB][2];
 #pragma unroll
@@ -807,8 +808,18 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
       s[cb][u] = acc;
     }
   }
-  const RunLoc L = locate(X, vb + j);
-  const bool interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);  // wave-uniform
+  // interior (wave-uniform): every token of the sub-tile lies at or before the wave's first query token and no run
+  // is a shifted one -- nothing to mask.  With whole runs per block the test is scalar arithmetic and the run's
+  // location is needed on the mask path only.
+  RunLoc L;
+  bool interior;
+  if (F::kParBytes == 0 && whole_runs) {
+    interior = vb + 4 <= X.v_end && 8 * (vb + 4) <= first_pos + 1;
+    if (!interior) L = locate(X, vb + j);
+  } else {
+    L = locate(X, vb + j);
+    interior = __all(L.lo == 0 && L.tok0 + 8 <= first_pos + 1);
+  }
   float ka[8], kb[8], va[8], vb2[8];
   if constexpr (F::kParBytes != 0) {
     const uint32_t par = *reinterpret_cast<const uint32_t*>(stage + stage_par(SUBS) + sub * 256 + lane * 4);
@@ -841,12 +852,22 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
       else x[cb][i] = v;
     }
   if (!interior) {
+    // Blocks whose token count is no multiple of 8 end in a shifted run, whose first slots repeat tokens of the run
+    // before: with 38 or 60 tokens per block most sub-tiles hold one.  Where every slot is a token that every
+    // column sees, those repeats are all there is to mask.
+    if (__all(L.tok0 + 8 <= first_pos + 1)) {
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
-      const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
+      for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) x[cb][i] = (uint32_t)(i - L.lo) < n_ok ? x[cb][i] : -INFINITY;
+        for (int i = 0; i < 8; ++i) x[cb][i] = i >= L.lo ? x[cb][i] : -INFINITY;
+    } else {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const int hi = min(L.hi_u, len_cb[cb] - L.tok0);  // causality: this lane's column sees tokens < len_cb
+        const uint32_t n_ok = (uint32_t)max(hi - L.lo, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[cb][i] = (uint32_t)(i - L.lo) < n_ok ? x[cb][i] : -INFINITY;
+      }
     }
   }
   float tmax[NCB];
@@ -921,6 +942,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
   static_assert(NW == SUBS || NW == 2 * SUBS, "staging roles");
   static_assert(!DEQ || Fmt<DT>::kParBytes != 0, "staged dequantization is for the formats with per-token parameters");
   constexpr int CDT = DEQ ? FS_KV_FP16 : DT;  // the format the consumer code sees
+  const bool whole_runs = P.whole_runs != 0;  // (uniform)
   const bool does_k = NW == SUBS || w < SUBS, does_v = NW == SUBS || w >= SUBS;  // wave-uniform staging roles
   const int sw = w % SUBS;                                                       // the sub-tile this wave stages
   const DevBatch& B = P.b;
@@ -1024,7 +1046,8 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
         // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
-        wg_tile<CDT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st);
+        wg_tile<CDT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st,
+                                whole_runs);
       }
       uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
       stage_to(next, vb_next);
@@ -1589,6 +1612,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   P.seg_runs = (int32_t)std::min<int64_t>(1024, std::max<int64_t>(4, (int64_t)500 * B.R / 4 * 4));
   P.table_entries = P.seg_runs / B.R + 4;
   P.n_rows = (int32_t)n_rows;
+  P.whole_runs = (g.tokens_per_block & 7) == 0;
   if (n_rows == 0) return FS_OK;
   hipStream_t s = (hipStream_t)stream;
   (void)hipGetLastError();
