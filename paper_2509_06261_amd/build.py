@@ -16,6 +16,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 FLAGS += os.environ.get("FS_EXTRA_HIPCC_FLAGS", "").split()  # experiments only
+# The prefill kernels keep MFMA accumulators and results in vector registers (no AccVGPR operands): their softmax
+# reads every S^T tile with the vector ALU, which cannot address AccVGPRs.
+FILE_FLAGS = {"fs_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose: bool = False) -> str:
@@ -24,7 +27,8 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(csrc, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", csrc, "-c", os.path.join(csrc, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), "-I", os.path.join(ROOT, "include"), "-I", csrc, "-c",
+               os.path.join(csrc, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

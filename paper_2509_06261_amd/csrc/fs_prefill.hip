@@ -203,20 +203,13 @@ struct WideState {
   float m[NCB], l[NCB], zc[NCB];
 };
 
-// The accumulators live in AccVGPRs for the whole item: the MFMAs read and write them there, and nothing on the
-// per-tile path touches them with the vector ALU (which cannot address AccVGPRs: a plain C++ multiply in the
-// rarely taken rescale branch makes the register allocator shuttle all of them to VGPRs and back on every
-// tile).  The rescale therefore goes through explicit accvgpr moves.  The wait states that the hardware does
-// not interlock are spelled out: an MFMA result may be read by v_accvgpr_read only after the MFMA has
-// drained (acc_settle, issued once at the head of the branch -- every MFMA that writes the accumulators
-// precedes the branch), and a v_accvgpr_write needs two states before an MFMA reads the register as C.
-__device__ __forceinline__ void acc_settle() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
-__device__ __forceinline__ void acc_scale(float& a, float f) {
-  float tmp;
-  asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\tv_accvgpr_write_b32 %0, %1\n\ts_nop 1"
-               : "+a"(a), "=&v"(tmp)
-               : "v"(f));
-}
+// This file is compiled with VGPR-form MFMAs (-mllvm -amdgpu-mfma-vgpr-form, see build.py): accumulators, S^T
+// results and operands all live in vector registers and the kernels use no AccVGPRs as MFMA operands.  With the
+// default (accumulators in AccVGPRs, which the vector ALU cannot address) every S^T tile had to be read out with
+// v_accvgpr_read before the softmax -- 16 of the ~100 vector instructions of a sub-tile -- and the rarely taken
+// rescale of the accumulators needed explicit accvgpr moves in inline assembly to keep the register allocator
+// from shuttling all of them between the register files on every tile.  256 vector registers per wave (two waves
+// per SIMD) hold everything; measured against the AccVGPR build on one machine: + 10-14 % on every format.
 
 // Moves the reference of column block cb (see the lazy online softmax of fs_mfma_tiles.h): tmax = this lane's
 // largest logit of the tile for its column.
@@ -236,11 +229,7 @@ __device__ __forceinline__ void wide_move_reference(WideState<NCB>& st, int cb, 
   for (int r = 0; r < 4; ++r) {
     const float cr = __shfl(corr, 4 * j + r, 64);  // column h keeps its factor in lane c = h
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float a = st.acc[cb][e][r];
-      acc_scale(a, cr);
-      st.acc[cb][e][r] = a;
-    }
+    for (int e = 0; e < 8; ++e) st.acc[cb][e][r] *= cr;
   }
   st.m[cb] = m_new;
 }
@@ -336,7 +325,6 @@ __device__ __forceinline__ void wide_tile(const ItemCtx& X, const DevGeom& g, Ti
     need |= mx - st.m[cb] > kTau;
   }
   if (__any(need)) {
-    acc_settle();
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, tmax[cb], j);
   }
@@ -883,7 +871,6 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
     need |= mx - st.m[cb] > kTau;
   }
   if (__any(need)) {
-    acc_settle();
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, tmax[cb], j);
   }
@@ -1041,7 +1028,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
       fetch(vb_next);
       const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
-#pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
+#pragma unroll 1  // (unrolled by two: measured 0.5 % slower)
       for (int sub = 0; sub < SUBS; ++sub) {
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
@@ -1283,11 +1270,10 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
         }
       Logits<DT, NCB> cur;
       if (__any(make_logits<DT, NCB, SUBS>(sn, stage, 0, X, qsum, len_cb, alpha, first_pos, v0 + i * 4 * SUBS, lane, c, st, cur))) {
-        acc_settle();
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, cur.tmax[cb], j);
       }
-#pragma unroll 1  // (unrolled, the accumulators get a different register assignment per copy, and moves between)
+#pragma unroll 1  // (unrolled by two: measured 0.5 % slower)
       for (int sub = 0; sub < SUBS; ++sub) {
         const int nsub = (sub + 1) & (SUBS - 1);  // after the last sub-tile: the first again, its result unused
         // ---- block 1: S^T of sub-tile nsub (MFMA) beside the exponentials of sub-tile sub (vector ALU) ----
@@ -1362,7 +1348,6 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
         const bool need = make_logits<DT, NCB, SUBS>(sn, stage, nsub, X, qsum, len_cb, alpha, first_pos,
                                                      v0 + (i * SUBS + nsub) * 4, lane, c, st, cur);
         if (sub + 1 < SUBS && __any(need)) {  // (the wrapped-around sub-tile's logits are discarded)
-          acc_settle();
 #pragma unroll
           for (int cb = 0; cb < NCB; ++cb) wide_move_reference<DT, NCB>(st, cb, cur.tmax[cb], j);
         }
