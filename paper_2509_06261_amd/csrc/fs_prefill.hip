@@ -776,7 +776,8 @@ __device__ __forceinline__ void stage_v_deq(uint8_t* stage, int sub, int lane, i
 }
 
 // One staged 32-token sub-tile for the wave's column blocks: wide_tile with the operands read from LDS.
-template <int DT, int NCB, int SUBS>
+// VPRE: V fragments requested in front of the softmax (registers permitting)
+template <int DT, int NCB, int SUBS, int VPRE = 0>
 __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const ItemCtx& X, const u32x4 (&qb)[NCB][4],
                                         const float (&qsum)[NCB], const int (&len_cb)[NCB], float alpha, int first_pos,
                                         int vb, int lane, int j, int c, WideState<NCB>& st, bool whole_runs = false) {
@@ -796,6 +797,12 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
       s[cb][u] = acc;
     }
   }
+  // the first V fragments are requested now, in front of the softmax's vector work, so that the P V MFMAs do not
+  // start by waiting for LDS
+  u32x4 vpre[VPRE > 0 ? VPRE : 1];
+#pragma unroll
+  for (int e = 0; e < VPRE; ++e)
+    vpre[e] = *reinterpret_cast<const u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
   // interior (wave-uniform): every token of the sub-tile lies at or before the wave's first query token and no run
   // is a shifted one -- nothing to mask.  With whole runs per block the test is scalar arithmetic and the run's
   // location is needed on the mask path only.
@@ -909,7 +916,9 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const u32x4 b = *reinterpret_cast<const u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
+    u32x4 b;
+    if (e < VPRE) b = vpre[e];
+    else b = *reinterpret_cast<const u32x4*>(stage + stage_v(SUBS) + (uint32_t)((sub * 8 + e) * kFrag) + lane * 16);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) st.acc[cb][e] = mfma(pk[cb], b, st.acc[cb][e]);
   }
@@ -929,6 +938,8 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
   static_assert(NW == SUBS || NW == 2 * SUBS, "staging roles");
   static_assert(!DEQ || Fmt<DT>::kParBytes != 0, "staged dequantization is for the formats with per-token parameters");
   constexpr int CDT = DEQ ? FS_KV_FP16 : DT;  // the format the consumer code sees
+  // V fragments read ahead of the softmax: what the format's register budget leaves room for (two waves per SIMD)
+  constexpr int kVPre = NW != 8 ? 0 : (DEQ && DT == FS_KV_INT4 ? 8 : 4);
   const bool whole_runs = P.whole_runs != 0;  // (uniform)
   const bool does_k = NW == SUBS || w < SUBS, does_v = NW == SUBS || w >= SUBS;  // wave-uniform staging roles
   const int sw = w % SUBS;                                                       // the sub-tile this wave stages
@@ -1033,7 +1044,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
         // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
-        wg_tile<CDT, NCB, SUBS>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st,
+        wg_tile<CDT, NCB, SUBS, kVPre>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st,
                                 whole_runs);
       }
       uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
