@@ -9,10 +9,11 @@
 // Work decomposition: a work item is (sequence, KV head, tile of query tokens); the 16 logit columns of the
 // MFMAs (see fs_mfma_tiles.h) are (query token, query head of the group) pairs, 16 / G tokens per block of 16
 // columns.  One wave streams the cached tokens 0 .. last position of the tile once for all its columns;
-// causality is a per-column sequence length, so only the tiles on the diagonal pay for masking.  Two kernels:
-// prefill_kernel keeps one block of 16 columns per wave (two waves per SIMD), prefill_wide_kernel 2 or 4
-// blocks (one wave per SIMD, accumulators in AccVGPRs): a tile's K and V rows are then loaded, unpacked and
-// transposed once for 32 or 64 columns.  Items of one (sequence, head) are neighbours in the queue, longest
+// causality is a per-column sequence length, so only the tiles on the diagonal pay for masking.  Three kernels:
+// prefill_kernel keeps one block of 16 columns per wave (two waves per SIMD); prefill_wide_kernel 2 or 4
+// blocks (one wave per SIMD): a tile's K and V rows are then loaded, unpacked and transposed once for 32 or 64
+// columns; prefill_wg_kernel (the default for launches with at least one item per compute unit) lets the waves
+// of a workgroup share every unpacked K/V fragment through LDS.  Items of one (sequence, head) are neighbours in the queue, longest
 // first, so that the waves streaming the same keys and values run side by side and share them through the
 // L2.  Waves draw items from the same pooled ticket counters as the decode kernel.  A long context is
 // streamed in segments, the wave's block-address table being refilled per segment.
@@ -1043,7 +1044,8 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       for (int sub = 0; sub < SUBS; ++sub) {
         // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
         // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
-        // makes the compiler move all the accumulators between register files at the join, on every sub-tile.
+        // made the compiler move all the accumulators between register files at the join when they lived in
+        // AccVGPRs; kept, since a wave has at most two such sub-tiles per item.
         wg_tile<CDT, NCB, SUBS, kVPre>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st,
                                 whole_runs);
       }
