@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
     ap.add_argument("--kernel", default="0,0", help="column blocks,waves for fs_set_prefill_kernel (0,0 = automatic)")
+    ap.add_argument("--cache-resident", action="store_true",
+                    help="diagnosis: the attention reads every block table entry as the sequence's first block (K/V "
+                         "stay in cache; results meaningless, timing = the kernel without its memory traffic)")
     ap.add_argument("--staged-dequant", type=int, default=1, help="fs_set_prefill_staged_dequant (INT8 / INT4 models)")
     ap.add_argument("--pipelined", action="store_true", help="fs_set_prefill_pipelined(1) (with --kernel 16,4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -103,8 +106,9 @@ def main():
             layers.append((kb, vb, q))
         out = torch.empty((n_rows, s.n_q_heads, s.head_dim), dtype=torch.float16, device=dev)
         ws = torch.empty(fs.fs_prefill_workspace_bytes(len(lens)), dtype=torch.uint8, device=dev)
+        one_block = gw.tables[k][:, :1].expand(-1, gw.tables[k].shape[1]).contiguous()
         per_model.append(dict(k=k, s=s, m=m, q_off=q_off, q_off_d=torch.from_numpy(q_off).to(dev), si=si, po=po,
-                              layers=layers, out=out, ws=ws, sm=float(1.0 / np.sqrt(s.head_dim))))
+                              layers=layers, out=out, ws=ws, sm=float(1.0 / np.sqrt(s.head_dim)), one_block=one_block))
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     attn_ms = []
@@ -116,7 +120,8 @@ def main():
             fs.fs_kv_append(gw.pool, pm["m"], layer, kb, vb, pm["si"], pm["po"], gw.tables[pm["k"]])
             if timed:
                 ev[0].record()
-            fs.fs_prefill_attention(gw.pool, pm["m"], layer, pm["s"].n_q_heads, pm["sm"], q, gw.tables[pm["k"]],
+            tab = pm["one_block"] if args.cache_resident else gw.tables[pm["k"]]
+            fs.fs_prefill_attention(gw.pool, pm["m"], layer, pm["s"].n_q_heads, pm["sm"], q, tab,
                                     gw.seq_lens[pm["k"]], pm["q_off_d"], pm["q_off"], pm["out"], None, pm["ws"])
             if timed:
                 ev[1].record()
