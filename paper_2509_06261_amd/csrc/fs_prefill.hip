@@ -1040,14 +1040,15 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
       fetch(vb_next);
       const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
+      // A wave with query tokens multiplies every sub-tile of the step, also those past its own diagonal or past
+      // the segment's end (fully masked there: weights 0 over finite operands; at most two per item).  A wave
+      // WITHOUT query tokens (a ragged last item of a chunk; chunks shorter than the workgroup's 16 NW / G tokens)
+      // only stages its share of K/V and leaves the SIMD to its sibling.
+      if (n_tok > 0) {
 #pragma unroll 1  // (unrolled by two: measured 0.5 % slower)
-      for (int sub = 0; sub < SUBS; ++sub) {
-        // Every wave multiplies every sub-tile of the step, also those past its own diagonal or past the
-        // segment's end (fully masked there: weights 0 over finite operands).  Skipping them under a branch
-        // made the compiler move all the accumulators between register files at the join when they lived in
-        // AccVGPRs; kept, since a wave has at most two such sub-tiles per item.
-        wg_tile<CDT, NCB, SUBS, kVPre>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c, st,
-                                whole_runs);
+        for (int sub = 0; sub < SUBS; ++sub)
+          wg_tile<CDT, NCB, SUBS, kVPre>(stage, sub, X, qb, qsum, len_cb, alpha, first_pos, v0 + (i * SUBS + sub) * 4, lane, j, c,
+                                         st, whole_runs);
       }
       uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
       stage_to(next, vb_next);
