@@ -211,7 +211,11 @@ __device__ __forceinline__ void combine_row(const float* P, uint64_t chunk_strid
   if (lse && lane == 0) *lse = M + logf(L);
 }
 
-__global__ __launch_bounds__(kCombineWaves * 64) void combine_kernel(MultiArgs A) {
+// MAXNK: the largest head_dim / 64 among the launch's batches.  The wider rows' code is compiled out of the
+// narrower kernels: with it the kernel needs 128 registers per lane, which halves the waves a compute unit holds,
+// and this kernel lives on the number of waves that wait for memory at the same time.
+template <int MAXNK>
+__global__ __launch_bounds__(kCombineWaves * 64, MAXNK <= 2 ? 8 : 4) void combine_kernel(MultiArgs A) {
   const int lane = threadIdx.x & 63;
   // one wave per (sequence, query head); the wave index is made provably uniform so that everything derived
   // from the row stays in scalar registers
@@ -239,9 +243,9 @@ __global__ __launch_bounds__(kCombineWaves * 64) void combine_kernel(MultiArgs A
   _Float16* out = B.out + ((int64_t)seq * B.n_q + h) * D;
   float* lse = B.lse ? B.lse + (int64_t)seq * B.n_q + h : nullptr;
   if (D <= 64) combine_row<1>(P, chunk_stride, n_chunks, D, lane, out, lse);
-  else if (D == 128) combine_row<2>(P, chunk_stride, n_chunks, D, lane, out, lse);
-  else if (D == 256) combine_row<4>(P, chunk_stride, n_chunks, D, lane, out, lse);
-  else combine_row<8>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else if (MAXNK >= 2 && D == 128) combine_row<2>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else if (MAXNK >= 4 && D == 256) combine_row<4>(P, chunk_stride, n_chunks, D, lane, out, lse);
+  else if (MAXNK >= 8) combine_row<8>(P, chunk_stride, n_chunks, D, lane, out, lse);
 }
 
 }  // namespace
@@ -252,7 +256,13 @@ hipError_t launch_prep(const MultiArgs& A, hipStream_t s) {
 }
 
 hipError_t launch_combine(const MultiArgs& A, hipStream_t s) {
-  hipLaunchKernelGGL(combine_kernel, dim3((A.n_qrows_total + kCombineWaves - 1) / kCombineWaves), dim3(kCombineWaves * 64), 0, s, A);
+  int max_d = 0;
+  for (int i = 0; i < A.n_batches; ++i) max_d = std::max(max_d, (int)A.b[i].g.D);
+  const dim3 grid((A.n_qrows_total + kCombineWaves - 1) / kCombineWaves), block(kCombineWaves * 64);
+  if (max_d <= 64) hipLaunchKernelGGL(combine_kernel<1>, grid, block, 0, s, A);
+  else if (max_d <= 128) hipLaunchKernelGGL(combine_kernel<2>, grid, block, 0, s, A);
+  else if (max_d <= 256) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, s, A);
+  else hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, s, A);
   return hipGetLastError();
 }
 
