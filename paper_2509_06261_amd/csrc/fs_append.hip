@@ -85,6 +85,30 @@ __device__ __forceinline__ uint32_t e4m3_bits(float y) {
   return sign | code;
 }
 
+// n / d for many n and one d.  The correctly rounded fp32 division is a reciprocal estimate, one Newton step on
+// it, and a quotient with two residual corrections, all in fused multiply-adds; the first half depends on d
+// alone and is done once per row here.  What is left out is the operand scaling of the general sequence, which
+// only matters near the ends of the exponent range: d must be a normal number of moderate size (the fp16-valued
+// scales of the integer formats: 2^-24 .. 65504) and n / d must stay finite (|n| <= the row's extremum, so the
+// quotient is bounded by the format's range unless the scale saturated, and then by 2^128 / 65504).  Within that
+// domain the result is the division's, bit for bit; a quotient in the subnormal range may differ in its last bits,
+// where every value rounds to the integer 0 anyway.
+struct Divisor {
+  float d, r;
+  __device__ __forceinline__ explicit Divisor(float d_) : d(d_) {
+    const float r0 = __builtin_amdgcn_rcpf(d);
+    const float e = __builtin_fmaf(-d, r0, 1.0f);
+    r = __builtin_fmaf(e, r0, r0);
+  }
+  __device__ __forceinline__ float operator()(float n) const {
+    float q = n * r;
+    const float e1 = __builtin_fmaf(-d, q, n);
+    q = __builtin_fmaf(e1, r, q);
+    const float e2 = __builtin_fmaf(-d, q, n);
+    return __builtin_fmaf(e2, r, q);
+  }
+};
+
 // the lane's eight source elements, widened exactly
 template <bool kSrcF32>
 __device__ __forceinline__ void load8(const void* src, int64_t idx, float (&x)[kEpl]) {
@@ -167,10 +191,11 @@ __global__ __launch_bounds__(kWaves * 64) void kv_append_kernel(AppendArgs A) {
       amax = row_max(amax, lpr);
       const uint16_t sb = scale_bits(__fdiv_rn(amax, 127.0f));
       const float sf = f16_value(sb);
+      const Divisor by_scale(sf);
       u32x2 w = {0u, 0u};
 #pragma unroll
       for (int q = 0; q < kEpl; ++q) {
-        const float c = fminf(fmaxf(rintf(__fdiv_rn(x[q], sf)), -127.f), 127.f);
+        const float c = fminf(fmaxf(rintf(by_scale(x[q])), -127.f), 127.f);
         w[q >> 2] |= ((uint32_t)(int)c & 0xFF) << (8 * (q & 3));
       }
       if (ok) {
@@ -188,11 +213,12 @@ __global__ __launch_bounds__(kWaves * 64) void kv_append_kernel(AppendArgs A) {
       hi = row_max(hi, lpr);
       const uint16_t sb = scale_bits(__fdiv_rn(hi - lo, 15.0f));
       const float sf = f16_value(sb);
-      const float z = fminf(fmaxf(rintf(__fdiv_rn(-lo, sf)), 0.f), 15.f);
+      const Divisor by_scale(sf);
+      const float z = fminf(fmaxf(rintf(by_scale(-lo)), 0.f), 15.f);
       uint32_t w = 0;
 #pragma unroll
       for (int q = 0; q < kEpl; ++q) {
-        const float c = fminf(fmaxf(rintf(__fdiv_rn(x[q], sf)) + z, 0.f), 15.f);
+        const float c = fminf(fmaxf(rintf(by_scale(x[q])) + z, 0.f), 15.f);
         w |= (uint32_t)c << (4 * q);  // element 2j in the low nibble of byte j
       }
       if (ok) {
