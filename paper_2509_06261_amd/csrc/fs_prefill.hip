@@ -784,6 +784,9 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
                                         int vb, int lane, int j, int c, WideState<NCB>& st, bool whole_runs = false) {
   using F = Fmt<DT>;
   float4v s[NCB][2];
+  // The wave raises its priority for its MFMA sections and drops it for the softmax: of the two waves of a SIMD
+  // the one that feeds the matrix pipe goes first, the other's vector work fills in (+ 2.4-3.5 % measured).
+  __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     u32x4 a[4];
@@ -798,6 +801,7 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
       s[cb][u] = acc;
     }
   }
+  __builtin_amdgcn_s_setprio(0);
   // the first V fragments are requested now, in front of the softmax's vector work, so that the P V MFMAs do not
   // start by waiting for LDS
   u32x4 vpre[VPRE > 0 ? VPRE : 1];
@@ -915,6 +919,7 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
       st.l[cb] = l;
     }
   }
+  __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     u32x4 b;
