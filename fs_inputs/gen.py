@@ -27,13 +27,15 @@ device generator, so no transcendental function is evaluated twice.
 from __future__ import annotations
 
 import functools
+import os
 
 import numpy as np
 
 GOLD = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
-MASTER_SEED = 20250906
+# every workload derives from this seed; FS_INPUT_SEED replays the tests and benchmarks on other draws
+MASTER_SEED = int(os.environ.get("FS_INPUT_SEED", "20250906"))
 
 WHICH_K, WHICH_V, WHICH_Q = 0, 1, 2
 
