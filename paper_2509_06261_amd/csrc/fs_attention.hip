@@ -159,6 +159,14 @@ __device__ __forceinline__ void combine_row(const float* P, uint64_t chunk_strid
     m0 = P[lane * chunk_stride + D];
     l0 = P[lane * chunk_stride + D + 1];
   }
+  // the first four splits' partial sums do not depend on the reference: requested before it is reduced (a row has
+  // four to five splits on average, so this is most rows' whole read); splits past the row's last repeat it with
+  // weight 0
+  float x0[4][NK];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int k = 0; k < NK; ++k) x0[u][k] = P[min(u, n_chunks - 1) * chunk_stride + dl + 64 * k];
   float M = m0;
   for (int c = lane + 64; c < n_chunks; c += 64) M = fmaxf(M, P[c * chunk_stride + D]);
 #pragma unroll
@@ -181,7 +189,21 @@ __device__ __forceinline__ void combine_row(const float* P, uint64_t chunk_strid
     }
     const int n = min(64, n_chunks - c0);
     const float* pg = P + c0 * chunk_stride + dl;
+    // weight of split c0 + i, 0 past the group's last split (i, n uniform)
+    auto weight = [&](int i) {
+      const float wi = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), min(i, 63)));
+      return i < n ? wi : 0.f;
+    };
     int c = 0;
+    if (c0 == 0) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float wc = weight(u);
+#pragma unroll
+        for (int k = 0; k < NK; ++k) o[k] += x0[u][k] * wc;
+      }
+      c = 4;
+    }
     for (; c + 8 <= n; c += 8) {  // eight splits' loads in flight together
       float x[8][NK];
 #pragma unroll
@@ -195,10 +217,18 @@ __device__ __forceinline__ void combine_row(const float* P, uint64_t chunk_strid
         for (int k = 0; k < NK; ++k) o[k] += x[u][k] * wc;
       }
     }
-    for (; c < n; ++c) {
-      const float wc = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), c));
+    for (; c < n; c += 4) {  // the rest in fours, again all in flight together; surplus splits repeat the last, weight 0
+      float x[4][NK];
 #pragma unroll
-      for (int k = 0; k < NK; ++k) o[k] += pg[c * chunk_stride + 64 * k] * wc;
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int k = 0; k < NK; ++k) x[u][k] = pg[min(c + u, n - 1) * chunk_stride + 64 * k];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float wc = weight(c + u);
+#pragma unroll
+        for (int k = 0; k < NK; ++k) o[k] += x[u][k] * wc;
+      }
     }
   }
 #pragma unroll

@@ -14,7 +14,7 @@ from fs_inputs import workloads
 pytestmark = pytest.mark.gpu
 
 
-def _full_size(cfg, layers, n_random, prefill_random=None):
+def _full_size(cfg, layers, n_random, prefill_random=None, many_items=False):
     import torch
     import gpu_harness
 
@@ -42,6 +42,25 @@ def _full_size(cfg, layers, n_random, prefill_random=None):
             tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
             d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
             assert np.all(np.isfinite(outs[0][k])) and d <= tol, f"model {k}: kernels differ by {d:.3e}"
+        if many_items:
+            # 16 KiB of KV per work item: more than 65535 items per batch (their products in the queue's interleaving
+            # of the batches pass 32 bits), some 140 splits per sequence for the combine
+            n_items = [sum(-(-int(l) // 32) for l in s.lens) * s.n_kv_heads for s in wl.models]
+            assert max(n_items) > 65535, n_items
+            fs.fs_set_split_bytes(16 * 1024)
+            try:
+                batches, keep = gw.make_batches(layers, with_lse=False)
+                ws = gw.decode(batches)
+                torch.cuda.synchronize()
+                assert fs.fs_decode_status(ws) == 0
+                fine = [o.float().cpu().numpy() for o in keep["out"]]
+            finally:
+                fs.fs_set_split_bytes(0)
+            for k, s in enumerate(wl.models):
+                tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
+                d = float(np.max(np.abs(outs[0][k] - fine[k])))
+                print(f"[full-size] config {cfg}: model {k}, {n_items[k]} items at 16 KiB: differs by {d:.2e}", flush=True)
+                assert np.all(np.isfinite(fine[k])) and d <= tol, f"model {k}: split sizes differ by {d:.3e}"
         if prefill_random is not None:
             for k in range(len(wl.models)):
                 print(f"[full-size] config {cfg}: whole-prompt prefill of model {k}", flush=True)
@@ -57,7 +76,7 @@ def test_config2_llama8b_fp16_full():
 
 
 def test_config3_fp16_fp8_interleaved_full():
-    _full_size(3, [3, 29], n_random=3, prefill_random=1)
+    _full_size(3, [3, 29], n_random=3, prefill_random=1, many_items=True)
 
 
 def test_config4_int4_full():
