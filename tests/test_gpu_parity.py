@@ -127,6 +127,24 @@ def test_group_sizes_and_head_dim_64(group, mode):
         par.close()
 
 
+@pytest.mark.parametrize("head_dim", [8, 32, 256, 512])
+@pytest.mark.parametrize("dtype,src_f32", [(FP16, False), (FP8, False), (INT8, False), (INT4, True)])
+def test_head_dims_from_8_to_512(dtype, src_f32, head_dim):
+    """The smallest and the largest head_dim the library accepts and two between (one lane to a whole wave per
+    row in the append and the vector kernel; every column-group count of the split combine), splits forced: two
+    splits for the longest sequence at head_dim 8, more than twenty at 512."""
+    lens = np.array([1, 5, 64, 129, 700], np.int32)
+    wl = Workload("hd", 64 * KiB, 32 * MiB, [ModelSpec("m", dtype, 2, head_dim, 1, 6, lens, tag=44, src_f32=src_f32)],
+                  "shuffle")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(16 * KiB)
+        print(par.run_and_check([0]))
+    finally:
+        par.fs.fs_set_split_bytes(0)
+        par.close()
+
+
 @pytest.mark.parametrize("mode", KERNEL_MODES)
 @pytest.mark.parametrize("group", [2, 3, 5, 8, 12, 16])
 @pytest.mark.parametrize("dtype", [FP16, INT4])
