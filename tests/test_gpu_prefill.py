@@ -110,6 +110,8 @@ def test_group_sizes(group):
     (INT4, 256, 2, 4, 128, True),    # head_dim 256
     (FP8, 32, 2, 6, 16, False),      # head_dim 32, three query heads per KV head (a ragged last group of the kernel)
     (FP16, 128, 8, 8, 16, False),    # head_dim 128 in 16 KiB slabs: 2 tokens per block, fewer than an MFMA run
+    (INT8, 8, 2, 4, 16, False),      # the smallest head_dim: one lane per row
+    (FP16, 512, 2, 2, 64, False),    # the largest: a whole wave per row
 ])
 def test_other_shapes_take_the_vector_kernel(dtype, head_dim, kv_heads, q_heads, slab_kib, src_f32):
     """Shapes the MFMA prefill kernels do not cover (head_dim other than 128, blocks of fewer than 8 tokens)."""
