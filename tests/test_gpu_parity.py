@@ -89,6 +89,25 @@ def test_mixed_four_model_pool_small(mode):
 
 
 @pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_eight_batches_in_one_launch(mode):
+    """The most batches a multi-model launch takes: eight models (each format twice, different head counts and
+    lengths) interleaved block by block in one pool, splits forced so that the queue merges eight item lists."""
+    la = np.array([3, 200, 64, 333], np.int32)
+    lb = np.array([150, 1, 257, 90, 31], np.int32)
+    models = [ModelSpec(f"m{i}", dt, 2, 128, 1, 2 * grp, lens, tag=50 + i, src_f32=dt == INT4)
+              for i, (dt, grp, lens) in enumerate([(FP16, 4, la), (FP8, 2, lb), (INT8, 1, la), (INT4, 8, lb),
+                                                   (INT4, 1, la), (INT8, 4, lb), (FP8, 16, la), (FP16, 3, lb)])]
+    wl = Workload("eight", 64 * KiB, 64 * MiB, models, "interleave")
+    par = _parity(wl)
+    try:
+        par.fs.fs_set_split_bytes(16 * KiB)
+        print("max abs err", par.run_and_check([0] * 8, kernel_mode=mode))
+    finally:
+        par.fs.fs_set_split_bytes(0)
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
 @pytest.mark.parametrize("sm_scale", [-0.07, 0.0, 0.3])
 def test_softmax_scales_other_than_the_usual(sm_scale, mode):
     """A negative, a zero (uniform weights: the mean of V) and a large softmax scale, four precisions in one launch."""
