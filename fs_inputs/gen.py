@@ -43,13 +43,13 @@ WHICH_K, WHICH_V, WHICH_Q = 0, 1, 2
 def mix64(z):
     """splitmix64 output function on uint64 scalars or arrays."""
     with np.errstate(over="ignore"):
-        z = np.asarray(z, dtype=np.uint64)
-        z = z ^ (z >> np.uint64(30))
-        z = z * _M1
-        z = z ^ (z >> np.uint64(27))
-        z = z * _M2
-        z = z ^ (z >> np.uint64(31))
-    return z
+        z = np.array(z, dtype=np.uint64)  # a private copy: the steps below work in place
+        z ^= z >> np.uint64(30)
+        z *= _M1
+        z ^= z >> np.uint64(27)
+        z *= _M2
+        z ^= z >> np.uint64(31)
+    return z if z.ndim else z[()]
 
 
 @functools.lru_cache(maxsize=1)
@@ -89,8 +89,35 @@ def normal_rows(seed: int, model: int, layer: int, which: int, seq: int, pos, n_
     """
     pos = np.asarray(pos, dtype=np.uint64).reshape(-1)
     key = stream_key(seed, model, layer, which, seq)
-    hd = np.uint64(n_heads * head_dim)
-    e = pos[:, None] * hd + np.arange(n_heads * head_dim, dtype=np.uint64)[None, :]
+    hd = n_heads * head_dim
+    if hd % 4 == 0 and np.little_endian:
+        # a row is hd / 4 whole words: draw each word once and read its four 16-bit fields in place
+        # (field e & 3 of a word is bits 16 (e & 3) .. 16 (e & 3) + 15: the little-endian uint16 view);
+        # rows go through in slices that reuse two work buffers
+        wq = hd // 4
+        out = np.empty((len(pos), hd), dtype=np.float32)
+        table = normal_table()
+        step = max(1, (1 << 18) // wq)
+        col = np.arange(wq, dtype=np.uint64)[None, :]
+        z = np.empty((step, wq), dtype=np.uint64)
+        t = np.empty((step, wq), dtype=np.uint64)
+        with np.errstate(over="ignore"):
+            for r0 in range(0, len(pos), step):
+                n = min(step, len(pos) - r0)
+                zz, tt = z[:n], t[:n]
+                np.multiply(pos[r0:r0 + n, None], np.uint64(wq), out=zz)
+                zz += col
+                zz += np.uint64(1)
+                zz *= GOLD
+                zz += key
+                for sh, mul in ((30, _M1), (27, _M2), (31, None)):  # mix64, in place
+                    np.right_shift(zz, np.uint64(sh), out=tt)
+                    zz ^= tt
+                    if mul is not None:
+                        zz *= mul
+                out[r0:r0 + n] = table[zz.view(np.uint16)]
+        return out.reshape(len(pos), n_heads, head_dim)
+    e = pos[:, None] * np.uint64(hd) + np.arange(hd, dtype=np.uint64)[None, :]
     x = normal_table()[_u16(key, e)]
     return x.reshape(len(pos), n_heads, head_dim)
 

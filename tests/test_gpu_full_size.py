@@ -1,11 +1,15 @@
 """GPU parity at the benchmark's full sizes (configs 2-5), in the launch configuration bench.py times:
 the whole workload is placed and decoded in one multi-model launch; the allocator is compared with
 the oracle operation by operation over the complete trace; appended bytes and attention outputs are
-compared on a seeded sample of sequences per model (always including the shortest and the longest)
-that the CPU oracle recomputes one by one; every other sequence is cross-checked between the two
-independently written GPU kernels (MFMA vs generic).  Whole-prompt prefill over the same full-size pools, as
+compared with the CPU oracle on every sequence of config 2 and, for configs 3-5, on 32 seeded sequences per
+model plus the shortest and the longest; on top of that all sequences are cross-checked between the
+two independently written GPU kernels (MFMA vs generic).  Whole-prompt prefill over the same full-size pools, as
 bench_prefill.py launches it (default kernel choice), is compared with the oracle on windows of query rows of
-sampled sequences."""
+sampled sequences.
+
+One workload is stood up once per config (module-scoped fixture: placement in lock-step with the oracle's
+allocator, one layer of KV per model, one multi-model decode launch); the comparisons are separate tests per
+model so that each one stays short."""
 import numpy as np
 import pytest
 
@@ -13,75 +17,102 @@ from fs_inputs import workloads
 
 pytestmark = pytest.mark.gpu
 
+# config -> (layer per model, oracle sample per model (None = every sequence), prefill sample per model)
+CONFIGS = {2: ([17], None, 3), 3: ([3, 29], 32, 1), 4: ([11], 32, 1), 5: ([7, 0, 3, 9], 32, 1)}
 
-def _full_size(cfg, layers, n_random, prefill_random=None, many_items=False):
-    import torch
+
+@pytest.fixture(scope="module", params=sorted(CONFIGS), ids=lambda c: f"config{c}")
+def stood_up(request):
     import gpu_harness
 
+    cfg = request.param
+    layers, n_random, prefill_random = CONFIGS[cfg]
     wl = workloads.config(cfg)
     print(f"[full-size] config {cfg}: placing", flush=True)
-    par = gpu_harness.Parity(wl, zero_pool=False)
+    par = gpu_harness.Parity(wl, zero_pool=False)  # asserts every allocator call and the final slab table identical
     try:
         print(f"[full-size] config {cfg}: {par.n_alloc_ops} allocator calls identical; decoding", flush=True)
-        errs = par.run_and_check(layers, n_random=n_random)
-        print(f"[full-size] config {cfg}: sampled max abs err {errs}", flush=True)
-        # all sequences: the MFMA kernel against the generic kernel on the same pool contents
-        gw, fs = par.gw, par.fs
-        outs = {}
-        for mode in (0, 1):
-            fs.fs_set_kernel_mode(mode)
-            try:
-                batches, keep = gw.make_batches(layers, with_lse=False)
-                ws = gw.decode(batches)
-                torch.cuda.synchronize()
-                assert fs.fs_decode_status(ws) == 0
-                outs[mode] = [o.float().cpu().numpy() for o in keep["out"]]
-            finally:
-                fs.fs_set_kernel_mode(0)
-        for k, s in enumerate(wl.models):
-            tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
-            d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
-            assert np.all(np.isfinite(outs[0][k])) and d <= tol, f"model {k}: kernels differ by {d:.3e}"
-        if many_items:
-            # 16 KiB of KV per work item: more than 65535 items per batch (their products in the queue's interleaving
-            # of the batches pass 32 bits), some 140 splits per sequence for the combine
-            n_items = [sum(-(-int(l) // 32) for l in s.lens) * s.n_kv_heads for s in wl.models]
-            assert max(n_items) > 65535, n_items
-            fs.fs_set_split_bytes(16 * 1024)
-            try:
-                batches, keep = gw.make_batches(layers, with_lse=False)
-                ws = gw.decode(batches)
-                torch.cuda.synchronize()
-                assert fs.fs_decode_status(ws) == 0
-                fine = [o.float().cpu().numpy() for o in keep["out"]]
-            finally:
-                fs.fs_set_split_bytes(0)
-            for k, s in enumerate(wl.models):
-                tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
-                d = float(np.max(np.abs(outs[0][k] - fine[k])))
-                print(f"[full-size] config {cfg}: model {k}, {n_items[k]} items at 16 KiB: differs by {d:.2e}", flush=True)
-                assert np.all(np.isfinite(fine[k])) and d <= tol, f"model {k}: split sizes differ by {d:.3e}"
-        if prefill_random is not None:
-            for k in range(len(wl.models)):
-                print(f"[full-size] config {cfg}: whole-prompt prefill of model {k}", flush=True)
-                perr = par.prefill_whole_prompts_and_check_windows(k, layers[k], prefill_random)
-                print(f"[full-size] config {cfg}: prefill model {k}: max abs err {perr[0]:.2e} on {perr[1]} rows", flush=True)
-        return errs
+        keep = par.populate_and_decode(layers)
+        yield dict(cfg=cfg, par=par, wl=wl, layers=layers, keep=keep, n_random=n_random, prefill_random=prefill_random)
     finally:
         par.close()
 
 
-def test_config2_llama8b_fp16_full():
-    _full_size(2, [17], n_random=6, prefill_random=3)
+def test_allocator_trace_identical_and_decode_ran(stood_up):
+    par, wl = stood_up["par"], stood_up["wl"]
+    assert par.n_alloc_ops >= sum(s.n_seq for s in wl.models)
+    par.check_allocator_state()
 
 
-def test_config3_fp16_fp8_interleaved_full():
-    _full_size(3, [3, 29], n_random=3, prefill_random=1, many_items=True)
+@pytest.mark.parametrize("k", range(4))
+def test_bytes_and_outputs_against_the_oracle(stood_up, k):
+    """Model k of the config: appended bytes bit-identical, decode outputs and lse within the tolerance, on every
+    sequence (config 2) or on 32 seeded sequences plus the shortest and the longest (configs 3-5)."""
+    par, wl = stood_up["par"], stood_up["wl"]
+    if k >= len(wl.models):
+        pytest.skip("the config has fewer models")
+    err, n = par.check_model(k, stood_up["layers"], stood_up["keep"], stood_up["n_random"])
+    want = wl.models[k].n_seq if stood_up["n_random"] is None else min(wl.models[k].n_seq, 32)
+    assert n >= want
+    print(f"[full-size] config {stood_up['cfg']} model {k} ({wl.models[k].name}): {n} sequences, max abs err {err:.2e}")
 
 
-def test_config4_int4_full():
-    _full_size(4, [11], n_random=4, prefill_random=1)
+def _decode_all(par, layers):
+    import torch
+
+    batches, keep = par.gw.make_batches(layers, with_lse=False)
+    ws = par.gw.decode(batches)
+    torch.cuda.synchronize()
+    assert par.fs.fs_decode_status(ws) == 0
+    return [o.float().cpu().numpy() for o in keep["out"]]
 
 
-def test_config5_four_model_churned_pool_full():
-    _full_size(5, [7, 0, 3, 9], n_random=2, prefill_random=1)
+def test_every_sequence_mfma_against_generic_kernel(stood_up):
+    par, wl, layers = stood_up["par"], stood_up["wl"], stood_up["layers"]
+    import gpu_harness
+
+    outs = {}
+    for mode in (0, 1):
+        par.fs.fs_set_kernel_mode(mode)
+        try:
+            outs[mode] = _decode_all(par, layers)
+        finally:
+            par.fs.fs_set_kernel_mode(0)
+    for k, s in enumerate(wl.models):
+        tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
+        d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
+        assert np.all(np.isfinite(outs[0][k])) and d <= tol, f"model {k}: kernels differ by {d:.3e}"
+        # and the launch the oracle tests looked at is this same deterministic launch
+        assert np.array_equal(outs[0][k], stood_up["keep"]["out"][k].float().cpu().numpy())
+
+
+def test_many_small_items(stood_up):
+    """16 KiB of KV per work item: more than 65535 items per batch (their products in the queue's interleaving of
+    the batches pass 32 bits), some 140 splits per sequence for the combine."""
+    if stood_up["cfg"] != 3:
+        pytest.skip("run on the two-model config")
+    par, wl, layers = stood_up["par"], stood_up["wl"], stood_up["layers"]
+    import gpu_harness
+
+    n_items = [sum(-(-int(l) // 32) for l in s.lens) * s.n_kv_heads for s in wl.models]
+    assert max(n_items) > 65535, n_items
+    base = [o.float().cpu().numpy() for o in stood_up["keep"]["out"]]
+    par.fs.fs_set_split_bytes(16 * 1024)
+    try:
+        fine = _decode_all(par, layers)
+    finally:
+        par.fs.fs_set_split_bytes(0)
+    for k, s in enumerate(wl.models):
+        tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
+        d = float(np.max(np.abs(base[k] - fine[k])))
+        print(f"[full-size] config 3: model {k}, {n_items[k]} items at 16 KiB: differs by {d:.2e}", flush=True)
+        assert np.all(np.isfinite(fine[k])) and d <= tol, f"model {k}: split sizes differ by {d:.3e}"
+
+
+@pytest.mark.parametrize("k", range(4))
+def test_whole_prompt_prefill_windows_against_the_oracle(stood_up, k):
+    par, wl = stood_up["par"], stood_up["wl"]
+    if k >= len(wl.models):
+        pytest.skip("the config has fewer models")
+    perr = par.prefill_whole_prompts_and_check_windows(k, stood_up["layers"][k], stood_up["prefill_random"])
+    print(f"[full-size] config {stood_up['cfg']}: prefill model {k}: max abs err {perr[0]:.2e} on {perr[1]} rows", flush=True)

@@ -44,10 +44,13 @@ def kernel_variant(request):
     assert fs.fs_set_prefill_kernel(blocks, waves) == 0
     fs.fs_set_prefill_pipelined(name == "wg4p")  # the software-pipelined form of the 4-wave workgroup kernel
     fs.fs_set_prefill_staged_dequant(name == "wg8dq")
+    import gpu_harness
+    gpu_harness.STAGED_DEQUANT = name == "wg8dq"  # the wider lse bound applies to that path alone
     yield name
     fs.fs_set_prefill_kernel(0, 0)
     fs.fs_set_prefill_pipelined(0)
     fs.fs_set_prefill_staged_dequant(-1)  # the default (on)
+    gpu_harness.STAGED_DEQUANT = True
 
 
 def _parity(wl):
