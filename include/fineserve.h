@@ -178,6 +178,19 @@ int fs_decode_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_head
 int fs_decode_attention_multi(fs_pool* pool, const fs_batch_t* batches, int n_batches, void* workspace,
                               uint64_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid it): fs_decode_attention_multi with its workspace in a 64 MiB array that the library holds in the
+ * device's memory from load until the process ends (one copy per GPU).  Calls no hipMalloc / hipFree and no
+ * allocating library routine; the caller still passes inputs and outputs.  The pool's device must be the current
+ * device.  FS_ERR_NOMEM if the batches need more than 64 MiB (about 30 000 work items of 192 KiB of KV each for
+ * four query heads per KV head: use fs_decode_attention_multi then), decided on the host before any launch.
+ *   status_out: optional device uint32; receives the launch's fs_decode_status word (by a 4-byte device copy
+ *   on `stream` behind the kernels).
+ * Every call on one GPU uses the same array: two such calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe. */
+int fs_decode_attention_multi_static(fs_pool* pool, const fs_batch_t* batches, int n_batches, uint32_t* status_out,
+                                     void* stream);
+
 /* After the stream has passed a decode call: 0 if every sequence length was in range and the
  * workspace sufficed, else a bit mask (1: length out of range, clamped; 2: workspace too small,
  * affected sequences left unwritten).  Synchronizes the stream. */

@@ -25,7 +25,7 @@ EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_regist
            "fs_block_bytes", "fs_slab_bytes_for_blocks", "fs_model_register_tokens",
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
-           "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_status", "fs_prefill_workspace_bytes",
+           "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_attention_multi_static", "fs_decode_status", "fs_prefill_workspace_bytes",
            "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_set_prefill_kernel", "fs_set_prefill_pipelined", "fs_set_prefill_staged_dequant",
            "fs_set_kernel_mode",
            "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
@@ -80,6 +80,7 @@ def _load():
         "fs_decode_workspace_bytes": (u64, [vp, ctypes.POINTER(fs_batch_t), i32]),
         "fs_decode_attention": (i32, [vp, i32, i32, i32, f32, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
         "fs_decode_attention_multi": (i32, [vp, ctypes.POINTER(fs_batch_t), i32, vp, u64, vp]),
+        "fs_decode_attention_multi_static": (i32, [vp, ctypes.POINTER(fs_batch_t), i32, vp, vp]),
         "fs_decode_status": (i32, [vp, vp]),
         "fs_prefill_workspace_bytes": (u64, [i32]),
         "fs_prefill_attention": (i32, [vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
@@ -295,6 +296,14 @@ def fs_decode_attention_multi(pool, batches, workspace, stream=None):
                                       workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != FS_OK:
         raise FsError(rc, "fs_decode_attention_multi")
+
+
+def fs_decode_attention_multi_static(pool, batches, status_out=None, stream=None):
+    """status_out: optional CUDA int32/uint32 tensor of one element."""
+    arr = (fs_batch_t * len(batches))(*batches)
+    rc = _L.fs_decode_attention_multi_static(pool, arr, len(batches), _dp(status_out), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_decode_attention_multi_static")
 
 
 def fs_decode_status(workspace, stream=None) -> int:

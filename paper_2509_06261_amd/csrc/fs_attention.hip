@@ -12,6 +12,15 @@
 
 #include "fs_attention.h"
 
+// Workspace of fs_decode_attention_multi_static, the entry point for callers that cannot allocate: one copy per
+// GPU, held until the process ends.  In host code the name is only a stand-in for the symbol: the device address
+// comes from hipGetSymbolAddress, once per device (g_scratch_ptr), and only that pointer is ever handed to a kernel
+// or a copy.  The launch's preparation kernel resets every counter it uses, so nothing else needs clearing.
+constexpr uint64_t kStaticScratchBytes = 64ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxScratchDevices = 64;
+static uint8_t* g_scratch_ptr[kMaxScratchDevices] = {};
+
 namespace fs {
 namespace {
 
@@ -449,6 +458,56 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
 
 using namespace fs;
 
+namespace {
+// Validates, lays the workspace out and enqueues work-list preparation, attention and split combine on `s`.
+// Allocates nothing.
+int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
+                  const char* too_small, hipStream_t s) {
+  Plan plan;
+  if (!workspace || ((uintptr_t)workspace & 255)) {
+    set_error("decode attention: workspace must be a 256-byte aligned device pointer");
+    return FS_ERR_INVALID;
+  }
+  int rc = make_plan(p, batches, n_batches, workspace, plan);
+  if (rc != FS_OK) return rc;
+  if (workspace_bytes < plan.workspace_bytes) {
+    set_error(too_small);
+    return FS_ERR_NOMEM;
+  }
+  if (p->n_cu == 0) {
+    set_error("decode attention: pool has no HIP device");
+    return FS_ERR_DEVICE;
+  }
+  const bool use_mfma = plan.use_mfma;
+  if (g_kernel_mode == 2 && !plan.all_mfma) {
+    set_error("decode attention: MFMA kernel forced but a batch has a shape it does not support");
+    return FS_ERR_INVALID;
+  }
+  (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
+  hipError_t e = launch_prep(plan.args, s);
+  if (e != hipSuccess) return device_error(e, "prep launch");
+  // Persistent grid: two workgroups (eight waves) per compute unit drain the queue (never more than the
+  // upper bound on work items, so tiny batches launch tiny grids).
+  static const int wgs_per_cu = [] {
+    const char* e = getenv("FS_WGS_PER_CU");  // tuning knob for measurements
+    const int v = e ? atoi(e) : 0;
+    return v >= 1 && v <= 8 ? v : 2;
+  }();
+  // (the MFMA kernel's workers are waves, four to a workgroup; the generic kernel's are workgroups)
+  const uint64_t workers_per_wg = use_mfma ? 4 : 1;
+  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,
+                                           std::max<uint64_t>((plan.ub_items + workers_per_wg - 1) / workers_per_wg, 1));
+  if (g_timing) (void)hipEventRecord(g_ev0, s);
+  e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
+  if (g_timing) (void)hipEventRecord(g_ev1, s);
+  if (e != hipSuccess) return device_error(e, "attention launch");
+  e = launch_combine(plan.args, s);
+  if (e != hipSuccess) return device_error(e, "combine launch");
+  return FS_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int fs_set_kernel_mode(int mode) {
@@ -489,47 +548,40 @@ uint64_t fs_decode_workspace_bytes(fs_pool* p, const fs_batch_t* batches, int n_
 
 int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace,
                               uint64_t workspace_bytes, void* stream) {
-  Plan plan;
-  if (!workspace || ((uintptr_t)workspace & 255)) {
-    set_error("decode attention: workspace must be a 256-byte aligned device pointer");
+  return decode_launch(p, batches, n_batches, workspace, workspace_bytes, "decode attention: workspace too small (see fs_decode_workspace_bytes)",
+                       (hipStream_t)stream);
+}
+
+int fs_decode_attention_multi_static(fs_pool* p, const fs_batch_t* batches, int n_batches, uint32_t* status_out,
+                                     void* stream) {
+  if (!p) {
+    set_error("decode attention: no pool");
     return FS_ERR_INVALID;
   }
-  int rc = make_plan(p, batches, n_batches, workspace, plan);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return device_error(e, "hipGetDevice");
+  if (p->n_cu == 0 || dev != p->device || dev < 0 || dev >= kMaxScratchDevices) {
+    set_error("decode attention (static scratch): the pool's device must be the current device");
+    return FS_ERR_INVALID;
+  }
+  if (!g_scratch_ptr[dev]) {
+    // once per device, with that device current: every GPU holds its own copy of the array at its own address
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return device_error(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = (uint8_t*)ptr;
+  }
+  uint8_t* ws = g_scratch_ptr[dev];
+  const int rc = decode_launch(p, batches, n_batches, ws, kStaticScratchBytes,
+                               "decode attention (static scratch): the batches need more than the 64 MiB static scratch; "
+                               "use fs_decode_attention_multi with a caller workspace",
+                               (hipStream_t)stream);
   if (rc != FS_OK) return rc;
-  if (workspace_bytes < plan.workspace_bytes) {
-    set_error("decode attention: workspace too small (see fs_decode_workspace_bytes)");
-    return FS_ERR_NOMEM;
+  if (status_out) {
+    e = hipMemcpyAsync(status_out, ws + 4 * kHdrStatus, 4, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return device_error(e, "hipMemcpyAsync(status)");
   }
-  if (p->n_cu == 0) {
-    set_error("decode attention: pool has no HIP device");
-    return FS_ERR_DEVICE;
-  }
-  const bool use_mfma = plan.use_mfma;
-  if (g_kernel_mode == 2 && !plan.all_mfma) {
-    set_error("decode attention: MFMA kernel forced but a batch has a shape it does not support");
-    return FS_ERR_INVALID;
-  }
-  hipStream_t s = (hipStream_t)stream;
-  (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
-  hipError_t e = launch_prep(plan.args, s);
-  if (e != hipSuccess) return device_error(e, "prep launch");
-  // Persistent grid: two workgroups (eight waves) per compute unit drain the queue (never more than the
-  // upper bound on work items, so tiny batches launch tiny grids).
-  static const int wgs_per_cu = [] {
-    const char* e = getenv("FS_WGS_PER_CU");  // tuning knob for measurements
-    const int v = e ? atoi(e) : 0;
-    return v >= 1 && v <= 8 ? v : 2;
-  }();
-  // (the MFMA kernel's workers are waves, four to a workgroup; the generic kernel's are workgroups)
-  const uint64_t workers_per_wg = use_mfma ? 4 : 1;
-  const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,
-                                           std::max<uint64_t>((plan.ub_items + workers_per_wg - 1) / workers_per_wg, 1));
-  if (g_timing) (void)hipEventRecord(g_ev0, s);
-  e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
-  if (g_timing) (void)hipEventRecord(g_ev1, s);
-  if (e != hipSuccess) return device_error(e, "attention launch");
-  e = launch_combine(plan.args, s);
-  if (e != hipSuccess) return device_error(e, "combine launch");
   return FS_OK;
 }
 
