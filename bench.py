@@ -9,9 +9,14 @@ is set up (its rate is reported under ``extra``).  KV, block tables, queries and
 resident in HBM before the timed region starts; the layer index rotates between steps so that no
 step re-reads what the previous one left in cache.
 
-Prints ONE JSON line: metric/value = algorithmic KV GB/s of the whole step, plus ``roofline`` for
-the attention kernel (HIP-event time of that kernel alone) and ``cpu_baseline`` (the CPU oracle
-timed on a bounded sample of the same workload).
+Prints ONE JSON line: metric/value = algorithmic KV GB/s of the whole step on the four-model mixed
+pool (config 5), plus ``roofline`` for the attention kernel (HIP-event time of that kernel alone)
+and ``cpu_baseline`` (the CPU oracle timed on a bounded sample of the same workload).  The default
+run adds under ``extra``:
+  mixed_pool_loss  the control the benchmark definition asks for -- each model of the mixed pool alone in a
+                   pool of its own precision with contiguous (identity) block tables and the SAME final
+                   lengths: loss = 1 - BW_multi / (sum bytes_m / sum t_m);
+  per_config       the same step timed on configs 2, 3 and 4 (value, kernel time, fraction of peak).
 """
 from __future__ import annotations
 
@@ -32,9 +37,13 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(gw, wl, layers, n_per_model, n_threads):
+def cpu_baseline(gw, wl, layers, n_random, n_threads):
     """Time the CPU oracle (append of the newest token + decode attention) on a seeded sample of sequences of
-    every model of the workload; returns (GB/s, tokens/s, description)."""
+    every model of the workload -- n_random seeded ones plus the shortest and the longest; returns
+    (GB/s, tokens/s, description, threads used).  Only the two oracle calls are timed; drawing the sample's
+    source rows and filling its host mirror of the cache (oracle append, one thread per sequence) are set-up."""
+    from concurrent.futures import ThreadPoolExecutor
+
     import numpy as np
 
     import oracle
@@ -46,8 +55,10 @@ def cpu_baseline(gw, wl, layers, n_per_model, n_threads):
     used_threads = 1
     for k, s in enumerate(wl.models):
         lens_all = gw.lens[k]
-        order = gen.permutation(wl.seed, 77 + k, len(lens_all))
-        seqs = np.sort(order[:n_per_model])
+        pick = set(gen.permutation(wl.seed, 77 + k, len(lens_all))[:n_random].tolist())
+        pick.add(int(np.argmin(lens_all)))
+        pick.add(int(np.argmax(lens_all)))
+        seqs = np.array(sorted(pick), dtype=np.int64)
         lens = lens_all[seqs]
         g = oracle.geometry(s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.block_budget or wl.slab_bytes)
         T = g.tokens_per_block
@@ -60,17 +71,24 @@ def cpu_baseline(gw, wl, layers, n_per_model, n_threads):
         mem = np.zeros(nxt * g.block_budget, np.uint8)
         layer = layers[k]
         dt = np.float32 if s.src_f32 else np.float16
-        kr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_K, lens, s.n_kv_heads, s.head_dim, seqs, dt)
-        vr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_V, lens, s.n_kv_heads, s.head_dim, seqs, dt)
         ks = vs = None
         if s.kv_dtype == workloads.FP8:
             ks, vs = workloads.fp8_scales_table(s.n_layers, s.n_kv_heads)
-        si, po = workloads.token_index(lens)
-        oracle.kv_append(mem, g, layer, kr, vr, si, po, tab, ks, vs)  # cache fill: not timed
+        k_last = np.empty((len(seqs), s.n_kv_heads, s.head_dim), dt)
+        v_last = np.empty_like(k_last)
+
+        def fill(r):  # cache fill of one sampled sequence (its blocks are its own): not timed
+            n = int(lens[r])
+            kr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_K, [n], s.n_kv_heads, s.head_dim, [seqs[r]], dt)
+            vr = workloads.source_rows(wl.seed, s.tag, layer, gen.WHICH_V, [n], s.n_kv_heads, s.head_dim, [seqs[r]], dt)
+            oracle.kv_append(mem, g, layer, kr, vr, np.zeros(n, np.int32), np.arange(n, dtype=np.int32), tab[r:r + 1], ks, vs)
+            k_last[r], v_last[r] = kr[-1], vr[-1]
+
+        with ThreadPoolExecutor(max_workers=n_threads) as ex:
+            list(ex.map(fill, range(len(seqs))))
         q = gen.normal_q(wl.seed, s.tag, layer, seqs, s.n_q_heads, s.head_dim)
-        last = np.cumsum(lens) - 1
         t0 = time.perf_counter()
-        oracle.kv_append(mem, g, layer, kr[last], vr[last], np.arange(len(seqs), dtype=np.int32),
+        oracle.kv_append(mem, g, layer, k_last, v_last, np.arange(len(seqs), dtype=np.int32),
                          (lens - 1).astype(np.int32), tab, ks, vs)
         oracle.decode_attention(mem, g, layer, s.n_q_heads, 1.0 / np.sqrt(s.head_dim), q, tab, lens, ks, vs,
                                 n_threads=n_threads, want_lse=False)
@@ -78,9 +96,152 @@ def cpu_baseline(gw, wl, layers, n_per_model, n_threads):
         total_bytes += int(lens.astype(np.int64).sum()) * workloads.kv_bytes_per_token_layer(s)
         total_seqs += len(seqs)
         used_threads = max(used_threads, min(n_threads, len(seqs)))
-    desc = (f"{n_per_model} seeded sequences per model ({total_seqs} of {sum(m.n_seq for m in wl.models)}), "
-            f"one layer each, append of the newest token + decode attention, {total_bytes / 1e6:.1f} MB of KV")
+        del mem
+    desc = (f"{n_random} seeded sequences per model plus its shortest and longest ({total_seqs} of "
+            f"{sum(m.n_seq for m in wl.models)}), one layer each, append of the newest token + decode attention, "
+            f"{total_bytes / 1e6:.1f} MB of KV")
     return total_bytes / total_time / 1e9, total_seqs / total_time, desc, used_threads
+
+
+class Timed:
+    """One workload stood up on the GPU and the step timed on it."""
+
+    def __init__(self, wl, layers_cap=0):
+        import torch
+
+        import paper_2509_06261_amd as fs
+        from paper_2509_06261_amd import harness
+
+        self.fs, self.wl, self.torch = fs, wl, torch
+        log(f"[bench] workload {wl.name}: pool {wl.pool_bytes / 2**30:.1f} GiB, slabs {wl.slab_bytes // 1024} KiB, "
+            f"placement {wl.placement}")
+        self.gw = gw = harness.GpuWorkload(wl)
+
+        class CountingAdapter(harness.AllocAdapter):
+            calls = 0
+
+            def alloc(self, model):
+                CountingAdapter.calls += 1
+                return super().alloc(model)
+
+            def free(self, model, blk):
+                CountingAdapter.calls += 1
+                return super().free(model, blk)
+
+        t0 = time.perf_counter()
+        gw.place(CountingAdapter(gw.pool))
+        self.t_place = time.perf_counter() - t0
+        self.n_alloc_ops = CountingAdapter.calls
+        self.stats = fs.fs_pool_stats(gw.pool)
+        log(f"[bench] placed: {self.stats.live_blocks} live blocks of {self.stats.n_slabs} slabs in {self.t_place:.1f} s")
+        self.n_layers_of = [s.n_layers if layers_cap <= 0 else min(layers_cap, s.n_layers) for s in wl.models]
+        t0 = time.perf_counter()
+        gw.populate([list(range(n)) for n in self.n_layers_of])
+        torch.cuda.synchronize()
+        log(f"[bench] KV populated for layers {self.n_layers_of} in {time.perf_counter() - t0:.1f} s")
+
+    def close(self):
+        self.gw.close()
+
+    def algorithmic_bytes(self):
+        """KV rows and parameters of every cached token (once per KV head), block-table entries and lengths read,
+        queries read and outputs written: what one decode launch of one layer has to move."""
+        import numpy as np
+
+        gw, wl = self.gw, self.wl
+        kv = gw.kv_bytes_per_layer_launch()
+        table = sum(int(np.sum((gw.lens[k] + gw.T[m] - 1) // gw.T[m])) * 4 + 4 * s.n_seq
+                    for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)))
+        qo = sum(2 * s.n_seq * s.n_q_heads * s.head_dim * 2 for s in wl.models)
+        return kv + table + qo, kv
+
+    def run(self, steps, warmup):
+        """Times `steps` whole steps (after `warmup`), then the attention kernel alone over as many steps (HIP
+        events on the launch stream).  Returns a dict of the measurements."""
+        import numpy as np
+
+        from fs_inputs import device as gen_device
+        from fs_inputs import gen
+
+        fs, gw, wl, torch = self.fs, self.gw, self.wl, self.torch
+        n_layers_of = self.n_layers_of
+        # per-layer batches (queries differ per layer), prepared before timing
+        n_rot = max(n_layers_of)
+        per_layer, keepalive = [], []
+        for r in range(n_rot):
+            layers = [r % n for n in n_layers_of]
+            batches, keep = gw.make_batches(layers, with_lse=False)
+            per_layer.append((layers, batches))
+            keepalive.append(keep)
+        self.first_layers = per_layer[0][0]
+        ws = gw.workspace_for(per_layer[0][1])
+        # newest-token rows for the per-step append (position n_b - 1 of every sequence), per model
+        new_rows = []
+        for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)):
+            n = s.n_seq
+            si = torch.arange(n, dtype=torch.int32, device=gw.device)
+            po = (gw.seq_lens[k] - 1).to(torch.int32)
+            dt = torch.float32 if s.src_f32 else torch.float16
+            rows = []
+            for layer in range(n_layers_of[k]):
+                kb = torch.empty((n, s.n_kv_heads, s.head_dim), dtype=dt, device=gw.device)
+                vb = torch.empty_like(kb)
+                gen_device.fill_rows(kb, wl.seed, s.tag, layer, gen.WHICH_K, si, po, s.n_kv_heads, s.head_dim)
+                gen_device.fill_rows(vb, wl.seed, s.tag, layer, gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
+                rows.append((kb, vb))
+            new_rows.append((si, po, rows))
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+
+        def step(i):
+            layers, batches = per_layer[i % n_rot]
+            for k, m in enumerate(gw.model_ids):
+                si, po, rows = new_rows[k]
+                kb, vb = rows[layers[k]]
+                fs.fs_kv_append(gw.pool, m, layers[k], kb, vb, si, po, gw.tables[k], stream)
+            fs.fs_decode_attention_multi(gw.pool, batches, ws, stream)
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        status = fs.fs_decode_status(ws)
+        assert status == 0, f"decode status {status}"
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(warmup + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        # attention kernel alone, HIP events on the launch stream
+        fs.fs_set_kernel_timing(1)
+        kms = []
+        for i in range(steps):
+            step(warmup + steps + i)
+            kms.append(fs.fs_last_attention_kernel_ms())
+        fs.fs_set_kernel_timing(0)
+        kms = np.array(kms)
+        algo, kv = self.algorithmic_bytes()
+        del keepalive
+        return {"ms_per_step": elapsed / steps * 1e3, "kernel_ms": kms, "algo_bytes": algo, "kv_bytes": kv,
+                "timed_s": elapsed}
+
+    def model_names(self):
+        return [f"{s.name}:{s.n_q_heads}q/{s.n_kv_heads}kv/d{s.head_dim}/L{self.n_layers_of[k]}of{s.n_layers}"
+                f"/T{self.gw.T[self.gw.model_ids[k]]}/{s.n_seq}seq" for k, s in enumerate(self.wl.models)]
+
+
+def summary(r):
+    """value / kernel numbers of one Timed.run result, for the `extra` entries."""
+    import numpy as np
+
+    kms = r["kernel_ms"]
+    k_mean = float(kms.mean())
+    return {"bytes_per_launch": int(r["algo_bytes"]), "ms_per_step": round(r["ms_per_step"], 4),
+            "value_GBps": round(r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9, 1),
+            "kernel_ms_mean": round(k_mean, 4),
+            "kernel_ms_p10_p50_p90": [round(float(x), 4) for x in np.percentile(kms, [10, 50, 90])],
+            "kernel_GBps": round(r["algo_bytes"] / (k_mean * 1e-3) / 1e9, 1),
+            "kernel_frac_of_peak": round(r["algo_bytes"] / (k_mean * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "step_frac_of_peak": round(r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
 
 def main():
@@ -95,7 +256,10 @@ def main():
     ap.add_argument("--identity", action="store_true", help="control run: contiguous (identity) block placement")
     ap.add_argument("--only-model", type=int, default=-1, help="control run: only model k of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=6, help="sequences per model for the CPU oracle timing")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the mixed-pool-loss control and the configs 2-4 runs of the default invocation")
+    ap.add_argument("--cpu-sample", type=int, default=32,
+                    help="seeded sequences per model for the CPU oracle timing (the shortest and longest are added)")
     ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
                     help="after the timed region also run a plain device copy of this size (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
@@ -110,7 +274,6 @@ def main():
 
     import paper_2509_06261_amd as fs
     from fs_inputs import workloads
-    from paper_2509_06261_amd import harness
 
     t_setup = time.perf_counter()
     wl = workloads.config(args.config)
@@ -118,96 +281,15 @@ def main():
         wl.placement = "identity"
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
-    log(f"[bench] workload {wl.name}: pool {wl.pool_bytes / 2**30:.0f} GiB, slabs {wl.slab_bytes // 1024} KiB, "
-        f"placement {wl.placement}")
-    gw = harness.GpuWorkload(wl)
-
-    class CountingAdapter(harness.AllocAdapter):
-        calls = 0
-
-        def alloc(self, model):
-            CountingAdapter.calls += 1
-            return super().alloc(model)
-
-        def free(self, model, blk):
-            CountingAdapter.calls += 1
-            return super().free(model, blk)
-
-    t0 = time.perf_counter()
-    gw.place(CountingAdapter(gw.pool))
-    t_place = time.perf_counter() - t0
-    n_alloc_ops = CountingAdapter.calls
-    st = fs.fs_pool_stats(gw.pool)
-    log(f"[bench] placed: {st.live_blocks} live blocks of {st.n_slabs} slabs in {t_place:.1f} s")
-    n_layers_of = [s.n_layers if args.layers <= 0 else min(args.layers, s.n_layers) for s in wl.models]
-    t0 = time.perf_counter()
-    gw.populate([list(range(n)) for n in n_layers_of])
-    torch.cuda.synchronize()
-    log(f"[bench] KV populated for layers {n_layers_of} in {time.perf_counter() - t0:.1f} s")
+    plain = not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers or args.split_bytes)
     if args.kernel_mode:
         fs.fs_set_kernel_mode(args.kernel_mode)
     if args.split_bytes:
         fs.fs_set_split_bytes(args.split_bytes)
-
-    # per-layer batches (queries differ per layer), prepared before timing
-    n_rot = max(n_layers_of)
-    per_layer = []
-    keepalive = []
-    for r in range(n_rot):
-        layers = [r % n for n in n_layers_of]
-        batches, keep = gw.make_batches(layers, with_lse=False)
-        per_layer.append((layers, batches))
-        keepalive.append(keep)
-    ws = gw.workspace_for(per_layer[0][1])
-    # newest-token rows for the per-step append (position n_b - 1 of every sequence), per model
-    new_rows = []
-    for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)):
-        n = s.n_seq
-        si = torch.arange(n, dtype=torch.int32, device=gw.device)
-        po = (gw.seq_lens[k] - 1).to(torch.int32)
-        dt = torch.float32 if s.src_f32 else torch.float16
-        rows = []
-        for layer in range(n_layers_of[k]):
-            kb = torch.empty((n, s.n_kv_heads, s.head_dim), dtype=dt, device=gw.device)
-            vb = torch.empty_like(kb)
-            from fs_inputs import device as gen_device
-            from fs_inputs import gen
-            gen_device.fill_rows(kb, wl.seed, s.tag, layer, gen.WHICH_K, si, po, s.n_kv_heads, s.head_dim)
-            gen_device.fill_rows(vb, wl.seed, s.tag, layer, gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
-            rows.append((kb, vb))
-        new_rows.append((si, po, rows))
-    torch.cuda.synchronize()
-
-    stream = torch.cuda.current_stream()
-
-    def step(i):
-        layers, batches = per_layer[i % n_rot]
-        for k, m in enumerate(gw.model_ids):
-            si, po, rows = new_rows[k]
-            kb, vb = rows[layers[k]]
-            fs.fs_kv_append(gw.pool, m, layers[k], kb, vb, si, po, gw.tables[k], stream)
-        fs.fs_decode_attention_multi(gw.pool, batches, ws, stream)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    status = fs.fs_decode_status(ws)
-    assert status == 0, f"decode status {status}"
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
-    # attention kernel alone, HIP events on the launch stream
-    fs.fs_set_kernel_timing(1)
-    kms = []
-    for i in range(args.steps):
-        step(args.warmup + args.steps + i)
-        kms.append(fs.fs_last_attention_kernel_ms())
-    fs.fs_set_kernel_timing(0)
-    kms = np.array(kms)
+    tw = Timed(wl, args.layers)
+    gw = tw.gw
+    r = tw.run(args.steps, args.warmup)
+    ms_per_step, kms, algo_bytes, kv_bytes = r["ms_per_step"], r["kernel_ms"], r["algo_bytes"], r["kv_bytes"]
     kernel_ms = float(kms.mean())
 
     if args.copy_calibration_gib > 0:
@@ -221,12 +303,7 @@ def main():
         log(f"[bench] calibration: 3 device copies of {n} bytes each (reads {n}, writes {n})")
         del src, dst
 
-    kv_bytes = gw.kv_bytes_per_layer_launch()
     n_seq_total = sum(s.n_seq for s in wl.models)
-    table_bytes = sum(int(np.sum((gw.lens[k] + gw.T[m] - 1) // gw.T[m])) * 4 + 4 * s.n_seq
-                      for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)))
-    qo_bytes = sum(2 * s.n_seq * s.n_q_heads * s.head_dim * 2 for s in wl.models)
-    algo_bytes = kv_bytes + table_bytes + qo_bytes
     value = algo_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
     full_depth_tok_s = n_seq_total / (ms_per_step * 1e-3) / np.mean([s.full_layers or s.n_layers for s in wl.models])
@@ -247,13 +324,12 @@ def main():
         "config": {
             "workload": wl.name + ("-identity" if args.identity else ""),
             "baseline_config_index": args.config,
-            "models": [f"{s.name}:{s.n_q_heads}q/{s.n_kv_heads}kv/d{s.head_dim}/L{n_layers_of[k]}of{s.n_layers}"
-                       f"/T{gw.T[gw.model_ids[k]]}/{s.n_seq}seq" for k, s in enumerate(wl.models)],
+            "models": tw.model_names(),
             "pool_GiB": wl.pool_bytes / 2**30,
             "slab_KiB": wl.slab_bytes // 1024,
             "placement": wl.placement,
             "churn_steps": wl.churn_steps if wl.placement == "churn" else 0,
-            "live_slabs": int(st.live_blocks),
+            "live_slabs": int(tw.stats.live_blocks),
             "step": "fs_kv_append(newest token of every sequence) + fs_decode_attention_multi, one layer",
             "kernel_mode": args.kernel_mode,
         },
@@ -273,15 +349,14 @@ def main():
             "tokens_per_s_layer": round(n_seq_total / (ms_per_step * 1e-3), 1),
             "tokens_per_s_full_depth_equiv": round(float(full_depth_tok_s), 1),
             "kv_bytes_per_launch": int(kv_bytes),
-            "alloc_free_calls": n_alloc_ops,
-            "alloc_free_calls_per_s_host": round(n_alloc_ops / max(t_place, 1e-9), 1),
-            "setup_s": round(time.perf_counter() - t_setup, 1),
+            "alloc_free_calls": tw.n_alloc_ops,
+            "alloc_free_calls_per_s_host": round(tw.n_alloc_ops / max(tw.t_place, 1e-9), 1),
         },
     }
     # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated against a plain
     # copy) is recorded under profiles/ for the default workload and kernel; quote it when it applies.
     tpath = os.path.join(ROOT, "profiles", f"attention_traffic_cfg{args.config}.json")
-    if os.path.exists(tpath) and not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers):
+    if os.path.exists(tpath) and plain:
         with open(tpath) as f:
             tr = json.load(f)
         result["roofline"]["traffic"] = tr.get("hbm_bytes_per_launch")
@@ -289,11 +364,56 @@ def main():
     if not args.no_cpu_baseline:
         n_threads = min(os.cpu_count() or 1, 16)
         t0 = time.perf_counter()
-        gbs, toks, desc, used = cpu_baseline(gw, wl, per_layer[0][0], args.cpu_sample, n_threads)
+        gbs, toks, desc, used = cpu_baseline(gw, wl, tw.first_layers, args.cpu_sample, n_threads)
         log(f"[bench] cpu oracle baseline took {time.perf_counter() - t0:.1f} s")
         result["cpu_baseline"] = {"value": round(gbs, 4), "unit": "GB/s", "cores": used, "kind": "oracle",
                                   "sample": desc, "tokens_per_s_layer": round(toks, 2)}
-    gw.close()
+    final_lens = [np.array(l, dtype=np.int32) for l in gw.lens]
+    tw.close()
+
+    if plain and args.config == 5 and not args.no_extras:
+        # ---- mixed-pool loss: every model alone, a pool of its own precision, identity tables, the same lengths ----
+        ctl = []
+        for k, s in enumerate(wl.models):
+            spec = workloads.ModelSpec(s.name, s.kv_dtype, s.n_kv_heads, s.head_dim, s.n_layers, s.n_q_heads,
+                                       final_lens[k], s.tag, s.src_f32, s.full_layers, s.block_budget)
+            n_blocks = int(sum(workloads.blocks_needed(int(n), gw.T[gw.model_ids[k]]) for n in final_lens[k]))
+            cw = workloads.Workload(f"control-{s.name}", wl.slab_bytes, (n_blocks + 8) * wl.slab_bytes, [spec],
+                                    "identity", wl.seed)
+            ct = Timed(cw)
+            cr = ct.run(max(10, args.steps // 2), 3)
+            ct.close()
+            e = summary(cr)
+            e["model"] = s.name
+            ctl.append(e)
+        sum_bytes = sum(e["bytes_per_launch"] for e in ctl)
+        sum_kernel = sum(e["kernel_ms_mean"] for e in ctl)
+        sum_step = sum(e["ms_per_step"] for e in ctl)
+        bw_ctl_kernel = sum_bytes / (sum_kernel * 1e-3) / 1e9
+        bw_ctl_step = sum_bytes / (sum_step * 1e-3) / 1e9
+        result["extra"]["mixed_pool_loss"] = {
+            "definition": "1 - BW_multi / (sum bytes_m / sum t_m); control = each model alone, single-precision pool, "
+                          "identity (contiguous) block tables, the mixed pool's final (churned) lengths",
+            "loss_kernel": round(1.0 - achieved / bw_ctl_kernel, 4),
+            "loss_step": round(1.0 - value / bw_ctl_step, 4),
+            "mixed_kernel_GBps": round(achieved, 1), "control_kernel_GBps": round(bw_ctl_kernel, 1),
+            "mixed_step_GBps": round(value, 1), "control_step_GBps": round(bw_ctl_step, 1),
+            "mixed_bytes": int(algo_bytes), "control_bytes": int(sum_bytes),
+            "control": ctl,
+        }
+        # ---- the other configs ----
+        per_config = {}
+        for cfg in (2, 3, 4):
+            cw = workloads.config(cfg)
+            ct = Timed(cw)
+            cr = ct.run(args.steps, args.warmup)
+            e = summary(cr)
+            e["workload"] = cw.name
+            e["models"] = ct.model_names()
+            ct.close()
+            per_config[f"config{cfg}"] = e
+        result["extra"]["per_config"] = per_config
+    result["extra"]["setup_s"] = round(time.perf_counter() - t_setup, 1)
     print(json.dumps(result), flush=True)
 
 

@@ -1,4 +1,4 @@
-"""Builds libfineserve.so (hipcc, gfx950) next to this file, and the stand-alone read-ceiling microbenchmark."""
+"""Builds libfineserve.so (hipcc, gfx950) next to this file."""
 from __future__ import annotations
 
 import os
@@ -7,7 +7,6 @@ import subprocess
 _DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_DIR)
 LIB = os.path.join(_DIR, "libfineserve.so")
-READ_CEILING = os.path.join(_DIR, "read_ceiling")  # executable of csrc/read_ceiling.hip (measurement aid)
 SOURCES = ["fs_pool.hip", "fs_append.hip", "fs_attention.hip", "fs_attention_generic.hip", "fs_attention_mfma.hip",
            "fs_prefill.hip", "fs_sched.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -41,11 +40,6 @@ def build(verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out)
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", LIB, *objs], check=True)
-    pr = subprocess.run([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wall", "-Xclang", "-target-feature", "-Xclang",
-                         "-packed-fp32-ops", os.path.join(csrc, "read_ceiling.hip"), "-o", READ_CEILING],
-                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if pr.returncode != 0:
-        raise RuntimeError("hipcc failed on read_ceiling.hip:\n" + pr.stdout)
     return LIB
 
 

@@ -34,7 +34,7 @@ int fs_sched_select_batch(const fs_request_t* waiting, int n_waiting, const fs_s
       set_error("fs_sched_select_batch: a request has a negative length or a NaN arrival time");
       return FS_ERR_INVALID;
     }
-  // lines 3-8: a request that misses its deadline even alone, served now, is dropped
+  // Algorithm 2 (Sec. 6.3), first step: a request that misses its deadline even alone, served now, is dropped
   std::vector<int32_t> S;
   S.reserve(n_waiting);
   int nd = 0;
@@ -44,11 +44,11 @@ int fs_sched_select_batch(const fs_request_t* waiting, int n_waiting, const fs_s
     if (now + ttft(M, n, n * n) < d) S.push_back(i);
     else dropped[nd++] = i;
   }
-  // line 10: earliest deadline first (queue order among equal deadlines)
+  // Algorithm 2 (Sec. 6.3): earliest deadline first (queue order among equal deadlines)
   std::stable_sort(S.begin(), S.end(), [&](int32_t a, int32_t b) {
     return waiting[a].arrival_time + M.slo < waiting[b].arrival_time + M.slo;
   });
-  // lines 11-16: while the whole batch's prefill would finish after the front request's deadline, remove the
+  // Algorithm 2 (Sec. 6.3), removal loop: while the whole batch's prefill would finish after the front request's deadline, remove the
   // longest request (the latest in deadline order among equally long ones).  Running integer sums, a max-heap over
   // (length, position) and a front pointer over removed flags replace the rescans.
   const int ns = (int)S.size();
@@ -74,7 +74,7 @@ int fs_sched_select_batch(const fs_request_t* waiting, int n_waiting, const fs_s
     s2 -= n * n;
     --left;
   }
-  // line 17: trim to the caps, in deadline order
+  // Algorithm 2 (Sec. 6.3), last step: trim to the caps, in deadline order
   int nsel = 0;
   int64_t total = 0;
   for (int k = 0; k < ns; ++k) {

@@ -59,7 +59,14 @@ __device__ __forceinline__ const RC_GLOBAL uint8_t* tile_of(const Args& a, int w
   return (const RC_GLOBAL uint8_t*)(a.pool + (size_t)a.chunk_slot[ch] * kChunk + (size_t)(tt % kTilesPerChunk) * kTile);
 }
 
-template <int PATTERN, int RING, bool TOGETHER>
+// one 16-byte load; NT: with the non-temporal hint (read-once data that should not displace anything in the caches)
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const RC_GLOBAL uint8_t* p) {
+  if (NT) return __builtin_nontemporal_load((const RC_GLOBAL u32x4*)p);
+  return *(const RC_GLOBAL u32x4*)p;
+}
+
+template <int PATTERN, int RING, bool TOGETHER, bool NT = false>
 __global__ __launch_bounds__(256, 2) void read_to_registers(Args a) {
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -70,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void read_to_registers(Args a) {
   for (int b = 0; b < RING; ++b) {
     const RC_GLOBAL uint8_t* p = tile_of<TOGETHER>(a, wave, n_waves, b);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ring[b][i] = *(const RC_GLOBAL u32x4*)(p + lane_offset<PATTERN>(i, lane));
+    for (int i = 0; i < 8; ++i) ring[b][i] = load16<NT>(p + lane_offset<PATTERN>(i, lane));
   }
   for (int t = 0; t < n_tiles; t += RING) {
 #pragma unroll
@@ -81,10 +88,26 @@ __global__ __launch_bounds__(256, 2) void read_to_registers(Args a) {
       __builtin_amdgcn_sched_barrier(0);
       const RC_GLOBAL uint8_t* p = tile_of<TOGETHER>(a, wave, n_waves, t + b + RING);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ring[b][i] = *(const RC_GLOBAL u32x4*)(p + lane_offset<PATTERN>(i, lane));
+      for (int i = 0; i < 8; ++i) ring[b][i] = load16<NT>(p + lane_offset<PATTERN>(i, lane));
     }
   }
   if (acc == 0x12345678u) a.sink[wave] = acc;  // (keeps the loads alive)
+}
+
+// The plain way to read a buffer: short-lived workgroups, workgroup g reads the contiguous piece g of PIECE bytes,
+// every lane 16 bytes per instruction, all of the piece's loads issued before the first is used.  No tiles, no
+// chunks, no persistent waves: what the memory system gives a kernel that does nothing but stream sequentially.
+template <int PIECE, bool NT>
+__global__ __launch_bounds__(256) void read_sequential(const uint8_t* pool, uint32_t* sink) {
+  constexpr int kLoads = PIECE / (256 * 16);
+  const RC_GLOBAL uint8_t* p = (const RC_GLOBAL uint8_t*)(pool + (size_t)blockIdx.x * PIECE) + threadIdx.x * 16;
+  u32x4 v[kLoads];
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) v[i] = load16<NT>(p + i * 4096);
+  uint32_t acc = 0;
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) acc ^= fold(v[i]);
+  if (acc == 0x12345678u) sink[blockIdx.x & 1023] = acc;
 }
 
 // 16 distinct values over the 16 rows that one K-operand read touches: the xor swizzle of the LDS columns
@@ -172,7 +195,7 @@ int main(int argc, char** argv) {
   for (size_t i = 0; i < n_chunks; ++i) slot[i] = (uint32_t)(order[i / group] * group + i % group);
   RC_CHECK(hipMalloc(&chunk_slot, n_chunks * 4));
   RC_CHECK(hipMemcpy(chunk_slot, slot.data(), n_chunks * 4, hipMemcpyHostToDevice));
-  RC_CHECK(hipMalloc(&sink, (size_t)n_waves * 4));
+  RC_CHECK(hipMalloc(&sink, (size_t)(n_waves > 1024 ? n_waves : 1024) * 4));
   hipEvent_t e0, e1;
   RC_CHECK(hipEventCreate(&e0));
   RC_CHECK(hipEventCreate(&e1));
@@ -182,10 +205,14 @@ int main(int argc, char** argv) {
   const double bytes = (double)n_chunks * kChunk;
   const char* names[] = {"K operand, ring 2", "contiguous, ring 2", "contiguous to LDS, ring 2", "contiguous, ring 4",
                          "K operand, ring 4", "contiguous, ring 2, all waves sweep together",
-                         "K operand, ring 2, all waves sweep together"};
+                         "K operand, ring 2, all waves sweep together", "K operand, ring 2, non-temporal loads",
+                         "K operand, ring 4, non-temporal loads", "sequential, 16 KiB per short-lived workgroup",
+                         "sequential, 64 KiB per short-lived workgroup", "sequential, 64 KiB, non-temporal loads"};
+  constexpr int kModes = 12;
+  const unsigned seq16 = (unsigned)(bytes / 16384), seq64 = (unsigned)(bytes / 65536);  // the same bytes, front of the pool
   std::printf("pool %zu GiB, %d workgroups x 4 waves, %d chunks of 32 KiB per wave (%.2f GB per launch), groups of %zu\n",
               pool_bytes >> 30, n_wg, chunks_per_wave, bytes / 1e9, group);
-  for (int mode = 0; mode < 7; ++mode) {
+  for (int mode = 0; mode < kModes; ++mode) {
     float best = 1e30f;
     for (int rep = 0; rep < 4; ++rep) {
       RC_CHECK(hipEventRecord(e0));
@@ -196,7 +223,12 @@ int main(int argc, char** argv) {
         case 3: hipLaunchKernelGGL((read_to_registers<kContiguous, 4, false>), dim3(n_wg), dim3(256), 0, 0, a); break;
         case 4: hipLaunchKernelGGL((read_to_registers<kOperand, 4, false>), dim3(n_wg), dim3(256), 0, 0, a); break;
         case 5: hipLaunchKernelGGL((read_to_registers<kContiguous, 2, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
-        default: hipLaunchKernelGGL((read_to_registers<kOperand, 2, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 6: hipLaunchKernelGGL((read_to_registers<kOperand, 2, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 7: hipLaunchKernelGGL((read_to_registers<kOperand, 2, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 8: hipLaunchKernelGGL((read_to_registers<kOperand, 4, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 9: hipLaunchKernelGGL((read_sequential<16384, false>), dim3(seq16), dim3(256), 0, 0, pool, sink); break;
+        case 10: hipLaunchKernelGGL((read_sequential<65536, false>), dim3(seq64), dim3(256), 0, 0, pool, sink); break;
+        default: hipLaunchKernelGGL((read_sequential<65536, true>), dim3(seq64), dim3(256), 0, 0, pool, sink); break;
       }
       RC_CHECK(hipGetLastError());
       RC_CHECK(hipEventRecord(e1));
