@@ -13,7 +13,9 @@
  * Conventions
  *  - Every function returns FS_OK (0) or a negative fs_status; nothing throws or aborts.
  *    fs_last_error() gives a thread-local text for the last failure.
- *  - Arguments are validated on the host before any kernel is launched.
+ *  - Arguments are validated on the host before any kernel is launched.  What lives in device memory (sequence
+ *    lengths, block tables, chunk offsets) is range-checked by the kernels themselves: out-of-range values are
+ *    clamped into the buffers and the pool and reported through fs_decode_status.
  *  - "device pointer" = HIP device memory of the current device; "host pointer" = ordinary
  *    process memory.  The library never frees caller memory.
  *  - Device calls are asynchronous on the given hipStream_t (passed as void*; NULL = the
@@ -191,9 +193,11 @@ int fs_decode_attention_multi(fs_pool* pool, const fs_batch_t* batches, int n_ba
 int fs_decode_attention_multi_static(fs_pool* pool, const fs_batch_t* batches, int n_batches, uint32_t* status_out,
                                      void* stream);
 
-/* After the stream has passed a decode call: 0 if every sequence length was in range and the
- * workspace sufficed, else a bit mask (1: length out of range, clamped; 2: workspace too small,
- * affected sequences left unwritten).  Synchronizes the stream. */
+/* After the stream has passed a decode call: 0 if every sequence length and block-table entry was in
+ * range and the workspace sufficed, else a bit mask (1: length out of range, clamped; 2: workspace too
+ * small, affected sequences left unwritten; 4: a block-table entry inside a sequence's length named no
+ * block of the pool -- it was read as block 0, so no byte outside the pool is touched, and the outputs
+ * of the affected sequences are meaningless).  Synchronizes the stream. */
 int fs_decode_status(const void* workspace, void* stream);
 
 /* ---- Prefill (chunked prefill) attention: FineServe Sec. 2.1 (the prefill phase processes the prompt's tokens),
@@ -209,7 +213,8 @@ int fs_decode_status(const void* workspace, void* stream);
  *            n_rows, so a mismatch cannot make them leave the buffers)
  *   workspace: device memory of fs_prefill_workspace_bytes(n_seq) bytes, 256-byte aligned, owned by the caller,
  *            in use until the stream has passed the call.  fs_decode_status(workspace, stream) afterwards: bit 0
- *            set if a length or a chunk size was out of range (clamped).
+ *            set if a length or a chunk size was out of range (clamped), bit 2 (value 4) if a block-table entry
+ *            named no block of the pool (read as block 0; the affected rows are meaningless).
  * At most 16 query heads per KV head (FS_ERR_INVALID otherwise).  head_dim 128 with at least 8 tokens per block
  * runs on the MFMA kernels; every other shape the pool accepts on a vector-ALU kernel (one workgroup per query
  * row and KV head: correct, far slower).  A softmax scale that is not positive and finite is served by the

@@ -28,13 +28,14 @@ struct DevBatch {
   int32_t chunk_runs;    // multiple of 4
   int32_t R;
   uint32_t r_magic;      // ceil(2^32 / R): run / R == umulhi(run, r_magic) while run * R < 2^32
-  uint32_t pad;
+  uint32_t n_blocks;     // blocks of this model's size the pool holds: valid table entries are 0 .. n_blocks - 1
 };
 
 // Workspace header words (uint32 unless noted).
 enum : int {
   kHdrCounter = 0,     // generic kernel: work-queue ticket counter
-  kHdrStatus = 1,      // bit 0: a sequence length was out of range; bit 1: partial buffer too small
+  kHdrStatus = 1,      // bit 0: a sequence length was out of range; bit 1: partial buffer too small;
+                       // bit 2: a block-table entry inside a sequence's length was outside the pool
   kHdrTotalItems = 2,  // number of work items
   kHdrBatchFirst = 8,  // [kMaxBatches] first work item of each batch (sequence-major numbering)
   kHdrPartOff = 32,    // [kMaxBatches] uint64: float offset of each batch's partials (word index of a uint64 array)
@@ -43,6 +44,15 @@ enum : int {
 constexpr int kPools = 64;
 constexpr int kPoolStride = 16;  // one counter per 64 bytes: neighbours never share a cache line
 constexpr uint32_t kHeaderBytes = 256 + kPools * kPoolStride * 4;
+
+// Block id of a block-table entry.  The tables live in device memory and cannot be validated on the host: an entry
+// outside the pool (a stale or -1 entry inside a sequence's length) is replaced by block 0 -- memory of the pool,
+// so nothing outside it is ever read -- and reported through bit 2 of the status word.
+__device__ __forceinline__ uint32_t checked_block(int32_t entry, uint32_t n_blocks, uint32_t* header) {
+  if ((uint32_t)entry < n_blocks) return (uint32_t)entry;
+  atomicOr(header + kHdrStatus, 4u);
+  return 0u;
+}
 
 // A work item's record in the queue: x = batch | KV head << 4, y = sequence, z = split, w = the item's index
 // within its batch in sequence-major order (sequence, split, KV head) -- the order of the partial records.

@@ -404,6 +404,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.R = (g.tokens_per_block + 7) / 8;
     B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);  // unused for R = 1
     B.chunk_runs = chunk_runs_for(g, split_bytes);
+    B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
     B.qrow_first = (int32_t)qrows;

@@ -131,7 +131,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
     for (int t = t0 + grp; t < t1; t += n_groups) {
       const int bi = t / T;
       const int tib = t - bi * T;
-      const uint8_t* chunkp = B.layer_base + (uint64_t)(uint32_t)table[bi] * g.block_budget + (uint64_t)head * g.head_chunk;
+      const uint8_t* chunkp = B.layer_base + (uint64_t)checked_block(table[bi], B.n_blocks, A.header) * g.block_budget + (uint64_t)head * g.head_chunk;
       float kf[8], vf[8];
       load8<DT>(chunkp + (uint64_t)tib * g.row_bytes + lig * kElemBytes8, kf);
       load8<DT>(chunkp + g.kv_tile + (uint64_t)tib * g.row_bytes + lig * kElemBytes8, vf);

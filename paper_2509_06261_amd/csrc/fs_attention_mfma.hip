@@ -50,7 +50,7 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   X.k0 = div_runs(v0, B.R, B.r_magic);
   X.chunk_ptr = s_ptr;
   fill_table(s_ptr, B.tables + (int64_t)seq * B.max_blocks, B.layer_base + (uint64_t)head * g.head_chunk, g.block_budget, X.k0,
-             div_runs(v1 - 1, B.R, B.r_magic) - X.k0 + 1, lane);
+             div_runs(v1 - 1, B.R, B.r_magic) - X.k0 + 1, lane, B.n_blocks, A.header);
 
   // Q operand and per-head constants
   u32x4 qb[4];

@@ -66,6 +66,22 @@ struct Fmt<FS_KV_INT4> {
   static constexpr int kRowBytes = 64, kKLoads = 1, kVBytes = 4, kParBytes = 4, kRing = 3;
 };
 
+// K/V bytes are read once per launch: FS_NT_K / FS_NT_V (0 or 1) select loads with the non-temporal hint.
+// Measured on the four-model pool: the hint helps loads that cover whole 128-byte lines per instruction (the V
+// rows: + 1.2 % on the kernel) and costs where an instruction takes half a line of each of 16 rows (the K operand
+// pattern: - 0.3 %, and - 2.5 % with both), so V rows carry it and K rows do not.
+#ifndef FS_NT_K
+#define FS_NT_K 0
+#endif
+#ifndef FS_NT_V
+#define FS_NT_V 1
+#endif
+template <bool NT, typename T>
+__device__ __forceinline__ T stream_load(const FS_GLOBAL T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
 __device__ __forceinline__ uint32_t h2u(half2v h) { return __builtin_bit_cast(uint32_t, h); }
 __device__ __forceinline__ half2v u2h(uint32_t u) { return __builtin_bit_cast(half2v, u); }
 __device__ __forceinline__ float f16lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFF)); }
@@ -168,23 +184,23 @@ __device__ __forceinline__ void issue_k(const ItemCtx& X, int vb, int j, int c, 
   for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int s = 0; s < F::kKLoads; ++s)
-      t.k[u][s] = *reinterpret_cast<const FS_GLOBAL u32x4*>(p + u * 4 * F::kRowBytes + 64 * s);
+      t.k[u][s] = stream_load<FS_NT_K>(reinterpret_cast<const FS_GLOBAL u32x4*>(p + u * 4 * F::kRowBytes + 64 * s));
 }
 
 template <int DT>
 __device__ __forceinline__ void load_v_row(gptr p, uint32_t (&v)[Fmt<DT>::kVBytes / 4]) {
   if constexpr (Fmt<DT>::kVBytes == 16) {
-    const u32x4 x = *reinterpret_cast<const FS_GLOBAL u32x4*>(p);
+    const u32x4 x = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL u32x4*>(p));
     v[0] = x[0];
     v[1] = x[1];
     v[2] = x[2];
     v[3] = x[3];
   } else if constexpr (Fmt<DT>::kVBytes == 8) {
-    const u32x2 x = *reinterpret_cast<const FS_GLOBAL u32x2*>(p);
+    const u32x2 x = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL u32x2*>(p));
     v[0] = x[0];
     v[1] = x[1];
   } else {
-    v[0] = *reinterpret_cast<const FS_GLOBAL uint32_t*>(p);
+    v[0] = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL uint32_t*>(p));
   }
 }
 
@@ -550,9 +566,10 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
 // Head-chunk addresses of blocks k0 .. k0 + nb - 1 of a sequence into this wave's LDS table: every lane of
 // every tile looks its blocks up there instead of gathering them from the block table in memory.
 __device__ __forceinline__ void fill_table(uint64_t* s_ptr, const int32_t* table, const uint8_t* head_base,
-                                           uint64_t block_budget, int k0, int nb, int lane) {
+                                           uint64_t block_budget, int k0, int nb, int lane, uint32_t n_blocks,
+                                           uint32_t* header) {
   for (int i = lane; i < nb; i += 64)
-    s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[k0 + i] * block_budget);
+    s_ptr[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)checked_block(table[k0 + i], n_blocks, header) * block_budget);
   // the table is private to this wave; LDS operations of a wave complete in order, the fence only keeps the
   // compiler from moving the look-ups above the writes of other lanes
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

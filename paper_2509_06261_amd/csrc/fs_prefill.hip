@@ -139,7 +139,7 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
   for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
     X.v_end = min(n_run, v0 + P.seg_runs);
     X.k0 = div_runs(v0, B.R, B.r_magic);
-    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane);
+    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane, B.n_blocks, P.header);
     stream_tiles<DT, GP>(X, g, v0, qb, qsum, alpha, st, j, c);
   }
 
@@ -442,7 +442,7 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
   for (int v0 = 0; v0 < n_run; v0 += P.seg_runs) {
     X.v_end = min(n_run, v0 + P.seg_runs);
     X.k0 = div_runs(v0, B.R, B.r_magic);
-    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane);
+    fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane, B.n_blocks, P.header);
     // the ring of stream_tiles (fs_mfma_tiles.h), with the wide tile step
     const int n_tiles = (X.v_end - v0 + 3) >> 2;
     Tile<DT, 16> t[NBUF];
@@ -1012,7 +1012,7 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       // the previous segment's (or item's) last barrier lies behind every use of the old table
       const int nb = div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1;
       for (int i = threadIdx.x; i < nb; i += NW * 64)
-        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
+        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)checked_block(table[X.k0 + i], B.n_blocks, P.header) * g.block_budget);
       __syncthreads();
     }
     const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
@@ -1254,7 +1254,7 @@ __device__ void prefill_item_wgp(const PrefillArgs& P, int seq, int head, int qt
     {
       const int nb = div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1;
       for (int i = threadIdx.x; i < nb; i += NW * 64)
-        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)(uint32_t)table[X.k0 + i] * g.block_budget);
+        s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)checked_block(table[X.k0 + i], B.n_blocks, P.header) * g.block_budget);
       __syncthreads();
     }
     const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
@@ -1604,6 +1604,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.sm_scale = sm_scale;
   B.R = (g.tokens_per_block + 7) / 8;
   B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);
+  B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
   const bool generic = !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
   if (generic && (g.head_dim & (g.head_dim - 1))) {
     set_error("prefill attention: head_dim must be a power of two");

@@ -206,12 +206,13 @@ int main(int argc, char** argv) {
   const char* names[] = {"K operand, ring 2", "contiguous, ring 2", "contiguous to LDS, ring 2", "contiguous, ring 4",
                          "K operand, ring 4", "contiguous, ring 2, all waves sweep together",
                          "K operand, ring 2, all waves sweep together", "K operand, ring 2, non-temporal loads",
-                         "K operand, ring 4, non-temporal loads", "sequential, 16 KiB per short-lived workgroup",
-                         "sequential, 64 KiB per short-lived workgroup", "sequential, 64 KiB, non-temporal loads"};
-  constexpr int kModes = 12;
-  const unsigned seq16 = (unsigned)(bytes / 16384), seq64 = (unsigned)(bytes / 65536);  // the same bytes, front of the pool
-  std::printf("pool %zu GiB, %d workgroups x 4 waves, %d chunks of 32 KiB per wave (%.2f GB per launch), groups of %zu\n",
-              pool_bytes >> 30, n_wg, chunks_per_wave, bytes / 1e9, group);
+                         "K operand, ring 4, non-temporal loads", "contiguous, ring 2, non-temporal loads",
+                         "contiguous, ring 4, non-temporal loads", "contiguous, ring 2, sweep together, non-temporal",
+                         "sequential, 16 KiB per short-lived workgroup", "sequential, 64 KiB per short-lived workgroup",
+                         "sequential, 16 KiB, non-temporal loads", "sequential, 32 KiB, non-temporal loads",
+                         "sequential, 64 KiB, non-temporal loads", "sequential, 128 KiB, non-temporal loads"};
+  constexpr int kModes = 18;
+  const auto seq_grid = [&](int piece) { return dim3((unsigned)(bytes / piece)); };  // the same bytes, front of the pool
   for (int mode = 0; mode < kModes; ++mode) {
     float best = 1e30f;
     for (int rep = 0; rep < 4; ++rep) {
@@ -226,9 +227,15 @@ int main(int argc, char** argv) {
         case 6: hipLaunchKernelGGL((read_to_registers<kOperand, 2, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
         case 7: hipLaunchKernelGGL((read_to_registers<kOperand, 2, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
         case 8: hipLaunchKernelGGL((read_to_registers<kOperand, 4, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
-        case 9: hipLaunchKernelGGL((read_sequential<16384, false>), dim3(seq16), dim3(256), 0, 0, pool, sink); break;
-        case 10: hipLaunchKernelGGL((read_sequential<65536, false>), dim3(seq64), dim3(256), 0, 0, pool, sink); break;
-        default: hipLaunchKernelGGL((read_sequential<65536, true>), dim3(seq64), dim3(256), 0, 0, pool, sink); break;
+        case 9: hipLaunchKernelGGL((read_to_registers<kContiguous, 2, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 10: hipLaunchKernelGGL((read_to_registers<kContiguous, 4, false, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 11: hipLaunchKernelGGL((read_to_registers<kContiguous, 2, true, true>), dim3(n_wg), dim3(256), 0, 0, a); break;
+        case 12: hipLaunchKernelGGL((read_sequential<16384, false>), seq_grid(16384), dim3(256), 0, 0, pool, sink); break;
+        case 13: hipLaunchKernelGGL((read_sequential<65536, false>), seq_grid(65536), dim3(256), 0, 0, pool, sink); break;
+        case 14: hipLaunchKernelGGL((read_sequential<16384, true>), seq_grid(16384), dim3(256), 0, 0, pool, sink); break;
+        case 15: hipLaunchKernelGGL((read_sequential<32768, true>), seq_grid(32768), dim3(256), 0, 0, pool, sink); break;
+        case 16: hipLaunchKernelGGL((read_sequential<65536, true>), seq_grid(65536), dim3(256), 0, 0, pool, sink); break;
+        default: hipLaunchKernelGGL((read_sequential<131072, true>), seq_grid(131072), dim3(256), 0, 0, pool, sink); break;
       }
       RC_CHECK(hipGetLastError());
       RC_CHECK(hipEventRecord(e1));

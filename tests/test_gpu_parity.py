@@ -436,3 +436,57 @@ def test_argument_errors_and_status_flags():
         assert torch.equal(out2, keep["out"][0])
     finally:
         gw.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+@pytest.mark.parametrize("bad_entry", [-1, 1 << 30])
+def test_block_table_entry_outside_the_pool_is_reported_not_followed(mode, bad_entry):
+    """A stale or -1 block-table entry inside a sequence's length: decode and prefill read block 0 of the pool in its
+    place (nothing outside the pool), raise bit 2 of the status word, and leave the other sequences' results as they
+    are without the bad entry.  The pool is zero-filled, so the affected rows come out finite as well."""
+    import torch
+    import paper_2509_06261_amd as fs
+    from paper_2509_06261_amd import harness
+
+    lens = np.array([300, 700, 50, 1200], np.int32)
+    wl = Workload("badtab", 64 * KiB, 32 * MiB, [ModelSpec("m", INT8, 2, 128, 1, 8, lens, tag=29)], "shuffle")
+    gw = harness.GpuWorkload(wl, zero_pool=True)
+    try:
+        gw.place()
+        gw.populate()
+        fs.fs_set_kernel_mode(mode)
+        batches, keep = gw.make_batches([0])
+        ws = gw.decode(batches)
+        assert fs.fs_decode_status(ws) == 0
+        clean = keep["out"][0].clone()
+        victim, T = 1, gw.T[gw.model_ids[0]]
+        assert lens[victim] > 3 * T
+        good = int(gw.tables[0][victim, 2])
+        gw.tables[0][victim, 2] = bad_entry          # inside the sequence's length
+        gw.tables[0][2, 7] = bad_entry               # past sequence 2's length (50 tokens): never read, not reported
+        assert lens[2] <= 7 * T
+        batches, keep = gw.make_batches([0])
+        ws = gw.decode(batches)
+        assert fs.fs_decode_status(ws) == 4
+        out = keep["out"][0]
+        assert bool(torch.isfinite(out).all())
+        others = [i for i in range(len(lens)) if i != victim]
+        assert torch.equal(out[others], clean[others])
+        assert not torch.equal(out[victim], clean[victim])
+        # prefill over the same tables
+        n_new = np.array([16, 16, 16, 16], np.int32)
+        q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        q = torch.randn((int(q_off[-1]), 8, 128), dtype=torch.float16, device=gw.device)
+        o = torch.full_like(q, float("nan"))
+        pws = torch.empty(fs.fs_prefill_workspace_bytes(len(lens)), dtype=torch.uint8, device=gw.device)
+        fs.fs_prefill_attention(gw.pool, gw.model_ids[0], 0, 8, 0.088, q, gw.tables[0], gw.seq_lens[0],
+                                torch.from_numpy(q_off).to(gw.device), q_off, o, None, pws)
+        assert fs.fs_decode_status(pws) == 4
+        assert bool(torch.isfinite(o).all())
+        gw.tables[0][victim, 2] = good
+        fs.fs_prefill_attention(gw.pool, gw.model_ids[0], 0, 8, 0.088, q, gw.tables[0], gw.seq_lens[0],
+                                torch.from_numpy(q_off).to(gw.device), q_off, o, None, pws)
+        assert fs.fs_decode_status(pws) == 0
+    finally:
+        fs.fs_set_kernel_mode(0)
+        gw.close()
