@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the KV-slab decode hot path on one MI355X.
 
-A *step* is one decode step of one layer over the whole batch: ``fs_kv_append`` of every
-sequence's newest token (quantize + scatter into its slab block) followed by one
-``fs_decode_attention_multi`` launch (work-list preparation, split-K paged attention over all
-co-located models, split combine).  Slab allocation is host bookkeeping done while the workload
+A *step* is one decode step of one layer over the whole batch, one ``fs_decode_step_multi`` call: the
+append of every sequence's newest token (quantize + scatter into its slab block; all models in the
+launch that also prepares the work list), split-K paged attention over all co-located models, split
+combine.  Slab allocation is host bookkeeping done while the workload
 is set up (its rate is reported under ``extra``).  KV, block tables, queries and lengths are
 resident in HBM before the timed region starts; the layer index rotates between steps so that no
 step re-reads what the previous one left in cache.
@@ -27,8 +27,9 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
+for _p in (ROOT, os.path.join(ROOT, "tests")):  # tests/: gpu_workload, the plumbing that stands a workload up
+    if _p not in sys.path:
+        sys.path.insert(0, _p)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
@@ -106,16 +107,16 @@ def cpu_baseline(gw, wl, layers, n_random, n_threads):
 class Timed:
     """One workload stood up on the GPU and the step timed on it."""
 
-    def __init__(self, wl, layers_cap=0):
+    def __init__(self, wl, layers_cap=0, options=None):
         import torch
 
+        import gpu_workload as harness
         import paper_2509_06261_amd as fs
-        from paper_2509_06261_amd import harness
 
         self.fs, self.wl, self.torch = fs, wl, torch
         log(f"[bench] workload {wl.name}: pool {wl.pool_bytes / 2**30:.1f} GiB, slabs {wl.slab_bytes // 1024} KiB, "
             f"placement {wl.placement}")
-        self.gw = gw = harness.GpuWorkload(wl)
+        self.gw = gw = harness.GpuWorkload(wl, options=options)
 
         class CountingAdapter(harness.AllocAdapter):
             calls = 0
@@ -160,9 +161,6 @@ class Timed:
         events on the launch stream).  Returns a dict of the measurements."""
         import numpy as np
 
-        from fs_inputs import device as gen_device
-        from fs_inputs import gen
-
         fs, gw, wl, torch = self.fs, self.gw, self.wl, self.torch
         n_layers_of = self.n_layers_of
         # per-layer batches (queries differ per layer), prepared before timing
@@ -175,31 +173,17 @@ class Timed:
             keepalive.append(keep)
         self.first_layers = per_layer[0][0]
         ws = gw.workspace_for(per_layer[0][1])
-        # newest-token rows for the per-step append (position n_b - 1 of every sequence), per model
-        new_rows = []
-        for k, (s, m) in enumerate(zip(wl.models, gw.model_ids)):
-            n = s.n_seq
-            si = torch.arange(n, dtype=torch.int32, device=gw.device)
-            po = (gw.seq_lens[k] - 1).to(torch.int32)
-            dt = torch.float32 if s.src_f32 else torch.float16
-            rows = []
-            for layer in range(n_layers_of[k]):
-                kb = torch.empty((n, s.n_kv_heads, s.head_dim), dtype=dt, device=gw.device)
-                vb = torch.empty_like(kb)
-                gen_device.fill_rows(kb, wl.seed, s.tag, layer, gen.WHICH_K, si, po, s.n_kv_heads, s.head_dim)
-                gen_device.fill_rows(vb, wl.seed, s.tag, layer, gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
-                rows.append((kb, vb))
-            new_rows.append((si, po, rows))
+        # newest-token rows for the per-step append (position n_b - 1 of every sequence), per model and layer
+        step_appends, keep_rows = [], []
+        for r in range(n_rot):
+            appends, keep = gw.newest_token_appends(per_layer[r][0])
+            step_appends.append(appends)
+            keep_rows.append(keep)
         torch.cuda.synchronize()
         stream = torch.cuda.current_stream()
 
         def step(i):
-            layers, batches = per_layer[i % n_rot]
-            for k, m in enumerate(gw.model_ids):
-                si, po, rows = new_rows[k]
-                kb, vb = rows[layers[k]]
-                fs.fs_kv_append(gw.pool, m, layers[k], kb, vb, si, po, gw.tables[k], stream)
-            fs.fs_decode_attention_multi(gw.pool, batches, ws, stream)
+            fs.fs_decode_step_multi(gw.pool, step_appends[i % n_rot], per_layer[i % n_rot][1], ws, stream)
 
         for i in range(warmup):
             step(i)
@@ -212,15 +196,15 @@ class Timed:
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         # attention kernel alone, HIP events on the launch stream
-        fs.fs_set_kernel_timing(1)
+        gw.set_option(fs.FS_OPT_KERNEL_TIMING, 1)
         kms = []
         for i in range(steps):
             step(warmup + steps + i)
-            kms.append(fs.fs_last_attention_kernel_ms())
-        fs.fs_set_kernel_timing(0)
+            kms.append(fs.fs_pool_last_attention_kernel_ms(gw.pool))
+        gw.set_option(fs.FS_OPT_KERNEL_TIMING, 0)
         kms = np.array(kms)
         algo, kv = self.algorithmic_bytes()
-        del keepalive
+        del keepalive, keep_rows
         return {"ms_per_step": elapsed / steps * 1e3, "kernel_ms": kms, "algo_bytes": algo, "kv_bytes": kv,
                 "timed_s": elapsed}
 
@@ -282,11 +266,12 @@ def main():
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
     plain = not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers or args.split_bytes)
+    options = {}
     if args.kernel_mode:
-        fs.fs_set_kernel_mode(args.kernel_mode)
+        options[fs.FS_OPT_DECODE_KERNEL] = args.kernel_mode
     if args.split_bytes:
-        fs.fs_set_split_bytes(args.split_bytes)
-    tw = Timed(wl, args.layers)
+        options[fs.FS_OPT_SPLIT_BYTES] = args.split_bytes
+    tw = Timed(wl, args.layers, options)
     gw = tw.gw
     r = tw.run(args.steps, args.warmup)
     ms_per_step, kms, algo_bytes, kv_bytes = r["ms_per_step"], r["kernel_ms"], r["algo_bytes"], r["kv_bytes"]
@@ -330,7 +315,7 @@ def main():
             "placement": wl.placement,
             "churn_steps": wl.churn_steps if wl.placement == "churn" else 0,
             "live_slabs": int(tw.stats.live_blocks),
-            "step": "fs_kv_append(newest token of every sequence) + fs_decode_attention_multi, one layer",
+            "step": "fs_decode_step_multi: append of the newest token of every sequence + multi-model decode attention, one layer",
             "kernel_mode": args.kernel_mode,
         },
         "roofline": {

@@ -20,8 +20,9 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
+for _p in (ROOT, os.path.join(ROOT, "tests")):  # tests/: gpu_workload, the plumbing that stands a workload up
+    if _p not in sys.path:
+        sys.path.insert(0, _p)
 
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix rate
 
@@ -39,12 +40,12 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="tokens prefilled per sequence (0 = the whole prompt)")
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
-    ap.add_argument("--kernel", default="0,0", help="column blocks,waves for fs_set_prefill_kernel (0,0 = automatic)")
+    ap.add_argument("--kernel", default="0,0", help="column blocks,waves: FS_OPT_PREFILL_COLUMN_BLOCKS / _WAVES (0,0 = automatic)")
     ap.add_argument("--cache-resident", action="store_true",
                     help="diagnosis: the attention reads every block table entry as the sequence's first block (K/V "
                          "stay in cache; results meaningless, timing = the kernel without its memory traffic)")
-    ap.add_argument("--staged-dequant", type=int, default=1, help="fs_set_prefill_staged_dequant (INT8 / INT4 models)")
-    ap.add_argument("--pipelined", action="store_true", help="fs_set_prefill_pipelined(1) (with --kernel 16,4)")
+    ap.add_argument("--staged-dequant", type=int, default=1, help="FS_OPT_PREFILL_STAGED_DEQUANT (INT8 / INT4 models)")
+    ap.add_argument("--pipelined", action="store_true", help="FS_OPT_PREFILL_PIPELINED (with --kernel 16,4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
                     help="after the timed region also run a plain device copy of this size (counter calibration "
@@ -60,17 +61,17 @@ def main():
     import paper_2509_06261_amd as fs
     from fs_inputs import gen, workloads
     from fs_inputs import device as gen_device
-    from paper_2509_06261_amd import harness
+    import gpu_workload as harness
 
     ker_blocks, ker_waves = (int(x) for x in args.kernel.split(","))
-    if fs.fs_set_prefill_kernel(ker_blocks, ker_waves) != 0:
+    if ker_blocks not in (0, 1, 2, 4, 16) or ker_waves not in (0, 4, 8):
         raise SystemExit("bench_prefill.py: --kernel must be blocks in {0,1,2,4,16} and waves in {0,4,8}")
-    fs.fs_set_prefill_pipelined(int(args.pipelined))
-    fs.fs_set_prefill_staged_dequant(int(args.staged_dequant))
+    options = {fs.FS_OPT_PREFILL_COLUMN_BLOCKS: ker_blocks, fs.FS_OPT_PREFILL_WAVES: ker_waves,
+               fs.FS_OPT_PREFILL_PIPELINED: int(args.pipelined), fs.FS_OPT_PREFILL_STAGED_DEQUANT: int(args.staged_dequant)}
     wl = workloads.config(args.config)
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
-    gw = harness.GpuWorkload(wl)
+    gw = harness.GpuWorkload(wl, options=options)
     gw.place()
     n_layers_of = [min(args.layers, s.n_layers) for s in wl.models]
     gw.populate([list(range(n)) for n in n_layers_of])

@@ -115,6 +115,17 @@ int fs_model_geometry(fs_pool* pool, fs_model_t model, fs_geometry_t* out);
 int fs_block_alloc(fs_pool* pool, fs_model_t model, int32_t* blk_id_out);
 int fs_block_free(fs_pool* pool, fs_model_t model, int32_t blk_id);
 int fs_pool_stats(fs_pool* pool, fs_pool_stats_t* out);
+/* Per-key view of the slab table (Sec. 5.2 keys every slab by the block size -- here the model -- it is formatted
+ * for): the slabs this model holds, its live blocks, the free blocks left in its PARTIAL slabs (what the next
+ * allocations of this key take before a FREE slab is carved), and its share of the pool's bytes. */
+typedef struct {
+  int64_t slabs_partial, slabs_full;
+  int64_t live_blocks;
+  int64_t free_blocks_in_partial_slabs;
+  uint64_t live_bytes;     /* live_blocks * block_budget */
+  uint64_t stranded_bytes; /* live_blocks * (block_budget - block_bytes) */
+} fs_model_stats_t;
+int fs_model_stats(fs_pool* pool, fs_model_t model, fs_model_stats_t* out);
 /* Copies the slab table for bit-exact comparison: state/key(model or -1)/used per slab
  * ([n_slabs] each) and the free stack bottom-to-top ([n_slabs] capacity, *n_free entries). */
 int fs_pool_dump(fs_pool* pool, int32_t* slab_state, int32_t* slab_key, int32_t* slab_used, int32_t* free_stack,
@@ -137,6 +148,22 @@ int fs_model_dump_live(fs_pool* pool, fs_model_t model, uint8_t* live);
 int fs_kv_append(fs_pool* pool, fs_model_t model, int layer, const void* k_new, const void* v_new, int src_dtype,
                  const int32_t* seq_idx, const int32_t* pos, const int32_t* block_tables, int max_blocks,
                  int64_t n_tokens, void* stream);
+
+/* The newest tokens of several models (Sec. 4: the co-located models decode side by side) in ONE launch: each entry
+ * is one fs_kv_append call's arguments (host array of 1..8 entries; pointers inside are device pointers). */
+typedef struct {
+  fs_model_t model;
+  int32_t layer;
+  int32_t src_dtype;  /* fs_src_dtype */
+  int32_t max_blocks;
+  const void* k_new;
+  const void* v_new;
+  const int32_t* seq_idx;
+  const int32_t* pos;
+  const int32_t* block_tables;
+  int64_t n_tokens;
+} fs_append_t;
+int fs_kv_append_multi(fs_pool* pool, const fs_append_t* appends, int n_appends, void* stream);
 
 /* ---- Decode attention (Sec. 2.1 / 2.3: one query per sequence reads all its cached tokens
  * through the block table as if the KV were contiguous) ---------------------------------------
@@ -179,6 +206,14 @@ int fs_decode_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_head
 /* Several models' batches (host array, at most 8) in one launch over one work queue. */
 int fs_decode_attention_multi(fs_pool* pool, const fs_batch_t* batches, int n_batches, void* workspace,
                               uint64_t workspace_bytes, void* stream);
+
+/* One decode step of one layer for all co-located models (Sec. 2.1: append the newest token's K/V, then attend over
+ * the whole cache): fs_kv_append_multi(appends) followed by fs_decode_attention_multi(batches), in three launches
+ * instead of n_appends + 3 -- the appends and the decode launch's work-list preparation do not depend on each other
+ * and run in one kernel.  n_appends may be 0 (then `appends` may be NULL).  Arguments, workspace and status as for
+ * the two calls it stands for. */
+int fs_decode_step_multi(fs_pool* pool, const fs_append_t* appends, int n_appends, const fs_batch_t* batches,
+                         int n_batches, void* workspace, uint64_t workspace_bytes, void* stream);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
  * that forbid it): fs_decode_attention_multi with its workspace in a 64 MiB array that the library holds in the
@@ -261,36 +296,44 @@ int fs_sched_select_batch(const fs_request_t* waiting, int n_waiting, const fs_s
 int fs_sched_place_models(const double* footprint, const double* mu, int n_models, const double* capacity, int n_gpus,
                           int32_t* placement);
 
-/* Prefill kernel selection for tests and measurements.  column_blocks: 0 = automatic (default: the workgroup
- * kernel, or the 16-column kernel for launches with fewer work items than compute units), 1 / 2 / 4 = the
- * wave-level kernels with 16 / 32 / 64 logit columns per wave, 16 = the workgroup kernel (waves: 8 x 32 columns,
- * the default, or 4 x 64).  FS_ERR_INVALID for other values (8, a variant with two workgroups per compute unit,
- * is switched off). */
-int fs_set_prefill_kernel(int column_blocks, int waves);
-/* The 4-wave workgroup kernel (column_blocks 16, waves 4) in its software-pipelined form: one wave interleaves the
- * MFMAs of the next sub-tile's S^T with the current sub-tile's exponentials.  0 = off (default). */
-int fs_set_prefill_pipelined(int enable);
-/* INT8 / INT4 models on the 8-wave workgroup kernel: the waves that stage K and V in LDS leave dequantized fp16
- * operands there, (code - zero point) * scale rounded to fp16, and every wave runs the FP16 tile code (no per-logit
- * scales or zero-point terms): 15-26 % faster, and the default (non-zero or negative `enable`).  With 0 the integer
- * codes reach the MFMAs exactly and scales and zero points are applied in fp32 around them, as in decode.  Both stay
- * inside the prefill tolerance. */
-int fs_set_prefill_staged_dequant(int enable);
-
-/* Kernel selection for tests and measurements: 0 = automatic (default), 1 = force the generic
- * vector-ALU kernel, 2 = force the MFMA kernel (FS_ERR_INVALID at launch for shapes it lacks). */
-int fs_set_kernel_mode(int mode);
-/* Target KV bytes per split-K work item, rounded to whole 32-token tiles.  0 (the default) lets every launch
- * choose: 192 KiB, less (down to 64 KiB) for launches too small to give each wave of the grid three items
- * (judged from seq_lens_host where given, otherwise from the upper bound max_blocks * tokens_per_block).
- * The workspace size depends on it: query fs_decode_workspace_bytes with the setting the launch will use. */
-int fs_set_split_bytes(uint64_t bytes);
-
-/* Measurement aid: while enabled, every decode call brackets its attention kernel (not the small
- * work-list and combine kernels) with HIP events on the call's stream; fs_last_attention_kernel_ms
- * waits for the latest such pair and returns the elapsed milliseconds (negative if none). */
-int fs_set_kernel_timing(int enable);
-float fs_last_attention_kernel_ms(void);
+/* ---- Per-pool options: kernel selection and measurement aids (no process-global state; a pool is driven by one
+ * host thread at a time, and so are its options).  fs_pool_set_option returns FS_ERR_INVALID for an unknown option
+ * or a value outside its range; fs_pool_get_option reads the current value. */
+enum fs_option {
+  /* decode kernel: 0 = automatic (default), 1 = the generic vector-ALU kernel, 2 = the MFMA kernel (a launch with a
+   * shape it lacks then fails with FS_ERR_INVALID) */
+  FS_OPT_DECODE_KERNEL = 0,
+  /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose:
+   * 192 KiB, less (down to 64 KiB) for launches too small to give each wave of the grid three items (judged from
+   * seq_lens_host where given, otherwise from max_blocks * tokens_per_block).  Otherwise 4096 .. 2^30.
+   * fs_decode_workspace_bytes answers for the pool's current setting. */
+  FS_OPT_SPLIT_BYTES = 1,
+  /* non-zero: every decode call brackets its attention kernel (not the work-list and combine kernels) with HIP
+   * events on the call's stream; fs_pool_last_attention_kernel_ms waits for the latest pair */
+  FS_OPT_KERNEL_TIMING = 2,
+  /* prefill kernel: 0 = automatic (default: the workgroup kernel, or the 16-column kernel for launches with fewer
+   * work items than compute units), 1 / 2 / 4 = the wave-level kernels with 16 / 32 / 64 logit columns per wave,
+   * 16 = the workgroup kernel */
+  FS_OPT_PREFILL_COLUMN_BLOCKS = 3,
+  /* waves of the workgroup kernel: 0 or 8 = 8 x 32 columns (default), 4 = 4 x 64 columns */
+  FS_OPT_PREFILL_WAVES = 4,
+  /* non-zero: the 4-wave workgroup kernel in its software-pipelined form (one wave interleaves the MFMAs of the next
+   * sub-tile's S^T with the current sub-tile's exponentials); default 0 */
+  FS_OPT_PREFILL_PIPELINED = 5,
+  /* INT8 / INT4 models on the 8-wave workgroup kernel: non-zero (default) = the waves that stage K and V in LDS leave
+   * dequantized fp16 operands there, (code - zero point) * scale rounded to fp16, and every wave runs the FP16 tile
+   * code: 15-26 % faster; 0 = the integer codes reach the MFMAs exactly and scales and zero points are applied in
+   * fp32 around them, as in decode.  Both stay inside the prefill tolerance. */
+  FS_OPT_PREFILL_STAGED_DEQUANT = 6,
+  /* read-only: the kernel the pool's latest fs_prefill_attention call launched:
+   * column blocks | waves << 8 | staged dequantization << 16 | pipelined << 17 (0: none yet; column blocks 0 with
+   * bit 18 set: the vector-ALU kernel) */
+  FS_OPT_LAST_PREFILL_KERNEL = 7
+};
+int fs_pool_set_option(fs_pool* pool, int option, int64_t value);
+int fs_pool_get_option(fs_pool* pool, int option, int64_t* value);
+/* Elapsed milliseconds of the latest attention kernel timed under FS_OPT_KERNEL_TIMING (negative if none). */
+float fs_pool_last_attention_kernel_ms(fs_pool* pool);
 
 const char* fs_last_error(void);
 

@@ -24,11 +24,14 @@ LIB_PATH = os.path.join(_DIR, "libfineserve.so")
 EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
            "fs_block_bytes", "fs_slab_bytes_for_blocks", "fs_model_register_tokens",
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
-           "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_decode_workspace_bytes",
+           "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_kv_append_multi", "fs_decode_step_multi",
+           "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_attention_multi_static", "fs_decode_status", "fs_prefill_workspace_bytes",
-           "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_set_prefill_kernel", "fs_set_prefill_pipelined", "fs_set_prefill_staged_dequant",
-           "fs_set_kernel_mode",
-           "fs_set_split_bytes", "fs_set_kernel_timing", "fs_last_attention_kernel_ms", "fs_last_error"]
+           "fs_prefill_attention", "fs_sched_select_batch", "fs_sched_place_models", "fs_model_stats", "fs_pool_set_option",
+           "fs_pool_get_option", "fs_pool_last_attention_kernel_ms", "fs_last_error"]
+
+(FS_OPT_DECODE_KERNEL, FS_OPT_SPLIT_BYTES, FS_OPT_KERNEL_TIMING, FS_OPT_PREFILL_COLUMN_BLOCKS, FS_OPT_PREFILL_WAVES,
+ FS_OPT_PREFILL_PIPELINED, FS_OPT_PREFILL_STAGED_DEQUANT, FS_OPT_LAST_PREFILL_KERNEL) = range(8)
 
 
 class fs_geometry_t(ctypes.Structure):
@@ -43,6 +46,19 @@ class fs_pool_stats_t(ctypes.Structure):
     _fields_ = [("n_slabs", ctypes.c_int64), ("slabs_free", ctypes.c_int64), ("slabs_partial", ctypes.c_int64),
                 ("slabs_full", ctypes.c_int64), ("live_blocks", ctypes.c_int64), ("n_models", ctypes.c_int64),
                 ("stranded_bytes", ctypes.c_uint64)]
+
+
+class fs_model_stats_t(ctypes.Structure):
+    _fields_ = [("slabs_partial", ctypes.c_int64), ("slabs_full", ctypes.c_int64), ("live_blocks", ctypes.c_int64),
+                ("free_blocks_in_partial_slabs", ctypes.c_int64), ("live_bytes", ctypes.c_uint64),
+                ("stranded_bytes", ctypes.c_uint64)]
+
+
+class fs_append_t(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_int32), ("layer", ctypes.c_int32), ("src_dtype", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
+                ("seq_idx", ctypes.c_void_p), ("pos", ctypes.c_void_p), ("block_tables", ctypes.c_void_p),
+                ("n_tokens", ctypes.c_int64)]
 
 
 class fs_batch_t(ctypes.Structure):
@@ -77,6 +93,8 @@ def _load():
         "fs_pool_dump": (i32, [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int64)]),
         "fs_model_dump_live": (i32, [vp, i32, vp]),
         "fs_kv_append": (i32, [vp, i32, i32, vp, vp, i32, vp, vp, vp, i32, i64, vp]),
+        "fs_kv_append_multi": (i32, [vp, ctypes.POINTER(fs_append_t), i32, vp]),
+        "fs_decode_step_multi": (i32, [vp, ctypes.POINTER(fs_append_t), i32, ctypes.POINTER(fs_batch_t), i32, vp, u64, vp]),
         "fs_decode_workspace_bytes": (u64, [vp, ctypes.POINTER(fs_batch_t), i32]),
         "fs_decode_attention": (i32, [vp, i32, i32, i32, f32, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
         "fs_decode_attention_multi": (i32, [vp, ctypes.POINTER(fs_batch_t), i32, vp, u64, vp]),
@@ -86,13 +104,10 @@ def _load():
         "fs_prefill_attention": (i32, [vp, i32, i32, i32, ctypes.c_float, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64, vp]),
         "fs_sched_select_batch": (i32, [vp, i32, vp, ctypes.c_double, vp, vp, vp, vp]),
         "fs_sched_place_models": (i32, [vp, vp, i32, vp, i32, vp]),
-        "fs_set_prefill_kernel": (i32, [i32, i32]),
-        "fs_set_prefill_pipelined": (i32, [i32]),
-        "fs_set_prefill_staged_dequant": (i32, [i32]),
-        "fs_set_kernel_mode": (i32, [i32]),
-        "fs_set_split_bytes": (i32, [u64]),
-        "fs_set_kernel_timing": (i32, [i32]),
-        "fs_last_attention_kernel_ms": (f32, []),
+        "fs_model_stats": (i32, [vp, i32, ctypes.POINTER(fs_model_stats_t)]),
+        "fs_pool_set_option": (i32, [vp, i32, i64]),
+        "fs_pool_get_option": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int64)]),
+        "fs_pool_last_attention_kernel_ms": (f32, [vp]),
         "fs_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -259,6 +274,37 @@ def fs_kv_append(pool, model, layer, k_new, v_new, seq_idx, pos, block_tables, s
         raise FsError(rc, "fs_kv_append")
 
 
+def make_append(model, layer, k_new, v_new, seq_idx, pos, block_tables) -> fs_append_t:
+    """Fill an fs_append_t from torch tensors (which the caller keeps alive); arguments as fs_kv_append."""
+    import torch
+    assert k_new.dtype == v_new.dtype and k_new.dtype in (torch.float16, torch.float32)
+    assert k_new.is_contiguous() and v_new.is_contiguous() and block_tables.is_contiguous()
+    assert seq_idx.dtype == torch.int32 and pos.dtype == torch.int32 and block_tables.dtype == torch.int32
+    a = fs_append_t()
+    a.model, a.layer = model, layer
+    a.src_dtype = FS_SRC_FP32 if k_new.dtype == torch.float32 else FS_SRC_FP16
+    a.max_blocks = block_tables.shape[1]
+    a.k_new, a.v_new, a.seq_idx, a.pos, a.block_tables = _dp(k_new), _dp(v_new), _dp(seq_idx), _dp(pos), _dp(block_tables)
+    a.n_tokens = seq_idx.numel()
+    return a
+
+
+def fs_kv_append_multi(pool, appends, stream=None):
+    arr = (fs_append_t * len(appends))(*appends)
+    rc = _L.fs_kv_append_multi(pool, arr, len(appends), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_kv_append_multi")
+
+
+def fs_decode_step_multi(pool, appends, batches, workspace, stream=None):
+    aarr = (fs_append_t * max(len(appends), 1))(*appends)
+    barr = (fs_batch_t * len(batches))(*batches)
+    rc = _L.fs_decode_step_multi(pool, aarr, len(appends), barr, len(batches), _dp(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_decode_step_multi")
+
+
 def make_batch(model, layer, n_q_heads, sm_scale, q, block_tables, seq_lens, out, lse=None,
                seq_lens_host=None) -> fs_batch_t:
     """Fill an fs_batch_t from torch tensors (which the caller keeps alive)."""
@@ -367,29 +413,26 @@ def fs_sched_place_models(footprint, mu, capacity):
     return out[:len(f)].copy()
 
 
-def fs_set_prefill_kernel(column_blocks: int, waves: int = 0) -> int:
-    return _L.fs_set_prefill_kernel(int(column_blocks), int(waves))
+def fs_model_stats(pool, model) -> fs_model_stats_t:
+    st = fs_model_stats_t()
+    rc = _L.fs_model_stats(pool, model, ctypes.byref(st))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_model_stats")
+    return st
 
 
-def fs_set_prefill_pipelined(enable: int) -> int:
-    return _L.fs_set_prefill_pipelined(int(enable))
+def fs_pool_set_option(pool, option: int, value: int) -> int:
+    """Returns the status code (FS_ERR_INVALID for an unknown option or a value out of range)."""
+    return _L.fs_pool_set_option(pool, int(option), int(value))
 
 
-def fs_set_prefill_staged_dequant(enable: int) -> int:
-    return _L.fs_set_prefill_staged_dequant(int(enable))
+def fs_pool_get_option(pool, option: int) -> int:
+    v = ctypes.c_int64(0)
+    rc = _L.fs_pool_get_option(pool, int(option), ctypes.byref(v))
+    if rc != FS_OK:
+        raise FsError(rc, "fs_pool_get_option")
+    return v.value
 
 
-def fs_set_kernel_mode(mode: int) -> int:
-    return _L.fs_set_kernel_mode(mode)
-
-
-def fs_set_split_bytes(n: int) -> int:
-    return _L.fs_set_split_bytes(n)
-
-
-def fs_set_kernel_timing(enable: int) -> int:
-    return _L.fs_set_kernel_timing(int(enable))
-
-
-def fs_last_attention_kernel_ms() -> float:
-    return _L.fs_last_attention_kernel_ms()
+def fs_pool_last_attention_kernel_ms(pool) -> float:
+    return _L.fs_pool_last_attention_kernel_ms(pool)

@@ -18,14 +18,24 @@ struct DevBatch {
   const float* v_scale;
   int32_t n_seq, max_blocks, n_q, G;
   float sm_scale;
-  int32_t chunk_tokens;  // generic kernel: tokens per split-K work item (multiple of 32)
+  int32_t chunk_tokens;  // generic kernel: tokens per split-K work item of size tier 0 (multiple of 32)
   int32_t seq_first;     // index of this batch's first sequence among all batches' sequences
   int32_t part_stride;   // floats per work item in the partial buffer: G * (D + 2)
   int32_t qrow_first;    // index of this batch's first (sequence, q head) row among all batches
   // MFMA kernel: a sequence is cut into runs of 8 token slots that never cross a block (R = ceil(T / 8) runs
   // per block, the last one of a block shifted back to end at slot T - 1); a work item is chunk_runs
   // consecutive runs.  chunk_runs == 0 selects the token-based splits of the generic kernel.
-  int32_t chunk_runs;    // multiple of 4
+  int32_t chunk_runs;    // of size tier 0; multiple of 4
+  // Size tiers: the sequences of a batch are queued in index order, so the last sequences' items are the last the
+  // grid works on.  Sequence i belongs to tier (i >= tier_seq[0]) + (i >= tier_seq[1]) + (i >= tier_seq[2]), and a
+  // tier's work items are half the size of the tier before: large items while there is plenty of work (less set-up
+  // per byte), small ones at the end (the waves finish within one small item of each other).  tier_seq[t] = n_seq
+  // where a tier is unused.
+  int32_t tier_seq[3];
+  // Runs one turn of the MFMA kernel's tile ring covers (4 per tile, 1 / 2 / 2 / 3 tiles for FP16 / FP8 / INT8 /
+  // INT4): the kernel works in whole turns, so items are whole turns long (their surplus tiles would be computed
+  // and masked, which the formats bound by the vector ALU cannot afford on small items).
+  int32_t ring_runs;
   int32_t R;
   uint32_t r_magic;      // ceil(2^32 / R): run / R == umulhi(run, r_magic) while run * R < 2^32
   uint32_t n_blocks;     // blocks of this model's size the pool holds: valid table entries are 0 .. n_blocks - 1
@@ -54,8 +64,11 @@ __device__ __forceinline__ uint32_t checked_block(int32_t entry, uint32_t n_bloc
   return 0u;
 }
 
-// A work item's record in the queue: x = batch | KV head << 4, y = sequence, z = split, w = the item's index
-// within its batch in sequence-major order (sequence, split, KV head) -- the order of the partial records.
+// A work item's record in the queue, two int4 (item_list[2 i] and item_list[2 i + 1]).  First: x = batch |
+// KV head << 4, y = sequence, z = split, w = the item's index within its batch in sequence-major order (sequence,
+// split, KV head) -- the order of the partial records.  Second: x = the sequence's length, already clamped into
+// [1, max_blocks * tokens_per_block] (so that a kernel needs no look-up of its own before it can address the
+// item's blocks); y, z, w = 0.
 __device__ __host__ inline int4 make_rec(int batch, int seq, int split, int head, uint32_t local) {
   return int4{batch | (head << 4), seq, split, (int)local};
 }
@@ -66,7 +79,7 @@ struct MultiArgs {
   DevBatch b[kMaxBatches];
   uint32_t* header;
   uint32_t* item_base;  // [n_seq_total + 1] first work item of each sequence
-  int4* item_list;      // [item_capacity] record of every work item, queue order (see make_rec)
+  int4* item_list;      // [2 * item_capacity] record of every work item (two int4 each), queue order (see make_rec)
   float* partials;
   uint64_t part_capacity;  // floats
   uint32_t item_capacity;  // entries of item_list
@@ -90,10 +103,27 @@ __device__ __host__ inline int n_runs(int len, int T, int R) {
   return (nblk - 1) * R + ((rem + 7) >> 3);
 }
 
-// Splits of a sequence of `len` (already clamped) tokens.
-__device__ __host__ inline int n_splits(const DevBatch& B, int len) {
-  if (B.chunk_runs) return (n_runs(len, B.g.T, B.R) + B.chunk_runs - 1) / B.chunk_runs;
-  return (len + B.chunk_tokens - 1) / B.chunk_tokens;
+__device__ __host__ inline int tier_of(const DevBatch& B, int seq) {
+  return (seq >= B.tier_seq[0]) + (seq >= B.tier_seq[1]) + (seq >= B.tier_seq[2]);
+}
+// Runs (MFMA kernel) or tokens (generic kernel) per work item of sequence `seq`.
+__device__ __host__ inline int chunk_runs_of(const DevBatch& B, int seq) {
+  const int cr = B.chunk_runs >> tier_of(B, seq);  // (the host makes tier 0 a multiple of 8 rings when tiers are on)
+  return cr < B.ring_runs ? B.ring_runs : cr - cr % 4;
+}
+__device__ __host__ inline int chunk_tokens_of(const DevBatch& B, int seq) {
+  const int ct = (B.chunk_tokens >> tier_of(B, seq)) & ~31;
+  return ct < 32 ? 32 : ct;
+}
+
+// Splits of sequence `seq`, `len` (already clamped) tokens long.
+__device__ __host__ inline int n_splits(const DevBatch& B, int seq, int len) {
+  if (B.chunk_runs) {
+    const int cr = chunk_runs_of(B, seq);
+    return (n_runs(len, B.g.T, B.R) + cr - 1) / cr;
+  }
+  const int ct = chunk_tokens_of(B, seq);
+  return (len + ct - 1) / ct;
 }
 
 // Launchers implemented in the kernel translation units.

@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cstdlib>
 
+#include "fs_append_rows.h"
 #include "fs_attention.h"
 
 // Workspace of fs_decode_attention_multi_static, the entry point for callers that cannot allocate: one copy per
@@ -24,11 +25,10 @@ static uint8_t* g_scratch_ptr[kMaxScratchDevices] = {};
 namespace fs {
 namespace {
 
-int g_kernel_mode = 0;
-uint64_t g_split_bytes = 0;  // 0: chosen per launch (see launch_split_bytes)
-constexpr uint64_t kSplitMax = 192u << 10, kSplitMin = 64u << 10;
-bool g_timing = false;
-hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
+// Largest work items of a launch (size tier 0): at most 768 KiB of KV, at least 64 KiB.
+constexpr uint64_t kSplitMax = 768u << 10, kSplitMin = 64u << 10;
+// The last 30 %, 15 % and 5 % of a batch's KV bytes (in sequence order) go to work items of 1/2, 1/4 and 1/8 the size.
+constexpr double kTierFrom[3] = {0.70, 0.85, 0.95};
 
 // ---------------------------------------------------------------------------------------
 // Work-list preparation: scans the sequences of all batches and writes, for every sequence,
@@ -45,24 +45,28 @@ hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 constexpr int kPrepThreads = 1024;
 constexpr int kPrepGroups = 64;
 
-// Items of the sequence a thread looks at (0 past the batch's last sequence); flags lengths out of range.
-__device__ __forceinline__ uint32_t seq_items(const MultiArgs& A, const DevBatch& B, int i, bool report) {
+// Items of the sequence a thread looks at (0 past the batch's last sequence) and its clamped length; flags lengths
+// out of range.
+__device__ __forceinline__ uint32_t seq_items(const MultiArgs& A, const DevBatch& B, int i, bool report, int& len) {
+  len = 1;
   if (i >= B.n_seq) return 0;
   const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
-  int len = B.seq_lens[i];
+  len = B.seq_lens[i];
   if (len < 1 || len > max_len) {
     if (report) atomicOr(A.header + kHdrStatus, 1u);
     len = len < 1 ? 1 : max_len;
   }
-  return (uint32_t)n_splits(B, len) * (uint32_t)B.g.H;
+  return (uint32_t)n_splits(B, i, len) * (uint32_t)B.g.H;
 }
 
-__global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
+// group: this workgroup's index among the n_groups workgroups that prepare the list
+__device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, uint32_t n_groups) {
   __shared__ uint32_t s_incl[kPrepThreads];  // inclusive scan of the item counts of this round's sequences
+  __shared__ int32_t s_len[kPrepThreads];    // clamped lengths of this round's sequences
   __shared__ uint32_t s_wave[kPrepThreads / 64];
   __shared__ uint32_t s_count[kMaxBatches];  // items of each batch
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool leader = blockIdx.x == 0;
+  const bool leader = group == 0;
   uint64_t* part_off = reinterpret_cast<uint64_t*>(A.header + kHdrPartOff);
   if (leader && tid == 0) A.header[kHdrStatus] = 0;
   if (leader && tid < kPools) A.header[kHdrPools + tid * kPoolStride] = 0;
@@ -73,7 +77,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
   for (int b = 0; b < A.n_batches; ++b) {
     const DevBatch& B = A.b[b];
     uint32_t v = 0;
-    for (int i = tid; i < B.n_seq; i += kPrepThreads) v += seq_items(A, B, i, leader);
+    int unused;
+    for (int i = tid; i < B.n_seq; i += kPrepThreads) v += seq_items(A, B, i, leader, unused);
 #pragma unroll
     for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off, 64);
     if (lane == 0 && v) atomicAdd(&s_count[b], v);
@@ -97,7 +102,9 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
     }
     for (int base = 0; base < B.n_seq; base += kPrepThreads) {
       const int i = base + tid;
-      const uint32_t v = seq_items(A, B, i, false);
+      int len_i;
+      const uint32_t v = seq_items(A, B, i, false, len_i);
+      s_len[tid] = len_i;
       // inclusive scan: within each wave by shuffles, then over the waves' totals
       uint32_t incl = v;
 #pragma unroll
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
       if (leader && i < B.n_seq) A.item_base[B.seq_first + i] = running + incl - v;
       // item r of the round (sequence-major: sequence, then split, KV heads innermost) belongs to the first
       // sequence k whose inclusive count exceeds r
-      for (uint32_t r = blockIdx.x * kPrepThreads + tid; r < round_items; r += gridDim.x * kPrepThreads) {
+      for (uint32_t r = group * kPrepThreads + tid; r < round_items; r += n_groups * kPrepThreads) {
         int lo = 0, hi = kPrepThreads - 1;
         while (lo < hi) {
           const int mid = (lo + hi) >> 1;
@@ -135,9 +142,12 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
           const uint64_t c = o < b ? num / n_b + 1 : (num + n_b - 1) / n_b;
           idx += c < n_o ? c : n_o;
         }
-        if (idx < A.item_capacity) A.item_list[idx] = make_rec(b, base + lo, (int)(rr / H), (int)(rr % H), (uint32_t)local);
+        if (idx < A.item_capacity) {
+          A.item_list[2 * idx] = make_rec(b, base + lo, (int)(rr / H), (int)(rr % H), (uint32_t)local);
+          A.item_list[2 * idx + 1] = int4{s_len[lo], 0, 0, 0};
+        }
       }
-      __syncthreads();  // s_incl and s_wave are rewritten by the next round
+      __syncthreads();  // s_incl, s_len and s_wave are rewritten by the next round
       running += round_items;
     }
     part_running += (uint64_t)(running - batch_first) * (uint64_t)B.part_stride;
@@ -149,6 +159,16 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) {
     A.header[kHdrCounter] = 0;
   }
 }
+
+__global__ __launch_bounds__(kPrepThreads) void prep_kernel(MultiArgs A) { prep_body(A, blockIdx.x, gridDim.x); }
+
+// Front kernel of a decode step: the first kPrepGroups workgroups prepare the work list, the others append the
+// step's new K/V rows.  Neither reads what the other writes, so they share one launch.
+__global__ __launch_bounds__(kPrepThreads) void step_front_kernel(MultiArgs A, append::MultiAppendArgs P) {
+  if (blockIdx.x < kPrepGroups) prep_body(A, blockIdx.x, kPrepGroups);
+  else append::append_block(P, blockIdx.x - kPrepGroups, kPrepThreads / 64);
+}
+static_assert(sizeof(MultiArgs) + sizeof(append::MultiAppendArgs) <= 4096, "kernel arguments of the front kernel");
 
 // ---------------------------------------------------------------------------------------
 // Split combine: m = max m_i, l = sum l_i e^(m_i - m), out = sum acc_i e^(m_i - m) / l for the
@@ -268,7 +288,7 @@ __global__ __launch_bounds__(kCombineWaves * 64, MAXNK <= 2 ? 8 : 4) void combin
   const int max_len = (int)min((int64_t)B.max_blocks * B.g.T, (int64_t)0x7fffffff);
   int len = B.seq_lens[seq];
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
-  const int n_chunks = n_splits(B, len);
+  const int n_chunks = n_splits(B, seq, len);
   if (n_chunks <= 1) return;
   const int D = B.g.D, H = B.g.H;
   const int kvh = h / B.G, gq = h % B.G;
@@ -291,6 +311,12 @@ __global__ __launch_bounds__(kCombineWaves * 64, MAXNK <= 2 ? 8 : 4) void combin
 
 hipError_t launch_prep(const MultiArgs& A, hipStream_t s) {
   hipLaunchKernelGGL(prep_kernel, dim3(kPrepGroups), dim3(kPrepThreads), 0, s, A);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_front(const fs_pool* p, const MultiArgs& A, append::MultiAppendArgs& P, hipStream_t s) {
+  const uint32_t append_blocks = plan_append_blocks(p, P, kPrepThreads / 64);
+  hipLaunchKernelGGL(step_front_kernel, dim3(kPrepGroups + append_blocks), dim3(kPrepThreads), 0, s, A, P);
   return hipGetLastError();
 }
 
@@ -317,36 +343,42 @@ struct Plan {
 
 uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 
-// Runs of 8 token slots per work item for a target of split_bytes per item (a multiple of 4, at most ~500 blocks).
+// Runs of 8 token slots per work item for a target of split_bytes per item (a multiple of 4, at most 250 blocks).
 int32_t chunk_runs_for(const fs_geometry_t& g, uint64_t split_bytes) {
   const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
   const int64_t R = (g.tokens_per_block + 7) / 8;
   int64_t cr = (int64_t)(split_bytes / (8 * token_bytes)) / 4 * 4;
-  cr = std::min<int64_t>(cr, 500 * R / 4 * 4);
+  cr = std::min<int64_t>(cr, 250 * R / 4 * 4);  // an item touches at most 256 blocks (the kernel's address table)
   return (int32_t)std::min<int64_t>(std::max<int64_t>(cr, 4), 1 << 17);
 }
 
-// KV bytes per split-K work item of this launch: 192 KiB, less (not below 64 KiB, where the per-item set-up
-// starts to dominate) when the launch is too small to give every wave of the grid about three such items to
-// draw.  Lengths not known on the host count at their upper bound.
+// KV bytes of one head that sequence s of a batch holds (lengths not known on the host count at their upper bound).
+uint64_t head_bytes(const fs_batch_t& b, const fs_geometry_t& g, int s) {
+  const uint64_t ub_len = (uint64_t)b.max_blocks * (uint64_t)g.tokens_per_block;
+  const uint64_t len = b.seq_lens_host ? std::min<uint64_t>((uint64_t)std::max(b.seq_lens_host[s], 1), ub_len) : ub_len;
+  return len * 2 * (g.row_bytes + (uint64_t)g.param_bytes);
+}
+
+// KV bytes per split-K work item of this launch (size tier 0).  A work item costs a few microseconds of set-up
+// whatever its size (measured: about 3 us against 66 us of streaming for 192 KiB), and the launch ends when the
+// last wave finishes its last item, on average 0.4 items after the others.  Large items for most of the launch and
+// small ones at its end serve both: tier 0 is 3/8 of a wave's share of the launch (about two such items per wave
+// before the smaller tiers begin), at most 768 KiB, and the later tiers halve it three times.  With
+// FS_OPT_SPLIT_BYTES set every item has that size (no tiers).
 uint64_t launch_split_bytes(const fs_pool* p, const fs_batch_t* batches, int n_batches) {
-  if (g_split_bytes) return g_split_bytes;
+  if (p && p->opt.split_bytes) return p->opt.split_bytes;
   if (!p || !batches || p->n_cu == 0) return kSplitMax;
   uint64_t total = 0;
   for (int i = 0; i < n_batches; ++i) {
     const fs_batch_t& b = batches[i];
     if (b.model < 0 || b.model >= kMaxModels || !p->models[b.model].in_use || b.n_seq < 1 || b.max_blocks < 1) return kSplitMax;
     const fs_geometry_t& g = p->models[b.model].g;
-    const uint64_t ub_len = (uint64_t)b.max_blocks * (uint64_t)g.tokens_per_block;
-    uint64_t tokens = 0;
-    if (b.seq_lens_host)
-      for (int s = 0; s < b.n_seq; ++s) tokens += std::min<uint64_t>((uint64_t)std::max(b.seq_lens_host[s], 1), ub_len);
-    else
-      tokens = (uint64_t)b.n_seq * ub_len;
-    total += tokens * 2 * (g.row_bytes + (uint64_t)g.param_bytes) * (uint64_t)g.n_kv_heads;
+    uint64_t bytes = 0;
+    for (int s = 0; s < b.n_seq; ++s) bytes += head_bytes(b, g, s);
+    total += bytes * (uint64_t)g.n_kv_heads;
   }
   const uint64_t waves = (uint64_t)p->n_cu * 8;
-  return std::min(kSplitMax, std::max(kSplitMin, total / (3 * waves) / 4096 * 4096));
+  return std::min(kSplitMax, std::max(kSplitMin, total / waves * 3 / 8 / 4096 * 4096));
 }
 
 // Validates the batches and lays the workspace out.  With workspace == nullptr only sizes are computed.
@@ -398,13 +430,32 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.G = b.n_q_heads / g.n_kv_heads;
     B.sm_scale = b.sm_scale;
     const uint64_t token_bytes = 2 * (g.row_bytes + (uint64_t)g.param_bytes);  // K+V of one head
+    const bool tiers = p->opt.split_bytes == 0;
     int64_t ct = (int64_t)(split_bytes / token_bytes) / 32 * 32;
     ct = std::min<int64_t>(ct, (int64_t)500 * g.tokens_per_block / 32 * 32);  // at most ~500 blocks per work item
-    B.chunk_tokens = (int32_t)std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
+    ct = std::min<int64_t>(std::max<int64_t>(ct, 32), 1 << 20);
+    if (tiers && ct >= 256) ct = ct / 256 * 256;  // every tier's size stays a multiple of 32
+    B.chunk_tokens = (int32_t)ct;
     B.R = (g.tokens_per_block + 7) / 8;
     B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);  // unused for R = 1
     B.chunk_runs = chunk_runs_for(g, split_bytes);
+    B.ring_runs = 4 * (g.kv_dtype == FS_KV_FP16 ? 1 : (g.kv_dtype == FS_KV_INT4 ? 3 : 2));
+    // with tiers every tier's size stays a whole number of ring turns; a forced size is rounded to whole tiles only
+    if (tiers) B.chunk_runs = std::max(B.chunk_runs / (8 * B.ring_runs), 1) * 8 * B.ring_runs;
+    else B.ring_runs = 4;
     B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
+    // size tiers: first sequence of tiers 1..3, by the share of the batch's KV bytes that lies in front of it
+    B.tier_seq[0] = B.tier_seq[1] = B.tier_seq[2] = b.n_seq;
+    if (tiers) {
+      uint64_t batch_bytes = 0;
+      for (int s = 0; s < b.n_seq; ++s) batch_bytes += head_bytes(b, g, s);
+      uint64_t before = 0;
+      int t = 0;
+      for (int s = 0; s < b.n_seq && t < 3; ++s) {
+        while (t < 3 && (double)before >= kTierFrom[t] * (double)batch_bytes) B.tier_seq[t++] = s;
+        before += head_bytes(b, g, s);
+      }
+    }
     B.seq_first = (int32_t)seq_total;
     B.part_stride = B.G * (g.head_dim + 2);
     B.qrow_first = (int32_t)qrows;
@@ -413,15 +464,11 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     // upper bound on this batch's work items under either split rule (which kernel runs is decided below)
     uint64_t items_tok = 0, items_run = 0;
     const int64_t ub_len = std::min<int64_t>((int64_t)b.max_blocks * g.tokens_per_block, 0x7fffffff);
-    if (b.seq_lens_host) {
-      for (int s = 0; s < b.n_seq; ++s) {
-        const int64_t len = std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[s], 1), ub_len);
-        items_tok += (uint64_t)((len + B.chunk_tokens - 1) / B.chunk_tokens);
-        items_run += (uint64_t)((n_runs((int)len, g.tokens_per_block, B.R) + B.chunk_runs - 1) / B.chunk_runs);
-      }
-    } else {
-      items_tok = (uint64_t)b.n_seq * (uint64_t)((ub_len + B.chunk_tokens - 1) / B.chunk_tokens);
-      items_run = (uint64_t)b.n_seq * (uint64_t)(((int64_t)b.max_blocks * B.R + B.chunk_runs - 1) / B.chunk_runs);
+    for (int s = 0; s < b.n_seq; ++s) {
+      const int64_t len = b.seq_lens_host ? std::min<int64_t>(std::max<int64_t>(b.seq_lens_host[s], 1), ub_len) : ub_len;
+      const int64_t cts = chunk_tokens_of(B, s), crs = chunk_runs_of(B, s);
+      items_tok += (uint64_t)((len + cts - 1) / cts);
+      items_run += (uint64_t)((n_runs((int)len, g.tokens_per_block, B.R) + crs - 1) / crs);
     }
     const uint64_t items = std::max(items_tok, items_run) * (uint64_t)g.n_kv_heads;
     plan.ub_items += items;
@@ -433,7 +480,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     return FS_ERR_INVALID;
   }
   // the generic kernel splits by tokens, the MFMA kernel by runs
-  plan.use_mfma = plan.all_mfma && g_kernel_mode != 1;
+  plan.use_mfma = plan.all_mfma && p->opt.decode_kernel != 1;
   if (!plan.use_mfma)
     for (int i = 0; i < n_batches; ++i) A.b[i].chunk_runs = 0;
   A.n_seq_total = (int32_t)seq_total;
@@ -441,7 +488,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
   A.part_capacity = part_floats;
   const uint64_t off_items = kHeaderBytes;
   const uint64_t off_list = align256(off_items + 4ull * (uint64_t)(seq_total + 1));
-  const uint64_t off_part = align256(off_list + 16ull * plan.ub_items);
+  const uint64_t off_part = align256(off_list + 32ull * plan.ub_items);
   A.item_capacity = (uint32_t)plan.ub_items;
   plan.workspace_bytes = align256(off_part + 4ull * part_floats);
   if (workspace) {
@@ -463,7 +510,7 @@ namespace {
 // Validates, lays the workspace out and enqueues work-list preparation, attention and split combine on `s`.
 // Allocates nothing.
 int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
-                  const char* too_small, hipStream_t s) {
+                  const char* too_small, hipStream_t s, const fs_append_t* appends = nullptr, int n_appends = 0) {
   Plan plan;
   if (!workspace || ((uintptr_t)workspace & 255)) {
     set_error("decode attention: workspace must be a 256-byte aligned device pointer");
@@ -480,27 +527,29 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
     return FS_ERR_DEVICE;
   }
   const bool use_mfma = plan.use_mfma;
-  if (g_kernel_mode == 2 && !plan.all_mfma) {
+  if (p->opt.decode_kernel == 2 && !plan.all_mfma) {
     set_error("decode attention: MFMA kernel forced but a batch has a shape it does not support");
     return FS_ERR_INVALID;
   }
+  append::MultiAppendArgs P{};
+  for (int i = 0; i < n_appends; ++i) {
+    rc = make_append_args(p, appends[i], P.a[P.n]);
+    if (rc != FS_OK) return rc;
+    if (appends[i].n_tokens > 0) ++P.n;
+  }
   (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
-  hipError_t e = launch_prep(plan.args, s);
+  hipError_t e = P.n ? launch_step_front(p, plan.args, P, s) : launch_prep(plan.args, s);
   if (e != hipSuccess) return device_error(e, "prep launch");
   // Persistent grid: two workgroups (eight waves) per compute unit drain the queue (never more than the
   // upper bound on work items, so tiny batches launch tiny grids).
-  static const int wgs_per_cu = [] {
-    const char* e = getenv("FS_WGS_PER_CU");  // tuning knob for measurements
-    const int v = e ? atoi(e) : 0;
-    return v >= 1 && v <= 8 ? v : 2;
-  }();
+  constexpr int wgs_per_cu = 2;
   // (the MFMA kernel's workers are waves, four to a workgroup; the generic kernel's are workgroups)
   const uint64_t workers_per_wg = use_mfma ? 4 : 1;
   const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,
                                            std::max<uint64_t>((plan.ub_items + workers_per_wg - 1) / workers_per_wg, 1));
-  if (g_timing) (void)hipEventRecord(g_ev0, s);
+  if (p->opt.timing) (void)hipEventRecord(p->opt.ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
-  if (g_timing) (void)hipEventRecord(g_ev1, s);
+  if (p->opt.timing) (void)hipEventRecord(p->opt.ev1, s);
   if (e != hipSuccess) return device_error(e, "attention launch");
   e = launch_combine(plan.args, s);
   if (e != hipSuccess) return device_error(e, "combine launch");
@@ -511,34 +560,72 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
 
 extern "C" {
 
-int fs_set_kernel_mode(int mode) {
-  if (mode < 0 || mode > 2) return FS_ERR_INVALID;
-  g_kernel_mode = mode;
-  return FS_OK;
-}
-
-int fs_set_kernel_timing(int enable) {
-  if (enable && !g_ev0) {
-    hipError_t e = hipEventCreate(&g_ev0);
-    if (e == hipSuccess) e = hipEventCreate(&g_ev1);
-    if (e != hipSuccess) return device_error(e, "hipEventCreate");
+int fs_pool_set_option(fs_pool* p, int option, int64_t value) {
+  if (!p) return FS_ERR_INVALID;
+  Options& o = p->opt;
+  switch (option) {
+    case FS_OPT_DECODE_KERNEL:
+      if (value < 0 || value > 2) break;
+      o.decode_kernel = (int)value;
+      return FS_OK;
+    case FS_OPT_SPLIT_BYTES:
+      if (value != 0 && (value < 4096 || value > (1ll << 30))) break;
+      o.split_bytes = (uint64_t)value;
+      return FS_OK;
+    case FS_OPT_KERNEL_TIMING:
+      if (value && !o.ev0) {
+        hipError_t e = hipEventCreate(&o.ev0);
+        if (e == hipSuccess) e = hipEventCreate(&o.ev1);
+        if (e != hipSuccess) return device_error(e, "hipEventCreate");
+      }
+      o.timing = value != 0;
+      return FS_OK;
+    case FS_OPT_PREFILL_COLUMN_BLOCKS:
+      // (8 once selected a variant with two workgroups per compute unit, which is no longer built)
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 16) break;
+      o.prefill_ncb = (int)value;
+      return FS_OK;
+    case FS_OPT_PREFILL_WAVES:
+      if (value != 0 && value != 4 && value != 8) break;
+      o.prefill_nw = (int)value;
+      return FS_OK;
+    case FS_OPT_PREFILL_PIPELINED:
+      o.prefill_pipe = value != 0;
+      return FS_OK;
+    case FS_OPT_PREFILL_STAGED_DEQUANT:
+      o.prefill_deq = value != 0;
+      return FS_OK;
+    default:
+      break;
   }
-  g_timing = enable != 0;
-  return FS_OK;
+  set_error("fs_pool_set_option: unknown option or value out of range");
+  return FS_ERR_INVALID;
 }
 
-float fs_last_attention_kernel_ms(void) {
-  if (!g_ev0) return -1.0f;
-  if (hipEventSynchronize(g_ev1) != hipSuccess) return -1.0f;
+int fs_pool_get_option(fs_pool* p, int option, int64_t* value) {
+  if (!p || !value) return FS_ERR_INVALID;
+  const Options& o = p->opt;
+  switch (option) {
+    case FS_OPT_DECODE_KERNEL: *value = o.decode_kernel; return FS_OK;
+    case FS_OPT_SPLIT_BYTES: *value = (int64_t)o.split_bytes; return FS_OK;
+    case FS_OPT_KERNEL_TIMING: *value = o.timing; return FS_OK;
+    case FS_OPT_PREFILL_COLUMN_BLOCKS: *value = o.prefill_ncb; return FS_OK;
+    case FS_OPT_PREFILL_WAVES: *value = o.prefill_nw; return FS_OK;
+    case FS_OPT_PREFILL_PIPELINED: *value = o.prefill_pipe; return FS_OK;
+    case FS_OPT_PREFILL_STAGED_DEQUANT: *value = o.prefill_deq; return FS_OK;
+    case FS_OPT_LAST_PREFILL_KERNEL: *value = o.last_prefill; return FS_OK;
+    default: break;
+  }
+  set_error("fs_pool_get_option: unknown option");
+  return FS_ERR_INVALID;
+}
+
+float fs_pool_last_attention_kernel_ms(fs_pool* p) {
+  if (!p || !p->opt.ev0) return -1.0f;
+  if (hipEventSynchronize(p->opt.ev1) != hipSuccess) return -1.0f;
   float ms = -1.0f;
-  if (hipEventElapsedTime(&ms, g_ev0, g_ev1) != hipSuccess) return -1.0f;
+  if (hipEventElapsedTime(&ms, p->opt.ev0, p->opt.ev1) != hipSuccess) return -1.0f;
   return ms;
-}
-
-int fs_set_split_bytes(uint64_t bytes) {
-  if (bytes != 0 && (bytes < 4096 || bytes > (1ull << 30))) return FS_ERR_INVALID;
-  g_split_bytes = bytes;
-  return FS_OK;
 }
 
 uint64_t fs_decode_workspace_bytes(fs_pool* p, const fs_batch_t* batches, int n_batches) {
@@ -551,6 +638,16 @@ int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batch
                               uint64_t workspace_bytes, void* stream) {
   return decode_launch(p, batches, n_batches, workspace, workspace_bytes, "decode attention: workspace too small (see fs_decode_workspace_bytes)",
                        (hipStream_t)stream);
+}
+
+int fs_decode_step_multi(fs_pool* p, const fs_append_t* appends, int n_appends, const fs_batch_t* batches, int n_batches,
+                         void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (n_appends < 0 || n_appends > append::kMaxAppends || (n_appends > 0 && !appends)) {
+    set_error("decode step: need 0..8 appends");
+    return FS_ERR_INVALID;
+  }
+  return decode_launch(p, batches, n_batches, workspace, workspace_bytes,
+                       "decode step: workspace too small (see fs_decode_workspace_bytes)", (hipStream_t)stream, appends, n_appends);
 }
 
 int fs_decode_attention_multi_static(fs_pool* p, const fs_batch_t* batches, int n_batches, uint32_t* status_out,

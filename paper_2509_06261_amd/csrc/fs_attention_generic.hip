@@ -92,9 +92,10 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   int len = B.seq_lens[seq];
   len = len < 1 ? 1 : (len > max_len ? max_len : len);
   if (len_override > 0) len = min(len, len_override);
-  const int n_chunks = len_override > 0 ? 1 : (len + B.chunk_tokens - 1) / B.chunk_tokens;
-  const int t0 = len_override > 0 ? 0 : chunk * B.chunk_tokens;
-  const int t1 = len_override > 0 ? len : min(len, t0 + B.chunk_tokens);
+  const int ct = chunk_tokens_of(B, seq);
+  const int n_chunks = len_override > 0 ? 1 : (len + ct - 1) / ct;
+  const int t0 = len_override > 0 ? 0 : chunk * ct;
+  const int t1 = len_override > 0 ? len : min(len, t0 + ct);
   const int32_t* table = B.tables + (int64_t)seq * B.max_blocks;
   constexpr int kElemBytes8 = Bits<DT>::value;  // bytes of 8 elements
   const float k_static = DT == FS_KV_FP8_E4M3 ? B.k_scale[head] : 1.0f;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void generic_attention_kernel(MultiArgs A
     const uint32_t item = s_item;
     __syncthreads();
     if (item >= total) break;  // every wave of every workgroup reaches this once the queue is empty
-    const int4 rec = A.item_list[item];
+    const int4 rec = A.item_list[2 * item];
     const int b = rec_batch(rec), seq = rec.y, chunk = rec.z, head = rec_head(rec);
     const uint32_t local = (uint32_t)rec.w;  // the item's index within its batch: where its partial record goes
     dispatch_dtype(A, b, seq, chunk, head, local, smem, seq, 0);

@@ -7,17 +7,73 @@
 //   a persistent grid of independent waves: each wave draws work items (sequence, split, KV head) from the
 //   queue, streams the split's 32-token tiles with a private online-softmax state and writes the output (or
 //   the split's partial record) straight from its accumulators.  No wave waits for another.
+//   An item's record carries its sequence's length, so the only look-up between a queue ticket and the item's
+//   first K/V requests is the record, then the block-table entries.
 #include "fs_mfma_tiles.h"
 
 namespace fs {
 namespace {
 
-// One work item, processed by ONE wave: all tiles of the split, then the output (or the split's partial
-// record) straight from the accumulator registers.  Waves never synchronise with each other.
-// s_ptr: this wave's LDS table of head-chunk addresses.
+// What the wave knows about an item before its tiles stream (all wave-uniform): the record's fields, the runs
+// [v0, v1) it covers and the blocks k0 .. k0 + nb - 1 they lie in.
+struct ItemPlan {
+  int b, seq, chunk, head, len;
+  uint32_t local;  // the item's index within its batch: where its partial record goes
+  int v0, v1, k0, nb;
+};
+
+// rec: lane l < 8 holds dword l of the item's record (see make_rec).
+__device__ __forceinline__ ItemPlan plan_item(const MultiArgs& A, uint32_t rec) {
+  ItemPlan P;
+  const int x = (int)__builtin_amdgcn_readlane(rec, 0);
+  P.b = x & 15;
+  P.head = x >> 4;
+  P.seq = (int)__builtin_amdgcn_readlane(rec, 1);
+  P.chunk = (int)__builtin_amdgcn_readlane(rec, 2);
+  P.local = __builtin_amdgcn_readlane(rec, 3);
+  P.len = (int)__builtin_amdgcn_readlane(rec, 4);
+  const DevBatch& B = A.b[P.b];
+  const int cr = chunk_runs_of(B, P.seq);
+  P.v0 = P.chunk * cr;
+  P.v1 = min(n_runs(P.len, B.g.T, B.R), P.v0 + cr);
+  P.k0 = div_runs(P.v0, B.R, B.r_magic);
+  P.nb = div_runs(P.v1 - 1, B.R, B.r_magic) - P.k0 + 1;
+  return P;
+}
+
+constexpr int kTabRegs = 4;  // an item touches at most 64 * kTabRegs blocks (the host caps the item size accordingly)
+
+// The item's block-table entries: entry i goes to register i / 64 of lane i % 64.
+__device__ __forceinline__ void load_entries(const MultiArgs& A, const ItemPlan& P, int lane, int32_t (&tab)[kTabRegs]) {
+  const DevBatch& B = A.b[P.b];
+  const int32_t* t = B.tables + (int64_t)P.seq * B.max_blocks + P.k0;
+#pragma unroll
+  for (int q = 0; q < kTabRegs; ++q) tab[q] = lane + 64 * q < P.nb ? t[lane + 64 * q] : 0;
+}
+
+// Head-chunk addresses of the item's blocks into this wave's LDS table (see fill_table).
+__device__ __forceinline__ void store_table(const MultiArgs& A, const ItemPlan& P, int lane, const int32_t (&tab)[kTabRegs],
+                                            uint64_t* s_ptr) {
+  const DevBatch& B = A.b[P.b];
+  const uint8_t* head_base = B.layer_base + (uint64_t)P.head * B.g.head_chunk;
+#pragma unroll
+  for (int q = 0; q < kTabRegs; ++q)
+    if (lane + 64 * q < P.nb)
+      s_ptr[lane + 64 * q] = reinterpret_cast<uint64_t>(head_base + (uint64_t)checked_block(tab[q], B.n_blocks, A.header) * B.g.block_budget);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// One work item is processed by ONE wave in two steps: stream_item runs all tiles of the split through the wave's
+// private online-softmax state; finish_item writes the output (or the split's partial record) straight from the
+// accumulator registers.  Waves never synchronise with each other.  (Two steps, so that the tile loops of the
+// eight format / group variants do not carry the output code's registers; the state has the same shape for all.)
+// s_ptr: this wave's LDS table of head-chunk addresses, already holding the item's blocks.
 template <int DT, int GP>
-__device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int head, uint32_t item, uint64_t* s_ptr) {  // item: index within the batch
-  const DevBatch& B = A.b[b];
+__device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st) {
+  const int seq = P.seq, head = P.head;
+  const DevBatch& B = A.b[P.b];
   const DevGeom& g = B.g;
   // The lane index is made opaque per item: otherwise the compiler hoists every variant's lane-dependent
   // constants out of the kernel's item loop, where they stay live across all other variants and push the
@@ -26,31 +82,16 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   asm volatile("" : "+v"(lane));
   const int j = lane >> 4, c = lane & 15;
   const int G = B.G;
-  const int max_len = (int)min((int64_t)B.max_blocks * g.T, (int64_t)0x7fffffff);
-  int len = B.seq_lens[seq];
-  len = len < 1 ? 1 : (len > max_len ? max_len : len);
-  const int n_chunks = n_splits(B, len);
-  const int v0 = chunk * B.chunk_runs;
-  const int v1 = min(n_runs(len, g.T, B.R), v0 + B.chunk_runs);
-
-  const uint64_t* part_off = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff);
-  const uint64_t part_base = part_off[b] + (uint64_t)item * (uint64_t)B.part_stride;  // item: index within the batch
-  if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {  // wave-uniform
-    if (lane == 0) atomicOr(A.header + kHdrStatus, 2u);
-    return;
-  }
 
   ItemCtx X;
   X.T = g.T;
   X.R = B.R;
   X.r_magic = B.r_magic;
-  X.len = len;
-  X.len_u = len;
-  X.v_end = v1;
-  X.k0 = div_runs(v0, B.R, B.r_magic);
+  X.len = P.len;
+  X.len_u = P.len;
+  X.v_end = P.v1;
+  X.k0 = P.k0;
   X.chunk_ptr = s_ptr;
-  fill_table(s_ptr, B.tables + (int64_t)seq * B.max_blocks, B.layer_base + (uint64_t)head * g.head_chunk, g.block_budget, X.k0,
-             div_runs(v1 - 1, B.R, B.r_magic) - X.k0 + 1, lane, B.n_blocks, A.header);
 
   // Q operand and per-head constants
   u32x4 qb[4];
@@ -64,14 +105,32 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   float alpha = B.sm_scale * kLog2e;
   if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
 
-  State st;
 #pragma unroll
   for (int e = 0; e < 8; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = -INFINITY;
   st.l = 0.f;
   st.zc = 0.f;
 
-  stream_tiles<DT, GP>(X, g, v0, qb, qsum, alpha, st, j, c);
+  stream_tiles<DT, GP>(X, g, P.v0, qb, qsum, alpha, st, j, c);
+}
+
+// part_off: the batches' offsets into the partial buffer (the workspace header's words, copied to LDS once per
+// workgroup: read from memory here they would be one more round trip in front of every item's stores).
+template <int DT, int GP>
+__device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& P, State& st, const uint64_t* part_off) {
+  const int b = P.b, seq = P.seq, head = P.head;
+  const DevBatch& B = A.b[b];
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  const int j = lane >> 4, c = lane & 15;
+  const int G = B.G;
+  const int n_chunks = n_splits(B, seq, P.len);
+  const uint64_t part_base = part_off[b] + (uint64_t)P.local * (uint64_t)B.part_stride;  // local: index within the batch
+  if (n_chunks > 1 && part_base + (uint64_t)B.part_stride > A.part_capacity) {  // wave-uniform
+    // the workspace was sized for shorter sequences: reported, the item's record is not written
+    if (lane == 0) atomicOr(A.header + kHdrStatus, 2u);
+    return;
+  }
 
   // ---- output: per-head sums over the lanes of the head, then rows h < G straight from the accumulators ----
   if constexpr (GP == 4) {
@@ -116,8 +175,9 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
         if (c == 0 && B.lse) B.lse[(int64_t)seq * B.n_q + qh] = (M + __builtin_amdgcn_logf(L)) * kLn2;
       } else {
         float* pr = A.partials + part_base + (uint64_t)h * (kD + 2);
+        // (a row starts at a multiple of 8 bytes: part_stride and kD + 2 are even)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pr[8 * c + e] = o[e];
+        for (int e = 0; e < 8; e += 2) *reinterpret_cast<float2*>(pr + 8 * c + e) = float2{o[e], o[e + 1]};
         if (c == 0) {
           pr[kD] = M * kLn2;  // partial records keep the reference in natural-log units
           pr[kD + 1] = L;
@@ -127,23 +187,28 @@ __device__ void process_item(const MultiArgs& A, int b, int seq, int chunk, int 
   }
 }
 
-template <int GP>
-__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, int b, int4 rec, uint64_t* s_ptr) {
-  const int head = rec_head(rec);
-  const uint32_t local = (uint32_t)rec.w;  // the item's index within its batch: where its partial record goes
-  switch (A.b[b].g.dtype) {
-    case FS_KV_FP16: process_item<FS_KV_FP16, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
-    case FS_KV_FP8_E4M3: process_item<FS_KV_FP8_E4M3, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
-    case FS_KV_INT8: process_item<FS_KV_INT8, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
-    default: process_item<FS_KV_INT4, GP>(A, b, rec.y, rec.z, head, local, s_ptr); break;
+// step 0: stream_item, step 1: finish_item
+template <int STEP, int GP>
+__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st,
+                                               const uint64_t* part_off) {
+  switch (A.b[P.b].g.dtype) {
+#define FS_STEP(DT)                                          \
+  if constexpr (STEP == 0) stream_item<DT, GP>(A, P, s_ptr, st); \
+  else finish_item<DT, GP>(A, P, st, part_off);              \
+  break
+    case FS_KV_FP16: FS_STEP(FS_KV_FP16);
+    case FS_KV_FP8_E4M3: FS_STEP(FS_KV_FP8_E4M3);
+    case FS_KV_INT8: FS_STEP(FS_KV_INT8);
+    default: FS_STEP(FS_KV_INT4);
+#undef FS_STEP
   }
 }
 
-__device__ __forceinline__ void dispatch_item(const MultiArgs& A, uint32_t item, uint64_t* s_ptr) {
-  const int4 rec = A.item_list[item];
-  const int b = rec_batch(rec);
-  if (A.b[b].G <= 4) dispatch_dtype<4>(A, b, rec, s_ptr);
-  else dispatch_dtype<16>(A, b, rec, s_ptr);
+template <int STEP>
+__device__ __forceinline__ void dispatch_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st,
+                                              const uint64_t* part_off) {
+  if (A.b[P.b].G <= 4) dispatch_dtype<STEP, 4>(A, P, s_ptr, st, part_off);
+  else dispatch_dtype<STEP, 16>(A, P, s_ptr, st, part_off);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A, int table_entries) {
@@ -151,6 +216,9 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint64_t* s_ptr = smem64 + (size_t)wave * table_entries;
+  __shared__ uint64_t s_part_off[kMaxBatches];
+  if (threadIdx.x < kMaxBatches) s_part_off[threadIdx.x] = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff)[threadIdx.x];
+  __syncthreads();
   const uint32_t total = A.header[kHdrTotalItems];
   // Every wave is its own worker and draws its items from kPools ticket counters: pool p holds the items
   // p, p + kPools, ... of the queue.  Waves that get short items, or sit on a faster compute unit, simply
@@ -158,23 +226,49 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A
   // measured to finish a quarter later than the median one.  One counter for all items is no option: an
   // address serves an atomic every ~11 ns when idle and several times slower under streaming load, which
   // was measured to bound the kernel; kPools counters with about a thousand draws each do not.
-  // A wave empties its home pool first, so every pool is emptied by its home waves whatever the others do;
-  // after that it tries a few more pools and leaves.  The next ticket is drawn before the current item is
-  // processed, so the atomic's latency is not waited for between items.
+  // A wave empties its home pool first.  After that it looks at all counters at once (lane p reads pool p's),
+  // moves to the next pool that still holds items and goes on; it leaves only when every pool is past its last
+  // item, so the launch ends within one of the queue's last (smallest) items whatever the pools' loads were.
+  // The next ticket is drawn before the current item is processed, so the atomic's latency is not waited for
+  // between items.
+  static_assert(kPools == 64, "one pool per lane in the look at all counters");
   const uint32_t worker = blockIdx.x * kWaves + wave;
   uint32_t pool = worker % kPools;
   uint32_t ticket = 0;
-  if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
-  for (int empty = 0;;) {
-    uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    while (item >= total && ++empty < 4) {  // this pool is empty: try another
-      pool = (pool + 17) % kPools;
-      if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
-      item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
-    }
-    if (item >= total) break;  // every wave leaves here after at most four empty pools
+  constexpr uint32_t kNone = 0xffffffffu;
+  auto draw = [&]() {
     if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
-    dispatch_item(A, item, s_ptr);
+  };
+  // the item the drawn ticket stands for, or kNone once every pool is empty (then no ticket is outstanding)
+  auto resolve = [&]() -> uint32_t {
+    for (;;) {
+      const uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+      if (item < total) return item;
+      // this pool is empty: which ones are not?  (the counters only grow)
+      const uint32_t cnt = __hip_atomic_load(A.header + kHdrPools + lane * kPoolStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint64_t left = __ballot((uint64_t)lane + (uint64_t)kPools * cnt < total);  // wave-uniform
+      if (left == 0) return kNone;  // every pass finds fewer items left or takes one
+      const uint32_t r = (pool + 1) % kPools;  // the first such pool after the current one, cyclically
+      const uint64_t rot = r ? (left >> r) | (left << (kPools - r)) : left;
+      pool = (r + (uint32_t)__builtin_ctzll(rot)) % kPools;
+      draw();
+    }
+  };
+  auto load_rec = [&](uint32_t item) -> uint32_t {
+    return lane < 8 ? reinterpret_cast<const uint32_t*>(A.item_list + 2 * (size_t)item)[lane] : 0u;
+  };
+  draw();
+  for (;;) {
+    const uint32_t item = resolve();
+    if (item == kNone) break;  // every wave leaves here, once all pools are empty
+    draw();                    // the next ticket, answered while this item streams
+    const ItemPlan P = plan_item(A, load_rec(item));
+    int32_t tab[kTabRegs];
+    load_entries(A, P, lane, tab);
+    store_table(A, P, lane, tab, s_ptr);
+    State st;
+    dispatch_item<0>(A, P, s_ptr, st, s_part_off);
+    dispatch_item<1>(A, P, s_ptr, st, s_part_off);
   }
 }
 

@@ -28,7 +28,23 @@ struct Model {
 
 }  // namespace fs
 
+namespace fs {
+// Per-pool settings (fs_pool_set_option): kernel selection and measurement aids.  Nothing here is process-global.
+struct Options {
+  int decode_kernel = 0;        // FS_OPT_DECODE_KERNEL
+  uint64_t split_bytes = 0;     // FS_OPT_SPLIT_BYTES (0: chosen per launch)
+  bool timing = false;          // FS_OPT_KERNEL_TIMING
+  int prefill_ncb = 0;          // FS_OPT_PREFILL_COLUMN_BLOCKS
+  int prefill_nw = 0;           // FS_OPT_PREFILL_WAVES
+  bool prefill_pipe = false;    // FS_OPT_PREFILL_PIPELINED
+  bool prefill_deq = true;      // FS_OPT_PREFILL_STAGED_DEQUANT
+  int64_t last_prefill = 0;     // FS_OPT_LAST_PREFILL_KERNEL (read-only)
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the latest timed attention kernel
+};
+}  // namespace fs
+
 struct fs_pool {
+  fs::Options opt;
   uint64_t slab_bytes = 0, pool_bytes = 0;
   int64_t n_slabs = 0;
   uint8_t* base = nullptr;  // device

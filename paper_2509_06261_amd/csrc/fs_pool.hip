@@ -121,6 +121,8 @@ int fs_pool_destroy(fs_pool* p) {
     if (m.d_v_scale) (void)hipFree(m.d_v_scale);
   }
   if (p->owns_base) (void)hipFree(p->base);
+  if (p->opt.ev0) (void)hipEventDestroy(p->opt.ev0);
+  if (p->opt.ev1) (void)hipEventDestroy(p->opt.ev1);
   delete p;
   return FS_OK;
 }
@@ -343,6 +345,26 @@ int fs_pool_stats(fs_pool* p, fs_pool_stats_t* out) {
     s.live_blocks += m.live_blocks;
     s.stranded_bytes += (uint64_t)m.live_blocks * (m.g.block_budget - m.g.block_bytes);
   }
+  *out = s;
+  return FS_OK;
+}
+
+int fs_model_stats(fs_pool* p, fs_model_t model, fs_model_stats_t* out) {
+  if (!p || !out || model < 0 || model >= kMaxModels || !p->models[model].in_use) {
+    set_error("fs_model_stats: unknown pool or model");
+    return FS_ERR_INVALID;
+  }
+  const Model& M = p->models[model];
+  fs_model_stats_t s{};
+  for (int64_t i = 0; i < p->n_slabs; ++i) {
+    if (p->key[i] != model) continue;
+    if (p->state[i] == FS_SLAB_PARTIAL) ++s.slabs_partial;
+    else if (p->state[i] == FS_SLAB_FULL) ++s.slabs_full;
+    s.free_blocks_in_partial_slabs += M.g.blocks_per_slab - p->used[i];
+  }
+  s.live_blocks = M.live_blocks;
+  s.live_bytes = (uint64_t)M.live_blocks * M.g.block_budget;
+  s.stranded_bytes = (uint64_t)M.live_blocks * (M.g.block_budget - M.g.block_bytes);
   *out = s;
   return FS_OK;
 }

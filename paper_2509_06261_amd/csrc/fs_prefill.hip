@@ -936,8 +936,9 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
 // and stages K and V of sub-tile w; with NW == 2 SUBS waves 0..SUBS-1 stage the K fragments of sub-tile w and the
 // others the V fragments and parameters of sub-tile w - SUBS.  Built variants: 8 waves x 2 blocks, 4 sub-tiles per
 // step, one workgroup per compute unit (two waves per SIMD, so that one's softmax runs under the other's MFMAs);
-// 4 x 4, 4 sub-tiles (one wave per SIMD); 4 x 2 with 2 sub-tiles per step, whose stages are small enough for TWO
-// workgroups per compute unit: the two waves of a SIMD then belong to different items and do not march in step.
+// 4 x 4, 4 sub-tiles (one wave per SIMD).  (A third one -- 4 x 2 with 2 sub-tiles per step, two workgroups per
+// compute unit -- passed its small cases but ended a full-size two-model run with the GPU faulted or hung; the
+// cause was not found and the variant is no longer built.)
 // smem: two stages, then the workgroup's block-address table.
 // DEQ (INT8 / INT4 only): the staging waves dequantize, the tile code is the FP16 one.
 template <int DT, int NW, int NCB, int SUBS, bool DEQ = false>
@@ -1445,7 +1446,7 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
   for (;;) {
     if (wave == 0) {  // one wave draws for the workgroup
       uint32_t item;
-      const bool ok = next_item(d, P.header, total, (uint32_t)P.chunk_shift + (WPC == 2 ? 1 : 0), lane, item);
+      const bool ok = next_item(d, P.header, total, (uint32_t)P.chunk_shift, lane, item);
       if (lane == 0) s_ctl[0] = ok ? item : 0xffffffffu;
     }
     __syncthreads();
@@ -1487,31 +1488,6 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 
 using namespace fs;
 
-namespace {
-int g_prefill_ncb = 0, g_prefill_nw = 0, g_prefill_pipe = 0, g_prefill_deq = 1;
-}
-
-int fs_set_prefill_kernel(int column_blocks, int waves) {
-  const bool ok_c = column_blocks == 0 || column_blocks == 1 || column_blocks == 2 || column_blocks == 4 || column_blocks == 16;
-  // column_blocks == 8 (two workgroups of 4 waves x 32 columns per compute unit, 64-token steps) is switched off:
-  // small cases pass, but a run over the two-model 128 GiB workload ended with the GPU faulted or hung and the cause
-  // has not been found; the variant stays unreachable until it has.
-  if (!ok_c || (waves != 0 && waves != 4 && waves != 8)) return FS_ERR_INVALID;
-  g_prefill_ncb = column_blocks;
-  g_prefill_nw = waves;
-  return FS_OK;
-}
-
-int fs_set_prefill_pipelined(int enable) {
-  g_prefill_pipe = enable != 0;
-  return FS_OK;
-}
-
-int fs_set_prefill_staged_dequant(int enable) {
-  g_prefill_deq = enable != 0;  // (a negative value: the default, on)
-  return FS_OK;
-}
-
 uint64_t fs_prefill_workspace_bytes(int n_seq) {
   if (n_seq < 1) return 0;
   return align256(kHeaderBytes + 4ull * ((uint64_t)n_seq + 1));
@@ -1546,7 +1522,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     return FS_ERR_INVALID;
   }
   const int tpt = 16 / G;
-  const int ncb_env = g_prefill_ncb;  // fs_set_prefill_kernel
+  const int ncb_env = p->opt.prefill_ncb;  // FS_OPT_PREFILL_COLUMN_BLOCKS
   // Default: the workgroup kernel (measured fastest for every format once a launch has a work item per
   // compute unit); the 16-column wave-level kernel, whose items are sixteen times finer, for smaller launches.
   const int ncb_default = 16;
@@ -1566,7 +1542,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
       tiles += (uint64_t)((n_new + tpt * ncb - 1) / (tpt * ncb));
     }
     // a launch with fewer workgroup-level items than compute units: the finest items instead
-    if (pass == 0 && ncb >= 8 && !ncb_env && tiles * (uint64_t)g.n_kv_heads < (uint64_t)p->n_cu) ncb = 1;
+    if (pass == 0 && ncb == 16 && !ncb_env && tiles * (uint64_t)g.n_kv_heads < (uint64_t)p->n_cu) ncb = 1;
     else break;
   }
   const int64_t n_rows = q_offsets_host[n_seq];
@@ -1605,6 +1581,8 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.R = (g.tokens_per_block + 7) / 8;
   B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);
   B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
+  B.tier_seq[0] = B.tier_seq[1] = B.tier_seq[2] = 0x7fffffff;  // (decode's split sizes: not used by prefill)
+  B.ring_runs = 4;
   const bool generic = !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
   if (generic && (g.head_dim & (g.head_dim - 1))) {
     set_error("prefill attention: head_dim must be a power of two");
@@ -1632,6 +1610,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     A.header = P.header;
     A.n_batches = 1;
     const uint64_t work = (uint64_t)n_rows * (uint64_t)g.n_kv_heads;
+    p->opt.last_prefill = 1 << 18;
     e = launch_generic_prefill(A, q_offsets, (int)n_rows, (int)std::min<uint64_t>(work, (uint64_t)p->n_cu * 8), s);
     if (e != hipSuccess) return device_error(e, "prefill launch (generic kernel)");
     return FS_OK;
@@ -1639,11 +1618,10 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
   // waves per SIMD: the 16-column kernel runs two, the wider wave-level ones one
   const int wps = ncb == 1 ? 2 : 1;
-  // workgroup kernels: 16 blocks = 8 waves x 2 (default) or 4 x 4, 4 sub-tiles per step, one workgroup per compute
-  // unit; 8 blocks = 4 waves x 2, 2 sub-tiles per step, two workgroups per compute unit
-  const bool wg = ncb >= 8;
-  const int nw = ncb == 8 ? 4 : (g_prefill_nw == 4 ? 4 : 8);
-  const int subs = ncb == 8 ? 2 : 4, wpc = ncb == 8 ? 2 : 1;
+  // workgroup kernels: 16 blocks = 8 waves x 2 (default) or 4 x 4, 4 sub-tiles per step, one workgroup per compute unit
+  const bool wg = ncb == 16;
+  const int nw = p->opt.prefill_nw == 4 ? 4 : 8;
+  const int subs = 4, wpc = 1;
   const int n_wg = wg ? (int)std::min<uint64_t>((uint64_t)p->n_cu * wpc, std::max<uint64_t>(items, 1))
                       : (int)std::min<uint64_t>((uint64_t)p->n_cu * wps, std::max<uint64_t>((items + kWaves - 1) / kWaves, 1));
   // Consecutive items -- the query tiles of one (sequence, head), which stream the same K/V -- go to one XCD in
@@ -1658,11 +1636,10 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
                          : (size_t)kWaves * P.table_entries * sizeof(uint64_t);
   if (wg) {
     void (*kern)(PrefillArgs) = nullptr;
-#define FS_WG(DT)                                                                                          \
-  (ncb == 8 ? prefill_wg_kernel<DT, 4, 2, 2, 2>                                                            \
-            : (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1>                                                 \
-                       : (g_prefill_pipe ? prefill_wg_kernel<DT, 4, 4, 4, 1, true> : prefill_wg_kernel<DT, 4, 4, 4, 1>)))
-    const bool deq = g_prefill_deq && ncb == 16 && nw == 8;  // (the 8-wave kernel only)
+#define FS_WG(DT)                                  \
+  (nw == 8 ? prefill_wg_kernel<DT, 8, 2, 4, 1> \
+           : (p->opt.prefill_pipe ? prefill_wg_kernel<DT, 4, 4, 4, 1, true> : prefill_wg_kernel<DT, 4, 4, 4, 1>))
+    const bool deq = p->opt.prefill_deq && nw == 8;  // (the 8-wave kernel only)
     switch (g.kv_dtype) {
       case FS_KV_FP16: kern = FS_WG(FS_KV_FP16); break;
       case FS_KV_FP8_E4M3: kern = FS_WG(FS_KV_FP8_E4M3); break;
@@ -1673,8 +1650,11 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     // more than 64 KiB of dynamic LDS has to be granted per kernel
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return device_error(e, "prefill LDS attribute");
+    const bool deq_used = deq && (g.kv_dtype == FS_KV_INT8 || g.kv_dtype == FS_KV_INT4);
+    p->opt.last_prefill = 16 | (nw << 8) | ((int64_t)deq_used << 16) | ((int64_t)(nw == 4 && p->opt.prefill_pipe) << 17);
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(nw * 64), smem, s, P);
   } else if (ncb == 1) {
+    p->opt.last_prefill = 1;
     hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
   } else {
     void (*kern)(PrefillArgs) = nullptr;
@@ -1686,6 +1666,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
       default: kern = FS_WIDE(FS_KV_INT4); break;
     }
 #undef FS_WIDE
+    p->opt.last_prefill = ncb;
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), smem, s, P);
   }
   e = hipGetLastError();

@@ -16,19 +16,14 @@ TOL_QUANT = 4e-3  # max-abs, FP8 / INT8 / INT4 KV
 TOL_LSE = 1e-3
 
 
-# Whether the library's INT8 / INT4 prefill kernels leave dequantized fp16 operands in LDS (its default for the
-# 8-wave workgroup kernel); the prefill tests that switch it off set this to False.
-STAGED_DEQUANT = True
-
-
-def prefill_lse_tolerance(sm_scale, head_dim, kv_dtype):
+def prefill_lse_tolerance(sm_scale, head_dim, staged_dequant):
     """lse = log sum exp(logits) moves by at most the largest logit error.  FP16 and FP8 keys reach the matrix cores
     exactly, and so do INT8 / INT4 codes on the exact-code path: the decode bound TOL_LSE holds.  With staged
     dequantization the INT8 / INT4 keys are rounded to fp16 (relative 2^-12 per element): a logit moves by at most
     |scale| 2^-12 sum_d |q_d k_d|, about |scale| 2^-12 * 0.64 * head_dim for unit-normal q and k, i.e. 1.8e-3 at
     scale 1/sqrt(128) if every element's error had the same sign (observed: up to 9.3e-4).  Hence 2e-3 at the usual
     scale, growing with |scale| sqrt(head_dim) beyond it -- for that path only."""
-    if STAGED_DEQUANT and kv_dtype in (workloads.INT8, workloads.INT4):
+    if staged_dequant:  # (FS_OPT_LAST_PREFILL_KERNEL bit 16: the launch really took that path)
         return 2e-3 * max(1.0, abs(float(sm_scale)) * float(np.sqrt(head_dim)))
     return TOL_LSE
 
@@ -58,7 +53,7 @@ class LockstepAdapter:
 class Parity:
     def __init__(self, wl: workloads.Workload, zero_pool=False):
         import paper_2509_06261_amd as fs
-        from paper_2509_06261_amd import harness
+        import gpu_workload as harness
 
         self.fs = fs
         self.wl = wl
@@ -78,6 +73,10 @@ class Parity:
 
     def close(self):
         self.gw.close()
+
+    def last_prefill_staged(self):
+        """Whether the pool's latest prefill launch dequantized INT8 / INT4 operands while staging them."""
+        return bool(self.fs.fs_pool_get_option(self.gw.pool, self.fs.FS_OPT_LAST_PREFILL_KERNEL) >> 16 & 1)
 
     def check_allocator_state(self):
         ost, ok, ou, ofs = self.opool.dump()
@@ -174,7 +173,7 @@ class Parity:
         err = float(np.max(diff))
         lerr = float(np.max(np.abs(lse[rows].astype(np.float64) - o_lse))) if len(rows) else 0.0
         assert np.all(diff <= allowed), f"prefill model {k} ({s.name}): max abs error {err:.3e}, tolerance {tol} + |ref| 2^-11"
-        tol_lse = prefill_lse_tolerance(scale, s.head_dim, s.kv_dtype)
+        tol_lse = prefill_lse_tolerance(scale, s.head_dim, self.last_prefill_staged())
         assert lerr <= tol_lse, f"prefill model {k} ({s.name}): lse error {lerr:.3e} > {tol_lse:.1e}"
         print(f"prefill model {k} ({s.name}) scale {scale:.4f}: max abs err {err:.2e}, lse err {lerr:.2e}")
         return err, len(rows)
@@ -246,7 +245,7 @@ class Parity:
         assert np.all(diff <= tol + np.abs(o_out) * 2.0 ** -11), \
             f"prefill model {k} ({s.name}): max abs error {err:.3e}, tolerance {tol} + |ref| 2^-11"
         lerr = float(np.max(np.abs(lse - o_lse)))
-        tol_lse = prefill_lse_tolerance(scale, s.head_dim, s.kv_dtype)
+        tol_lse = prefill_lse_tolerance(scale, s.head_dim, self.last_prefill_staged())
         assert lerr <= tol_lse, f"prefill model {k} ({s.name}): lse error {lerr:.3e} > {tol_lse:.1e}"
         return err, len(rows)
 
@@ -299,7 +298,7 @@ class Parity:
         import torch
 
         gw = self.gw
-        self.fs.fs_set_kernel_mode(kernel_mode)
+        gw.set_option(self.fs.FS_OPT_DECODE_KERNEL, kernel_mode)
         try:
             gw.populate([[l] for l in layers])
             batches, keep = gw.make_batches(layers, sm_scale=sm_scale)
@@ -308,7 +307,7 @@ class Parity:
             status = self.fs.fs_decode_status(ws)
             assert status == 0, f"decode status {status}"
         finally:
-            self.fs.fs_set_kernel_mode(0)
+            gw.set_option(self.fs.FS_OPT_DECODE_KERNEL, 0)
         return keep
 
     def check_model(self, k, layers, keep, n_random=None, with_bytes=True, sm_scale=None):

@@ -1,6 +1,7 @@
-"""Driver that stands a synthetic workload up on the GPU through the C ABI.
+"""Driver that stands a synthetic workload up on the GPU through the C ABI (test and benchmark plumbing, no part
+of the library).
 
-Used by the GPU tests, ``__graft_entry__.smoke()`` and ``bench.py``: it creates the pool,
+Used by the GPU tests, ``__graft_entry__.smoke()`` and the ``bench*.py`` programs: it creates the pool,
 registers the models, replays the workload's allocation recipe against ``fs_block_alloc`` /
 ``fs_block_free``, fills the KV cache with ``fs_kv_append`` from the device-side input generator,
 and issues ``fs_decode_attention_multi``.  Argument plumbing only -- every step of the path runs in
@@ -14,7 +15,11 @@ import torch
 from fs_inputs import device as gen_device
 from fs_inputs import gen, workloads
 
-from . import binding as fs
+from paper_2509_06261_amd import binding as fs
+
+# Pool options (fs_pool_set_option) applied to every workload stood up from here on: {option: value}.  The prefill
+# tests select their kernel variant this way before the pool exists.
+DEFAULT_OPTIONS = {}
 
 
 class AllocAdapter:
@@ -31,13 +36,15 @@ class AllocAdapter:
 
 
 class GpuWorkload:
-    def __init__(self, wl: workloads.Workload, device="cuda:0", zero_pool=False):
+    def __init__(self, wl: workloads.Workload, device="cuda:0", zero_pool=False, options=None):
         self.wl = wl
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         alloc = torch.zeros if zero_pool else torch.empty
         self.pool_mem = alloc(wl.pool_bytes, dtype=torch.uint8, device=self.device)
         self.pool = fs.fs_pool_create(wl.slab_bytes, wl.pool_bytes, self.pool_mem)
+        for opt, value in {**DEFAULT_OPTIONS, **(options or {})}.items():
+            self.set_option(opt, value)
         self.model_ids, self.T, self.geom, self.scales = [], {}, {}, {}
         for s in wl.models:
             if s.tokens_per_block:
@@ -56,6 +63,11 @@ class GpuWorkload:
         self.lens = [np.array(s.lens, dtype=np.int32) for s in wl.models]
         self.tables_host, self.tables, self.seq_lens = [], [], []
         self._ws = None
+
+    def set_option(self, option, value):
+        rc = fs.fs_pool_set_option(self.pool, option, value)
+        if rc != fs.FS_OK:
+            raise fs.FsError(rc, f"fs_pool_set_option({option}, {value})")
 
     def close(self):
         if self.pool is not None:
@@ -81,9 +93,9 @@ class GpuWorkload:
         return blocks
 
     # ------------------------------------------------------------------ KV fill
-    def populate(self, layers_of_model=None, chunk_tokens=1 << 17, seq_subset=None):
+    def populate(self, layers_of_model=None, chunk_tokens=1 << 17, seq_subset=None, hold_back_newest=False):
         """Append every token of every sequence (or of ``seq_subset[k]``) for the given layers
-        (default: all layers) from the device-side generator."""
+        (default: all layers) from the device-side generator; with hold_back_newest all but each sequence's last."""
         for k, (s, m) in enumerate(zip(self.wl.models, self.model_ids)):
             layers = range(s.n_layers) if layers_of_model is None else layers_of_model[k]
             lens = self.lens[k]
@@ -92,6 +104,9 @@ class GpuWorkload:
                 keep[np.asarray(seq_subset[k], dtype=np.int64)] = True
                 lens = np.where(keep, lens, 0)
             seq_idx, pos = workloads.token_index(lens)
+            if hold_back_newest:
+                older = pos < (np.asarray(self.lens[k])[seq_idx] - 1)
+                seq_idx, pos = seq_idx[older], pos[older]
             n = len(pos)
             dt = torch.float32 if s.src_f32 else torch.float16
             for c0 in range(0, n, chunk_tokens):
@@ -105,6 +120,24 @@ class GpuWorkload:
                     gen_device.fill_rows(vb, self.wl.seed, s.tag, layer, gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
                     fs.fs_kv_append(self.pool, m, layer, kb, vb, si, po, self.tables[k])
             torch.cuda.synchronize(self.device)
+
+    def newest_token_appends(self, layers, models=None):
+        """One fs_append_t per model: the newest token (position n_b - 1) of every sequence at ``layers[k]``, its rows
+        drawn from the device-side generator.  Returns (appends, keepalive list)."""
+        appends, keep = [], []
+        for k, (s, m) in enumerate(zip(self.wl.models, self.model_ids)):
+            if models is not None and k not in models:
+                continue
+            si = torch.arange(s.n_seq, dtype=torch.int32, device=self.device)
+            po = (self.seq_lens[k] - 1).to(torch.int32)
+            dt = torch.float32 if s.src_f32 else torch.float16
+            kb = torch.empty((s.n_seq, s.n_kv_heads, s.head_dim), dtype=dt, device=self.device)
+            vb = torch.empty_like(kb)
+            gen_device.fill_rows(kb, self.wl.seed, s.tag, layers[k], gen.WHICH_K, si, po, s.n_kv_heads, s.head_dim)
+            gen_device.fill_rows(vb, self.wl.seed, s.tag, layers[k], gen.WHICH_V, si, po, s.n_kv_heads, s.head_dim)
+            appends.append(fs.make_append(m, layers[k], kb, vb, si, po, self.tables[k]))
+            keep.append((si, po, kb, vb))
+        return appends, keep
 
     # ------------------------------------------------------------------ decode
     def make_q(self, k, layer):

@@ -73,11 +73,11 @@ def test_every_sequence_mfma_against_generic_kernel(stood_up):
 
     outs = {}
     for mode in (0, 1):
-        par.fs.fs_set_kernel_mode(mode)
+        par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, mode)
         try:
             outs[mode] = _decode_all(par, layers)
         finally:
-            par.fs.fs_set_kernel_mode(0)
+            par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, 0)
     for k, s in enumerate(wl.models):
         tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
         d = float(np.max(np.abs(outs[0][k] - outs[1][k])))
@@ -97,11 +97,11 @@ def test_many_small_items(stood_up):
     n_items = [sum(-(-int(l) // 32) for l in s.lens) * s.n_kv_heads for s in wl.models]
     assert max(n_items) > 65535, n_items
     base = [o.float().cpu().numpy() for o in stood_up["keep"]["out"]]
-    par.fs.fs_set_split_bytes(16 * 1024)
+    par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 16 * 1024)
     try:
         fine = _decode_all(par, layers)
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
     for k, s in enumerate(wl.models):
         tol = 2 * (gpu_harness.TOL_FP16 if s.kv_dtype == workloads.FP16 else gpu_harness.TOL_QUANT)
         d = float(np.max(np.abs(base[k] - fine[k])))

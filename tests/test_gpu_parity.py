@@ -51,11 +51,11 @@ def test_gqa_8b_shape_all_dtypes(dtype, src_f32, mode):
                   "shuffle")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(64 * KiB)  # force several splits per long sequence
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 64 * KiB)  # force several splits per long sequence
         errs = par.run_and_check([1], kernel_mode=mode)
         print("max abs err", errs)
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -68,11 +68,11 @@ def test_mha_13b_shape(dtype, mode):
                   "shuffle")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(32 * KiB)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 32 * KiB)
         errs = par.run_and_check([2], kernel_mode=mode)
         print("T", par.gw.T, "max abs err", errs)
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -89,6 +89,57 @@ def test_mixed_four_model_pool_small(mode):
 
 
 @pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_decode_step_appends_newest_tokens_and_attends_in_one_call(mode):
+    """fs_decode_step_multi on the small four-model pool: the cache holds all but every sequence's newest token; the
+    step appends the newest tokens of all four models (fp16 and fp32 sources, four formats) in its front kernel and
+    attends.  Bytes and outputs against the oracle, which appends every token itself.  Then fs_kv_append_multi alone
+    rewrites the same rows into a second layer."""
+    import torch
+
+    wl = workloads.scaled_down(workloads.config(5), n_seq=5, max_len=700, pool_bytes=640 * MiB, churn_steps=300)
+    par = _parity(wl)
+    try:
+        gw, fs = par.gw, par.fs
+        layers = [7, 0, 3, 9]
+        gw.set_option(fs.FS_OPT_DECODE_KERNEL, mode)
+        gw.populate([[l] for l in layers], hold_back_newest=True)
+        appends, keep_a = gw.newest_token_appends(layers)
+        batches, keep = gw.make_batches(layers)
+        ws = gw.workspace_for(batches)
+        fs.fs_decode_step_multi(gw.pool, appends, batches, ws)
+        torch.cuda.synchronize()
+        assert fs.fs_decode_status(ws) == 0
+        for k in range(len(wl.models)):
+            err, n = par.check_model(k, layers, keep, None)
+            print(f"model {k}: {n} sequences, max abs err {err:.2e}")
+        # no appends: the call is the plain multi-model decode
+        batches2, keep2 = gw.make_batches(layers)
+        fs.fs_decode_step_multi(gw.pool, [], batches2, ws)
+        torch.cuda.synchronize()
+        for a, b in zip(keep["out"], keep2["out"]):
+            assert torch.equal(a, b)
+        # fs_kv_append_multi: the same newest tokens into other layers, older tokens by the single-model call
+        layers2 = [0, 5, 6, 2]
+        gw.populate([[l] for l in layers2], hold_back_newest=True)
+        appends2, keep_b = gw.newest_token_appends(layers2)
+        fs.fs_kv_append_multi(gw.pool, appends2)
+        torch.cuda.synchronize()
+        for k in range(len(wl.models)):
+            ref = par.oracle_sequences(k, layers2[k], np.arange(len(gw.lens[k])))
+            par.check_bytes(k, ref)
+        # argument checks: refused before any launch
+        appends2[1].layer = 99
+        with pytest.raises(fs.FsError):
+            fs.fs_kv_append_multi(gw.pool, appends2)
+        with pytest.raises(fs.FsError):
+            fs.fs_decode_step_multi(gw.pool, appends2, batches, ws)
+        with pytest.raises(fs.FsError):
+            fs.fs_kv_append_multi(gw.pool, appends * 3)
+    finally:
+        par.close()
+
+
+@pytest.mark.parametrize("mode", KERNEL_MODES)
 def test_eight_batches_in_one_launch(mode):
     """The most batches a multi-model launch takes: eight models (each format twice, different head counts and
     lengths) interleaved block by block in one pool, splits forced so that the queue merges eight item lists."""
@@ -100,10 +151,10 @@ def test_eight_batches_in_one_launch(mode):
     wl = Workload("eight", 64 * KiB, 64 * MiB, models, "interleave")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(16 * KiB)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 16 * KiB)
         print("max abs err", par.run_and_check([0] * 8, kernel_mode=mode))
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -139,10 +190,10 @@ def test_group_sizes_and_head_dim_64(group, mode):
     wl = Workload("g", 64 * KiB, 16 * MiB, [ModelSpec("m", FP16, 2, 64, 1, 2 * group, lens, tag=23)], "shuffle")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(16 * KiB)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 16 * KiB)
         par.run_and_check([0], kernel_mode=mode)
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -157,10 +208,10 @@ def test_head_dims_from_8_to_512(dtype, src_f32, head_dim):
                   "shuffle")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(16 * KiB)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 16 * KiB)
         print(par.run_and_check([0]))
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -175,10 +226,10 @@ def test_group_sizes_head_dim_128(dtype, group, mode):
                   [ModelSpec("m", dtype, 2, 128, 1, 2 * group, lens, tag=43, src_f32=dtype == INT4)], "shuffle")
     par = _parity(wl)
     try:
-        par.fs.fs_set_split_bytes(32 * KiB)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 32 * KiB)
         print(par.run_and_check([0], kernel_mode=mode))
     finally:
-        par.fs.fs_set_split_bytes(0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
 
 
@@ -240,16 +291,16 @@ def test_placement_invariance_and_split_independence_on_gpu(mode):
                           placement)
             par = _parity(wl)
             try:
-                par.fs.fs_set_split_bytes(split)
-                par.fs.fs_set_kernel_mode(mode)
+                par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, split)
+                par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, mode)
                 par.gw.populate([[0]])
                 batches, keep = par.gw.make_batches([0])
                 par.gw.decode(batches)
                 torch.cuda.synchronize()
                 outs[(placement, split)] = keep["out"][0].cpu().numpy().copy()
             finally:
-                par.fs.fs_set_split_bytes(0)
-                par.fs.fs_set_kernel_mode(0)
+                par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
+                par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, 0)
                 par.close()
     for split in (8 * KiB, 4 * MiB):
         assert np.array_equal(outs[("identity", split)], outs[("shuffle", split)])
@@ -284,12 +335,10 @@ def test_fp8_every_code_decodes_exactly(mode):
     lens = torch.ones(2, dtype=torch.int32, device="cuda:0")
     b = fs.make_batch(m, 0, 1, 0.1, q, tables, lens, out)
     ws = torch.empty(fs.fs_decode_workspace_bytes(pool, [b]), dtype=torch.uint8, device="cuda:0")
-    fs.fs_set_kernel_mode(mode)
-    try:
-        fs.fs_decode_attention_multi(pool, [b], ws)
-        torch.cuda.synchronize()
-    finally:
-        fs.fs_set_kernel_mode(0)
+    assert fs.fs_pool_set_option(pool, fs.FS_OPT_DECODE_KERNEL, mode) == 0
+    assert fs.fs_pool_get_option(pool, fs.FS_OPT_DECODE_KERNEL) == mode
+    fs.fs_decode_attention_multi(pool, [b], ws)
+    torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float32).reshape(-1)[: len(vals)]
     assert np.array_equal(got, vals.astype(np.float16).astype(np.float32))
     # and the stored bytes are the codes themselves
@@ -366,7 +415,7 @@ def test_weights_sum_to_one_on_gpu():
     """V == 1 everywhere gives out == 1 and the lse of a zero query is ln(n)."""
     import torch
     import paper_2509_06261_amd as fs
-    from paper_2509_06261_amd import harness
+    import gpu_workload as harness
 
     lens = np.array([1, 77, 1000, 3000], np.int32)
     wl = Workload("ones", 64 * KiB, 32 * MiB, [ModelSpec("m", FP16, 2, 128, 1, 8, lens, tag=27)], "shuffle")
@@ -378,7 +427,7 @@ def test_weights_sum_to_one_on_gpu():
         k = torch.randn((len(po), 2, 128), dtype=torch.float16, device="cuda:0")
         fs.fs_kv_append(gw.pool, gw.model_ids[0], 0, k, torch.ones_like(k), si, po, gw.tables[0])
         for mode in KERNEL_MODES:
-            fs.fs_set_kernel_mode(mode)
+            gw.set_option(fs.FS_OPT_DECODE_KERNEL, mode)
             batches, keep = gw.make_batches([0])
             keep["q"][0].zero_()
             gw.decode(batches)
@@ -388,14 +437,13 @@ def test_weights_sum_to_one_on_gpu():
             assert np.max(np.abs(out - 1.0)) <= 1e-3
             assert np.max(np.abs(lse - np.log(lens)[:, None])) <= 1e-3
     finally:
-        fs.fs_set_kernel_mode(0)
         gw.close()
 
 
 def test_argument_errors_and_status_flags():
     import torch
     import paper_2509_06261_amd as fs
-    from paper_2509_06261_amd import harness
+    import gpu_workload as harness
 
     lens = np.array([10, 20], np.int32)
     wl = Workload("err", 64 * KiB, 4 * MiB, [ModelSpec("m", FP16, 2, 64, 2, 4, lens, tag=28)], "identity")
@@ -446,7 +494,7 @@ def test_block_table_entry_outside_the_pool_is_reported_not_followed(mode, bad_e
     are without the bad entry.  The pool is zero-filled, so the affected rows come out finite as well."""
     import torch
     import paper_2509_06261_amd as fs
-    from paper_2509_06261_amd import harness
+    import gpu_workload as harness
 
     lens = np.array([300, 700, 50, 1200], np.int32)
     wl = Workload("badtab", 64 * KiB, 32 * MiB, [ModelSpec("m", INT8, 2, 128, 1, 8, lens, tag=29)], "shuffle")
@@ -454,7 +502,7 @@ def test_block_table_entry_outside_the_pool_is_reported_not_followed(mode, bad_e
     try:
         gw.place()
         gw.populate()
-        fs.fs_set_kernel_mode(mode)
+        gw.set_option(fs.FS_OPT_DECODE_KERNEL, mode)
         batches, keep = gw.make_batches([0])
         ws = gw.decode(batches)
         assert fs.fs_decode_status(ws) == 0
@@ -488,5 +536,4 @@ def test_block_table_entry_outside_the_pool_is_reported_not_followed(mode, bad_e
                                 torch.from_numpy(q_off).to(gw.device), q_off, o, None, pws)
         assert fs.fs_decode_status(pws) == 0
     finally:
-        fs.fs_set_kernel_mode(0)
         gw.close()

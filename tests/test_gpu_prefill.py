@@ -8,7 +8,7 @@ from fs_inputs.workloads import FP16, FP8, INT4, INT8, KiB, MiB, ModelSpec, Work
 
 pytestmark = pytest.mark.gpu
 
-# (name, column blocks, waves) for fs_set_prefill_kernel.  The workgroup kernel with 8 waves (what large launches
+# (name, column blocks, waves) for the FS_OPT_PREFILL_* pool options.  The workgroup kernel with 8 waves (what large launches
 # run) takes every test; the automatic choice (the 16-column kernel on launches this small) the four-format and
 # the two-model tests; the other variants the four-format test on FP16 and INT4 (without and with parameters).
 # wg8dq = the same kernel with staged dequantization (INT8 / INT4 only; the library's default, switched off for the
@@ -38,19 +38,22 @@ def kernel_variant(request):
         pytest.skip("the pipelined variant takes the four-format, odd-block and long-context tests")
     if name not in ("wg8", "wg8dq", "auto", "wg4p") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
         pytest.skip("variant covered by the four-format test on FP16 and INT4")
+    import gpu_workload
+
     if name == "wg4x2":
-        assert fs.fs_set_prefill_kernel(blocks, waves) != 0  # refused by the library
-        pytest.skip("variant switched off in the library: a full-size run faulted or hung the GPU, cause not found")
-    assert fs.fs_set_prefill_kernel(blocks, waves) == 0
-    fs.fs_set_prefill_pipelined(name == "wg4p")  # the software-pipelined form of the 4-wave workgroup kernel
-    fs.fs_set_prefill_staged_dequant(name == "wg8dq")
-    import gpu_harness
-    gpu_harness.STAGED_DEQUANT = name == "wg8dq"  # the wider lse bound applies to that path alone
+        pool = fs.fs_pool_create(64 * KiB, 1 * MiB, 256)  # bookkeeping only: no device memory is touched
+        try:
+            assert fs.fs_pool_set_option(pool, fs.FS_OPT_PREFILL_COLUMN_BLOCKS, blocks) != 0  # refused by the library
+        finally:
+            fs.fs_pool_destroy(pool)
+        pytest.skip("variant taken out of the library: a full-size run faulted or hung the GPU and the cause was not found")
+    # every pool stood up by this test gets the variant's options (the wider lse bound of staged dequantization is
+    # applied by the harness from the pool's own record of the kernel that ran)
+    gpu_workload.DEFAULT_OPTIONS = {fs.FS_OPT_PREFILL_COLUMN_BLOCKS: blocks, fs.FS_OPT_PREFILL_WAVES: waves,
+                                    fs.FS_OPT_PREFILL_PIPELINED: int(name == "wg4p"),
+                                    fs.FS_OPT_PREFILL_STAGED_DEQUANT: int(name == "wg8dq")}
     yield name
-    fs.fs_set_prefill_kernel(0, 0)
-    fs.fs_set_prefill_pipelined(0)
-    fs.fs_set_prefill_staged_dequant(-1)  # the default (on)
-    gpu_harness.STAGED_DEQUANT = True
+    gpu_workload.DEFAULT_OPTIONS = {}
 
 
 def _parity(wl):

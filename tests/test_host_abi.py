@@ -186,3 +186,66 @@ def test_error_codes_without_device():
     assert fs.fs_block_free(p, m, 0) == 0
     assert fs.fs_model_unregister(p, m) == 0
     fs.fs_pool_destroy(p)
+
+
+def test_pool_options_are_per_pool_and_range_checked():
+    a = fs.fs_pool_create(64 * KiB, 1 * MiB, FAKE_BASE)
+    b = fs.fs_pool_create(64 * KiB, 1 * MiB, FAKE_BASE)
+    try:
+        defaults = {fs.FS_OPT_DECODE_KERNEL: 0, fs.FS_OPT_SPLIT_BYTES: 0, fs.FS_OPT_KERNEL_TIMING: 0,
+                    fs.FS_OPT_PREFILL_COLUMN_BLOCKS: 0, fs.FS_OPT_PREFILL_WAVES: 0, fs.FS_OPT_PREFILL_PIPELINED: 0,
+                    fs.FS_OPT_PREFILL_STAGED_DEQUANT: 1, fs.FS_OPT_LAST_PREFILL_KERNEL: 0}
+        for opt, v in defaults.items():
+            assert fs.fs_pool_get_option(a, opt) == v
+        assert fs.fs_pool_set_option(a, fs.FS_OPT_DECODE_KERNEL, 2) == fs.FS_OK
+        assert fs.fs_pool_set_option(a, fs.FS_OPT_SPLIT_BYTES, 64 * KiB) == fs.FS_OK
+        assert fs.fs_pool_set_option(a, fs.FS_OPT_PREFILL_COLUMN_BLOCKS, 16) == fs.FS_OK
+        assert fs.fs_pool_set_option(a, fs.FS_OPT_PREFILL_WAVES, 4) == fs.FS_OK
+        assert fs.fs_pool_set_option(a, fs.FS_OPT_PREFILL_STAGED_DEQUANT, 0) == fs.FS_OK
+        assert fs.fs_pool_get_option(a, fs.FS_OPT_DECODE_KERNEL) == 2
+        assert fs.fs_pool_get_option(a, fs.FS_OPT_SPLIT_BYTES) == 64 * KiB
+        assert fs.fs_pool_get_option(a, fs.FS_OPT_PREFILL_STAGED_DEQUANT) == 0
+        for opt, v in defaults.items():  # the other pool is untouched
+            assert fs.fs_pool_get_option(b, opt) == v
+        for opt, bad in ((fs.FS_OPT_DECODE_KERNEL, 3), (fs.FS_OPT_DECODE_KERNEL, -1), (fs.FS_OPT_SPLIT_BYTES, 100),
+                         (fs.FS_OPT_SPLIT_BYTES, 1 << 31), (fs.FS_OPT_PREFILL_COLUMN_BLOCKS, 8),
+                         (fs.FS_OPT_PREFILL_COLUMN_BLOCKS, 3), (fs.FS_OPT_PREFILL_WAVES, 2),
+                         (fs.FS_OPT_LAST_PREFILL_KERNEL, 1), (99, 0)):
+            assert fs.fs_pool_set_option(a, opt, bad) == fs.FS_ERR_INVALID, (opt, bad)
+        with pytest.raises(fs.FsError):
+            fs.fs_pool_get_option(a, 99)
+        assert fs.fs_pool_last_attention_kernel_ms(a) < 0  # nothing timed
+    finally:
+        fs.fs_pool_destroy(a)
+        fs.fs_pool_destroy(b)
+
+
+def test_model_stats_count_slabs_per_key():
+    slab = 64 * KiB
+    p = fs.fs_pool_create(slab, 64 * slab, FAKE_BASE)
+    try:
+        _, m1 = fs.fs_model_register(p, fs.FS_KV_FP16, 2, 64, 1, slab // 4)   # four blocks per slab
+        _, m2 = fs.fs_model_register(p, fs.FS_KV_INT4, 2, 64, 1)              # one block per slab
+        g1, g2 = fs.fs_model_geometry(p, m1), fs.fs_model_geometry(p, m2)
+        ids1 = [fs.fs_block_alloc(p, m1)[1] for _ in range(10)]   # 2 full slabs + 1 partial holding 2 of 4
+        ids2 = [fs.fs_block_alloc(p, m2)[1] for _ in range(3)]
+        s1, s2 = fs.fs_model_stats(p, m1), fs.fs_model_stats(p, m2)
+        assert (s1.slabs_full, s1.slabs_partial, s1.live_blocks, s1.free_blocks_in_partial_slabs) == (2, 1, 10, 2)
+        assert (s2.slabs_full, s2.slabs_partial, s2.live_blocks, s2.free_blocks_in_partial_slabs) == (3, 0, 3, 0)
+        assert s1.live_bytes == 10 * g1.block_budget and s2.live_bytes == 3 * slab
+        assert s1.stranded_bytes == 10 * (g1.block_budget - g1.block_bytes)
+        assert s2.stranded_bytes == 3 * (g2.block_budget - g2.block_bytes)
+        tot = fs.fs_pool_stats(p)
+        assert tot.slabs_full == s1.slabs_full + s2.slabs_full and tot.slabs_partial == s1.slabs_partial + s2.slabs_partial
+        assert tot.live_blocks == 13 and tot.stranded_bytes == s1.stranded_bytes + s2.stranded_bytes
+        assert fs.fs_block_free(p, m1, ids1[0]) == 0     # a full slab of key 1 becomes partial
+        s1 = fs.fs_model_stats(p, m1)
+        assert (s1.slabs_full, s1.slabs_partial, s1.live_blocks, s1.free_blocks_in_partial_slabs) == (1, 2, 9, 3)
+        for b in ids2:
+            assert fs.fs_block_free(p, m2, b) == 0
+        s2 = fs.fs_model_stats(p, m2)
+        assert (s2.slabs_full, s2.slabs_partial, s2.live_blocks, s2.live_bytes) == (0, 0, 0, 0)
+        with pytest.raises(fs.FsError):
+            fs.fs_model_stats(p, 7)
+    finally:
+        fs.fs_pool_destroy(p)

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle
-import scenario
+from fs_inputs import workloads as scenario
 from fs_inputs import gen
 
 SEED = gen.MASTER_SEED
@@ -44,7 +44,7 @@ def build(dtype, H, D, L, n_q, lens, slab=64 * KiB, n_slabs=64, budget=None, shu
     v = scenario.source_rows(SEED, model_id, layer, gen.WHICH_V, lens, H, D, dtype=src_dtype)
     ks = vs = None
     if dtype == oracle.FP8:
-        ks1, vs1 = scenario.fp8_scales(k, v)
+        ks1, vs1 = scenario.fp8_scales_from_rows(k, v)
         ks = np.ones((L, H), np.float32)
         vs = np.ones((L, H), np.float32)
         ks[layer], vs[layer] = ks1, vs1

@@ -51,7 +51,7 @@ def test_static_scratch_entry_matches_workspace_entry_twice():
         gw, fs = par.gw, par.fs
         layers = [1, 0]
         gw.populate([[1], [0]])
-        fs.fs_set_split_bytes(64 * KiB)  # several splits per long sequence: partial records go through the scratch
+        gw.set_option(fs.FS_OPT_SPLIT_BYTES, 64 * KiB)  # several splits per long sequence: partial records go through the scratch
         try:
             # call 1: both models, all sequences; call 2: one model, its first three sequences
             for models, n_keep in (([0, 1], None), ([1], 3)):
@@ -68,7 +68,7 @@ def test_static_scratch_entry_matches_workspace_entry_twice():
                     print(f"models {models} keep {n_keep}: model {k} max abs err vs oracle {err:.2e}, identical to the "
                           "workspace entry point")
         finally:
-            fs.fs_set_split_bytes(0)
+            gw.set_option(fs.FS_OPT_SPLIT_BYTES, 0)
         # a batch whose upper bound exceeds the array is refused on the host, before any launch
         batches, keep = gw.make_batches(layers, models=[0], host_lens=False)
         batches[0].max_blocks = 1 << 22  # no host lengths: sized for max_blocks * tokens_per_block per sequence
