@@ -16,7 +16,8 @@ run adds under ``extra``:
   mixed_pool_loss  the control the benchmark definition asks for -- each model of the mixed pool alone in a
                    pool of its own precision with contiguous (identity) block tables and the SAME final
                    lengths: loss = 1 - BW_multi / (sum bytes_m / sum t_m);
-  per_config       the same step timed on configs 2, 3 and 4 (value, kernel time, fraction of peak).
+  per_config       the same step timed on configs 2, 3 and 4, and on copies of config 2 with head_dim 64 and 256
+                   (value, kernel time, fraction of peak).
 """
 from __future__ import annotations
 
@@ -388,15 +389,18 @@ def main():
         }
         # ---- the other configs ----
         per_config = {}
-        for cfg in (2, 3, 4):
+        # (and config 2 with head_dim 64 and 256: the MFMA kernel's other two instantiations)
+        for cfg, head_dim in ((2, 128), (3, 128), (4, 128), (2, 64), (2, 256)):
             cw = workloads.config(cfg)
+            if head_dim != 128:
+                cw = workloads.with_head_dim(cw, head_dim)
             ct = Timed(cw)
             cr = ct.run(args.steps, args.warmup)
             e = summary(cr)
             e["workload"] = cw.name
             e["models"] = ct.model_names()
             ct.close()
-            per_config[f"config{cfg}"] = e
+            per_config[f"config{cfg}" + (f"_d{head_dim}" if head_dim != 128 else "")] = e
         result["extra"]["per_config"] = per_config
     result["extra"]["setup_s"] = round(time.perf_counter() - t_setup, 1)
     print(json.dumps(result), flush=True)

@@ -12,6 +12,7 @@ ShareGPT conversation lengths the paper serves; K/V/q values are N(0,1) table de
 """
 from __future__ import annotations
 
+import dataclasses
 from dataclasses import dataclass, field
 from typing import List, Optional
 
@@ -232,6 +233,15 @@ def config(n: int, seed: int = gen.MASTER_SEED) -> Workload:
         return Workload("cfg5-mixed-4-models", 2 * MiB, 160 * GiB, models, "churn", seed, churn_steps=100_000,
                         notes={"lognormal": ln})
     raise ValueError(f"no config {n}")
+
+
+def with_head_dim(wl: Workload, head_dim: int) -> Workload:
+    """A copy of a workload whose models have another head_dim (same heads, layers, lengths, placement; the pool grows
+    with the rows): what the decode kernels are timed on beside head_dim 128."""
+    models = [dataclasses.replace(s, head_dim=head_dim) for s in wl.models]
+    grow = max(1, -(-head_dim // max(s.head_dim for s in wl.models)))
+    return dataclasses.replace(wl, name=f"{wl.name}-d{head_dim}", pool_bytes=wl.pool_bytes * grow, models=models,
+                               notes=dict(wl.notes))
 
 
 def scaled_down(wl: Workload, n_seq: int, max_len: int, pool_bytes: int, churn_steps: int = 2000) -> Workload:

@@ -300,8 +300,9 @@ int fs_sched_place_models(const double* footprint, const double* mu, int n_model
  * host thread at a time, and so are its options).  fs_pool_set_option returns FS_ERR_INVALID for an unknown option
  * or a value outside its range; fs_pool_get_option reads the current value. */
 enum fs_option {
-  /* decode kernel: 0 = automatic (default), 1 = the generic vector-ALU kernel, 2 = the MFMA kernel (a launch with a
-   * shape it lacks then fails with FS_ERR_INVALID) */
+  /* decode kernel: 0 = automatic (default: the MFMA kernel where every batch of the launch has the same head_dim of
+   * 64, 128 or 256 and at least 8 tokens per block, else the generic kernel), 1 = the generic vector-ALU kernel,
+   * 2 = the MFMA kernel (a launch with a shape it lacks then fails with FS_ERR_INVALID) */
   FS_OPT_DECODE_KERNEL = 0,
   /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose:
    * 192 KiB, less (down to 64 KiB) for launches too small to give each wave of the grid three items (judged from

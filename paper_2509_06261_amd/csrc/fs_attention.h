@@ -96,6 +96,17 @@ struct MultiArgs {
 // the grid works on all batches -- all KV formats -- at once: formats bound by the vector ALU and formats
 // bound by memory then share every compute unit instead of taking turns.
 
+// Workgroups (of four waves) of the MFMA decode kernel per compute unit: two, or one at head_dim 256, whose 64
+// accumulator registers per lane next to a 32 KiB tile need more than the 256 registers a wave gets at two.
+constexpr int mfma_wgs_per_cu(int head_dim) { return head_dim == 256 ? 1 : 2; }
+
+// 32-token tiles the MFMA decode kernel keeps in flight per wave: about 16 KiB of K/V rows (32 KiB at head_dim
+// 256, where half as many waves run).  The host sizes work items in whole turns of this ring.
+constexpr int ring_tiles(int kv_dtype, int head_dim) {
+  const bool f16 = kv_dtype == FS_KV_FP16, i4 = kv_dtype == FS_KV_INT4;
+  return head_dim <= 64 ? (f16 ? 2 : 4) : head_dim == 128 ? (f16 ? 1 : i4 ? 3 : 2) : (f16 ? 1 : i4 ? 4 : 2);
+}
+
 // Runs of 8 token slots that a sequence of `len` tokens occupies (MFMA kernel's unit of work).
 __device__ __host__ inline int n_runs(int len, int T, int R) {
   const int nblk = (len + T - 1) / T;

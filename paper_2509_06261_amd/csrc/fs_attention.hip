@@ -377,7 +377,7 @@ uint64_t launch_split_bytes(const fs_pool* p, const fs_batch_t* batches, int n_b
     for (int s = 0; s < b.n_seq; ++s) bytes += head_bytes(b, g, s);
     total += bytes * (uint64_t)g.n_kv_heads;
   }
-  const uint64_t waves = (uint64_t)p->n_cu * 8;
+  const uint64_t waves = (uint64_t)p->n_cu * 4 * mfma_wgs_per_cu(p->models[batches[0].model].g.head_dim);
   return std::min(kSplitMax, std::max(kSplitMin, total / waves * 3 / 8 / 4096 * 4096));
 }
 
@@ -439,7 +439,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     B.R = (g.tokens_per_block + 7) / 8;
     B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);  // unused for R = 1
     B.chunk_runs = chunk_runs_for(g, split_bytes);
-    B.ring_runs = 4 * (g.kv_dtype == FS_KV_FP16 ? 1 : (g.kv_dtype == FS_KV_INT4 ? 3 : 2));
+    B.ring_runs = 4 * ring_tiles(g.kv_dtype, g.head_dim);
     // with tiers every tier's size stays a whole number of ring turns; a forced size is rounded to whole tiles only
     if (tiers) B.chunk_runs = std::max(B.chunk_runs / (8 * B.ring_runs), 1) * 8 * B.ring_runs;
     else B.ring_runs = 4;
@@ -473,7 +473,8 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
     const uint64_t items = std::max(items_tok, items_run) * (uint64_t)g.n_kv_heads;
     plan.ub_items += items;
     part_floats += items * (uint64_t)B.part_stride;
-    if (!mfma_supports(B)) plan.all_mfma = false;
+    // one launch of the MFMA kernel serves one head_dim
+    if (!mfma_supports(B) || B.g.D != A.b[0].g.D) plan.all_mfma = false;
   }
   if (seq_total > 0x3fffffff || qrows > 0x7fffffff || plan.ub_items > 0xfffffff0ull) {
     set_error("decode attention: batch too large");
@@ -540,9 +541,10 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
   (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
   hipError_t e = P.n ? launch_step_front(p, plan.args, P, s) : launch_prep(plan.args, s);
   if (e != hipSuccess) return device_error(e, "prep launch");
-  // Persistent grid: two workgroups (eight waves) per compute unit drain the queue (never more than the
-  // upper bound on work items, so tiny batches launch tiny grids).
-  constexpr int wgs_per_cu = 2;
+  // Persistent grid: as many workgroups as fit the compute units at once (two each, eight waves; one for the MFMA
+  // kernel at head_dim 256) drain the queue (never more than the upper bound on work items, so tiny batches launch
+  // tiny grids).
+  const int wgs_per_cu = use_mfma ? mfma_wgs_per_cu(plan.args.b[0].g.D) : 2;
   // (the MFMA kernel's workers are waves, four to a workgroup; the generic kernel's are workgroups)
   const uint64_t workers_per_wg = use_mfma ? 4 : 1;
   const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,

@@ -1,4 +1,4 @@
-// MFMA split-K paged decode-attention kernel for gfx950 (head_dim 128, all four KV formats).
+// MFMA split-K paged decode-attention kernel for gfx950 (head_dim 64, 128 or 256, all four KV formats).
 //
 // FineServe Sec. 2.1: the decode phase re-reads the whole KV cache for every generated token and is bound by
 // memory bandwidth; Sec. 2.3 / 5.1: the cache is reached through each model's own block table over the
@@ -70,8 +70,8 @@ __device__ __forceinline__ void store_table(const MultiArgs& A, const ItemPlan& 
 // accumulator registers.  Waves never synchronise with each other.  (Two steps, so that the tile loops of the
 // eight format / group variants do not carry the output code's registers; the state has the same shape for all.)
 // s_ptr: this wave's LDS table of head-chunk addresses, already holding the item's blocks.
-template <int DT, int GP>
-__device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st) {
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, StateT<HD>& st) {
   const int seq = P.seq, head = P.head;
   const DevBatch& B = A.b[P.b];
   const DevGeom& g = B.g;
@@ -94,10 +94,10 @@ __device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& 
   X.chunk_ptr = s_ptr;
 
   // Q operand and per-head constants
-  u32x4 qb[4];
+  u32x4 qb[HD / 32];
   float qsum;
-  load_q<DT>(B.q + ((int64_t)seq * B.n_q + head * G + c) * kD, c < G, j, qb, qsum);
-  if constexpr (Fmt<DT>::kParBytes != 0) {
+  load_q<DT, true, HD>(B.q + ((int64_t)seq * B.n_q + head * G + c) * HD, c < G, j, qb, qsum);
+  if constexpr (Fmt<DT, HD>::kParBytes != 0) {
     qsum += __shfl_xor(qsum, 16, 64);
     qsum += __shfl_xor(qsum, 32, 64);
     if constexpr (GP == 4) qsum = __shfl(qsum, c & 3, 64);  // of the head this lane exponentiates
@@ -106,18 +106,19 @@ __device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& 
   if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
 
 #pragma unroll
-  for (int e = 0; e < 8; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
+  for (int e = 0; e < HD / 16; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = -INFINITY;
   st.l = 0.f;
   st.zc = 0.f;
 
-  stream_tiles<DT, GP>(X, g, P.v0, qb, qsum, alpha, st, j, c);
+  stream_tiles<DT, GP, HD>(X, g, P.v0, qb, qsum, alpha, st, j, c);
 }
 
 // part_off: the batches' offsets into the partial buffer (the workspace header's words, copied to LDS once per
 // workgroup: read from memory here they would be one more round trip in front of every item's stores).
-template <int DT, int GP>
-__device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& P, State& st, const uint64_t* part_off) {
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& P, StateT<HD>& st, const uint64_t* part_off) {
+  constexpr int NE = HD / 16;  // output columns NE c .. NE c + NE - 1 are this lane's
   const int b = P.b, seq = P.seq, head = P.head;
   const DevBatch& B = A.b[b];
   int lane = threadIdx.x & 63;
@@ -139,7 +140,7 @@ __device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& 
   }
   st.l += __shfl_xor(st.l, 16, 64);
   st.l += __shfl_xor(st.l, 32, 64);
-  if constexpr (Fmt<DT>::kParBytes != 0) {
+  if constexpr (Fmt<DT, HD>::kParBytes != 0) {
     if constexpr (GP == 4) {
       st.zc += __shfl_xor(st.zc, 4, 64);
       st.zc += __shfl_xor(st.zc, 8, 64);
@@ -153,34 +154,41 @@ __device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& 
     const int h = 4 * j + r;  // accumulator row r of this lane; its m, l, zc live in lane c = h
     const float L = __shfl(st.l, h, 64), M = __shfl(st.m, h, 64), Z = __shfl(st.zc, h, 64);
     if (h < G) {
-      float o[8];
+      float o[NE];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
+      for (int e = 0; e < NE; ++e) {
         // integer formats: undo the 2^-24 of the subnormal encoding (and the 16 of INT4's odd code positions)
         const float f = DT == FS_KV_INT8 ? kTwo24 : (DT == FS_KV_INT4 ? ((e & 1) ? kTwo20 : kTwo24) : 1.0f);
         o[e] = st.acc[e][r] * f;
-        if constexpr (Fmt<DT>::kParBytes != 0) o[e] += Z;
+        if constexpr (Fmt<DT, HD>::kParBytes != 0) o[e] += Z;
         o[e] *= v_static;
       }
       const int qh = head * G + h;
       if (n_chunks == 1) {
         const float inv = 1.0f / L;
-        u32x4 w;
+        uint32_t w[NE / 2];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NE / 2; ++q) {
           const half2v hv = {(_Float16)(o[2 * q] * inv), (_Float16)(o[2 * q + 1] * inv)};
           w[q] = h2u(hv);
         }
-        *reinterpret_cast<u32x4*>(B.out + ((int64_t)seq * B.n_q + qh) * kD + 8 * c) = w;
+        _Float16* orow = B.out + ((int64_t)seq * B.n_q + qh) * HD + NE * c;
+        if constexpr (NE == 4) {
+          *reinterpret_cast<u32x2*>(orow) = u32x2{w[0], w[1]};
+        } else {
+#pragma unroll
+          for (int q = 0; q < NE / 8; ++q)
+            reinterpret_cast<u32x4*>(orow)[q] = u32x4{w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]};
+        }
         if (c == 0 && B.lse) B.lse[(int64_t)seq * B.n_q + qh] = (M + __builtin_amdgcn_logf(L)) * kLn2;
       } else {
-        float* pr = A.partials + part_base + (uint64_t)h * (kD + 2);
-        // (a row starts at a multiple of 8 bytes: part_stride and kD + 2 are even)
+        float* pr = A.partials + part_base + (uint64_t)h * (HD + 2);
+        // (a row starts at a multiple of 8 bytes: part_stride and HD + 2 are even)
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) *reinterpret_cast<float2*>(pr + 8 * c + e) = float2{o[e], o[e + 1]};
+        for (int e = 0; e < NE; e += 2) *reinterpret_cast<float2*>(pr + NE * c + e) = float2{o[e], o[e + 1]};
         if (c == 0) {
-          pr[kD] = M * kLn2;  // partial records keep the reference in natural-log units
-          pr[kD + 1] = L;
+          pr[HD] = M * kLn2;  // partial records keep the reference in natural-log units
+          pr[HD + 1] = L;
         }
       }
     }
@@ -188,13 +196,13 @@ __device__ __forceinline__ void finish_item(const MultiArgs& A, const ItemPlan& 
 }
 
 // step 0: stream_item, step 1: finish_item
-template <int STEP, int GP>
-__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st,
+template <int STEP, int GP, int HD>
+__device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, StateT<HD>& st,
                                                const uint64_t* part_off) {
   switch (A.b[P.b].g.dtype) {
-#define FS_STEP(DT)                                          \
-  if constexpr (STEP == 0) stream_item<DT, GP>(A, P, s_ptr, st); \
-  else finish_item<DT, GP>(A, P, st, part_off);              \
+#define FS_STEP(DT)                                                  \
+  if constexpr (STEP == 0) stream_item<DT, GP, HD>(A, P, s_ptr, st); \
+  else finish_item<DT, GP, HD>(A, P, st, part_off);                  \
   break
     case FS_KV_FP16: FS_STEP(FS_KV_FP16);
     case FS_KV_FP8_E4M3: FS_STEP(FS_KV_FP8_E4M3);
@@ -204,14 +212,16 @@ __device__ __forceinline__ void dispatch_dtype(const MultiArgs& A, const ItemPla
   }
 }
 
-template <int STEP>
-__device__ __forceinline__ void dispatch_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, State& st,
+template <int STEP, int HD>
+__device__ __forceinline__ void dispatch_item(const MultiArgs& A, const ItemPlan& P, uint64_t* s_ptr, StateT<HD>& st,
                                               const uint64_t* part_off) {
-  if (A.b[P.b].G <= 4) dispatch_dtype<STEP, 4>(A, P, s_ptr, st, part_off);
-  else dispatch_dtype<STEP, 16>(A, P, s_ptr, st, part_off);
+  if (A.b[P.b].G <= 4) dispatch_dtype<STEP, 4, HD>(A, P, s_ptr, st, part_off);
+  else dispatch_dtype<STEP, 16, HD>(A, P, s_ptr, st, part_off);
 }
 
-__global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A, int table_entries) {
+// One kernel per head_dim (every batch of a launch has the same one).
+template <int HD>
+__global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_kernel(MultiArgs A, int table_entries) {
   extern __shared__ uint64_t smem64[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -266,18 +276,18 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_attention_kernel(MultiArgs A
     int32_t tab[kTabRegs];
     load_entries(A, P, lane, tab);
     store_table(A, P, lane, tab, s_ptr);
-    State st;
-    dispatch_item<0>(A, P, s_ptr, st, s_part_off);
-    dispatch_item<1>(A, P, s_ptr, st, s_part_off);
+    StateT<HD> st;
+    dispatch_item<0, HD>(A, P, s_ptr, st, s_part_off);
+    dispatch_item<1, HD>(A, P, s_ptr, st, s_part_off);
   }
 }
 
 }  // namespace
 
-// Shapes this kernel covers: head_dim 128, at least 8 tokens per block (a run of 8 slots fits a block), and
-// run indices small enough for the multiply-high division by R.
+// Shapes this kernel covers: head_dim 64, 128 or 256, at least 8 tokens per block (a run of 8 slots fits a block),
+// and run indices small enough for the multiply-high division by R.
 bool mfma_supports(const DevBatch& b) {
-  if (b.g.D != kD || b.g.T < 8 || b.G > 16) return false;
+  if ((b.g.D != 64 && b.g.D != 128 && b.g.D != 256) || b.g.T < 8 || b.G > 16) return false;
   const uint64_t max_tok = (uint64_t)b.max_blocks * (uint64_t)b.g.T;
   const uint64_t max_run = (uint64_t)b.max_blocks * (uint64_t)b.R + 8;
   return max_tok < (1ull << 31) && max_run * (uint64_t)b.R < (1ull << 32);
@@ -288,7 +298,11 @@ hipError_t launch_mfma(const MultiArgs& A, int n_workgroups, hipStream_t s) {
   int entries = 0;
   for (int i = 0; i < A.n_batches; ++i) entries = std::max(entries, A.b[i].chunk_runs / A.b[i].R + 4);
   const size_t smem = (size_t)kWaves * entries * sizeof(uint64_t);
-  hipLaunchKernelGGL(mfma_attention_kernel, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries);
+  switch (A.b[0].g.D) {  // (the caller checked that all batches share it)
+    case 64: hipLaunchKernelGGL(mfma_attention_kernel<64>, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries); break;
+    case 128: hipLaunchKernelGGL(mfma_attention_kernel<128>, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries); break;
+    default: hipLaunchKernelGGL(mfma_attention_kernel<256>, dim3(n_workgroups), dim3(kThreads), smem, s, A, entries); break;
+  }
   return hipGetLastError();
 }
 

@@ -1,5 +1,5 @@
-// MFMA tile machinery of the paged attention kernels for gfx950 (head_dim 128, all four KV formats):
-// shared by the split-K decode kernel and the prefill kernel.
+// MFMA tile machinery of the paged attention kernels for gfx950 (all four KV formats; head_dim HD = 64, 128 or 256,
+// a template parameter that defaults to 128): shared by the split-K decode kernel and the prefill kernel.
 //
 // FineServe Sec. 2.1 / 2.3 / 5.1: attention reaches the KV cache through each model's own block table over
 // the shared slab pool.  K/V rows stream straight from the slabs into registers (no LDS staging: every byte
@@ -17,6 +17,8 @@
 //   K is loaded as the A operand of S^T: lane (j, c) reads 16 bytes of the row of token
 //   tb + 8*(c/4) + 4u + (c%4); the d order inside a k-step is whatever the format's unpacking yields,
 //   and the Q operand is pre-arranged once per item in the same order.
+//   The head dimension decides the counts only: HD / 32 k-steps for S^T, HD / 16 output columns per lane (one
+//   16x16 accumulator tile each), HD / 16 elements of every V row per lane.
 //
 // Dequantization is folded around the MFMAs: FP8 static scales and INT8/INT4 per-token K scales
 // multiply the logits, per-token V scales multiply P; integer codes enter the MFMA unconverted, as fp16
@@ -47,23 +49,32 @@ constexpr int kD = 128;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-template <int DT>
-struct Fmt;
-template <>
-struct Fmt<FS_KV_FP16> {
-  static constexpr int kRowBytes = 256, kKLoads = 4, kVBytes = 16, kParBytes = 0, kRing = 1;
+template <int DT, int HD = 128>
+struct Fmt {
+  static_assert(HD == 64 || HD == 128 || HD == 256, "head_dim of the MFMA kernels");
+  static constexpr int kBits = DT == FS_KV_FP16 ? 16 : (DT == FS_KV_INT4 ? 4 : 8);
+  static constexpr int kRowBytes = HD * kBits / 8;
+  // K rows: the four lanes j of a row take kKLane bytes each per load (16, or 8 where the row has only 32 bytes)
+  static constexpr int kKLane = kRowBytes / 4 < 16 ? kRowBytes / 4 : 16;
+  static constexpr int kKLoads = kRowBytes / (4 * kKLane);
+  static constexpr int kSteps = HD / 32;  // k-steps of S^T
+  static constexpr int kNE = HD / 16;     // output columns (accumulator tiles) per lane
+  // V rows: the sixteen lanes c of a row take kVBytes each (kNE elements)
+  static constexpr int kVBytes = kRowBytes / 16;
+  static constexpr int kVWords = kVBytes < 4 ? 1 : kVBytes / 4;
+  // packed-fp16 registers one lane's share of a V row unpacks to (INT4: four per word, see int4x8)
+  static constexpr int kVRegs = DT == FS_KV_INT4 ? 4 * kVWords : kNE / 2;
+  static constexpr int kParBytes = DT == FS_KV_INT8 ? 2 : (DT == FS_KV_INT4 ? 4 : 0);
+  static constexpr int kRing = ring_tiles(DT, HD);
+};
+
+template <int BYTES>
+struct KVec {
+  typedef u32x4 type;
 };
 template <>
-struct Fmt<FS_KV_FP8_E4M3> {
-  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 0, kRing = 2;
-};
-template <>
-struct Fmt<FS_KV_INT8> {
-  static constexpr int kRowBytes = 128, kKLoads = 2, kVBytes = 8, kParBytes = 2, kRing = 2;
-};
-template <>
-struct Fmt<FS_KV_INT4> {
-  static constexpr int kRowBytes = 64, kKLoads = 1, kVBytes = 4, kParBytes = 4, kRing = 3;
+struct KVec<8> {
+  typedef u32x2 type;
 };
 
 // K/V bytes are read once per launch: FS_NT_K / FS_NT_V (0 or 1) select loads with the non-temporal hint.
@@ -122,10 +133,10 @@ constexpr float kTau = 3.0f;  // log2 of the largest softmax weight tolerated be
 
 // GP = padded group size: 4 when the KV head serves at most 4 query heads, else 16.  The MFMAs always work on 16
 // head columns; GP decides how the softmax between them is spread over the lanes (see softmax_pv).
-template <int DT, int GP>
+template <int DT, int GP, int HD = 128>
 struct Tile {
-  u32x4 k[2][Fmt<DT>::kKLoads];
-  uint32_t v[8][Fmt<DT>::kVBytes / 4];
+  typename KVec<Fmt<DT, HD>::kKLane>::type k[2][Fmt<DT, HD>::kKLoads];
+  uint32_t v[8][Fmt<DT, HD>::kVWords];
   // INT8/INT4 per-token parameters.  GP == 16: one register; lanes c < 8 hold the K parameters of token c of
   // the lane's run, lanes c >= 8 the V ones.  GP == 4: those of the lane's own two tokens, K K V V.
   uint32_t par[GP == 16 ? 1 : 4];
@@ -174,39 +185,52 @@ __device__ __forceinline__ RunLoc locate(const ItemCtx& X, int vr) {
   return L;
 }
 
-template <int DT, int GP>
-__device__ __forceinline__ void issue_k(const ItemCtx& X, int vb, int j, int c, Tile<DT, GP>& t) {
-  using F = Fmt<DT>;
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void issue_k(const ItemCtx& X, int vb, int j, int c, Tile<DT, GP, HD>& t) {
+  using F = Fmt<DT, HD>;
+  typedef typename KVec<F::kKLane>::type kvec;
   // row m = c of S^T tile u is slot 4u + (c & 3) of run c >> 2
   const RunLoc L = locate(X, vb + (c >> 2));
-  const gptr p = L.base + (uint32_t)((L.start + (c & 3)) * F::kRowBytes) + 16 * j;
+  const gptr p = L.base + (uint32_t)((L.start + (c & 3)) * F::kRowBytes) + F::kKLane * j;
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int s = 0; s < F::kKLoads; ++s)
-      t.k[u][s] = stream_load<FS_NT_K>(reinterpret_cast<const FS_GLOBAL u32x4*>(p + u * 4 * F::kRowBytes + 64 * s));
+      t.k[u][s] = stream_load<FS_NT_K>(reinterpret_cast<const FS_GLOBAL kvec*>(p + u * 4 * F::kRowBytes + 4 * F::kKLane * s));
 }
 
-template <int DT>
-__device__ __forceinline__ void load_v_row(gptr p, uint32_t (&v)[Fmt<DT>::kVBytes / 4]) {
-  if constexpr (Fmt<DT>::kVBytes == 16) {
+template <int DT, int HD>
+__device__ __forceinline__ void load_v_row(gptr p, uint32_t (&v)[Fmt<DT, HD>::kVWords]) {
+  constexpr int kVBytes = Fmt<DT, HD>::kVBytes;
+  if constexpr (kVBytes == 32) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const u32x4 x = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL u32x4*>(p) + h);
+      v[4 * h + 0] = x[0];
+      v[4 * h + 1] = x[1];
+      v[4 * h + 2] = x[2];
+      v[4 * h + 3] = x[3];
+    }
+  } else if constexpr (kVBytes == 16) {
     const u32x4 x = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL u32x4*>(p));
     v[0] = x[0];
     v[1] = x[1];
     v[2] = x[2];
     v[3] = x[3];
-  } else if constexpr (Fmt<DT>::kVBytes == 8) {
+  } else if constexpr (kVBytes == 8) {
     const u32x2 x = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL u32x2*>(p));
     v[0] = x[0];
     v[1] = x[1];
-  } else {
+  } else if constexpr (kVBytes == 4) {
     v[0] = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL uint32_t*>(p));
+  } else {
+    v[0] = stream_load<FS_NT_V>(reinterpret_cast<const FS_GLOBAL uint16_t*>(p));
   }
 }
 
-template <int DT, int GP>
-__device__ __forceinline__ void issue_v(const ItemCtx& X, const DevGeom& g, int vb, int j, int c, Tile<DT, GP>& t) {
-  using F = Fmt<DT>;
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void issue_v(const ItemCtx& X, const DevGeom& g, int vb, int j, int c, Tile<DT, GP, HD>& t) {
+  using F = Fmt<DT, HD>;
   const RunLoc L = locate(X, vb + j);
   if constexpr (F::kParBytes != 0) {  // parameters first: the softmax needs them before the V rows
     const gptr pk = L.base + 2u * g.kv_tile;
@@ -232,21 +256,22 @@ __device__ __forceinline__ void issue_v(const ItemCtx& X, const DevGeom& g, int 
   }
   const gptr p0 = L.base + g.kv_tile + (uint32_t)(L.start * F::kRowBytes) + c * F::kVBytes;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) load_v_row<DT>(p0 + i * F::kRowBytes, t.v[i]);
+  for (int i = 0; i < 8; ++i) load_v_row<DT, HD>(p0 + i * F::kRowBytes, t.v[i]);
 }
 
 // The Q operand (B of S^T = K Q^T) of lane (j, c) for k-step ks: 8 halves of q[head c] in the d order
 // (and with the per-position factors) that the format's K unpacking produces.  qsum = sum_d q[d].
 // ODD16 (INT4): the K operand holds its odd code positions 16-fold, the query carries 1/16 there.  Without it the
 // query keeps its values (a K operand that was dequantized on the way holds plain values at every position).
-template <int DT, bool ODD16 = true>
-__device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u32x4 (&qb)[4], float& qsum) {
+template <int DT, bool ODD16 = true, int HD = 128>
+__device__ __forceinline__ void load_q(const _Float16* qrow, bool live, int j, u32x4 (&qb)[HD / 32], float& qsum) {
   qsum = 0.f;
+  constexpr int W = Fmt<DT, HD>::kKLane / 4;  // dwords (k-steps, for INT4) one lane takes of a K row per load
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
+  for (int ks = 0; ks < HD / 32; ++ks) {
     int d0;
     if (DT == FS_KV_FP16) d0 = 32 * ks + 8 * j;
-    else if (DT == FS_KV_INT4) d0 = 32 * j + 8 * ks;
+    else if (DT == FS_KV_INT4) d0 = 32 * W * (ks / W) + 8 * W * j + 8 * (ks % W);
     else d0 = 64 * (ks >> 1) + 16 * j + 8 * (ks & 1);
     u32x4 x = {0u, 0u, 0u, 0u};
     if (live) x = *reinterpret_cast<const u32x4*>(qrow + d0);
@@ -273,15 +298,17 @@ __device__ __forceinline__ float4v mfma(u32x4 a, u32x4 b, float4v acc) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), acc, 0, 0, 0);
 }
 
-// K fragments of one 16-token tile -> the four A operands of S^T.
-template <int DT>
-__device__ __forceinline__ void k_operands(const u32x4 (&k)[Fmt<DT>::kKLoads], u32x4 (&a)[4]) {
+// K fragments of one 16-token tile -> the A operands of S^T, one per k-step.
+template <int DT, int HD = 128>
+__device__ __forceinline__ void k_operands(const typename KVec<Fmt<DT, HD>::kKLane>::type (&k)[Fmt<DT, HD>::kKLoads],
+                                           u32x4 (&a)[HD / 32]) {
+  constexpr int KS = HD / 32;
   if constexpr (DT == FS_KV_FP16) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) a[s] = k[s];
+    for (int s = 0; s < KS; ++s) a[s] = k[s];
   } else if constexpr (DT == FS_KV_FP8_E4M3) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const u32x4 x = k[ks >> 1];
       const uint32_t w0 = x[2 * (ks & 1)], w1 = x[2 * (ks & 1) + 1];
       a[ks][0] = fp8x2_lo(w0);
@@ -291,7 +318,7 @@ __device__ __forceinline__ void k_operands(const u32x4 (&k)[Fmt<DT>::kKLoads], u
     }
   } else if constexpr (DT == FS_KV_INT8) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const u32x4 x = k[ks >> 1];
       uint32_t r0, r1, r2, r3;
       int8x4(x[2 * (ks & 1)], r0, r1);
@@ -302,10 +329,11 @@ __device__ __forceinline__ void k_operands(const u32x4 (&k)[Fmt<DT>::kKLoads], u
       a[ks][3] = r3;
     }
   } else {
+    constexpr int W = Fmt<DT, HD>::kKLane / 4;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       uint32_t r[4];
-      int4x8(k[0][ks], r);
+      int4x8(k[ks / W][ks % W], r);
       a[ks][0] = r[0];
       a[ks][1] = r[1];
       a[ks][2] = r[2];
@@ -314,22 +342,30 @@ __device__ __forceinline__ void k_operands(const u32x4 (&k)[Fmt<DT>::kKLoads], u
   }
 }
 
-// 8 elements of one V row -> four packed-fp16 registers (layout note above).
-template <int DT>
-__device__ __forceinline__ void v_unpack(const uint32_t (&v)[Fmt<DT>::kVBytes / 4], uint32_t (&x)[4]) {
+// One lane's elements of a V row -> packed-fp16 registers (layout note above).
+template <int DT, int HD = 128>
+__device__ __forceinline__ void v_unpack(const uint32_t (&v)[Fmt<DT, HD>::kVWords], uint32_t (&x)[Fmt<DT, HD>::kVRegs]) {
+  using F = Fmt<DT, HD>;
   if constexpr (DT == FS_KV_FP16) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) x[p] = v[p];
+    for (int p = 0; p < F::kVRegs; ++p) x[p] = v[p];
   } else if constexpr (DT == FS_KV_FP8_E4M3) {
-    x[0] = fp8x2_lo(v[0]);
-    x[1] = fp8x2_hi(v[0]);
-    x[2] = fp8x2_lo(v[1]);
-    x[3] = fp8x2_hi(v[1]);
+#pragma unroll
+    for (int w = 0; w < F::kVWords; ++w) {
+      x[2 * w] = fp8x2_lo(v[w]);
+      x[2 * w + 1] = fp8x2_hi(v[w]);
+    }
   } else if constexpr (DT == FS_KV_INT8) {
-    int8x4(v[0], x[0], x[1]);
-    int8x4(v[1], x[2], x[3]);
+#pragma unroll
+    for (int w = 0; w < F::kVWords; ++w) int8x4(v[w], x[2 * w], x[2 * w + 1]);
   } else {
-    int4x8(v[0], x);
+#pragma unroll
+    for (int w = 0; w < F::kVWords; ++w) {
+      uint32_t r[4];
+      int4x8(v[w], r);  // (a 16-bit share, head_dim 64: the high halves are zero and never selected)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) x[4 * w + q] = r[q];
+    }
   }
 }
 
@@ -344,26 +380,28 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
   (f(std::integral_constant<int, Is>{}), ...);
 }
 
-// Per-wave online-softmax state.  acc[e] is the 16x16 output tile of d columns {8c' + e}: lane (j', c')
+// Per-wave online-softmax state.  acc[e] is the 16x16 output tile of d columns {kNE c' + e}: lane (j', c')
 // holds rows (heads) 4j'..4j'+3.  m, l, zc belong to the head whose logits the lane exponentiates (see
 // softmax_pv): m is the same in all lanes of a head, l and zc are the lane's share.
-struct State {
-  float4v acc[8];
+template <int HD>
+struct StateT {
+  float4v acc[HD / 16];
   float m;   // reference subtracted from the logits (base-2 domain): within kTau of the running max
   float l;   // this lane's share of the running sum
   float zc;  // INT8/INT4: this lane's share of the zero-point term  -sum_t p_t s_t z_t
 };
+typedef StateT<128> State;
 
 // S^T = K Q^T for the 32 tokens of the tile: s[u][r] = raw logit of head c, slot 4u + r of run j.
-template <int DT, int GP>
-__device__ __forceinline__ void qk_tile(const Tile<DT, GP>& t, const u32x4 (&qb)[4], float4v (&s)[2]) {
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void qk_tile(const Tile<DT, GP, HD>& t, const u32x4 (&qb)[HD / 32], float4v (&s)[2]) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    u32x4 a[4];
-    k_operands<DT>(t.k[u], a);
+    u32x4 a[HD / 32];
+    k_operands<DT, HD>(t.k[u], a);
     float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) acc = mfma(a[ks], qb[ks], acc);
+    for (int ks = 0; ks < HD / 32; ++ks) acc = mfma(a[ks], qb[ks], acc);
     s[u] = acc;
   }
 }
@@ -383,8 +421,8 @@ __device__ __forceinline__ uint32_t from_shl(uint32_t src) {
 // Moves the reference of the lazy online softmax: called when some logit of the tile exceeds its head's
 // reference by more than kTau (always on the first tile, where m = -inf).  tmax = largest logit among this
 // lane's tokens; the lanes of a head are those with equal c % GP.
-template <int DT, int GP>
-__device__ __forceinline__ void move_reference(State& st, float tmax, int j) {
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void move_reference(StateT<HD>& st, float tmax, int j) {
   if constexpr (GP == 4) {
     tmax = fmaxf(tmax, __shfl_xor(tmax, 4, 64));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 8, 64));
@@ -399,7 +437,7 @@ __device__ __forceinline__ void move_reference(State& st, float tmax, int j) {
   for (int r = 0; r < 4; ++r) {
     const float cr = __shfl(corr, (4 * j + r) % GP, 64);  // head h keeps its factor in lane c = h
 #pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e][r] *= cr;
+    for (int e = 0; e < HD / 16; ++e) st.acc[e][r] *= cr;
   }
   st.m = m_new;
 }
@@ -415,10 +453,10 @@ __device__ __forceinline__ void move_reference(State& st, float tmax, int j) {
 // (j, c) takes head c % 4 and slots 2 (c / 4), + 1 of run j: it fetches those two logits from lane (j, c % 4)
 // (DPP row shifts), loads the parameters of its own two tokens itself, and hands its packed pair of P back to
 // lanes c < 4 (DPP again), which assemble the A operand.  A quarter of the exponentials, no broadcasts.
-template <int DT, int GP>
-__device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, const float4v (&s)[2], int vb, int j, int c,
-                                           float qsum, float alpha, State& st) {
-  using F = Fmt<DT>;
+template <int DT, int GP, int HD>
+__device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP, HD>& t, const float4v (&s)[2], int vb, int j, int c,
+                                           float qsum, float alpha, StateT<HD>& st) {
+  using F = Fmt<DT, HD>;
   const RunLoc L = locate(X, vb + j);
   const uint32_t n_ok = (uint32_t)max(L.hi - L.lo, 0);   // slot i of the run is live iff (unsigned)(i - lo) < n_ok
   const bool partial = !__all(L.lo == 0 && L.hi == 8);   // wave-uniform
@@ -429,7 +467,7 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int w = 0; w < F::kVBytes / 4; ++w) t.v[i][w] = i < L.hi_u ? t.v[i][w] : 0u;
+        for (int w = 0; w < F::kVWords; ++w) t.v[i][w] = i < L.hi_u ? t.v[i][w] : 0u;
     }
   }
   u32x4 pk;  // A operand of P V: halves (2q, 2q + 1) of pk[q] = weights of slots 2q, 2q + 1 of run j, head c
@@ -470,7 +508,7 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
     float tmax = x[0];
 #pragma unroll
     for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, x[i]);
-    if (__any(tmax - st.m > kTau)) move_reference<DT, GP>(st, tmax, j);
+    if (__any(tmax - st.m > kTau)) move_reference<DT, GP, HD>(st, tmax, j);
     const float m = st.m;
     float p[8];
     float lsum = 0.f;
@@ -523,7 +561,7 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
       x1 = ok1 ? x1 : -INFINITY;
     }
     const float tmax = fmaxf(x0, x1);
-    if (__any(tmax - st.m > kTau)) move_reference<DT, GP>(st, tmax, j);
+    if (__any(tmax - st.m > kTau)) move_reference<DT, GP, HD>(st, tmax, j);
     const float m = st.m;
     const float e0 = __builtin_amdgcn_exp2f(x0 - m), e1 = __builtin_amdgcn_exp2f(x1 - m);
     st.l += e0 + e1;
@@ -549,13 +587,14 @@ __device__ __forceinline__ void softmax_pv(const ItemCtx& X, Tile<DT, GP>& t, co
     pk[3] = from_shl<12>(pp);
   }
   // ---- V rows of the run -> B operands (8x8 in-register transpose) and out += P V ----
-  uint32_t vx[8][4];
+  uint32_t vx[8][F::kVRegs];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) v_unpack<DT>(t.v[i], vx[i]);
+  for (int i = 0; i < 8; ++i) v_unpack<DT, HD>(t.v[i], vx[i]);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int reg = DT == FS_KV_INT4 ? (e & 3) : (e >> 1);
-    const uint32_t sel = (DT == FS_KV_INT4 ? (e >> 2) : (e & 1)) ? 0x07060302u : 0x05040100u;
+  for (int e = 0; e < F::kNE; ++e) {
+    // element e of the lane's share: INT4 word e / 8 holds codes (p, p + 4) of its eight in register p
+    const int reg = DT == FS_KV_INT4 ? 4 * (e >> 3) + (e & 3) : (e >> 1);
+    const uint32_t sel = (DT == FS_KV_INT4 ? ((e >> 2) & 1) : (e & 1)) ? 0x07060302u : 0x05040100u;
     u32x4 b;
 #pragma unroll
     for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(vx[2 * q + 1][reg], vx[2 * q][reg], sel);
@@ -582,41 +621,37 @@ __device__ __forceinline__ void fill_table(uint64_t* s_ptr, const int32_t* table
 // will next occupy a slot are requested as soon as S^T of its current occupant is done, the V rows as soon
 // as P V is done, so the narrower the format the more tiles are in flight (about 16 KiB per wave for every
 // format).
-// Every step but those of the last turn refills its slot unconditionally: past the last tile the runs are mapped
+// Every step refills its slot unconditionally: past the last tile the runs are mapped
 // onto the last run (rows just read, so the refill hits in cache) and the data is never used.  With refills that depend on a
 // condition the compiler cannot know how many loads are outstanding behind the one it needs and waits for
 // all of them, the ones just issued included, which exposes the full memory latency on every tile.  For the
 // same reason the tile count is rounded up to whole rings: the surplus tiles lie past the end, are fully
 // masked and contribute zeros.
-template <int DT, int GP>
-__device__ __forceinline__ void stream_tiles(const ItemCtx& X, const DevGeom& g, int v0, const u32x4 (&qb)[4], float qsum,
-                                             float alpha, State& st, int j, int c) {
-  constexpr int NBUF = Fmt<DT>::kRing;
+template <int DT, int GP, int HD = 128>
+__device__ __forceinline__ void stream_tiles(const ItemCtx& X, const DevGeom& g, int v0, const u32x4 (&qb)[HD / 32], float qsum,
+                                             float alpha, StateT<HD>& st, int j, int c) {
+  constexpr int NBUF = Fmt<DT, HD>::kRing;
   const int n_tiles = (X.v_end - v0 + 3) >> 2;
-  Tile<DT, GP> t[NBUF];
+  Tile<DT, GP, HD> t[NBUF];
   static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
     constexpr int bi = decltype(Bi)::value;
-    issue_k<DT, GP>(X, v0 + bi * 4, j, c, t[bi]);
-    issue_v<DT, GP>(X, g, v0 + bi * 4, j, c, t[bi]);
+    issue_k<DT, GP, HD>(X, v0 + bi * 4, j, c, t[bi]);
+    issue_v<DT, GP, HD>(X, g, v0 + bi * 4, j, c, t[bi]);
   });
-  // One turn of the ring: every slot's tile is consumed and, REFILL, replaced by the tile NBUF further on.
-  auto turn = [&](int k0, auto Refill) {
-    constexpr bool REFILL = decltype(Refill)::value;
+  // One turn of the ring: every slot's tile is consumed and replaced by the tile NBUF further on.  (The last turn's
+  // refills lie past the item's end: mapped onto its last run, served from cache, never consumed.)
+  for (int k0 = 0; k0 < n_tiles; k0 += NBUF) {
     static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
       constexpr int bi = decltype(Bi)::value;
       const int vb = v0 + (k0 + bi) * 4;
       const int vb_next = vb + NBUF * 4;
       float4v s[2];
-      qk_tile<DT, GP>(t[bi], qb, s);
-      if constexpr (REFILL) issue_k<DT, GP>(X, vb_next, j, c, t[bi]);
-      softmax_pv<DT, GP>(X, t[bi], s, vb, j, c, qsum, alpha, st);
-      if constexpr (REFILL) issue_v<DT, GP>(X, g, vb_next, j, c, t[bi]);
+      qk_tile<DT, GP, HD>(t[bi], qb, s);
+      issue_k<DT, GP, HD>(X, vb_next, j, c, t[bi]);
+      softmax_pv<DT, GP, HD>(X, t[bi], s, vb, j, c, qsum, alpha, st);
+      issue_v<DT, GP, HD>(X, g, vb_next, j, c, t[bi]);
     });
-  };
-  // The last turn requests nothing: its refills would lie past the item's end, and although they hit in cache the
-  // wave's next wait for memory -- the first look-up of the next item -- would have to sit them out behind
-  // everything the memory pipeline has queued (measured: about 3 us per item).
-  for (int k0 = 0; k0 < n_tiles; k0 += NBUF) turn(k0, std::true_type{});
+  }
 }
 
 }  // namespace

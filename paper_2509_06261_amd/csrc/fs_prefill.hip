@@ -1583,7 +1583,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
   B.tier_seq[0] = B.tier_seq[1] = B.tier_seq[2] = 0x7fffffff;  // (decode's split sizes: not used by prefill)
   B.ring_runs = 4;
-  const bool generic = !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
+  const bool generic = B.g.D != kD || !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
   if (generic && (g.head_dim & (g.head_dim - 1))) {
     set_error("prefill attention: head_dim must be a power of two");
     return FS_ERR_INVALID;

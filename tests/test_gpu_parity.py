@@ -215,6 +215,46 @@ def test_head_dims_from_8_to_512(dtype, src_f32, head_dim):
         par.close()
 
 
+@pytest.mark.parametrize("group", [1, 4, 8])
+@pytest.mark.parametrize("head_dim", [64, 256])
+@pytest.mark.parametrize("dtype,src_f32", [(FP16, False), (FP8, False), (INT8, False), (INT4, True)])
+def test_mfma_kernel_head_dim_64_and_256(dtype, src_f32, head_dim, group):
+    """The MFMA kernel (forced: a shape it does not cover would be an error, not a fallback) at the two head_dims next
+    to 128: two and eight k-steps, four and sixteen output columns per lane; both softmax layouts (<= 4 and > 4 query
+    heads per KV head); 48 KiB slabs give blocks whose token count is no multiple of 8 for some of the formats;
+    lengths of one token, inside one run, across blocks and across splits."""
+    lens = np.array([1, 5, 64, 129, 700, 1031], np.int32)
+    wl = Workload("hd-mfma", 48 * KiB, 48 * MiB,
+                  [ModelSpec("m", dtype, 2, head_dim, 1, 2 * group, lens, tag=45, src_f32=src_f32)], "shuffle")
+    par = _parity(wl)
+    try:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 16 * KiB)
+        print(par.run_and_check([0], kernel_mode=2))
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)  # size tiers, whole ring turns
+        print(par.run_and_check([0], kernel_mode=2))
+    finally:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
+        par.close()
+
+
+def test_one_launch_over_models_of_different_head_dim():
+    """Two models of head_dim 64 and 128 in one pool and one multi-model launch: the MFMA kernel serves one head_dim
+    per launch, so the automatic choice falls to the generic kernel (results as always), and forcing the MFMA kernel
+    is refused."""
+    lens = np.array([3, 200, 777], np.int32)
+    wl = Workload("two-hd", 64 * KiB, 32 * MiB,
+                  [ModelSpec("a", FP16, 2, 64, 1, 8, lens, tag=46), ModelSpec("b", INT8, 2, 128, 1, 8, lens, tag=47)],
+                  "interleave")
+    par = _parity(wl)
+    try:
+        print(par.run_and_check([0, 0]))
+        with pytest.raises(Exception, match="MFMA kernel forced"):
+            par.populate_and_decode([0, 0], kernel_mode=2)
+    finally:
+        par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, 0)
+        par.close()
+
+
 @pytest.mark.parametrize("mode", KERNEL_MODES)
 @pytest.mark.parametrize("group", [2, 3, 5, 8, 12, 16])
 @pytest.mark.parametrize("dtype", [FP16, INT4])
