@@ -18,7 +18,11 @@ from fs_inputs import workloads
 pytestmark = pytest.mark.gpu
 
 # config -> (layer per model, oracle sample per model (None = every sequence), prefill sample per model)
-CONFIGS = {2: ([17], None, 3), 3: ([3, 29], 32, 1), 4: ([11], 32, 1), 5: ([7, 0, 3, 9], 32, 1)}
+# "2-d64" / "2-d256": config 2 with head_dim 64 / 256, the launches bench.py times on the MFMA decode kernel's other two
+# instantiations (whole-prompt prefill is not run there: the MFMA prefill kernels cover head_dim 128, and the
+# vector-ALU prefill path of other shapes, one workgroup per query row, is a small-workload parity case)
+CONFIGS = {"2": ([17], None, 3), "3": ([3, 29], 32, 1), "4": ([11], 32, 1), "5": ([7, 0, 3, 9], 32, 1),
+           "2-d64": ([17], None, 0), "2-d256": ([17], None, 0)}
 
 
 @pytest.fixture(scope="module", params=sorted(CONFIGS), ids=lambda c: f"config{c}")
@@ -27,7 +31,9 @@ def stood_up(request):
 
     cfg = request.param
     layers, n_random, prefill_random = CONFIGS[cfg]
-    wl = workloads.config(cfg)
+    wl = workloads.config(int(cfg.split("-")[0]))
+    if "-d" in cfg:
+        wl = workloads.with_head_dim(wl, int(cfg.split("-d")[1]))
     print(f"[full-size] config {cfg}: placing", flush=True)
     par = gpu_harness.Parity(wl, zero_pool=False)  # asserts every allocator call and the final slab table identical
     try:
@@ -89,7 +95,7 @@ def test_every_sequence_mfma_against_generic_kernel(stood_up):
 def test_many_small_items(stood_up):
     """16 KiB of KV per work item: more than 65535 items per batch (their products in the queue's interleaving of
     the batches pass 32 bits), some 140 splits per sequence for the combine."""
-    if stood_up["cfg"] != 3:
+    if stood_up["cfg"] != "3":
         pytest.skip("run on the two-model config")
     par, wl, layers = stood_up["par"], stood_up["wl"], stood_up["layers"]
     import gpu_harness
@@ -114,5 +120,7 @@ def test_whole_prompt_prefill_windows_against_the_oracle(stood_up, k):
     par, wl = stood_up["par"], stood_up["wl"]
     if k >= len(wl.models):
         pytest.skip("the config has fewer models")
+    if not stood_up["prefill_random"]:
+        pytest.skip("head_dim copy of a config: decode only (whole-prompt prefill is timed and checked at head_dim 128)")
     perr = par.prefill_whole_prompts_and_check_windows(k, stood_up["layers"][k], stood_up["prefill_random"])
     print(f"[full-size] config {stood_up['cfg']}: prefill model {k}: max abs err {perr[0]:.2e} on {perr[1]} rows", flush=True)
