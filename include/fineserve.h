@@ -304,9 +304,10 @@ enum fs_option {
    * 64, 128 or 256 and at least 8 tokens per block, else the generic kernel), 1 = the generic vector-ALU kernel,
    * 2 = the MFMA kernel (a launch with a shape it lacks then fails with FS_ERR_INVALID) */
   FS_OPT_DECODE_KERNEL = 0,
-  /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose:
-   * 192 KiB, less (down to 64 KiB) for launches too small to give each wave of the grid three items (judged from
-   * seq_lens_host where given, otherwise from max_blocks * tokens_per_block).  Otherwise 4096 .. 2^30.
+  /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose
+   * sizes in four tiers: 3/8 of a wave's share of the launch's KV bytes (judged from seq_lens_host where given,
+   * otherwise from max_blocks * tokens_per_block), between 64 and 768 KiB, for the sequences that hold the first
+   * 70 % of a batch's bytes, then half, a quarter and an eighth of it.  Otherwise 4096 .. 2^30: every item that size.
    * fs_decode_workspace_bytes answers for the pool's current setting. */
   FS_OPT_SPLIT_BYTES = 1,
   /* non-zero: every decode call brackets its attention kernel (not the work-list and combine kernels) with HIP
