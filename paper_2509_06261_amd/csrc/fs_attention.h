@@ -83,7 +83,9 @@ struct MultiArgs {
   float* partials;
   uint64_t part_capacity;  // floats
   uint32_t item_capacity;  // entries of item_list
-  uint32_t pad1;
+  // MFMA kernel: waves of the grid.  Wave w's first item is item w of the queue without a draw (its home pool is
+  // w % kPools, its first ticket w / kPools), so the pools' counters start past those tickets.
+  uint32_t n_workers;
   int32_t n_batches;
   int32_t n_seq_total;
   int32_t n_qrows_total;

@@ -69,7 +69,8 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
   const bool leader = group == 0;
   uint64_t* part_off = reinterpret_cast<uint64_t*>(A.header + kHdrPartOff);
   if (leader && tid == 0) A.header[kHdrStatus] = 0;
-  if (leader && tid < kPools) A.header[kHdrPools + tid * kPoolStride] = 0;
+  // (the tickets below a pool's number of home waves are taken: every wave starts with its own)
+  if (leader && tid < kPools) A.header[kHdrPools + tid * kPoolStride] = (A.n_workers + kPools - 1 - tid) / kPools;
   if (tid < kMaxBatches) s_count[tid] = 0;
   __syncthreads();  // workgroup 0: the reset precedes every flag its threads may raise below
 
@@ -539,8 +540,6 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
     if (appends[i].n_tokens > 0) ++P.n;
   }
   (void)hipGetLastError();  // drop any stale error of an earlier, unrelated runtime call
-  hipError_t e = P.n ? launch_step_front(p, plan.args, P, s) : launch_prep(plan.args, s);
-  if (e != hipSuccess) return device_error(e, "prep launch");
   // Persistent grid: as many workgroups as fit the compute units at once (two each, eight waves; one for the MFMA
   // kernel at head_dim 256) drain the queue (never more than the upper bound on work items, so tiny batches launch
   // tiny grids).
@@ -549,6 +548,9 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
   const uint64_t workers_per_wg = use_mfma ? 4 : 1;
   const int n_wg = (int)std::min<uint64_t>((uint64_t)p->n_cu * wgs_per_cu,
                                            std::max<uint64_t>((plan.ub_items + workers_per_wg - 1) / workers_per_wg, 1));
+  plan.args.n_workers = use_mfma ? (uint32_t)n_wg * (uint32_t)workers_per_wg : 0u;
+  hipError_t e = P.n ? launch_step_front(p, plan.args, P, s) : launch_prep(plan.args, s);
+  if (e != hipSuccess) return device_error(e, "prep launch");
   if (p->opt.timing) (void)hipEventRecord(p->opt.ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
   if (p->opt.timing) (void)hipEventRecord(p->opt.ev1, s);

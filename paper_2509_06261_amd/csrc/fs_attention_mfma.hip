@@ -240,11 +240,12 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   // moves to the next pool that still holds items and goes on; it leaves only when every pool is past its last
   // item, so the launch ends within one of the queue's last (smallest) items whatever the pools' loads were.
   // The next ticket is drawn before the current item is processed, so the atomic's latency is not waited for
-  // between items.
+  // between items; a wave's first ticket needs no draw at all (the work-list kernel starts the counters past the
+  // pools' home waves), which takes one round trip off the start of every launch.
   static_assert(kPools == 64, "one pool per lane in the look at all counters");
   const uint32_t worker = blockIdx.x * kWaves + wave;
   uint32_t pool = worker % kPools;
-  uint32_t ticket = 0;
+  uint32_t ticket = worker / kPools;
   constexpr uint32_t kNone = 0xffffffffu;
   auto draw = [&]() {
     if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
@@ -267,7 +268,6 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   auto load_rec = [&](uint32_t item) -> uint32_t {
     return lane < 8 ? reinterpret_cast<const uint32_t*>(A.item_list + 2 * (size_t)item)[lane] : 0u;
   };
-  draw();
   for (;;) {
     const uint32_t item = resolve();
     if (item == kNone) break;  // every wave leaves here, once all pools are empty
