@@ -1,5 +1,7 @@
 """GPU parity tests: the HIP library (through its C ABI) against the CPU oracle, element by element,
 on small seeded workloads that still span several tiles, splits and ragged tails."""
+import os
+
 import numpy as np
 import pytest
 
@@ -232,6 +234,50 @@ def test_mfma_kernel_head_dim_64_and_256(dtype, src_f32, head_dim, group):
         print(par.run_and_check([0], kernel_mode=2))
         par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)  # size tiers, whole ring turns
         print(par.run_and_check([0], kernel_mode=2))
+    finally:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
+        par.close()
+
+
+def _random_mfma_cases(n_cases, seed=20250906):
+    """Seeded shapes for the MFMA kernel: every head_dim and format, group sizes on both softmax layouts, slab sizes
+    that give blocks of 8 to a few hundred tokens (mostly no multiple of 8), one to three KV heads and layers, lengths
+    around the block and run boundaries, forced split sizes or the size tiers."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n_cases):
+        dtype = [FP16, FP8, INT8, INT4][i % 4]
+        head_dim = [64, 128, 256][(i // 4) % 3]
+        group = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+        n_kv = int(rng.integers(1, 4))
+        n_layers = int(rng.integers(1, 4))
+        bits = {FP16: 16, FP8: 8, INT8: 8, INT4: 4}[dtype]
+        tok_bytes = 2 * n_kv * n_layers * (head_dim * bits // 8 + {FP16: 0, FP8: 0, INT8: 2, INT4: 4}[dtype])
+        want_T = int(rng.choice([8, 9, 13, 16, 23, 38, 60, 64, 126, 200]))
+        slab = max(4096, -(-want_T * tok_bytes // 1024) * 1024 + int(rng.integers(0, 2)) * 1024)
+        split = int(rng.choice([0, 0, 8 * KiB, 24 * KiB, 100 * KiB]))
+        n_seq = int(rng.integers(2, 7))
+        T = max(slab // tok_bytes, 1)
+        special = [1, 2, 7, 8, 9, T - 1, T, T + 1, 2 * T, 4 * T + 3, 31, 32, 33, 700, 1500]
+        lens = [int(max(1, rng.choice(special))) for _ in range(n_seq - 1)] + [int(rng.integers(300, 2500))]
+        cases.append(pytest.param(dtype, head_dim, group, n_kv, n_layers, slab, split, lens,
+                                  id=f"{i}-dt{dtype}-d{head_dim}-g{group}-h{n_kv}-l{n_layers}-slab{slab}-split{split}"))
+    return cases
+
+
+# (FS_RANDOM_SHAPES=<n> widens the sweep for a one-off run)
+@pytest.mark.parametrize("dtype,head_dim,group,n_kv,n_layers,slab,split,lens",
+                         _random_mfma_cases(int(os.environ.get("FS_RANDOM_SHAPES", "36"))))
+def test_mfma_kernel_on_seeded_random_shapes(dtype, head_dim, group, n_kv, n_layers, slab, split, lens):
+    lens = np.array(lens, np.int32)
+    spec = ModelSpec("m", dtype, n_kv, head_dim, n_layers, n_kv * group, lens, tag=48, src_f32=dtype == INT4)
+    wl = Workload("rand", slab, slab * (96 * MiB // slab), [spec], "shuffle")
+    par = _parity(wl)
+    try:
+        if par.gw.T[par.gw.model_ids[0]] < 8:
+            pytest.skip("fewer than 8 tokens per block: the generic kernel's shape")
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, split)
+        print(par.gw.T, par.run_and_check([n_layers - 1], kernel_mode=2))
     finally:
         par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
         par.close()
