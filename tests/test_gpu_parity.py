@@ -283,6 +283,26 @@ def test_mfma_kernel_on_seeded_random_shapes(dtype, head_dim, group, n_kv, n_lay
         par.close()
 
 
+@pytest.mark.parametrize("mode", KERNEL_MODES)
+def test_many_sequences_per_batch(mode):
+    """700 and 300 short sequences in two batches: the work-list kernel walks a batch in rounds of 256 sequences, and
+    most sequences are a single unsplit item while a few long ones are split."""
+    la = gen.uniform_lengths(11, 1, 700, 1, 150)
+    lb = gen.uniform_lengths(11, 2, 300, 1, 90)
+    la[[5, 300, 699]] = [2000, 1500, 1777]
+    lb[[0, 299]] = [1200, 900]
+    wl = Workload("many", 64 * KiB, 640 * MiB,
+                  [ModelSpec("a", FP16, 2, 128, 1, 8, la, tag=49), ModelSpec("b", INT8, 2, 128, 1, 2, lb, tag=50)],
+                  "interleave")
+    par = _parity(wl)
+    try:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 32 * KiB)
+        print(par.run_and_check([0, 0], kernel_mode=mode))
+    finally:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
+        par.close()
+
+
 def test_one_launch_over_models_of_different_head_dim():
     """Two models of head_dim 64 and 128 in one pool and one multi-model launch: the MFMA kernel serves one head_dim
     per launch, so the automatic choice falls to the generic kernel (results as always), and forcing the MFMA kernel
