@@ -4,6 +4,7 @@ sizes that fill the 16 logit columns differently, odd tokens per block, contexts
 import numpy as np
 import pytest
 
+from fs_inputs import gen
 from fs_inputs.workloads import FP16, FP8, INT4, INT8, KiB, MiB, ModelSpec, Workload
 
 pytestmark = pytest.mark.gpu
@@ -147,6 +148,23 @@ def test_softmax_scales_other_than_the_usual(sm_scale):
         par.gw.populate([[0], [0]])
         for k in (0, 1):
             print("scale", sm_scale, "model", k, par.prefill_and_check(k, 0, lens, sm_scale=sm_scale))
+    finally:
+        par.close()
+
+
+def test_five_thousand_short_sequences():
+    """More sequences than the workgroup kernels keep tile counts for in LDS (4095) and than one round of the
+    preparation kernel's scan: short prompts, chunks of one to a few tokens, some empty."""
+    lens = gen.uniform_lengths(13, 1, 5000, 1, 40)
+    wl = Workload("pf5k", 64 * KiB, 512 * MiB, [ModelSpec("m", FP8, 2, 128, 1, 8, lens, tag=37)], "shuffle")
+    par = _parity(wl)
+    try:
+        par.gw.populate([[0]])
+        n_new = np.minimum(lens, gen.uniform_lengths(13, 2, 5000, 0, 5)).astype(np.int32)
+        err, rows = par.prefill_and_check(0, 0, n_new)
+        print("chunks: rows", rows, "max abs err", err)
+        err, rows = par.prefill_and_check(0, 0, lens, seqs=np.arange(0, 5000, 7))  # whole prompts, every seventh checked
+        print("whole prompts: rows", rows, "max abs err", err)
     finally:
         par.close()
 
