@@ -214,6 +214,26 @@ class Timed:
                 f"/T{self.gw.T[self.gw.model_ids[k]]}/{s.n_seq}seq" for k, s in enumerate(self.wl.models)]
 
 
+def batched_allocator_rate(slab_bytes, n_slabs=65536, seq_blocks=64, rounds=40):
+    """Blocks allocated + freed per second through fs_blocks_alloc / fs_blocks_free, a sequence's blocks per call
+    (host bookkeeping only: the pool is created over an address that is never touched)."""
+    from paper_2509_06261_amd import binding as fs
+
+    pool = fs.fs_pool_create(slab_bytes, n_slabs * slab_bytes, 0x10000000)
+    try:
+        _, m = fs.fs_model_register(pool, 0, 8, 128, 8, None)
+        n_seq = n_slabs // seq_blocks
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            held = [fs.fs_blocks_alloc(pool, m, seq_blocks)[1] for _ in range(n_seq)]
+            for ids in held[::2] + held[1::2]:
+                fs.fs_blocks_free(pool, m, ids)
+        dt = time.perf_counter() - t0
+        return 2.0 * rounds * n_seq * seq_blocks / dt
+    finally:
+        fs.fs_pool_destroy(pool)
+
+
 def summary(r):
     """value / kernel numbers of one Timed.run result, for the `extra` entries."""
     import numpy as np
@@ -337,6 +357,7 @@ def main():
             "kv_bytes_per_launch": int(kv_bytes),
             "alloc_free_calls": tw.n_alloc_ops,
             "alloc_free_calls_per_s_host": round(tw.n_alloc_ops / max(tw.t_place, 1e-9), 1),
+            "alloc_free_blocks_per_s_batched": round(batched_allocator_rate(wl.slab_bytes), 1),
         },
     }
     # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, calibrated against a plain

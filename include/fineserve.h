@@ -114,6 +114,13 @@ int fs_model_geometry(fs_pool* pool, fs_model_t model, fs_geometry_t* out);
  * a slab whose last block is freed returns to the shared tensor as FREE. */
 int fs_block_alloc(fs_pool* pool, fs_model_t model, int32_t* blk_id_out);
 int fs_block_free(fs_pool* pool, fs_model_t model, int32_t blk_id);
+/* The blocks of a whole sequence (or prefill chunk) in one call, host pointers: fs_blocks_alloc writes the n ids that
+ * n successive fs_block_alloc calls would return, in that order, or returns FS_ERR_NOMEM and takes none if fewer
+ * than n are left for this model (its PARTIAL slabs' free blocks plus the FREE slabs).  fs_blocks_free frees ids[0],
+ * ids[1], ... like successive fs_block_free calls and stops at the first one that fails (its error is returned, the
+ * ids before it stay freed).  n == 0 is a no-op. */
+int fs_blocks_alloc(fs_pool* pool, fs_model_t model, int32_t n, int32_t* blk_ids_out);
+int fs_blocks_free(fs_pool* pool, fs_model_t model, const int32_t* blk_ids, int32_t n);
 int fs_pool_stats(fs_pool* pool, fs_pool_stats_t* out);
 /* Per-key view of the slab table (Sec. 5.2 keys every slab by the block size -- here the model -- it is formatted
  * for): the slabs this model holds, its live blocks, the free blocks left in its PARTIAL slabs (what the next

@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(_DIR, "libfineserve.so")
 EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
            "fs_block_bytes", "fs_slab_bytes_for_blocks", "fs_model_register_tokens",
            "fs_model_set_fp8_scales", "fs_model_unregister", "fs_model_geometry", "fs_block_alloc", "fs_block_free",
+           "fs_blocks_alloc", "fs_blocks_free",
            "fs_pool_stats", "fs_pool_dump", "fs_model_dump_live", "fs_kv_append", "fs_kv_append_multi", "fs_decode_step_multi",
            "fs_decode_workspace_bytes",
            "fs_decode_attention", "fs_decode_attention_multi", "fs_decode_attention_multi_static", "fs_decode_status", "fs_prefill_workspace_bytes",
@@ -89,6 +90,8 @@ def _load():
         "fs_model_geometry": (i32, [vp, i32, ctypes.POINTER(fs_geometry_t)]),
         "fs_block_alloc": (i32, [vp, i32, pi32]),
         "fs_block_free": (i32, [vp, i32, ctypes.c_int32]),
+        "fs_blocks_alloc": (i32, [vp, i32, i32, vp]),
+        "fs_blocks_free": (i32, [vp, i32, vp, i32]),
         "fs_pool_stats": (i32, [vp, ctypes.POINTER(fs_pool_stats_t)]),
         "fs_pool_dump": (i32, [vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_int64)]),
         "fs_model_dump_live": (i32, [vp, i32, vp]),
@@ -228,6 +231,18 @@ def fs_block_alloc(pool, model):
 
 def fs_block_free(pool, model, blk_id) -> int:
     return _L.fs_block_free(pool, model, blk_id)
+
+
+def fs_blocks_alloc(pool, model, n: int):
+    """Returns (rc, ids): ids is an int32 numpy array of n block ids (meaningless unless rc == FS_OK)."""
+    ids = np.empty(max(int(n), 1), dtype=np.int32)
+    rc = _L.fs_blocks_alloc(pool, model, int(n), ids.ctypes.data)
+    return rc, ids[:max(int(n), 0)]
+
+
+def fs_blocks_free(pool, model, ids) -> int:
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    return _L.fs_blocks_free(pool, model, ids.ctypes.data, len(ids))
 
 
 def fs_pool_stats(pool) -> fs_pool_stats_t:

@@ -330,6 +330,30 @@ int fs_block_free(fs_pool* p, fs_model_t model, int32_t blk_id) {
   return FS_OK;
 }
 
+int fs_blocks_alloc(fs_pool* p, fs_model_t model, int32_t n, int32_t* blk_ids_out) {
+  Model* M = get_model(p, model);
+  if (!M || n < 0 || (n > 0 && !blk_ids_out)) return FS_ERR_INVALID;
+  // all or none: what this model can still get
+  const int64_t bps = M->g.blocks_per_slab;
+  int64_t avail = (int64_t)p->free_stack.size() * bps;
+  for (auto it = M->partial_slabs.begin(); it != M->partial_slabs.end() && avail < n; ++it) avail += bps - p->used[*it];
+  if (avail < n) return FS_ERR_NOMEM;
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = fs_block_alloc(p, model, blk_ids_out + i);
+    if (rc != FS_OK) return rc;  // (cannot happen: counted above)
+  }
+  return FS_OK;
+}
+
+int fs_blocks_free(fs_pool* p, fs_model_t model, const int32_t* blk_ids, int32_t n) {
+  if (!get_model(p, model) || n < 0 || (n > 0 && !blk_ids)) return FS_ERR_INVALID;
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = fs_block_free(p, model, blk_ids[i]);
+    if (rc != FS_OK) return rc;
+  }
+  return FS_OK;
+}
+
 int fs_pool_stats(fs_pool* p, fs_pool_stats_t* out) {
   if (!p || !out) return FS_ERR_INVALID;
   fs_pool_stats_t s{};

@@ -109,6 +109,18 @@ void allocator_traces() {
     CHECK(fs_model_unregister(p, m[0]) == (held[0].empty() ? FS_OK : FS_ERR_STATE));
     for (int k = 0; k < 3; ++k)
       for (int32_t b : held[k]) CHECK(fs_block_free(p, m[k], b) == FS_OK);
+    // the batched calls: a whole sequence's blocks at once, more than the pool holds, none, bad arguments
+    {
+      std::vector<int32_t> ids(33);
+      CHECK(fs_blocks_alloc(p, m[1], 33, ids.data()) == FS_OK);
+      CHECK(fs_blocks_alloc(p, m[1], 1 << 30, ids.data()) == FS_ERR_NOMEM);
+      CHECK(fs_blocks_alloc(p, m[1], 0, nullptr) == FS_OK);
+      CHECK(fs_blocks_alloc(p, m[1], -3, ids.data()) == FS_ERR_INVALID);
+      CHECK(fs_blocks_alloc(p, m[1], 2, nullptr) == FS_ERR_INVALID);
+      CHECK(fs_blocks_free(p, m[1], ids.data(), 33) == FS_OK);
+      CHECK(fs_blocks_free(p, m[1], ids.data(), 1) == FS_ERR_STATE);
+      CHECK(fs_blocks_free(p, m[1], nullptr, 0) == FS_OK);
+    }
     fs_pool_stats_t st;
     CHECK(fs_pool_stats(p, &st) == FS_OK);
     CHECK(st.slabs_free == st.n_slabs && st.live_blocks == 0);

@@ -138,6 +138,59 @@ def test_allocator_matches_oracle_many_blocks_per_slab():
     _run_trace(slab, 96, specs, 300_000, seed=12)
 
 
+def test_batched_alloc_and_free_equal_successive_single_calls():
+    """fs_blocks_alloc / fs_blocks_free against the oracle's allocator called once per block: the same ids in the same
+    order, the same slab table afterwards; a request the pool cannot serve whole takes nothing."""
+    slab = 256 * KiB
+    specs = [(0, 4, 64, 1, slab // 4), (2, 4, 64, 1, slab), (3, 2, 64, 2, slab // 16)]
+    n_slabs = 64
+    o = oracle.Pool(slab, n_slabs * slab)
+    a = FsPoolAdapter(slab, n_slabs * slab)
+    om = [o.model_add(*sp) for sp in specs]
+    am = [a.model_add(*sp) for sp in specs]
+    held = [[] for _ in specs]
+    r = gen.uniform_ints(21, 6, 4000, 1 << 40)
+    refused = 0
+    for step in range(4000):
+        x = int(r[step])
+        k = x % len(specs)
+        if (x >> 8) % 100 < 45 and held[k]:
+            ids = held[k].pop((x >> 16) % len(held[k]))
+            for b in ids:
+                assert o.free(om[k], int(b)) == 0
+            assert fs.fs_blocks_free(a.pool, am[k], ids) == 0
+        else:
+            n = (x >> 20) % 40
+            rc, ids = fs.fs_blocks_alloc(a.pool, am[k], n)
+            want, rco = [], 0
+            before = o.dump()
+            for _ in range(n):
+                rco, b = o.alloc(om[k])
+                if rco != 0:
+                    break
+                want.append(b)
+            if rco != 0:  # the oracle ran out part-way: the batched call must have refused and taken nothing
+                for b in reversed(want):
+                    assert o.free(om[k], b) == 0
+                assert all(np.array_equal(u, v) for u, v in zip(before, o.dump()))  # (freeing in reverse restores it)
+                assert rc == fs.FS_ERR_NOMEM
+                refused += 1
+            else:
+                assert rc == 0 and list(ids) == want
+                if n:
+                    held[k].append(np.array(want, np.int32))
+        if step % 500 == 499 or step == 3999:
+            for u, v in zip(o.dump(), fs.fs_pool_dump(a.pool)):
+                assert np.array_equal(u, v)
+            for u, v in zip(om, am):
+                assert np.array_equal(o.dump_live(u), fs.fs_model_dump_live(a.pool, v))
+    assert refused > 0
+    bad = np.array([held[0][0][0], 10 ** 6], np.int32) if held[0] else np.array([10 ** 6], np.int32)
+    assert fs.fs_blocks_free(a.pool, am[0], bad) < 0
+    assert fs.fs_blocks_alloc(a.pool, am[0], -1)[0] == fs.FS_ERR_INVALID
+    a.close()
+
+
 def test_paper_direction_sizing_matches_oracle():
     """fs_block_bytes / fs_slab_bytes_for_blocks / fs_model_register_tokens (Sec. 3.2 forward, Sec. 5.2 lcm slab)."""
     rng = np.random.default_rng(21)
