@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="workload: 2..5 (BASELINE.json configs, 1-based)")
+    ap.add_argument("--head-dim", type=int, default=0, help="a copy of the workload with this head_dim (0 = as configured)")
     ap.add_argument("--chunk", type=int, default=0, help="tokens prefilled per sequence (0 = the whole prompt)")
     ap.add_argument("--layers", type=int, default=2, help="layers populated and rotated over")
     ap.add_argument("--only-model", type=int, default=-1, help="only model k of the workload")
@@ -69,6 +70,8 @@ def main():
     options = {fs.FS_OPT_PREFILL_COLUMN_BLOCKS: ker_blocks, fs.FS_OPT_PREFILL_WAVES: ker_waves,
                fs.FS_OPT_PREFILL_PIPELINED: int(args.pipelined), fs.FS_OPT_PREFILL_STAGED_DEQUANT: int(args.staged_dequant)}
     wl = workloads.config(args.config)
+    if args.head_dim:
+        wl = workloads.with_head_dim(wl, args.head_dim)
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
     gw = harness.GpuWorkload(wl, options=options)

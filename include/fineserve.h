@@ -258,9 +258,10 @@ int fs_decode_status(const void* workspace, void* stream);
  *            set if a length or a chunk size was out of range (clamped), bit 2 (value 4) if a block-table entry
  *            named no block of the pool (read as block 0; the affected rows are meaningless).
  * At most 16 query heads per KV head (FS_ERR_INVALID otherwise).  head_dim 128 with at least 8 tokens per block
- * runs on the MFMA kernels; every other shape the pool accepts on a vector-ALU kernel (one workgroup per query
- * row and KV head: correct, far slower).  A softmax scale that is not positive and finite is served by the
- * slowest MFMA kernel variant.
+ * runs on the MFMA kernels; head_dim 64 and 256 on the 16-column MFMA kernel (the other variants are built for 128;
+ * FS_OPT_PREFILL_COLUMN_BLOCKS is not consulted); every other shape the pool accepts on a vector-ALU kernel (one
+ * workgroup per query row and KV head: correct, far slower).  A softmax scale that is not positive and finite is
+ * served by the 16-column kernel as well.
  * Asynchronous on `stream`; no allocation, no host synchronisation. */
 uint64_t fs_prefill_workspace_bytes(int n_seq);
 int fs_prefill_attention(fs_pool* pool, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,

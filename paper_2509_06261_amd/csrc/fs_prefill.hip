@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kPrepThreads) void prefill_prep_kernel(PrefillArgs 
   if (tid == 0) P.tile_first[B.n_seq] = s_running;
 }
 
-template <int DT>
+template <int DT, int HD = kD>
 __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, uint64_t* s_ptr) {
   constexpr int GP = 16;  // every logit column is live: one column per lane in the softmax
   const DevBatch& B = P.b;
@@ -116,9 +116,10 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
   X.len = live ? first_pos + tok_c + 1 : 1;     // causality: a column sees the tokens up to its own position
   X.chunk_ptr = s_ptr;
 
-  u32x4 qb[4];
+  constexpr int NE = HD / 16;  // output columns NE c .. NE c + NE - 1 are this lane's
+  u32x4 qb[HD / 32];
   float qsum;
-  load_q<DT>(B.q + ((int64_t)row_c * B.n_q + head * G + hg_c) * kD, live, j, qb, qsum);
+  load_q<DT, true, HD>(B.q + ((int64_t)row_c * B.n_q + head * G + hg_c) * HD, live, j, qb, qsum);
   if constexpr (Fmt<DT>::kParBytes != 0) {
     qsum += __shfl_xor(qsum, 16, 64);
     qsum += __shfl_xor(qsum, 32, 64);
@@ -126,9 +127,9 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
   float alpha = B.sm_scale * kLog2e;
   if (DT == FS_KV_FP8_E4M3) alpha *= B.k_scale[head];
 
-  State st;
+  StateT<HD> st;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
+  for (int e = 0; e < NE; ++e) st.acc[e] = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = -INFINITY;
   st.l = 0.f;
   st.zc = 0.f;
@@ -140,7 +141,7 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
     X.v_end = min(n_run, v0 + P.seg_runs);
     X.k0 = div_runs(v0, B.R, B.r_magic);
     fill_table(s_ptr, table, head_base, g.block_budget, X.k0, div_runs(X.v_end - 1, B.R, B.r_magic) - X.k0 + 1, lane, B.n_blocks, P.header);
-    stream_tiles<DT, GP>(X, g, v0, qb, qsum, alpha, st, j, c);
+    stream_tiles<DT, GP, HD>(X, g, v0, qb, qsum, alpha, st, j, c);
   }
 
   // ---- output: per-column sums over the four lane groups, then the live rows straight from the accumulators ----
@@ -159,9 +160,9 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
     const int tok_h = h / G, hg_h = h - tok_h * G;
     if (tok_h < n_tok) {
       const float inv = 1.0f / L;
-      u32x4 w;
+      uint32_t w[NE / 2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < NE / 2; ++q) {
         float o[2];
 #pragma unroll
         for (int z = 0; z < 2; ++z) {
@@ -176,7 +177,14 @@ __device__ void prefill_item(const PrefillArgs& P, int seq, int head, int qt, ui
         w[q] = h2u(hv);
       }
       const int64_t qrow = (int64_t)row_h * B.n_q + head * G + hg_h;
-      *reinterpret_cast<u32x4*>(B.out + qrow * kD + 8 * c) = w;
+      _Float16* orow = B.out + qrow * HD + NE * c;
+      if constexpr (NE == 4) {
+        *reinterpret_cast<u32x2*>(orow) = u32x2{w[0], w[1]};
+      } else {
+#pragma unroll
+        for (int q = 0; q < NE / 8; ++q)
+          reinterpret_cast<u32x4*>(orow)[q] = u32x4{w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]};
+      }
       if (c == 0 && B.lse) B.lse[qrow] = (M + __builtin_amdgcn_logf(L)) * kLn2;
     }
   }
@@ -1460,7 +1468,9 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
   }
 }
 
-__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
+// The 16-column kernel; the only MFMA prefill kernel for head_dim 64 and 256 (HD: its tile code takes any of the three).
+template <int HD>
+__global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void prefill_kernel(PrefillArgs P) {
   extern __shared__ uint64_t smem64[];
   const DevBatch& B = P.b;
   const int lane = threadIdx.x & 63;
@@ -1473,10 +1483,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillArgs P) {
     int seq, head, qt;
     if (!decode_item(P, P.tile_first, item, H, seq, head, qt)) continue;
     switch (B.g.dtype) {
-      case FS_KV_FP16: prefill_item<FS_KV_FP16>(P, seq, head, qt, s_ptr); break;
-      case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3>(P, seq, head, qt, s_ptr); break;
-      case FS_KV_INT8: prefill_item<FS_KV_INT8>(P, seq, head, qt, s_ptr); break;
-      default: prefill_item<FS_KV_INT4>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_FP16: prefill_item<FS_KV_FP16, HD>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_FP8_E4M3: prefill_item<FS_KV_FP8_E4M3, HD>(P, seq, head, qt, s_ptr); break;
+      case FS_KV_INT8: prefill_item<FS_KV_INT8, HD>(P, seq, head, qt, s_ptr); break;
+      default: prefill_item<FS_KV_INT4, HD>(P, seq, head, qt, s_ptr); break;
     }
   }
 }
@@ -1529,7 +1539,8 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   // the wide kernels fold the (positive) softmax scale into the exponential's argument; any other scale takes
   // the 16-column kernel, which does not
   const bool scale_ok = sm_scale > 0.f && sm_scale < INFINITY;
-  int ncb = !scale_ok ? 1 : (ncb_env ? ncb_env : ncb_default);
+  // (head_dim 64 and 256: the 16-column kernel is the one whose tile code is built for them)
+  int ncb = !scale_ok || g.head_dim != kD ? 1 : (ncb_env ? ncb_env : ncb_default);
   uint64_t tiles = 0;
   for (int pass = 0; pass < 2; ++pass) {
     tiles = 0;
@@ -1583,7 +1594,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
   B.tier_seq[0] = B.tier_seq[1] = B.tier_seq[2] = 0x7fffffff;  // (decode's split sizes: not used by prefill)
   B.ring_runs = 4;
-  const bool generic = B.g.D != kD || !mfma_supports(B);  // head_dim other than 128, or blocks of fewer than 8 tokens
+  const bool generic = !mfma_supports(B);  // head_dim other than 64, 128 or 256, or blocks of fewer than 8 tokens
   if (generic && (g.head_dim & (g.head_dim - 1))) {
     set_error("prefill attention: head_dim must be a power of two");
     return FS_ERR_INVALID;
@@ -1617,7 +1628,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   }
   const uint64_t items = tiles * (uint64_t)g.n_kv_heads;
   // waves per SIMD: the 16-column kernel runs two, the wider wave-level ones one
-  const int wps = ncb == 1 ? 2 : 1;
+  const int wps = ncb == 1 ? mfma_wgs_per_cu(g.head_dim) : 1;
   // workgroup kernels: 16 blocks = 8 waves x 2 (default) or 4 x 4, 4 sub-tiles per step, one workgroup per compute unit
   const bool wg = ncb == 16;
   const int nw = p->opt.prefill_nw == 4 ? 4 : 8;
@@ -1655,7 +1666,9 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
     hipLaunchKernelGGL(kern, dim3(n_wg), dim3(nw * 64), smem, s, P);
   } else if (ncb == 1) {
     p->opt.last_prefill = 1;
-    hipLaunchKernelGGL(prefill_kernel, dim3(n_wg), dim3(kThreads), smem, s, P);
+    if (g.head_dim == 64) hipLaunchKernelGGL(prefill_kernel<64>, dim3(n_wg), dim3(kThreads), smem, s, P);
+    else if (g.head_dim == 256) hipLaunchKernelGGL(prefill_kernel<256>, dim3(n_wg), dim3(kThreads), smem, s, P);
+    else hipLaunchKernelGGL(prefill_kernel<kD>, dim3(n_wg), dim3(kThreads), smem, s, P);
   } else {
     void (*kern)(PrefillArgs) = nullptr;
 #define FS_WIDE(DT) (ncb == 4 ? prefill_wide_kernel<DT, 4, 1> : prefill_wide_kernel<DT, 2, 1>)

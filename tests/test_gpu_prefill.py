@@ -23,9 +23,9 @@ def kernel_variant(request):
 
     name, blocks, waves = request.param
     test = request.node.name
-    if test.startswith("test_other_shapes"):
+    if test.startswith("test_shapes_beside_head_dim_128"):
         if name != "auto":
-            pytest.skip("shapes outside the MFMA kernels take the vector-ALU kernel whatever variant is set")
+            pytest.skip("shapes beside head_dim 128 take the same kernel whatever variant is set")
     elif name == "wg8dq":
         fp = test.startswith(("test_gqa_8b_shape", "test_mha_13b")) and ("[wg8dq-0" in test or "[wg8dq-1" in test)
         if test.startswith("test_long_context") or fp:
@@ -115,22 +115,32 @@ def test_group_sizes(group):
     (FP16, 64, 4, 4, 64, False),     # the tiny configuration's layer: head_dim 64, MHA
     (INT8, 64, 2, 8, 64, False),     # head_dim 64, four query heads per KV head
     (INT4, 256, 2, 4, 128, True),    # head_dim 256
+    (FP8, 64, 2, 4, 32, False),      # the other formats at head_dim 64 and 256; more than four query heads per KV head
+    (INT4, 64, 2, 16, 24, True),
+    (FP16, 256, 2, 2, 128, False),
+    (FP8, 256, 1, 6, 64, False),
+    (INT8, 256, 2, 10, 96, False),
     (FP8, 32, 2, 6, 16, False),      # head_dim 32, three query heads per KV head (a ragged last group of the kernel)
     (FP16, 128, 8, 8, 16, False),    # head_dim 128 in 16 KiB slabs: 2 tokens per block, fewer than an MFMA run
     (INT8, 8, 2, 4, 16, False),      # the smallest head_dim: one lane per row
     (FP16, 512, 2, 2, 64, False),    # the largest: a whole wave per row
 ])
-def test_other_shapes_take_the_vector_kernel(dtype, head_dim, kv_heads, q_heads, slab_kib, src_f32):
-    """Shapes the MFMA prefill kernels do not cover (head_dim other than 128, blocks of fewer than 8 tokens)."""
+def test_shapes_beside_head_dim_128(dtype, head_dim, kv_heads, q_heads, slab_kib, src_f32):
+    """Head_dim 64 and 256 with at least 8 tokens per block run the 16-column MFMA kernel (whatever kernel the options
+    ask for); every other shape the pool accepts (other head_dims, blocks of fewer than 8 tokens) the vector-ALU
+    kernel.  The pool's record of the launched kernel says which one ran."""
     lens = np.array([1, 2, 7, 33, 100, 257], np.int32)
-    wl = Workload("pfgen", slab_kib * KiB, 32 * MiB,
+    wl = Workload("pfgen", slab_kib * KiB, slab_kib * KiB * (32 * MiB // (slab_kib * KiB)),
                   [ModelSpec("m", dtype, kv_heads, head_dim, 2, q_heads, lens, tag=37, src_f32=src_f32)], "shuffle")
     par = _parity(wl)
     try:
         par.gw.populate([[1]])
-        print("T", par.gw.T)
+        T = par.gw.T[par.gw.model_ids[0]]
+        print("T", T)
         print(par.prefill_and_check(0, 1, lens))
         print(par.prefill_and_check(0, 1, np.array([1, 0, 3, 33, 17, 200], np.int32)))
+        ran = par.fs.fs_pool_get_option(par.gw.pool, par.fs.FS_OPT_LAST_PREFILL_KERNEL)
+        assert ran == (1 if head_dim in (64, 256) and T >= 8 else 1 << 18), ran
     finally:
         par.close()
 
