@@ -19,10 +19,9 @@ pytestmark = pytest.mark.gpu
 
 # config -> (layer per model, oracle sample per model (None = every sequence), prefill sample per model)
 # "2-d64" / "2-d256": config 2 with head_dim 64 / 256, the launches bench.py times on the MFMA decode kernel's other two
-# instantiations (whole-prompt prefill is not run there: the MFMA prefill kernels cover head_dim 128, and the
-# vector-ALU prefill path of other shapes, one workgroup per query row, is a small-workload parity case)
+# instantiations (whole-prompt prefill there runs the 16-column MFMA kernel)
 CONFIGS = {"2": ([17], None, 3), "3": ([3, 29], 32, 1), "4": ([11], 32, 1), "5": ([7, 0, 3, 9], 32, 1),
-           "2-d64": ([17], None, 0), "2-d256": ([17], None, 0)}
+           "2-d64": ([17], None, 1), "2-d256": ([17], None, 1)}
 
 
 @pytest.fixture(scope="module", params=sorted(CONFIGS), ids=lambda c: f"config{c}")
@@ -120,7 +119,5 @@ def test_whole_prompt_prefill_windows_against_the_oracle(stood_up, k):
     par, wl = stood_up["par"], stood_up["wl"]
     if k >= len(wl.models):
         pytest.skip("the config has fewer models")
-    if not stood_up["prefill_random"]:
-        pytest.skip("head_dim copy of a config: decode only (whole-prompt prefill is timed and checked at head_dim 128)")
     perr = par.prefill_whole_prompts_and_check_windows(k, stood_up["layers"][k], stood_up["prefill_random"])
     print(f"[full-size] config {stood_up['cfg']}: prefill model {k}: max abs err {perr[0]:.2e} on {perr[1]} rows", flush=True)
