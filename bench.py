@@ -255,6 +255,7 @@ def main():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload: 2..5 (BASELINE.json configs, 1-based)")
+    ap.add_argument("--head-dim", type=int, default=0, help="a copy of the workload with this head_dim (0 = as configured)")
     ap.add_argument("--kernel-mode", type=int, default=0, help="0 auto, 1 generic kernel, 2 MFMA kernel")
     ap.add_argument("--split-bytes", type=int, default=0)
     ap.add_argument("--layers", type=int, default=0, help="populate only the first N layers (0 = all)")
@@ -282,11 +283,14 @@ def main():
 
     t_setup = time.perf_counter()
     wl = workloads.config(args.config)
+    if args.head_dim:
+        wl = workloads.with_head_dim(wl, args.head_dim)
     if args.identity:
         wl.placement = "identity"
     if args.only_model >= 0:
         wl.models = [wl.models[args.only_model]]
-    plain = not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers or args.split_bytes)
+    plain = not (args.identity or args.only_model >= 0 or args.kernel_mode == 1 or args.layers or args.split_bytes or
+                 args.head_dim)
     options = {}
     if args.kernel_mode:
         options[fs.FS_OPT_DECODE_KERNEL] = args.kernel_mode
