@@ -285,11 +285,11 @@ def test_mfma_kernel_on_seeded_random_shapes(dtype, head_dim, group, n_kv, n_lay
 
 @pytest.mark.parametrize("mode", KERNEL_MODES)
 def test_many_sequences_per_batch(mode):
-    """700 and 300 short sequences in two batches: the work-list kernel walks a batch in rounds of 256 sequences, and
-    most sequences are a single unsplit item while a few long ones are split."""
-    la = gen.uniform_lengths(11, 1, 700, 1, 150)
+    """2500 and 300 short sequences in two batches: the work-list kernel walks a batch in rounds of 1024 sequences
+    (three for the first batch), and most sequences are a single unsplit item while a few long ones are split."""
+    la = gen.uniform_lengths(11, 1, 2500, 1, 60)
     lb = gen.uniform_lengths(11, 2, 300, 1, 90)
-    la[[5, 300, 699]] = [2000, 1500, 1777]
+    la[[5, 1023, 1024, 2499]] = [2000, 1500, 1777, 1300]
     lb[[0, 299]] = [1200, 900]
     wl = Workload("many", 64 * KiB, 640 * MiB,
                   [ModelSpec("a", FP16, 2, 128, 1, 8, la, tag=49), ModelSpec("b", INT8, 2, 128, 1, 2, lb, tag=50)],
