@@ -89,17 +89,30 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
 #pragma unroll
   for (int b = 0; b < kMaxBatches; ++b) count[b] = b < A.n_batches ? s_count[b] : 0u;
 
-  // pass 2: per-sequence first items and the records
-  uint32_t running = 0;  // items before the current round, sequence-major (same value in every thread)
+  // pass 2: per-sequence first items and the records.  The batches are dealt to the workgroups (workgroup g walks
+  // the batches g % n_batches, + n_groups, ...: with as many workgroups as batches or more, exactly one), so that
+  // the batches' scans run side by side instead of one after the other in every workgroup; the first workgroup of a
+  // batch writes the batch's and its sequences' words.
+  uint32_t total_items = 0;
   uint64_t part_running = 0;
   for (int b = 0; b < A.n_batches; ++b) {
     const DevBatch& B = A.b[b];
     const uint32_t H = (uint32_t)B.g.H;
-    const uint32_t batch_first = running;
+    const uint32_t batch_first = total_items;
     const uint64_t n_b = count[b];
-    if (leader && tid == 0) {
+    const uint64_t batch_part = part_running;
+    total_items += count[b];
+    part_running += (uint64_t)count[b] * (uint64_t)B.part_stride;
+    // the workgroups of this batch: b, b + n_batches, ... (all of them if there are fewer workgroups than batches)
+    const bool dealt = n_groups >= (uint32_t)A.n_batches;
+    if (dealt && group % (uint32_t)A.n_batches != (uint32_t)b) continue;
+    const uint32_t b_group = dealt ? group / (uint32_t)A.n_batches : group;
+    const uint32_t b_groups = dealt ? (n_groups - (uint32_t)b + (uint32_t)A.n_batches - 1) / (uint32_t)A.n_batches : n_groups;
+    const bool b_leader = b_group == 0;
+    uint32_t running = batch_first;  // items before the current round, sequence-major (same value in every thread)
+    if (b_leader && tid == 0) {
       A.header[kHdrBatchFirst + b] = batch_first;
-      part_off[b] = part_running;
+      part_off[b] = batch_part;
     }
     for (int base = 0; base < B.n_seq; base += kPrepThreads) {
       const int i = base + tid;
@@ -121,10 +134,10 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
       s_incl[tid] = incl;
       __syncthreads();
       const uint32_t round_items = s_incl[kPrepThreads - 1];
-      if (leader && i < B.n_seq) A.item_base[B.seq_first + i] = running + incl - v;
+      if (b_leader && i < B.n_seq) A.item_base[B.seq_first + i] = running + incl - v;
       // item r of the round (sequence-major: sequence, then split, KV heads innermost) belongs to the first
       // sequence k whose inclusive count exceeds r
-      for (uint32_t r = group * kPrepThreads + tid; r < round_items; r += n_groups * kPrepThreads) {
+      for (uint32_t r = b_group * kPrepThreads + tid; r < round_items; r += b_groups * kPrepThreads) {
         int lo = 0, hi = kPrepThreads - 1;
         while (lo < hi) {
           const int mid = (lo + hi) >> 1;
@@ -151,12 +164,11 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
       __syncthreads();  // s_incl, s_len and s_wave are rewritten by the next round
       running += round_items;
     }
-    part_running += (uint64_t)(running - batch_first) * (uint64_t)B.part_stride;
   }
   if (leader && tid == 0) {
-    A.item_base[A.n_seq_total] = running;
-    if (running > A.item_capacity) atomicOr(A.header + kHdrStatus, 2u);  // lengths exceed what the workspace was sized for
-    A.header[kHdrTotalItems] = min(running, A.item_capacity);
+    A.item_base[A.n_seq_total] = total_items;
+    if (total_items > A.item_capacity) atomicOr(A.header + kHdrStatus, 2u);  // lengths exceed what the workspace was sized for
+    A.header[kHdrTotalItems] = min(total_items, A.item_capacity);
     A.header[kHdrCounter] = 0;
   }
 }
