@@ -308,9 +308,10 @@ int fs_sched_place_models(const double* footprint, const double* mu, int n_model
  * host thread at a time, and so are its options).  fs_pool_set_option returns FS_ERR_INVALID for an unknown option
  * or a value outside its range; fs_pool_get_option reads the current value. */
 enum fs_option {
-  /* decode kernel: 0 = automatic (default: the MFMA kernel where every batch of the launch has the same head_dim of
-   * 64, 128 or 256 and at least 8 tokens per block, else the generic kernel), 1 = the generic vector-ALU kernel,
-   * 2 = the MFMA kernel (a launch with a shape it lacks then fails with FS_ERR_INVALID) */
+  /* decode kernel: 0 = automatic (default: the MFMA kernel where every batch of the call has a head_dim of 64, 128
+   * or 256 and at least 8 tokens per block -- batches of different head_dims are then served by one launch sequence
+   * per head_dim --, else the generic kernel for the whole call), 1 = the generic vector-ALU kernel, 2 = the MFMA
+   * kernel (a call with a shape it lacks then fails with FS_ERR_INVALID) */
   FS_OPT_DECODE_KERNEL = 0,
   /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose
    * sizes in four tiers: 3/8 of a wave's share of the launch's KV bytes (judged from seq_lens_host where given,
@@ -319,7 +320,8 @@ enum fs_option {
    * fs_decode_workspace_bytes answers for the pool's current setting. */
   FS_OPT_SPLIT_BYTES = 1,
   /* non-zero: every decode call brackets its attention kernel (not the work-list and combine kernels) with HIP
-   * events on the call's stream; fs_pool_last_attention_kernel_ms waits for the latest pair */
+   * events on the call's stream; fs_pool_last_attention_kernel_ms waits for the latest pair.  (A call served by
+   * several launch sequences, one per head_dim: from the first attention kernel's start to the last one's end.) */
   FS_OPT_KERNEL_TIMING = 2,
   /* prefill kernel: 0 = automatic (default: the workgroup kernel, or the 16-column kernel for launches with fewer
    * work items than compute units), 1 / 2 / 4 = the wave-level kernels with 16 / 32 / 64 logit columns per wave,

@@ -523,8 +523,10 @@ using namespace fs;
 namespace {
 // Validates, lays the workspace out and enqueues work-list preparation, attention and split combine on `s`.
 // Allocates nothing.
-int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
-                  const char* too_small, hipStream_t s, const fs_append_t* appends = nullptr, int n_appends = 0) {
+// time_begin / time_end: this launch holds the start / the end of what FS_OPT_KERNEL_TIMING brackets.
+int decode_launch_one(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
+                      const char* too_small, hipStream_t s, const fs_append_t* appends, int n_appends, bool time_begin,
+                      bool time_end) {
   Plan plan;
   if (!workspace || ((uintptr_t)workspace & 255)) {
     set_error("decode attention: workspace must be a 256-byte aligned device pointer");
@@ -563,12 +565,91 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
   plan.args.n_workers = use_mfma ? (uint32_t)n_wg * (uint32_t)workers_per_wg : 0u;
   hipError_t e = P.n ? launch_step_front(p, plan.args, P, s) : launch_prep(plan.args, s);
   if (e != hipSuccess) return device_error(e, "prep launch");
-  if (p->opt.timing) (void)hipEventRecord(p->opt.ev0, s);
+  if (p->opt.timing && time_begin) (void)hipEventRecord(p->opt.ev0, s);
   e = use_mfma ? launch_mfma(plan.args, n_wg, s) : launch_generic(plan.args, n_wg, s);
-  if (p->opt.timing) (void)hipEventRecord(p->opt.ev1, s);
+  if (p->opt.timing && time_end) (void)hipEventRecord(p->opt.ev1, s);
   if (e != hipSuccess) return device_error(e, "attention launch");
   e = launch_combine(plan.args, s);
   if (e != hipSuccess) return device_error(e, "combine launch");
+  return FS_OK;
+}
+
+// The MFMA kernel serves one head_dim per launch.  A call whose batches have several head_dims, all of them shapes
+// the MFMA kernel covers, is therefore run as one launch sequence (work list, attention, combine) per head_dim, each
+// in its own slice of the workspace, instead of falling to the vector-ALU kernel as a whole.
+struct HeadDimGroups {
+  int n = 1;                       // 1: the call is one launch
+  int count[3] = {0, 0, 0};
+  fs_batch_t b[3][kMaxBatches];
+};
+
+void group_by_head_dim(const fs_pool* p, const fs_batch_t* batches, int n_batches, HeadDimGroups& G) {
+  G.n = 1;
+  if (!p || !batches || n_batches < 2 || n_batches > kMaxBatches || p->opt.decode_kernel == 1) return;
+  int dims[3] = {0, 0, 0}, n_dims = 0;
+  for (int i = 0; i < n_batches; ++i) {
+    const fs_batch_t& b = batches[i];
+    if (b.model < 0 || b.model >= kMaxModels || !p->models[b.model].in_use) return;  // (make_plan reports it)
+    const fs_geometry_t& g = p->models[b.model].g;
+    if (g.n_kv_heads < 1 || b.n_q_heads < g.n_kv_heads || b.max_blocks < 1) return;
+    DevBatch B{};
+    B.g = dev_geom(g);
+    B.G = b.n_q_heads / g.n_kv_heads;
+    B.max_blocks = b.max_blocks;
+    B.R = (g.tokens_per_block + 7) / 8;
+    if (!mfma_supports(B)) return;
+    int k = 0;
+    while (k < n_dims && dims[k] != g.head_dim) ++k;
+    if (k == n_dims) dims[n_dims++] = g.head_dim;  // (mfma_supports admits three head_dims)
+    G.b[k][G.count[k]++] = b;
+  }
+  if (n_dims < 2) {
+    G.count[0] = G.count[1] = G.count[2] = 0;
+    return;
+  }
+  G.n = n_dims;
+}
+
+__global__ void merge_status_kernel(uint32_t* first, const uint32_t* second, const uint32_t* third) {
+  if (threadIdx.x == 0) first[kHdrStatus] |= second[kHdrStatus] | (third ? third[kHdrStatus] : 0u);
+}
+
+int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
+                  const char* too_small, hipStream_t s, const fs_append_t* appends = nullptr, int n_appends = 0) {
+  HeadDimGroups G;
+  group_by_head_dim(p, batches, n_batches, G);
+  if (G.n == 1)
+    return decode_launch_one(p, batches, n_batches, workspace, workspace_bytes, too_small, s, appends, n_appends, true, true);
+  if (!workspace || ((uintptr_t)workspace & 255)) {
+    set_error("decode attention: workspace must be a 256-byte aligned device pointer");
+    return FS_ERR_INVALID;
+  }
+  // every launch's slice of the workspace; nothing is enqueued unless all of them fit
+  uint8_t* slice[3] = {nullptr, nullptr, nullptr};
+  uint64_t bytes[3] = {0, 0, 0}, used = 0;
+  for (int k = 0; k < G.n; ++k) {
+    Plan plan;
+    const int rc = make_plan(p, G.b[k], G.count[k], nullptr, plan);
+    if (rc != FS_OK) return rc;
+    slice[k] = (uint8_t*)workspace + used;
+    bytes[k] = plan.workspace_bytes;  // (a multiple of 256)
+    used += plan.workspace_bytes;
+  }
+  if (used > workspace_bytes) {
+    set_error(too_small);
+    return FS_ERR_NOMEM;
+  }
+  for (int k = 0; k < G.n; ++k) {
+    // the step's appends ride in the first launch's front kernel: they precede every attention launch of the call
+    const int rc = decode_launch_one(p, G.b[k], G.count[k], slice[k], bytes[k], too_small, s, k == 0 ? appends : nullptr,
+                                     k == 0 ? n_appends : 0, k == 0, k == G.n - 1);
+    if (rc != FS_OK) return rc;
+  }
+  // fs_decode_status reads the first slice's header
+  hipLaunchKernelGGL(merge_status_kernel, dim3(1), dim3(64), 0, s, (uint32_t*)slice[0], (const uint32_t*)slice[1],
+                     (const uint32_t*)slice[2]);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return device_error(e, "status merge launch");
   return FS_OK;
 }
 
@@ -645,9 +726,15 @@ float fs_pool_last_attention_kernel_ms(fs_pool* p) {
 }
 
 uint64_t fs_decode_workspace_bytes(fs_pool* p, const fs_batch_t* batches, int n_batches) {
-  Plan plan;
-  if (make_plan(p, batches, n_batches, nullptr, plan) != FS_OK) return 0;
-  return plan.workspace_bytes;
+  HeadDimGroups G;
+  group_by_head_dim(p, batches, n_batches, G);
+  uint64_t bytes = 0;
+  for (int k = 0; k < G.n; ++k) {
+    Plan plan;
+    if (make_plan(p, G.n == 1 ? batches : G.b[k], G.n == 1 ? n_batches : G.count[k], nullptr, plan) != FS_OK) return 0;
+    bytes += plan.workspace_bytes;
+  }
+  return bytes;
 }
 
 int fs_decode_attention_multi(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace,
