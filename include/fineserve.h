@@ -308,10 +308,10 @@ int fs_sched_place_models(const double* footprint, const double* mu, int n_model
  * host thread at a time, and so are its options).  fs_pool_set_option returns FS_ERR_INVALID for an unknown option
  * or a value outside its range; fs_pool_get_option reads the current value. */
 enum fs_option {
-  /* decode kernel: 0 = automatic (default: the MFMA kernel where every batch of the call has a head_dim of 64, 128
-   * or 256 and at least 8 tokens per block -- batches of different head_dims are then served by one launch sequence
-   * per head_dim --, else the generic kernel for the whole call), 1 = the generic vector-ALU kernel, 2 = the MFMA
-   * kernel (a call with a shape it lacks then fails with FS_ERR_INVALID) */
+  /* decode kernel: 0 = automatic (default: the MFMA kernel for the batches with a head_dim of 64, 128 or 256 and at
+   * least 8 tokens per block, one launch sequence per head_dim, and the generic kernel, in a launch sequence of its
+   * own, for the other batches of the call), 1 = the generic vector-ALU kernel for all, 2 = the MFMA kernel (a call
+   * with a shape it lacks then fails with FS_ERR_INVALID before anything is enqueued) */
   FS_OPT_DECODE_KERNEL = 0,
   /* target KV bytes per split-K work item, rounded to whole 32-token tiles; 0 (default) lets every launch choose
    * sizes in four tiers: 3/8 of a wave's share of the launch's KV bytes (judged from seq_lens_host where given,

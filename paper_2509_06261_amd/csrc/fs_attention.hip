@@ -574,19 +574,21 @@ int decode_launch_one(fs_pool* p, const fs_batch_t* batches, int n_batches, void
   return FS_OK;
 }
 
-// The MFMA kernel serves one head_dim per launch.  A call whose batches have several head_dims, all of them shapes
-// the MFMA kernel covers, is therefore run as one launch sequence (work list, attention, combine) per head_dim, each
-// in its own slice of the workspace, instead of falling to the vector-ALU kernel as a whole.
+// The MFMA kernel serves one head_dim per launch, and a launch with a batch it does not cover runs on the vector-ALU
+// kernel as a whole.  A call whose batches differ in that respect is therefore run as one launch sequence (work list,
+// attention, combine) per kind -- head_dim 64, 128, 256 on the MFMA kernel, everything else on the vector-ALU kernel --
+// each in its own slice of the workspace.
+constexpr int kMaxGroups = 4;
 struct HeadDimGroups {
   int n = 1;                       // 1: the call is one launch
-  int count[3] = {0, 0, 0};
-  fs_batch_t b[3][kMaxBatches];
+  int count[kMaxGroups] = {0, 0, 0, 0};
+  fs_batch_t b[kMaxGroups][kMaxBatches];
 };
 
 void group_by_head_dim(const fs_pool* p, const fs_batch_t* batches, int n_batches, HeadDimGroups& G) {
   G.n = 1;
   if (!p || !batches || n_batches < 2 || n_batches > kMaxBatches || p->opt.decode_kernel == 1) return;
-  int dims[3] = {0, 0, 0}, n_dims = 0;
+  int dims[kMaxGroups] = {0, 0, 0, 0}, n_dims = 0;  // a group's head_dim; 0: the batches the MFMA kernel does not cover
   for (int i = 0; i < n_batches; ++i) {
     const fs_batch_t& b = batches[i];
     if (b.model < 0 || b.model >= kMaxModels || !p->models[b.model].in_use) return;  // (make_plan reports it)
@@ -597,21 +599,22 @@ void group_by_head_dim(const fs_pool* p, const fs_batch_t* batches, int n_batche
     B.G = b.n_q_heads / g.n_kv_heads;
     B.max_blocks = b.max_blocks;
     B.R = (g.tokens_per_block + 7) / 8;
-    if (!mfma_supports(B)) return;
+    const int key = mfma_supports(B) ? g.head_dim : 0;
     int k = 0;
-    while (k < n_dims && dims[k] != g.head_dim) ++k;
-    if (k == n_dims) dims[n_dims++] = g.head_dim;  // (mfma_supports admits three head_dims)
+    while (k < n_dims && dims[k] != key) ++k;
+    if (k == n_dims) dims[n_dims++] = key;  // (mfma_supports admits three head_dims: at most four kinds)
     G.b[k][G.count[k]++] = b;
   }
   if (n_dims < 2) {
-    G.count[0] = G.count[1] = G.count[2] = 0;
+    for (int k = 0; k < kMaxGroups; ++k) G.count[k] = 0;
     return;
   }
   G.n = n_dims;
 }
 
-__global__ void merge_status_kernel(uint32_t* first, const uint32_t* second, const uint32_t* third) {
-  if (threadIdx.x == 0) first[kHdrStatus] |= second[kHdrStatus] | (third ? third[kHdrStatus] : 0u);
+__global__ void merge_status_kernel(uint32_t* first, const uint32_t* second, const uint32_t* third, const uint32_t* fourth) {
+  if (threadIdx.x == 0)
+    first[kHdrStatus] |= second[kHdrStatus] | (third ? third[kHdrStatus] : 0u) | (fourth ? fourth[kHdrStatus] : 0u);
 }
 
 int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, uint64_t workspace_bytes,
@@ -625,12 +628,16 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
     return FS_ERR_INVALID;
   }
   // every launch's slice of the workspace; nothing is enqueued unless all of them fit
-  uint8_t* slice[3] = {nullptr, nullptr, nullptr};
-  uint64_t bytes[3] = {0, 0, 0}, used = 0;
+  uint8_t* slice[kMaxGroups] = {nullptr, nullptr, nullptr, nullptr};
+  uint64_t bytes[kMaxGroups] = {0, 0, 0, 0}, used = 0;
   for (int k = 0; k < G.n; ++k) {
     Plan plan;
     const int rc = make_plan(p, G.b[k], G.count[k], nullptr, plan);
     if (rc != FS_OK) return rc;
+    if (p->opt.decode_kernel == 2 && !plan.all_mfma) {
+      set_error("decode attention: MFMA kernel forced but a batch has a shape it does not support");
+      return FS_ERR_INVALID;
+    }
     slice[k] = (uint8_t*)workspace + used;
     bytes[k] = plan.workspace_bytes;  // (a multiple of 256)
     used += plan.workspace_bytes;
@@ -647,7 +654,7 @@ int decode_launch(fs_pool* p, const fs_batch_t* batches, int n_batches, void* wo
   }
   // fs_decode_status reads the first slice's header
   hipLaunchKernelGGL(merge_status_kernel, dim3(1), dim3(64), 0, s, (uint32_t*)slice[0], (const uint32_t*)slice[1],
-                     (const uint32_t*)slice[2]);
+                     (const uint32_t*)slice[2], (const uint32_t*)slice[3]);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return device_error(e, "status merge launch");
   return FS_OK;

@@ -351,6 +351,27 @@ def test_one_call_over_models_of_different_head_dim(mode):
         par.close()
 
 
+def test_one_call_over_shapes_inside_and_outside_the_mfma_kernel():
+    """Models the MFMA kernel covers (head_dim 128 and 64) beside models it does not (head_dim 512 and 32) in one call:
+    the covered ones keep the MFMA kernel (one launch sequence per head_dim), the others share a launch sequence on
+    the vector-ALU kernel; forcing the MFMA kernel on such a call is refused before anything is enqueued."""
+    lens = np.array([2, 150, 900], np.int32)
+    wl = Workload("in-out", 64 * KiB, 96 * MiB,
+                  [ModelSpec("a", INT8, 2, 128, 1, 8, lens, tag=53), ModelSpec("e", FP16, 2, 512, 1, 4, lens, tag=54),
+                   ModelSpec("f", FP8, 2, 32, 1, 2, lens, tag=55), ModelSpec("g", FP16, 2, 64, 1, 2, lens, tag=56)],
+                  "interleave")
+    par = _parity(wl)
+    try:
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 24 * KiB)
+        print(par.run_and_check([0, 0, 0, 0], kernel_mode=0))
+        with pytest.raises(Exception, match="MFMA kernel forced"):
+            par.populate_and_decode([0, 0, 0, 0], kernel_mode=2)
+    finally:
+        par.gw.set_option(par.fs.FS_OPT_DECODE_KERNEL, 0)
+        par.gw.set_option(par.fs.FS_OPT_SPLIT_BYTES, 0)
+        par.close()
+
+
 @pytest.mark.parametrize("mode", KERNEL_MODES)
 @pytest.mark.parametrize("group", [2, 3, 5, 8, 12, 16])
 @pytest.mark.parametrize("dtype", [FP16, INT4])
