@@ -139,6 +139,71 @@ __device__ __host__ inline int n_splits(const DevBatch& B, int seq, int len) {
   return (len + ct - 1) / ct;
 }
 
+// ---- The MFMA kernels' walk over a sequence (plain integer arithmetic, host and device: the host-compiled check of
+// tests/sanitize/fs_index_check.cpp runs exactly these functions over whole launches with every index asserted) ----
+// A sequence is walked in runs of 8 token slots that never cross a block: block k holds runs k R .. k R + R - 1
+// (R = ceil(T / 8)); run r of a block covers slots 8 r .. 8 r + 7, except that the last run of a block whose T
+// is no multiple of 8 is shifted back to end at slot T - 1 and its first slots, which repeat tokens of the run
+// before, are masked.  A tile is 4 consecutive runs.
+struct ItemCtx {
+  const uint64_t* chunk_ptr;  // LDS: head-chunk address of blocks k0 .. of this item's range
+  int k0;                     // first block the item touches
+  int v_end;                  // one past the item's last run
+  int len;                    // tokens this lane's logit column may attend to (decode: the sequence length)
+  int len_u;                  // tokens the sequence holds for any column (wave-uniform); decode: == len
+  int T, R;
+  uint32_t r_magic;           // ceil(2^32 / R)
+};
+
+// run / R  (r_magic = ceil(2^32 / R) does not fit 32 bits for R = 1; exact while run * R < 2^32)
+__device__ __host__ inline int div_runs(int vr, int R, uint32_t r_magic) {
+  return R == 1 ? vr : (int)(((uint64_t)(uint32_t)vr * (uint64_t)r_magic) >> 32);
+}
+
+// Run vr of an item: its block relative to the item's first (k_rel: the index into the item's address table), its
+// first slot in the block, and the slots [lo, hi) of it that hold tokens this lane's column attends to (none for a
+// run past the item's end, which is mapped onto the item's last run: valid memory); [lo, hi_u): the slots that hold
+// tokens of the sequence at all (what V rows and per-token parameters, which all columns share, are judged by).
+struct RunGeom {
+  int k_rel, start, lo, hi, hi_u;
+  int tok0;  // token index of the run's slot 0 (a huge value for a run past the item's end: no column reaches it)
+};
+
+__device__ __host__ inline RunGeom run_geom(const ItemCtx& X, int vr) {
+  const int vc = vr < X.v_end - 1 ? vr : X.v_end - 1;
+  const int k = div_runs(vc, X.R, X.r_magic);
+  const int r8 = 8 * (vc - k * X.R);
+  RunGeom L;
+  L.start = r8 < X.T - 8 ? r8 : X.T - 8;
+  L.lo = r8 - L.start;
+  L.tok0 = vr < X.v_end ? k * X.T + L.start : 0x3fffffff;
+  L.hi = 8 < X.len - L.tok0 ? 8 : X.len - L.tok0;
+  L.hi_u = 8 < X.len_u - L.tok0 ? 8 : X.len_u - L.tok0;
+  L.k_rel = k - X.k0;
+  return L;
+}
+
+// Split `chunk` of a sequence of `len` (clamped) tokens as a decode work item: its runs [v0, v1) and the blocks
+// k0 .. k0 + nb - 1 they lie in.
+struct ItemRange {
+  int v0, v1, k0, nb;
+};
+
+__device__ __host__ inline ItemRange item_range(const DevBatch& B, int seq, int chunk, int len) {
+  ItemRange r;
+  const int cr = chunk_runs_of(B, seq);
+  const int all = n_runs(len, B.g.T, B.R);
+  r.v0 = chunk * cr;
+  r.v1 = all < r.v0 + cr ? all : r.v0 + cr;
+  r.k0 = div_runs(r.v0, B.R, B.r_magic);
+  r.nb = div_runs(r.v1 - 1, B.R, B.r_magic) - r.k0 + 1;
+  return r;
+}
+
+// The device-side records of a decode call as the launch would build them (no workspace pointers, nothing
+// enqueued): for checks that replay the kernels' index arithmetic on the host.  use_mfma: which kernel would run.
+int debug_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, MultiArgs* out, bool* use_mfma);
+
 // Launchers implemented in the kernel translation units.
 hipError_t launch_prep(const MultiArgs& A, hipStream_t s);
 hipError_t launch_generic(const MultiArgs& A, int n_workgroups, hipStream_t s);

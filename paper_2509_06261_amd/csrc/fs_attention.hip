@@ -395,7 +395,8 @@ uint64_t launch_split_bytes(const fs_pool* p, const fs_batch_t* batches, int n_b
 }
 
 // Validates the batches and lays the workspace out.  With workspace == nullptr only sizes are computed.
-int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, Plan& plan) {
+// need_scales: an FP8 model without its scales is refused (what every launch wants; the index check asks without).
+int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* workspace, Plan& plan, bool need_scales = true) {
   if (!p || !batches || n_batches < 1 || n_batches > kMaxBatches) {
     set_error("decode attention: need 1..8 batches");
     return FS_ERR_INVALID;
@@ -423,7 +424,7 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
       set_error("decode attention: q and out must be 16-byte aligned");
       return FS_ERR_INVALID;
     }
-    if (g.kv_dtype == FS_KV_FP8_E4M3 && !M.d_k_scale) {
+    if (need_scales && g.kv_dtype == FS_KV_FP8_E4M3 && !M.d_k_scale) {
       set_error("decode attention: FP8 model has no scales (fs_model_set_fp8_scales)");
       return FS_ERR_INVALID;
     }
@@ -516,6 +517,16 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
 }
 
 }  // namespace
+
+int debug_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, MultiArgs* out, bool* use_mfma) {
+  Plan plan;
+  const int rc = make_plan(p, batches, n_batches, nullptr, plan, false);
+  if (rc != FS_OK) return rc;
+  if (out) *out = plan.args;
+  if (use_mfma) *use_mfma = plan.use_mfma;
+  return FS_OK;
+}
+
 }  // namespace fs
 
 using namespace fs;

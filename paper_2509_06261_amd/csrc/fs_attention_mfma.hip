@@ -32,12 +32,11 @@ __device__ __forceinline__ ItemPlan plan_item(const MultiArgs& A, uint32_t rec) 
   P.chunk = (int)__builtin_amdgcn_readlane(rec, 2);
   P.local = __builtin_amdgcn_readlane(rec, 3);
   P.len = (int)__builtin_amdgcn_readlane(rec, 4);
-  const DevBatch& B = A.b[P.b];
-  const int cr = chunk_runs_of(B, P.seq);
-  P.v0 = P.chunk * cr;
-  P.v1 = min(n_runs(P.len, B.g.T, B.R), P.v0 + cr);
-  P.k0 = div_runs(P.v0, B.R, B.r_magic);
-  P.nb = div_runs(P.v1 - 1, B.R, B.r_magic) - P.k0 + 1;
+  const ItemRange r = item_range(A.b[P.b], P.seq, P.chunk, P.len);
+  P.v0 = r.v0;
+  P.v1 = r.v1;
+  P.k0 = r.k0;
+  P.nb = r.nb;
   return P;
 }
 

@@ -142,46 +142,22 @@ struct Tile {
   uint32_t par[GP == 16 ? 1 : 4];
 };
 
-// A sequence is walked in runs of 8 token slots that never cross a block: block k holds runs k R .. k R + R - 1
-// (R = ceil(T / 8)); run r of a block covers slots 8 r .. 8 r + 7, except that the last run of a block whose T
-// is no multiple of 8 is shifted back to end at slot T - 1 and its first slots, which repeat tokens of the run
-// before, are masked.  A tile is 4 consecutive runs.
-struct ItemCtx {
-  const uint64_t* chunk_ptr;  // LDS: head-chunk address of blocks k0 .. of this item's range
-  int k0;                     // first block the item touches
-  int v_end;                  // one past the item's last run
-  int len;                    // tokens this lane's logit column may attend to (decode: the sequence length)
-  int len_u;                  // tokens the sequence holds for any column (wave-uniform); decode: == len
-  int T, R;
-  uint32_t r_magic;           // ceil(2^32 / R)
-};
-
-// Run vr: head-chunk address of its block, first slot, and the slots [lo, hi) of it that hold tokens this
-// lane's column attends to (none for a run past the item's end, which is mapped onto the item's last run:
-// valid memory); [lo, hi_u): the slots that hold tokens of the sequence at all (what V rows and per-token
-// parameters, which all columns share, are judged by).
+// Run vr of an item (run_geom, fs_attention.h) with the head-chunk address of its block.
 struct RunLoc {
   gptr base;
   int start, lo, hi, hi_u;
   int tok0;  // token index of the run's slot 0 (a huge value for a run past the item's end: no column reaches it)
 };
 
-// run / R  (r_magic = ceil(2^32 / R) does not fit 32 bits for R = 1)
-__device__ __forceinline__ int div_runs(int vr, int R, uint32_t r_magic) {
-  return R == 1 ? vr : (int)__umulhi((uint32_t)vr, r_magic);
-}
-
 __device__ __forceinline__ RunLoc locate(const ItemCtx& X, int vr) {
-  const int vc = min(vr, X.v_end - 1);
-  const int k = div_runs(vc, X.R, X.r_magic);
-  const int r8 = 8 * (vc - k * X.R);
+  const RunGeom r = run_geom(X, vr);
   RunLoc L;
-  L.start = min(r8, X.T - 8);
-  L.lo = r8 - L.start;
-  L.tok0 = vr < X.v_end ? k * X.T + L.start : 0x3fffffff;
-  L.hi = min(8, X.len - L.tok0);
-  L.hi_u = min(8, X.len_u - L.tok0);
-  L.base = (gptr)X.chunk_ptr[k - X.k0];
+  L.start = r.start;
+  L.lo = r.lo;
+  L.tok0 = r.tok0;
+  L.hi = r.hi;
+  L.hi_u = r.hi_u;
+  L.base = (gptr)X.chunk_ptr[r.k_rel];
   return L;
 }
 

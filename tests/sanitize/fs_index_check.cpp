@@ -1,0 +1,196 @@
+// Host-compiled replay of the MFMA decode kernel's index arithmetic, every index asserted (no GPU needed).
+//
+// Compiled together with the library's sources by tests/test_host_sanitizers.py (host sanitizers on).  For seeded
+// pools, models and batches it asks the library for the device-side records of a decode call (fs::debug_plan: what
+// the launch would hand its kernels) and then walks every work item the work-list kernel would queue -- sequence,
+// split, KV head -- with the very functions the kernels use (n_splits, item_range, run_geom, ring_tiles): for every
+// tile of the item's ring turns, refills past the item's end included, and every lane of the wave it computes the
+// addresses the K, V and parameter loads would form and checks that
+//   * the block index stays inside the item's address table (0 <= k_rel < nb <= 256 entries),
+//   * every K row, V row and parameter word lies inside its tile of the block's head chunk,
+//   * the runs of a sequence's items cover every token exactly once with the slots [lo, hi) the softmax keeps,
+//     and no kept slot lies at or past the sequence's length,
+//   * the items of a sequence tile its runs without gap or overlap, and their number is what n_splits says.
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "fs_attention.h"
+
+namespace {
+
+uint64_t g_state = 0xD1B54A32D192ED03ull;
+uint64_t rnd() {
+  g_state ^= g_state >> 12;
+  g_state ^= g_state << 25;
+  g_state ^= g_state >> 27;
+  return g_state * 0x2545F4914F6CDD1Dull;
+}
+int rnd_int(int n) { return (int)(rnd() % (uint64_t)n); }
+
+long g_failures = 0, g_items = 0, g_tiles = 0;
+#define CHECK(cond)                                                                  \
+  do {                                                                               \
+    if (!(cond)) {                                                                   \
+      if (g_failures < 20) std::printf("CHECK failed at line %d: %s\n", __LINE__, #cond); \
+      ++g_failures;                                                                  \
+    }                                                                                \
+  } while (0)
+
+void* const kFakeBase = (void*)0x10000000;
+
+// Bytes per lane of the K and V loads of a tile, as the tile code derives them from the format and the head_dim.
+struct LoadShape {
+  int row_bytes, k_lane, k_loads, v_bytes, par_bytes;
+};
+LoadShape load_shape(int dtype, int D) {
+  LoadShape s;
+  const int bits = dtype == FS_KV_FP16 ? 16 : (dtype == FS_KV_INT4 ? 4 : 8);
+  s.row_bytes = D * bits / 8;
+  s.k_lane = s.row_bytes / 4 < 16 ? s.row_bytes / 4 : 16;
+  s.k_loads = s.row_bytes / (4 * s.k_lane);
+  s.v_bytes = s.row_bytes / 16;
+  s.par_bytes = dtype == FS_KV_INT8 ? 2 : (dtype == FS_KV_INT4 ? 4 : 0);
+  return s;
+}
+
+void check_batch(const fs::DevBatch& B, const std::vector<int32_t>& lens) {
+  const fs::DevGeom& g = B.g;
+  const LoadShape S = load_shape(g.dtype, g.D);
+  CHECK((uint32_t)S.row_bytes == g.row_bytes);
+  CHECK((uint64_t)g.T * g.row_bytes <= g.kv_tile);
+  CHECK(2ull * g.kv_tile + 2ull * g.par_tile <= g.head_chunk);
+  const int ring = fs::ring_tiles(g.dtype, g.D);
+  std::vector<int> seen;
+  for (int seq = 0; seq < B.n_seq; ++seq) {
+    const int64_t max_len = (int64_t)B.max_blocks * g.T;
+    const int len = (int)std::min<int64_t>(std::max(lens[seq], 1), max_len);
+    const int n_items = fs::n_splits(B, seq, len);
+    const int all_runs = fs::n_runs(len, g.T, B.R);
+    seen.assign(len, 0);
+    int next_run = 0;
+    for (int chunk = 0; chunk < n_items; ++chunk) {
+      ++g_items;
+      const fs::ItemRange r = fs::item_range(B, seq, chunk, len);
+      CHECK(r.v0 == next_run && r.v1 > r.v0 && r.v1 <= all_runs);
+      next_run = r.v1;
+      CHECK(r.nb >= 1 && r.nb <= 256);  // the kernel's address table: four registers of 64 lanes
+      CHECK(r.k0 >= 0 && r.k0 + r.nb <= B.max_blocks);
+      fs::ItemCtx X;
+      X.chunk_ptr = nullptr;
+      X.T = g.T;
+      X.R = B.R;
+      X.r_magic = B.r_magic;
+      X.len = len;
+      X.len_u = len;
+      X.v_end = r.v1;
+      X.k0 = r.k0;
+      const int n_tiles = (r.v1 - r.v0 + 3) >> 2;
+      const int turns = (n_tiles + ring - 1) / ring;
+      // tiles consumed: turns * ring; tiles requested: one ring more (the last turn's refills)
+      for (int tile = 0; tile < (turns + 1) * ring; ++tile) {
+        ++g_tiles;
+        const int vb = r.v0 + 4 * tile;
+        const bool consumed = tile < turns * ring;
+        for (int lane = 0; lane < 64; ++lane) {
+          const int j = lane >> 4, c = lane & 15;
+          // K operand rows: run c / 4 of the tile, slots 4 u + c % 4
+          const fs::RunGeom Lk = fs::run_geom(X, vb + (c >> 2));
+          CHECK(Lk.k_rel >= 0 && Lk.k_rel < r.nb);
+          CHECK(Lk.start >= 0 && Lk.start + 8 <= g.T);
+          for (int u = 0; u < 2; ++u)
+            for (int s = 0; s < S.k_loads; ++s) {
+              const int64_t off = (int64_t)(Lk.start + (c & 3) + 4 * u) * S.row_bytes + S.k_lane * j + 4 * S.k_lane * s;
+              CHECK(off >= 0 && off + S.k_lane <= (int64_t)g.T * S.row_bytes);
+            }
+          // V rows and parameters: run j of the tile
+          const fs::RunGeom Lv = fs::run_geom(X, vb + j);
+          CHECK(Lv.k_rel >= 0 && Lv.k_rel < r.nb);
+          for (int i = 0; i < 8; ++i) {
+            const int64_t off = (int64_t)(Lv.start + i) * S.row_bytes + c * S.v_bytes;
+            CHECK(off >= 0 && off + S.v_bytes <= (int64_t)g.T * S.row_bytes);
+          }
+          if (S.par_bytes) {
+            const int64_t off16 = (int64_t)(Lv.start + (c & 7)) * S.par_bytes;           // one column per lane
+            const int64_t off4 = (int64_t)(Lv.start + 2 * (c >> 2) + 1) * S.par_bytes;   // four lanes per column
+            CHECK(off16 + S.par_bytes <= (int64_t)g.par_tile && off4 + S.par_bytes <= (int64_t)g.par_tile);
+          }
+          // what the softmax keeps of run j: counted once per run (by the lane c == 0 of its lane group)
+          if (consumed && c == 0) {
+            CHECK(Lv.lo >= 0 && Lv.lo <= 8 && Lv.hi <= 8);
+            for (int i = std::max(Lv.lo, 0); i < Lv.hi; ++i) {
+              const int tok = Lv.tok0 + i;
+              CHECK(tok >= 0 && tok < len);
+              if (tok >= 0 && tok < len) ++seen[tok];
+            }
+            if (vb + j >= r.v1) CHECK(Lv.hi <= Lv.lo || Lv.hi <= 0);  // a run past the item's end keeps nothing
+          }
+        }
+      }
+    }
+    CHECK(next_run == all_runs);
+    for (int t = 0; t < len; ++t) CHECK(seen[t] == 1);
+  }
+}
+
+void run(int rounds) {
+  const int dtypes[4] = {FS_KV_FP16, FS_KV_FP8_E4M3, FS_KV_INT8, FS_KV_INT4};
+  const int dims[3] = {64, 128, 256};
+  const int want_T[12] = {8, 9, 13, 16, 23, 38, 60, 64, 126, 128, 200, 333};
+  for (int round = 0; round < rounds; ++round) {
+    const int dtype = dtypes[round % 4], D = dims[(round / 4) % 3];
+    const int H = 1 + rnd_int(3), L = 1 + rnd_int(2);
+    const int bits = dtype == FS_KV_FP16 ? 16 : (dtype == FS_KV_INT4 ? 4 : 8);
+    const int par = dtype == FS_KV_INT8 ? 2 : (dtype == FS_KV_INT4 ? 4 : 0);
+    const uint64_t tok_bytes = 2ull * H * L * (uint64_t)(D * bits / 8 + par);
+    const uint64_t slab = std::max<uint64_t>(4096, (want_T[rnd_int(12)] * tok_bytes + 255) / 256 * 256 + 256 * (uint64_t)rnd_int(3));
+    fs_pool* p = nullptr;
+    CHECK(fs_pool_create(slab, 4096 * slab, kFakeBase, &p) == FS_OK);
+    if (!p) continue;
+    fs_model_t m;
+    const int T = fs_model_register(p, dtype, H, D, L, &m);
+    CHECK(T > 0);
+    if (T < 8) {  // the vector-ALU kernel's shape
+      fs_pool_destroy(p);
+      continue;
+    }
+    const int n_seq = 1 + rnd_int(6);
+    std::vector<int32_t> lens(n_seq);
+    const int special[12] = {1, 2, 7, 8, 9, T - 1, T, T + 1, 2 * T, 4 * T + 3, 31, 33};
+    int max_len = 1;
+    for (int i = 0; i < n_seq; ++i) {
+      lens[i] = rnd_int(3) ? std::max(1, special[rnd_int(12)]) : 1 + rnd_int(6000);
+      max_len = std::max(max_len, (int)lens[i]);
+    }
+    const int G[8] = {1, 2, 3, 4, 5, 8, 12, 16};
+    fs_batch_t b{};
+    b.model = m;
+    b.layer = rnd_int(L);
+    b.n_q_heads = H * G[rnd_int(8)];
+    b.sm_scale = 0.1f;
+    b.q = (const void*)0x20000000;
+    b.block_tables = (const int32_t*)0x30000000;
+    b.seq_lens = (const int32_t*)0x40000000;
+    b.seq_lens_host = rnd_int(4) ? lens.data() : nullptr;
+    b.n_seq = n_seq;
+    b.max_blocks = (max_len + T - 1) / T + rnd_int(2);
+    b.out = (void*)0x50000000;
+    const int64_t split[5] = {0, 0, 8 << 10, 24 << 10, 100 << 10};
+    CHECK(fs_pool_set_option(p, FS_OPT_SPLIT_BYTES, split[rnd_int(5)]) == FS_OK);
+    fs::MultiArgs A{};
+    bool use_mfma = false;
+    CHECK(fs::debug_plan(p, &b, 1, &A, &use_mfma) == FS_OK);
+    CHECK(use_mfma);
+    if (use_mfma) check_batch(A.b[0], lens);
+    fs_pool_destroy(p);
+  }
+}
+
+}  // namespace
+
+int main() {
+  run(600);
+  std::printf("fs_index_check: %ld items, %ld tiles, %ld failed checks\n", g_items, g_tiles, g_failures);
+  return g_failures ? 1 : 0;
+}

@@ -3,6 +3,8 @@
 * the library's host side -- slab allocator and geometry (fs_pool), scheduler (fs_sched), the host validation and
   planning of the append and decode entry points -- compiled by hipcc with the host sanitizers on (device code
   is built as usual and never runs) and driven by tests/sanitize/fs_host_driver.cpp;
+* the MFMA decode kernel's index arithmetic (the host + device functions of csrc/fs_attention.h), replayed item by
+  item, tile by tile and lane by lane with every index asserted, by tests/sanitize/fs_index_check.cpp;
 * the CPU oracle (oracle/fs_oracle.c), compiled by gcc with the sanitizers on and driven by
   tests/sanitize/oracle_driver.c.
 A sanitizer report aborts the driver, a failed check makes it return 1; either fails the test."""
@@ -40,6 +42,25 @@ def test_library_host_side_under_asan_and_ubsan():
           os.path.join(ROOT, "tests", "sanitize", "fs_host_driver.cpp"), "-o", exe])
     out = _run([exe], env=ENV, timeout=600)
     assert "fs_host_driver: 0 failed checks" in out, out[-2000:]
+
+
+def test_decode_kernel_index_arithmetic_replayed_on_the_host():
+    """tests/sanitize/fs_index_check.cpp: the MFMA decode kernel's own index functions, compiled for the host and run
+    over every item, tile and lane of seeded launches with every table index and byte offset asserted."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not found")
+    os.makedirs(BUILD, exist_ok=True)
+    csrc = os.path.join(ROOT, "paper_2509_06261_amd", "csrc")
+    srcs = [os.path.join(csrc, f) for f in ("fs_pool.hip", "fs_sched.hip", "fs_append.hip", "fs_attention.hip",
+                                            "fs_attention_generic.hip", "fs_attention_mfma.hip")]
+    exe = os.path.join(BUILD, "fs_index_check")
+    _run([hipcc, "--offload-arch=gfx950", "-std=c++17", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang",
+          "-packed-fp32-ops", *SAN, "-fno-gpu-sanitize", "-I", os.path.join(ROOT, "include"), "-I", csrc, *srcs,
+          "-x", "hip", os.path.join(ROOT, "tests", "sanitize", "fs_index_check.cpp"), "-o", exe])
+    out = _run([exe], env=ENV, timeout=600)
+    assert " 0 failed checks" in out and "fs_index_check:" in out, out[-2000:]
+    print(out.strip().splitlines()[-1])
 
 
 def test_oracle_under_asan_and_ubsan():
