@@ -20,6 +20,7 @@
 #include <cstdlib>
 
 #include "fs_mfma_tiles.h"
+#include "fs_prefill_index.h"
 
 namespace fs {
 namespace {
@@ -520,32 +521,15 @@ __device__ void prefill_item_wide(const PrefillArgs& P, int seq, int head, int q
 static_assert(kPools == 64, "pool = 8 * sub-pool + XCD");
 // chunk = 2^shift items = the workers resident per XCD (wave-level items: 128 waves, workgroup-level items: 32)
 constexpr uint32_t kWaveChunkShift = 7, kWgChunkShift = 5;
-__device__ __forceinline__ uint32_t pool_item(uint32_t pool, uint32_t ticket, uint32_t shift) {
-  const uint32_t xcd = pool & 7, u = (pool >> 3) + 8 * ticket;  // u: index among the XCD's items
-  return ((((u >> shift) << 3) + xcd) << shift) + (u & ((1u << shift) - 1));
-}
 __device__ __forceinline__ uint32_t home_pool(uint32_t worker) {  // worker: index among the workers of its XCD
   const uint32_t xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7;  // hwreg(HW_REG_XCC_ID, 0, 4)
   return (worker & 7) * 8 + xcd;
 }
 
-// item -> (sequence, KV head, tile): sequence-major, then head, tiles of a head longest first
 // tf: tile_first, in global memory or its copy in LDS (ten dependent look-ups: a round trip to memory each otherwise)
 __device__ __forceinline__ bool decode_item(const PrefillArgs& P, const uint32_t* tf, uint32_t item, uint32_t H, int& seq,
                                             int& head, int& qt) {
-  int lo = 0, hi = P.b.n_seq - 1;
-  while (lo < hi) {  // last sequence whose first item is <= item
-    const int mid = (lo + hi + 1) >> 1;
-    if (tf[mid] * H <= item) lo = mid;
-    else hi = mid - 1;
-  }
-  const uint32_t nt = tf[lo + 1] - tf[lo];
-  if (nt == 0) return false;  // (cannot happen: an item lies in a sequence that has tiles)
-  const uint32_t li = item - tf[lo] * H;
-  seq = lo;
-  head = (int)(li / nt);
-  qt = (int)(nt - 1 - li % nt);
-  return true;
+  return fs::decode_item(tf, P.b.n_seq, item, H, seq, head, qt);
 }
 
 // Drawing work items until none is left.  A wave first empties its home pool; after that it looks at all 64
@@ -1604,8 +1588,8 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   P.tile_first = (uint32_t*)((uint8_t*)workspace + kHeaderBytes);
   P.tpt = tpt;
   P.ncb = ncb;
-  P.seg_runs = (int32_t)std::min<int64_t>(1024, std::max<int64_t>(4, (int64_t)500 * B.R / 4 * 4));
-  P.table_entries = P.seg_runs / B.R + 4;
+  P.seg_runs = prefill_seg_runs(B.R);
+  P.table_entries = prefill_table_entries(P.seg_runs, B.R);
   P.n_rows = (int32_t)n_rows;
   P.whole_runs = (g.tokens_per_block & 7) == 0;
   if (n_rows == 0) return FS_OK;

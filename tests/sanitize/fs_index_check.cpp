@@ -11,12 +11,17 @@
 //   * the runs of a sequence's items cover every token exactly once with the slots [lo, hi) the softmax keeps,
 //     and no kept slot lies at or past the sequence's length,
 //   * the items of a sequence tile its runs without gap or overlap, and their number is what n_splits says.
+// The prefill kernels' queue arithmetic (fs_prefill_index.h) is replayed the same way: every item of a queue belongs
+// to exactly one (pool, ticket) and a pool's items grow with the ticket (what lets a wave call a pool empty at its
+// first ticket past the end); item -> (sequence, KV head, query tile) is one-to-one onto the tiles the sequences
+// have; and a table segment of a context never touches more blocks than the wave's address table holds.
 #include <algorithm>
 #include <cstdint>
 #include <cstdio>
 #include <vector>
 
 #include "fs_attention.h"
+#include "fs_prefill_index.h"
 
 namespace {
 
@@ -187,10 +192,70 @@ void run(int rounds) {
   }
 }
 
+void prefill_queues(int rounds) {
+  for (int round = 0; round < rounds; ++round) {
+    const int n_seq = 1 + rnd_int(round % 7 == 0 ? 3000 : 40);
+    const uint32_t H = 1 + (uint32_t)rnd_int(40);
+    std::vector<uint32_t> tf(n_seq + 1, 0);
+    for (int i = 0; i < n_seq; ++i) tf[i + 1] = tf[i] + (rnd_int(5) ? 1 + (uint32_t)rnd_int(rnd_int(4) ? 6 : 200) : 0u);
+    const uint32_t total = tf[n_seq] * H;
+    if (total == 0 || total > 3000000) continue;
+    // item -> (sequence, head, tile)
+    std::vector<uint8_t> hit(total, 0);
+    for (uint32_t item = 0; item < total; ++item) {
+      int seq = -1, head = -1, qt = -1;
+      const bool ok = fs::decode_item(tf.data(), n_seq, item, H, seq, head, qt);
+      CHECK(ok);
+      if (!ok) continue;
+      CHECK(seq >= 0 && seq < n_seq && head >= 0 && (uint32_t)head < H);
+      const uint32_t nt = tf[seq + 1] - tf[seq];
+      CHECK(qt >= 0 && (uint32_t)qt < nt);
+      const uint64_t back = (uint64_t)tf[seq] * H + (uint64_t)head * nt + (nt - 1 - (uint32_t)qt);
+      CHECK(back == item);
+      ++g_items;
+    }
+    // (pool, ticket) -> item
+    for (uint32_t shift = 5; shift <= 7; ++shift) {
+      std::fill(hit.begin(), hit.end(), 0);
+      for (uint32_t pool = 0; pool < 64; ++pool) {
+        uint32_t prev = 0;
+        for (uint32_t ticket = 0;; ++ticket) {
+          const uint32_t item = fs::pool_item(pool, ticket, shift);
+          CHECK(ticket == 0 || item > prev);
+          prev = item;
+          if (item >= total) break;
+          CHECK(hit[item] == 0);
+          hit[item] = 1;
+        }
+      }
+      for (uint32_t item = 0; item < total; ++item) CHECK(hit[item] == 1);
+    }
+  }
+  // table segments: tokens per block 8 .. 340, contexts up to 40000 tokens
+  for (int T = 8; T <= 340; ++T) {
+    const int R = (T + 7) / 8;
+    const uint32_t r_magic = R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)R - 1) / (uint64_t)R);
+    const int seg = fs::prefill_seg_runs(R), entries = fs::prefill_table_entries(seg, R);
+    CHECK(seg >= 4 && seg % 4 == 0 && entries <= 1024 / 1 + 4);
+    const int lens[6] = {1, T, T + 1, 1000, 8191, 40000};
+    for (int li = 0; li < 6; ++li) {
+      const int n_run = fs::n_runs(lens[li], T, R);
+      for (int v0 = 0; v0 < n_run; v0 += seg) {
+        const int v_end = std::min(n_run, v0 + seg);
+        const int k0 = fs::div_runs(v0, R, r_magic);
+        const int nb = fs::div_runs(v_end - 1, R, r_magic) - k0 + 1;
+        CHECK(k0 == v0 / R && nb >= 1 && nb <= entries);
+        CHECK((int64_t)(k0 + nb - 1) * T < (int64_t)lens[li] + T);  // the last block touched holds a token of the context
+      }
+    }
+  }
+}
+
 }  // namespace
 
 int main() {
   run(600);
+  prefill_queues(60);
   std::printf("fs_index_check: %ld items, %ld tiles, %ld failed checks\n", g_items, g_tiles, g_failures);
   return g_failures ? 1 : 0;
 }
