@@ -139,6 +139,24 @@ __device__ __host__ inline int n_splits(const DevBatch& B, int seq, int len) {
   return (len + ct - 1) / ct;
 }
 
+// Place in the queue of item `local` (of n[b]) of batch b: the batches' sequence-major item lists merged
+// proportionally -- item i of batch b sorts by (i / n[b], b) -- so the place is i plus the number of items of the
+// other batches that sort before it: those of a batch o < b with i' / n[o] <= i / n[b], of a batch o > b with
+// i' / n[o] < i / n[b].  One-to-one onto 0 .. sum(n) - 1.
+__device__ __host__ inline uint64_t queue_place(uint64_t local, int b, const uint32_t (&n)[kMaxBatches]) {
+  const uint64_t n_b = n[b];
+  uint64_t idx = local;
+#pragma unroll
+  for (int o = 0; o < kMaxBatches; ++o) {
+    const uint64_t n_o = n[o];
+    if (o == b || n_o == 0) continue;
+    const uint64_t num = local * n_o;
+    const uint64_t c = o < b ? num / n_b + 1 : (num + n_b - 1) / n_b;
+    idx += c < n_o ? c : n_o;
+  }
+  return idx;
+}
+
 // ---- The MFMA kernels' walk over a sequence (plain integer arithmetic, host and device: the host-compiled check of
 // tests/sanitize/fs_index_check.cpp runs exactly these functions over whole launches with every index asserted) ----
 // A sequence is walked in runs of 8 token slots that never cross a block: block k holds runs k R .. k R + R - 1

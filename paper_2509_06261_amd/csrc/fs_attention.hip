@@ -99,7 +99,6 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
     const DevBatch& B = A.b[b];
     const uint32_t H = (uint32_t)B.g.H;
     const uint32_t batch_first = total_items;
-    const uint64_t n_b = count[b];
     const uint64_t batch_part = part_running;
     total_items += count[b];
     part_running += (uint64_t)count[b] * (uint64_t)B.part_stride;
@@ -146,16 +145,7 @@ __device__ __forceinline__ void prep_body(const MultiArgs& A, uint32_t group, ui
         }
         const uint32_t rr = r - (lo ? s_incl[lo - 1] : 0u);
         const uint64_t local = running - batch_first + r;  // index within the batch
-        // place in the queue: items of batch b' < b with i' / n_b' <= local / n_b, of b' > b with i' / n_b' < local / n_b
-        uint64_t idx = local;
-#pragma unroll
-        for (int o = 0; o < kMaxBatches; ++o) {
-          const uint64_t n_o = count[o];
-          if (o == b || n_o == 0) continue;
-          const uint64_t num = local * n_o;
-          const uint64_t c = o < b ? num / n_b + 1 : (num + n_b - 1) / n_b;
-          idx += c < n_o ? c : n_o;
-        }
+        const uint64_t idx = queue_place(local, b, count);
         if (idx < A.item_capacity) {
           A.item_list[2 * idx] = make_rec(b, base + lo, (int)(rr / H), (int)(rr % H), (uint32_t)local);
           A.item_list[2 * idx + 1] = int4{s_len[lo], 0, 0, 0};

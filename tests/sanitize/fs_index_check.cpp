@@ -15,6 +15,8 @@
 // to exactly one (pool, ticket) and a pool's items grow with the ticket (what lets a wave call a pool empty at its
 // first ticket past the end); item -> (sequence, KV head, query tile) is one-to-one onto the tiles the sequences
 // have; and a table segment of a context never touches more blocks than the wave's address table holds.
+// The decode work queue's closed-form placement (queue_place: the batches' item lists merged proportionally) is
+// checked to be one-to-one onto the queue and order-preserving within a batch.
 #include <algorithm>
 #include <cstdint>
 #include <cstdio>
@@ -251,11 +253,42 @@ void prefill_queues(int rounds) {
   }
 }
 
+// The decode work queue: every item of every batch gets one place, the places are 0 .. total - 1, and each batch's
+// items keep their order (so a sequence's size tiers stay in queue order).
+void decode_queue_places(int rounds) {
+  for (int round = 0; round < rounds; ++round) {
+    uint32_t n[fs::kMaxBatches] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int nb = 1 + rnd_int(fs::kMaxBatches);
+    uint64_t total = 0;
+    for (int b = 0; b < nb; ++b) {
+      n[b] = rnd_int(6) == 0 ? 1u : 1u + (uint32_t)rnd_int(round % 5 == 0 ? 70000 : 3000);
+      total += n[b];
+    }
+    std::vector<uint8_t> hit(total, 0);
+    for (int b = 0; b < nb; ++b) {
+      uint64_t prev = 0;
+      for (uint32_t i = 0; i < n[b]; ++i) {
+        const uint64_t at = fs::queue_place(i, b, n);
+        CHECK(at < total);
+        CHECK(i == 0 || at > prev);
+        prev = at;
+        if (at < total) {
+          CHECK(hit[at] == 0);
+          hit[at] = 1;
+        }
+        ++g_items;
+      }
+    }
+    for (uint64_t at = 0; at < total; ++at) CHECK(hit[at] == 1);
+  }
+}
+
 }  // namespace
 
 int main() {
   run(600);
   prefill_queues(60);
+  decode_queue_places(200);
   std::printf("fs_index_check: %ld items, %ld tiles, %ld failed checks\n", g_items, g_tiles, g_failures);
   return g_failures ? 1 : 0;
 }
