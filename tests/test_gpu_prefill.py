@@ -17,28 +17,35 @@ pytestmark = pytest.mark.gpu
 VARIANTS = [("wg8", 16, 8), ("wg8dq", 16, 8), ("auto", 0, 0), ("wg4", 16, 4), ("wg4p", 16, 4), ("wg4x2", 8, 4), ("cols32", 2, 0), ("cols64", 4, 0)]
 
 
+GQA, MHA, LONG = "test_gqa_8b_shape_whole_prompts_and_chunks", "test_mha_13b_shape_odd_tokens_per_block", "test_long_context_spans_several_table_segments"
+
+
+def combination_applies(test, params):
+    """Which (test, kernel variant) pairs are collected (see VARIANTS above)."""
+    name = params["kernel_variant"][0]
+    dtype = params.get("dtype")
+    if test == "test_shapes_beside_head_dim_128":
+        return name == "auto"  # shapes beside head_dim 128 take the same kernel whatever variant is set
+    if name == "wg8dq":
+        if test == LONG or (test in (GQA, MHA) and dtype in (FP16, FP8)):
+            return False  # staged dequantization concerns INT8 and INT4 models only
+    elif test == "test_softmax_scales_other_than_the_usual":
+        if name not in ("wg8", "wg8dq", "auto"):
+            return False  # the scale's sign decides the kernel inside the library; three settings suffice
+    elif name == "auto" and test not in (GQA, "test_two_models_in_one_pool_and_argument_checks"):
+        return False  # the automatic choice is covered by the four-format and two-model tests
+    if name == "wg4p" and test not in (GQA, MHA, LONG):
+        return False  # the pipelined variant takes the four-format, odd-block and long-context tests
+    if name not in ("wg8", "wg8dq", "auto", "wg4p") and not (test == GQA and dtype in (FP16, INT4)):
+        return False  # the other variants: the four-format test on FP16 and INT4
+    return True
+
+
 @pytest.fixture(params=VARIANTS, ids=[v[0] for v in VARIANTS], autouse=True)
 def kernel_variant(request):
     import paper_2509_06261_amd as fs
 
     name, blocks, waves = request.param
-    test = request.node.name
-    if test.startswith("test_shapes_beside_head_dim_128"):
-        if name != "auto":
-            pytest.skip("shapes beside head_dim 128 take the same kernel whatever variant is set")
-    elif name == "wg8dq":
-        fp = test.startswith(("test_gqa_8b_shape", "test_mha_13b")) and ("[wg8dq-0" in test or "[wg8dq-1" in test)
-        if test.startswith("test_long_context") or fp:
-            pytest.skip("staged dequantization concerns INT8 and INT4 models only")
-    elif test.startswith("test_softmax_scales"):
-        if name not in ("wg8", "wg8dq", "auto"):
-            pytest.skip("the scale's sign decides the kernel inside the library; three settings suffice")
-    elif name == "auto" and not test.startswith(("test_gqa_8b_shape", "test_two_models")):
-        pytest.skip("the automatic choice is covered by the four-format and two-model tests")
-    if name == "wg4p" and not test.startswith(("test_gqa_8b_shape", "test_mha_13b", "test_long_context")):
-        pytest.skip("the pipelined variant takes the four-format, odd-block and long-context tests")
-    if name not in ("wg8", "wg8dq", "auto", "wg4p") and not (test.startswith("test_gqa_8b_shape") and ("-0-" in test or "-3-" in test)):
-        pytest.skip("variant covered by the four-format test on FP16 and INT4")
     import gpu_workload
 
     if name == "wg4x2":
