@@ -5,6 +5,8 @@
 
 namespace fs {
 
+constexpr int kTierSteps = 3;  // size tiers 0 .. kTierSteps of the work items (see DevBatch::tier_seq)
+
 // One model's batch as the kernels see it.
 struct DevBatch {
   DevGeom g;
@@ -27,11 +29,11 @@ struct DevBatch {
   // consecutive runs.  chunk_runs == 0 selects the token-based splits of the generic kernel.
   int32_t chunk_runs;    // of size tier 0; multiple of 4
   // Size tiers: the sequences of a batch are queued in index order, so the last sequences' items are the last the
-  // grid works on.  Sequence i belongs to tier (i >= tier_seq[0]) + (i >= tier_seq[1]) + (i >= tier_seq[2]), and a
+  // grid works on.  Sequence i belongs to tier (i >= tier_seq[0]) + ... + (i >= tier_seq[kTierSteps - 1]), and a
   // tier's work items are half the size of the tier before: large items while there is plenty of work (less set-up
   // per byte), small ones at the end (the waves finish within one small item of each other).  tier_seq[t] = n_seq
   // where a tier is unused.
-  int32_t tier_seq[3];
+  int32_t tier_seq[kTierSteps];
   // Runs one turn of the MFMA kernel's tile ring covers (4 per tile, 1 / 2 / 2 / 3 tiles for FP16 / FP8 / INT8 /
   // INT4): the kernel works in whole turns, so items are whole turns long (their surplus tiles would be computed
   // and masked, which the formats bound by the vector ALU cannot afford on small items).
@@ -52,6 +54,8 @@ enum : int {
   kHdrPools = 64       // [kPools] ticket counters of the MFMA kernel's end-of-launch pools, kPoolStride words apart
 };
 constexpr int kPools = 64;
+constexpr int kDecodePools = 64;  // the decode kernel's share of them (prefill uses all, eight per XCD)
+static_assert(kDecodePools <= kPools, "the header holds kPools counters");
 constexpr int kPoolStride = 16;  // one counter per 64 bytes: neighbours never share a cache line
 constexpr uint32_t kHeaderBytes = 256 + kPools * kPoolStride * 4;
 
@@ -84,7 +88,7 @@ struct MultiArgs {
   uint64_t part_capacity;  // floats
   uint32_t item_capacity;  // entries of item_list
   // MFMA kernel: waves of the grid.  Wave w's first item is item w of the queue without a draw (its home pool is
-  // w % kPools, its first ticket w / kPools), so the pools' counters start past those tickets.
+  // w % kDecodePools, its first ticket w / kDecodePools), so the pools' counters start past those tickets.
   uint32_t n_workers;
   int32_t n_batches;
   int32_t n_seq_total;
@@ -117,12 +121,17 @@ __device__ __host__ inline int n_runs(int len, int T, int R) {
 }
 
 __device__ __host__ inline int tier_of(const DevBatch& B, int seq) {
-  return (seq >= B.tier_seq[0]) + (seq >= B.tier_seq[1]) + (seq >= B.tier_seq[2]);
+  int t = 0;
+#pragma unroll
+  for (int i = 0; i < kTierSteps; ++i) t += seq >= B.tier_seq[i];
+  return t;
 }
 // Runs (MFMA kernel) or tokens (generic kernel) per work item of sequence `seq`.
 __device__ __host__ inline int chunk_runs_of(const DevBatch& B, int seq) {
-  const int cr = B.chunk_runs >> tier_of(B, seq);  // (the host makes tier 0 a multiple of 8 rings when tiers are on)
-  return cr < B.ring_runs ? B.ring_runs : cr - cr % 4;
+  // whole turns of the tile ring, at least one (the host makes tier 0 a multiple of 8 turns when tiers are on, and
+  // ring_runs = 4, one tile, when a size is forced)
+  const int cr = B.chunk_runs >> tier_of(B, seq);
+  return cr < B.ring_runs ? B.ring_runs : cr - cr % B.ring_runs;
 }
 __device__ __host__ inline int chunk_tokens_of(const DevBatch& B, int seq) {
   const int ct = (B.chunk_tokens >> tier_of(B, seq)) & ~31;

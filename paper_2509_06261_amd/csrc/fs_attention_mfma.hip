@@ -229,22 +229,30 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   if (threadIdx.x < kMaxBatches) s_part_off[threadIdx.x] = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff)[threadIdx.x];
   __syncthreads();
   const uint32_t total = A.header[kHdrTotalItems];
-  // Every wave is its own worker and draws its items from kPools ticket counters: pool p holds the items
-  // p, p + kPools, ... of the queue.  Waves that get short items, or sit on a faster compute unit, simply
+  // Every wave is its own worker and draws its items from kDecodePools ticket counters: pool p holds the items
+  // p, p + kDecodePools, ... of the queue.  Waves that get short items, or sit on a faster compute unit, simply
   // draw more often; with a fixed deal (wave w takes items w, w + n_workers, ...) the slowest wave was
   // measured to finish a quarter later than the median one.  One counter for all items is no option: an
   // address serves an atomic every ~11 ns when idle and several times slower under streaming load, which
-  // was measured to bound the kernel; kPools counters with about a thousand draws each do not.
-  // A wave empties its home pool first.  After that it looks at all counters at once (lane p reads pool p's),
-  // moves to the next pool that still holds items and goes on; it leaves only when every pool is past its last
-  // item, so the launch ends within one of the queue's last (smallest) items whatever the pools' loads were.
+  // was measured to bound the kernel (and still to cost short launches a tenth with 8 counters); 64 do not.
+  // A wave takes its tickets from the pools in turn (its k-th from pool w + k), so all counters advance at
+  // about the same rate and the grid as a whole walks the queue roughly front to back: the large items of the
+  // queue's front are all under way before its small last items are handed out.  (With a home pool per wave that
+  // was emptied before the wave looked elsewhere, the pools drifted apart and the slowest pool's large items
+  // started when the others were done: waves idled 5 % of the launch at its end, against 3.5 %.)
+  // Once a wave meets an empty pool the launch is in its last few per cent.  From then on the wave looks at all
+  // counters at once (lane p reads pool p's) and picks the pool of a random one of the items that are left, so
+  // pools that lag get helpers in proportion to what they still hold, and stays there until that pool is
+  // empty too.  It leaves only when every pool is past its last item.
   // The next ticket is drawn before the current item is processed, so the atomic's latency is not waited for
   // between items; a wave's first ticket needs no draw at all (the work-list kernel starts the counters past the
-  // pools' home waves), which takes one round trip off the start of every launch.
-  static_assert(kPools == 64, "one pool per lane in the look at all counters");
+  // pools' first waves), which takes one round trip off the start of every launch.
+  static_assert(kDecodePools <= 64, "one pool per lane in the look at all counters");
   const uint32_t worker = blockIdx.x * kWaves + wave;
-  uint32_t pool = worker % kPools;
-  uint32_t ticket = worker / kPools;
+  uint32_t pool = worker % kDecodePools;
+  uint32_t ticket = worker / kDecodePools;
+  bool in_turn = true;                            // false once an empty pool was met
+  uint32_t rng = worker * 2654435761u + 0x9e3779b9u;  // wave-uniform
   constexpr uint32_t kNone = 0xffffffffu;
   auto draw = [&]() {
     if (lane == 0) ticket = atomicAdd(A.header + kHdrPools + pool * kPoolStride, 1u);
@@ -252,15 +260,23 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   // the item the drawn ticket stands for, or kNone once every pool is empty (then no ticket is outstanding)
   auto resolve = [&]() -> uint32_t {
     for (;;) {
-      const uint32_t item = pool + kPools * __builtin_amdgcn_readfirstlane(ticket);
+      const uint32_t item = pool + kDecodePools * __builtin_amdgcn_readfirstlane(ticket);
       if (item < total) return item;
-      // this pool is empty: which ones are not?  (the counters only grow)
-      const uint32_t cnt = __hip_atomic_load(A.header + kHdrPools + lane * kPoolStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const uint64_t left = __ballot((uint64_t)lane + (uint64_t)kPools * cnt < total);  // wave-uniform
+      // this pool is empty: what do the others hold?  (the counters only grow)
+      in_turn = false;
+      const uint32_t cnt = lane < kDecodePools ? __hip_atomic_load(A.header + kHdrPools + lane * kPoolStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      const uint32_t held = lane < kDecodePools && (uint32_t)lane < total ? (total - lane + kDecodePools - 1) / kDecodePools : 0u;
+      uint32_t incl = held > cnt ? held - cnt : 0u;  // items left in pool `lane`, then their inclusive sum over the lanes
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+      }
+      const uint32_t left = __builtin_amdgcn_readlane(incl, 63);
       if (left == 0) return kNone;  // every pass finds fewer items left or takes one
-      const uint32_t r = (pool + 1) % kPools;  // the first such pool after the current one, cyclically
-      const uint64_t rot = r ? (left >> r) | (left << (kPools - r)) : left;
-      pool = (r + (uint32_t)__builtin_ctzll(rot)) % kPools;
+      rng = rng * 1664525u + 1013904223u;
+      const uint32_t k = (uint32_t)(((uint64_t)rng * (uint64_t)left) >> 32);  // one of the items left, uniformly
+      pool = (uint32_t)__builtin_ctzll(__ballot(incl > k));                    // the pool it lies in (wave-uniform)
       draw();
     }
   };
@@ -270,6 +286,7 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   for (;;) {
     const uint32_t item = resolve();
     if (item == kNone) break;  // every wave leaves here, once all pools are empty
+    if (in_turn) pool = (pool + 1) % kDecodePools;
     draw();                    // the next ticket, answered while this item streams
     const ItemPlan P = plan_item(A, load_rec(item));
     int32_t tab[kTabRegs];

@@ -1580,7 +1580,7 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   B.R = (g.tokens_per_block + 7) / 8;
   B.r_magic = B.R == 1 ? 0u : (uint32_t)(((1ull << 32) + (uint64_t)B.R - 1) / (uint64_t)B.R);
   B.n_blocks = (uint32_t)(p->pool_bytes / g.block_budget);
-  B.tier_seq[0] = B.tier_seq[1] = B.tier_seq[2] = 0x7fffffff;  // (decode's split sizes: not used by prefill)
+  for (int t = 0; t < kTierSteps; ++t) B.tier_seq[t] = 0x7fffffff;  // (decode's split sizes: not used by prefill)
   B.ring_runs = 4;
   const bool generic = !mfma_supports(B);  // head_dim other than 64, 128 or 256, or blocks of fewer than 8 tokens
   if (generic && (g.head_dim & (g.head_dim - 1))) {
