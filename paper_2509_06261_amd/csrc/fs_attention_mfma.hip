@@ -110,7 +110,7 @@ __device__ __forceinline__ void stream_item(const MultiArgs& A, const ItemPlan& 
   st.l = 0.f;
   st.zc = 0.f;
 
-  stream_tiles<DT, GP, HD>(X, g, P.v0, qb, qsum, alpha, st, j, c);
+  stream_tiles<DT, GP, HD, true>(X, g, P.v0, qb, qsum, alpha, st, j, c);
 }
 
 // part_off: the batches' offsets into the partial buffer (the workspace header's words, copied to LDS once per

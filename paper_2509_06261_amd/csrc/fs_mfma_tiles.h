@@ -597,13 +597,18 @@ __device__ __forceinline__ void fill_table(uint64_t* s_ptr, const int32_t* table
 // will next occupy a slot are requested as soon as S^T of its current occupant is done, the V rows as soon
 // as P V is done, so the narrower the format the more tiles are in flight (about 16 KiB per wave for every
 // format).
-// Every step refills its slot unconditionally: past the last tile the runs are mapped
-// onto the last run (rows just read, so the refill hits in cache) and the data is never used.  With refills that depend on a
-// condition the compiler cannot know how many loads are outstanding behind the one it needs and waits for
-// all of them, the ones just issued included, which exposes the full memory latency on every tile.  For the
-// same reason the tile count is rounded up to whole rings: the surplus tiles lie past the end, are fully
-// masked and contribute zeros.
-template <int DT, int GP, int HD = 128>
+// Every step of a turn refills its slot unconditionally: in the last refilling turn some refills may lie past the
+// last tile, where the runs are mapped onto the last run (rows just read, so the refill hits in cache) and the data is
+// never used.  With refills that depend on a condition the compiler cannot know how many loads are outstanding behind
+// the one it needs and waits for all of them, the ones just issued included, which exposes the full memory latency on
+// every tile.
+// PEEL (decode): the last turn is a second copy of the step without any refill.  Then nothing is requested that no
+// one will read (a ring of rows per item), and nothing is in flight when the caller goes on to write the item's
+// result: that code reuses the tiles' registers and otherwise waits for those loads to land (a per-item timeline
+// showed 4 us per item between the last tile and the end of the output, 4 % of the mixed launch and 14 % of a short
+// one).  Without PEEL every turn refills, the last one past the item's end (runs mapped onto the last run, never used),
+// and the tile count is rounded up to whole turns of masked tiles.
+template <int DT, int GP, int HD = 128, bool PEEL = false>
 __device__ __forceinline__ void stream_tiles(const ItemCtx& X, const DevGeom& g, int v0, const u32x4 (&qb)[HD / 32], float qsum,
                                              float alpha, StateT<HD>& st, int j, int c) {
   constexpr int NBUF = Fmt<DT, HD>::kRing;
@@ -614,9 +619,11 @@ __device__ __forceinline__ void stream_tiles(const ItemCtx& X, const DevGeom& g,
     issue_k<DT, GP, HD>(X, v0 + bi * 4, j, c, t[bi]);
     issue_v<DT, GP, HD>(X, g, v0 + bi * 4, j, c, t[bi]);
   });
-  // One turn of the ring: every slot's tile is consumed and replaced by the tile NBUF further on.  (The last turn's
-  // refills lie past the item's end: mapped onto its last run, served from cache, never consumed.)
-  for (int k0 = 0; k0 < n_tiles; k0 += NBUF) {
+  // One turn of the ring: every slot's tile is consumed and replaced by the tile NBUF further on.
+  // (not for INT4, nor INT8 at head_dim 64: with the second copy of the step their tile loops spill registers)
+  constexpr bool kPeel = PEEL && DT != FS_KV_INT4 && !(DT == FS_KV_INT8 && HD == 64);
+  int k0 = 0;
+  for (; k0 + (kPeel ? NBUF : 0) < n_tiles; k0 += NBUF) {
     static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
       constexpr int bi = decltype(Bi)::value;
       const int vb = v0 + (k0 + bi) * 4;
@@ -626,6 +633,17 @@ __device__ __forceinline__ void stream_tiles(const ItemCtx& X, const DevGeom& g,
       issue_k<DT, GP, HD>(X, vb_next, j, c, t[bi]);
       softmax_pv<DT, GP, HD>(X, t[bi], s, vb, j, c, qsum, alpha, st);
       issue_v<DT, GP, HD>(X, g, vb_next, j, c, t[bi]);
+    });
+  }
+  // the last turn: the 1 .. NBUF tiles that are left, no refills (slots past the last tile hold rows nobody needs)
+  if constexpr (kPeel) {
+    static_for(std::make_integer_sequence<int, NBUF>{}, [&](auto Bi) {
+      constexpr int bi = decltype(Bi)::value;
+      if (bi == 0 || k0 + bi < n_tiles) {  // wave-uniform
+        float4v s[2];
+        qk_tile<DT, GP, HD>(t[bi], qb, s);
+        softmax_pv<DT, GP, HD>(X, t[bi], s, v0 + (k0 + bi) * 4, j, c, qsum, alpha, st);
+      }
     });
   }
 }

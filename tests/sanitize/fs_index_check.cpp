@@ -95,7 +95,8 @@ void check_batch(const fs::DevBatch& B, const std::vector<int32_t>& lens) {
       X.k0 = r.k0;
       const int n_tiles = (r.v1 - r.v0 + 3) >> 2;
       const int turns = (n_tiles + ring - 1) / ring;
-      // tiles consumed: turns * ring; tiles requested: one ring more (the last turn's refills)
+      // tiles consumed: at most turns * ring (the surplus ones of the last turn keep nothing); tiles requested: at
+      // most one ring more (the last turn's refills, which the formats with a refill-free last turn leave out)
       for (int tile = 0; tile < (turns + 1) * ring; ++tile) {
         ++g_tiles;
         const int vb = r.v0 + 4 * tile;
