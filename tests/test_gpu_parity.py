@@ -351,6 +351,49 @@ def test_one_call_over_models_of_different_head_dim(mode):
         par.close()
 
 
+def test_kernel_timing_option_changes_nothing_but_the_clock():
+    """FS_OPT_KERNEL_TIMING: events around the attention kernel (one launch, the vector-ALU
+    kernel, and a call of several launch sequences); outputs are bit-identical to the untimed call's and the reading is
+    positive and below the wall-clock time around the call."""
+    import time
+
+    import torch
+
+    lens = np.array([3, 200, 777, 1500], np.int32)
+    one = Workload("timed-one", 64 * KiB, 32 * MiB, [ModelSpec("a", INT8, 2, 128, 1, 8, lens, tag=57)], "shuffle")
+    mix = Workload("timed-mix", 64 * KiB, 96 * MiB,
+                   [ModelSpec("a", FP16, 2, 64, 1, 8, lens, tag=58), ModelSpec("b", INT8, 2, 128, 1, 8, lens, tag=59),
+                    ModelSpec("c", FP8, 1, 256, 1, 2, lens, tag=60)], "interleave")
+    for wl, modes in ((one, (0, 1)), (mix, (0,))):
+        par = _parity(wl)
+        fs, gw = par.fs, par.gw
+        try:
+            for mode in modes:
+                layers = [0] * len(wl.models)
+                keep = par.populate_and_decode(layers, kernel_mode=mode)
+                plain = [o.clone() for o in keep["out"]]
+                gw.set_option(fs.FS_OPT_DECODE_KERNEL, mode)
+                gw.set_option(fs.FS_OPT_KERNEL_TIMING, 1)
+                try:
+                    batches, keep2 = gw.make_batches(layers)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    ws = gw.decode(batches)
+                    ms = fs.fs_pool_last_attention_kernel_ms(gw.pool)
+                    torch.cuda.synchronize()
+                    wall_ms = (time.perf_counter() - t0) * 1e3
+                    assert fs.fs_decode_status(ws) == 0
+                finally:
+                    gw.set_option(fs.FS_OPT_KERNEL_TIMING, 0)
+                    gw.set_option(fs.FS_OPT_DECODE_KERNEL, 0)
+                print(f"{wl.name} mode {mode}: kernel {ms * 1e3:.1f} us, wall {wall_ms * 1e3:.1f} us")
+                assert 0.0 < ms < wall_ms
+                for a, b in zip(plain, keep2["out"]):
+                    assert torch.equal(a, b)
+        finally:
+            par.close()
+
+
 def test_one_call_over_shapes_inside_and_outside_the_mfma_kernel():
     """Models the MFMA kernel covers (head_dim 128 and 64) beside models it does not (head_dim 512 and 32) in one call:
     the covered ones keep the MFMA kernel (one launch sequence per head_dim), the others share a launch sequence on
