@@ -1039,9 +1039,11 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) settle_q(qb[cb]);
     for (int i = 0; i < n_super; ++i) {
-      // next step's sub-tile of this wave (past the segment's end: mapped onto its last run, never used)
+      // next step's sub-tile of this wave; the segment's last step fetches and stages nothing (the wait in stage_to
+      // is for this step's fetch alone, so the condition costs the compiler's wait counts nothing)
       const int vb_next = v0 + (i + 1) * 4 * SUBS + 4 * sw;
-      fetch(vb_next);
+      const bool more = i + 1 < n_super;  // wave-uniform
+      if (more) fetch(vb_next);
       const uint8_t* stage = smem + (uint32_t)(i & 1) * stage_bytes(SUBS);
       // A wave with query tokens multiplies every sub-tile of the step, also those past its own diagonal or past
       // the segment's end (fully masked there: weights 0 over finite operands; at most two per item).  A wave
@@ -1054,8 +1056,8 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
                                          st, whole_runs);
       }
       uint8_t* next = smem + (uint32_t)((i + 1) & 1) * stage_bytes(SUBS);
-      stage_to(next, vb_next);
-      __syncthreads();
+      if (more) stage_to(next, vb_next);
+      __syncthreads();  // (also after the last step: the next staging overwrites what other waves may still read)
     }
   }
   if (n_tok == 0) return;
