@@ -17,6 +17,9 @@
 // have; and a table segment of a context never touches more blocks than the wave's address table holds.
 // The decode work queue's closed-form placement (queue_place: the batches' item lists merged proportionally) is
 // checked to be one-to-one onto the queue and order-preserving within a batch.
+// The vector-ALU kernel's launch is replayed where the device's lengths are not the ones the host sized the workspace
+// for: what is queued, every queued item's tokens and table entries, the partial records and the combine's rows stay
+// inside the plan's capacities or are the ones the kernels skip and report.
 #include <algorithm>
 #include <cstdint>
 #include <cstdio>
@@ -284,12 +287,130 @@ void decode_queue_places(int rounds) {
   }
 }
 
+
+// The vector-ALU kernel's launch when the lengths on the device are not the ones the host sized the workspace for
+// (longer, far out of range, zero): the work list, the kernel's item loop and the combine are replayed with the plan's
+// own capacities -- what the work-list kernel would count, where every queued item's tokens, table entries and partial
+// record lie, and which rows the combine reads.  Everything stays inside its buffer, or the item / row is one of
+// those the kernels skip and report.
+void token_split_overflow(int rounds) {
+  const int dtypes[4] = {FS_KV_FP16, FS_KV_FP8_E4M3, FS_KV_INT8, FS_KV_INT4};
+  const int dims[5] = {32, 64, 128, 256, 512};
+  for (int round = 0; round < rounds; ++round) {
+    const uint64_t slab = 64 << 10;
+    fs_pool* p = nullptr;
+    CHECK(fs_pool_create(slab, 2048 * slab, kFakeBase, &p) == FS_OK);
+    if (!p) continue;
+    const int nb = 1 + rnd_int(4);
+    fs_batch_t b[4] = {};
+    std::vector<int32_t> host[4], dev[4];
+    bool ok = true;
+    for (int k = 0; k < nb; ++k) {
+      const int dtype = dtypes[rnd_int(4)], D = dims[rnd_int(5)], H = 1 + rnd_int(2);
+      fs_model_t m;
+      const int T = fs_model_register(p, dtype, H, D, 1 + rnd_int(2), &m);
+      ok = ok && T > 0;
+      if (!ok) break;
+      const int n_seq = 1 + rnd_int(5);
+      int max_len = 1;
+      for (int i = 0; i < n_seq; ++i) {
+        host[k].push_back(1 + rnd_int(rnd_int(3) ? 300 : 2000));
+        max_len = std::max(max_len, (int)host[k].back());
+      }
+      dev[k] = host[k];
+      if (round % 3)  // the device disagrees on some sequences
+        for (int i = 0; i < n_seq; ++i)
+          if (rnd_int(2)) dev[k][i] = rnd_int(4) == 0 ? 1000000 : (rnd_int(4) == 0 ? -rnd_int(2) : 1 + rnd_int(3 * max_len));
+      const int G[5] = {1, 2, 4, 8, 16};
+      b[k].model = m;
+      b[k].layer = 0;
+      b[k].n_q_heads = H * G[rnd_int(5)];
+      b[k].sm_scale = 0.1f;
+      b[k].q = (const void*)0x20000000;
+      b[k].block_tables = (const int32_t*)0x30000000;
+      b[k].seq_lens = (const int32_t*)0x40000000;
+      b[k].seq_lens_host = rnd_int(3) ? host[k].data() : nullptr;
+      b[k].n_seq = n_seq;
+      b[k].max_blocks = (max_len + T - 1) / T + rnd_int(2);
+      b[k].out = (void*)0x50000000;
+    }
+    if (ok) {
+      CHECK(fs_pool_set_option(p, FS_OPT_DECODE_KERNEL, 1) == FS_OK);
+      const int64_t split[3] = {0, 8 << 10, 24 << 10};
+      CHECK(fs_pool_set_option(p, FS_OPT_SPLIT_BYTES, split[rnd_int(3)]) == FS_OK);
+      fs::MultiArgs A{};
+      bool use_mfma = true;
+      CHECK(fs::debug_plan(p, b, nb, &A, &use_mfma) == FS_OK);
+      CHECK(!use_mfma);
+      // the work-list kernel: items per batch from the device's (clamped) lengths
+      uint32_t count[fs::kMaxBatches] = {0, 0, 0, 0, 0, 0, 0, 0};
+      std::vector<int> clen[4];
+      for (int k = 0; k < nb; ++k) {
+        const fs::DevBatch& B = A.b[k];
+        CHECK(B.chunk_runs == 0);
+        const int max_len = (int)std::min<int64_t>((int64_t)B.max_blocks * B.g.T, 0x7fffffff);
+        for (int i = 0; i < B.n_seq; ++i) {
+          const int l = dev[k][i] < 1 ? 1 : std::min((int)dev[k][i], max_len);
+          clen[k].push_back(l);
+          count[k] += (uint32_t)fs::n_splits(B, i, l) * (uint32_t)B.g.H;
+        }
+      }
+      uint64_t total = 0, part_off[4] = {0, 0, 0, 0}, running = 0;
+      for (int k = 0; k < nb; ++k) {
+        part_off[k] = running;
+        running += (uint64_t)count[k] * (uint64_t)A.b[k].part_stride;
+        total += count[k];
+      }
+      const bool same = [&] { for (int k = 0; k < nb; ++k) if (!b[k].seq_lens_host || dev[k] != host[k]) return false; return true; }();
+      // (the workspace is sized for the larger of the two kernels' split rules)
+      if (same) CHECK(total <= A.item_capacity && running <= A.part_capacity);
+      const uint64_t queued = std::min<uint64_t>(total, A.item_capacity);
+      std::vector<uint8_t> hit(total, 0);
+      for (int k = 0; k < nb; ++k) {
+        const fs::DevBatch& B = A.b[k];
+        uint64_t local = 0;
+        for (int i = 0; i < B.n_seq; ++i) {
+          const int len = clen[k][i], ct = fs::chunk_tokens_of(B, i), n_chunks = fs::n_splits(B, i, len);
+          const uint64_t first_local = local;
+          for (int chunk = 0; chunk < n_chunks; ++chunk)
+            for (int head = 0; head < B.g.H; ++head, ++local) {
+              ++g_items;
+              const uint64_t at = fs::queue_place(local, k, count);
+              CHECK(at < total && hit[at] == 0);
+              if (at < total) hit[at] = 1;
+              if (at >= queued) continue;  // not queued: the launch reports the overflow
+              // the item as the vector-ALU kernel walks it
+              const int t0 = chunk * ct, t1 = std::min(len, t0 + ct);
+              CHECK(t0 < t1);
+              CHECK((t1 - 1) / B.g.T < B.max_blocks);
+              const uint64_t part_base = part_off[k] + local * (uint64_t)B.part_stride;
+              if (same) CHECK(n_chunks == 1 || part_base + (uint64_t)B.part_stride <= A.part_capacity);
+            }
+          // the combine's rows of this sequence
+          if (n_chunks > 1)
+            for (int h = 0; h < B.n_q; ++h) {
+              const int kvh = h / B.G, gq = h % B.G;
+              const uint64_t base = part_off[k] + first_local * (uint64_t)B.part_stride;
+              const uint64_t last = base + (uint64_t)((uint32_t)(n_chunks - 1) * B.g.H + kvh) * B.part_stride + (uint64_t)(gq + 1) * (B.g.D + 2);
+              if (same) CHECK(last <= A.part_capacity);  // (otherwise: read only if it lies inside, the kernel's own test)
+              CHECK(base <= last);
+            }
+        }
+        CHECK(local == count[k]);
+      }
+      for (uint64_t at = 0; at < total; ++at) CHECK(hit[at] == 1);
+    }
+    fs_pool_destroy(p);
+  }
+}
+
 }  // namespace
 
 int main() {
   run(600);
   prefill_queues(60);
   decode_queue_places(200);
+  token_split_overflow(400);
   std::printf("fs_index_check: %ld items, %ld tiles, %ld failed checks\n", g_items, g_tiles, g_failures);
   return g_failures ? 1 : 0;
 }
