@@ -19,7 +19,8 @@ FS_OK, FS_ERR_INVALID, FS_ERR_NOMEM, FS_ERR_STATE, FS_ERR_DEVICE = 0, -1, -2, -3
 FS_SLAB_FREE, FS_SLAB_PARTIAL, FS_SLAB_FULL = 0, 1, 2
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_DIR, "libfineserve.so")
+# FINESERVE_LIBRARY: another build of the same library (bench_timeline.py sets it to the profiling twin)
+LIB_PATH = os.environ.get("FINESERVE_LIBRARY") or os.path.join(_DIR, "libfineserve.so")
 
 EXPORTS = ["fs_pool_create", "fs_pool_destroy", "fs_pool_base", "fs_model_register", "fs_model_register_ex",
            "fs_block_bytes", "fs_slab_bytes_for_blocks", "fs_model_register_tokens",

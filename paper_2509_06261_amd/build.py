@@ -20,14 +20,19 @@ FLAGS += os.environ.get("FS_EXTRA_HIPCC_FLAGS", "").split()  # experiments only
 FILE_FLAGS = {"fs_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
-def build(verbose: bool = False) -> str:
+TIMELINE_LIB = os.path.join(_DIR, "libfineserve_timeline.so")
+
+
+def build(verbose: bool = False, timeline: bool = False) -> str:
+    """The library; timeline=True: its profiling twin libfineserve_timeline.so (-DFS_TIMELINE: the decode kernel
+    leaves clock readings at the end of the workspace; what bench_timeline.py loads, never the product path)."""
     csrc = os.path.join(_DIR, "csrc")
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(csrc, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), "-I", os.path.join(ROOT, "include"), "-I", csrc, "-c",
-               os.path.join(csrc, src), "-o", obj]
+        obj = os.path.join(csrc, src.replace(".hip", ".timeline.o" if timeline else ".o"))
+        cmd = [HIPCC, *FLAGS, *(["-DFS_TIMELINE"] if timeline else []), *FILE_FLAGS.get(src, []), "-I",
+               os.path.join(ROOT, "include"), "-I", csrc, "-c", os.path.join(csrc, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -39,9 +44,12 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", LIB, *objs], check=True)
-    return LIB
+    lib = TIMELINE_LIB if timeline else LIB
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-o", lib, *objs], check=True)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+
+    print(build(verbose=True, timeline="--timeline" in sys.argv[1:]))

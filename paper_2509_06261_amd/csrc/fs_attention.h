@@ -79,6 +79,16 @@ __device__ __host__ inline int4 make_rec(int batch, int seq, int split, int head
 __device__ __host__ inline int rec_batch(const int4& r) { return r.x & 15; }
 __device__ __host__ inline int rec_head(const int4& r) { return r.x >> 4; }
 
+// Timeline build (-DFS_TIMELINE, bench_timeline.py; never the product library): the MFMA decode kernel leaves clock
+// readings in a block at the end of the workspace, which fs_decode_workspace_bytes then includes.  Rows of eight
+// 64-bit words: kTimelineWaves rows of waves (start, end, items, XCD), then kTimelineItems rows of work items, by
+// queue index (draw resolved, address table ready, last tile done, output written, wave | batch << 32 | tier << 40,
+// runs | sequence << 32).  Clock: the 100 MHz constant clock.
+#ifdef FS_TIMELINE
+constexpr uint64_t kTimelineWaves = 4096, kTimelineItems = 1ull << 17;
+constexpr uint64_t kTimelineBytes = 64 * (kTimelineWaves + kTimelineItems);
+#endif
+
 struct MultiArgs {
   DevBatch b[kMaxBatches];
   uint32_t* header;
@@ -94,6 +104,9 @@ struct MultiArgs {
   int32_t n_seq_total;
   int32_t n_qrows_total;
   int32_t pad;
+#ifdef FS_TIMELINE
+  uint64_t* timeline;
+#endif
 };
 
 // Work item r of a sequence with n_chunks splits and H KV heads: chunk = r / H, head = r % H, so the heads

@@ -500,6 +500,11 @@ int make_plan(fs_pool* p, const fs_batch_t* batches, int n_batches, void* worksp
   const uint64_t off_part = align256(off_list + 32ull * plan.ub_items);
   A.item_capacity = (uint32_t)plan.ub_items;
   plan.workspace_bytes = align256(off_part + 4ull * part_floats);
+#ifdef FS_TIMELINE
+  const uint64_t off_timeline = plan.workspace_bytes;
+  plan.workspace_bytes += kTimelineBytes;
+  if (workspace) A.timeline = (uint64_t*)((uint8_t*)workspace + off_timeline);
+#endif
   if (workspace) {
     uint8_t* w = (uint8_t*)workspace;
     A.header = (uint32_t*)w;
@@ -736,6 +741,15 @@ float fs_pool_last_attention_kernel_ms(fs_pool* p) {
   if (hipEventElapsedTime(&ms, p->opt.ev0, p->opt.ev1) != hipSuccess) return -1.0f;
   return ms;
 }
+
+#ifdef FS_TIMELINE
+// (timeline build only) bytes of the clock readings at the end of a launch's workspace, and their layout
+uint64_t fs_timeline_bytes(uint64_t* wave_rows, uint64_t* item_rows) {
+  if (wave_rows) *wave_rows = kTimelineWaves;
+  if (item_rows) *item_rows = kTimelineItems;
+  return kTimelineBytes;
+}
+#endif
 
 uint64_t fs_decode_workspace_bytes(fs_pool* p, const fs_batch_t* batches, int n_batches) {
   HeadDimGroups G;

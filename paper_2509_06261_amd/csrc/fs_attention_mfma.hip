@@ -229,6 +229,10 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   if (threadIdx.x < kMaxBatches) s_part_off[threadIdx.x] = reinterpret_cast<const uint64_t*>(A.header + kHdrPartOff)[threadIdx.x];
   __syncthreads();
   const uint32_t total = A.header[kHdrTotalItems];
+#ifdef FS_TIMELINE
+  const uint64_t tl_start = wall_clock64();
+  uint64_t tl_items = 0;
+#endif
   // Every wave is its own worker and draws its items from kDecodePools ticket counters: pool p holds the items
   // p, p + kDecodePools, ... of the queue.  Waves that get short items, or sit on a faster compute unit, simply
   // draw more often; with a fixed deal (wave w takes items w, w + n_workers, ...) the slowest wave was
@@ -286,16 +290,46 @@ __global__ __launch_bounds__(kThreads, mfma_wgs_per_cu(HD)) void mfma_attention_
   for (;;) {
     const uint32_t item = resolve();
     if (item == kNone) break;  // every wave leaves here, once all pools are empty
+#ifdef FS_TIMELINE
+    const uint64_t tl_begin = wall_clock64();
+#endif
     if (in_turn) pool = (pool + 1) % kDecodePools;
     draw();                    // the next ticket, answered while this item streams
     const ItemPlan P = plan_item(A, load_rec(item));
     int32_t tab[kTabRegs];
     load_entries(A, P, lane, tab);
     store_table(A, P, lane, tab, s_ptr);
+#ifdef FS_TIMELINE
+    const uint64_t tl_table = wall_clock64();
+    ++tl_items;
+#endif
     StateT<HD> st;
     dispatch_item<0, HD>(A, P, s_ptr, st, s_part_off);
+#ifdef FS_TIMELINE
+    const uint64_t tl_tiles = wall_clock64();
+#endif
     dispatch_item<1, HD>(A, P, s_ptr, st, s_part_off);
+#ifdef FS_TIMELINE
+    if (lane == 0 && item < kTimelineItems) {
+      uint64_t* row = A.timeline + 8 * (kTimelineWaves + item);
+      row[0] = tl_begin;
+      row[1] = tl_table;
+      row[2] = tl_tiles;
+      row[3] = wall_clock64();
+      row[4] = (uint64_t)(blockIdx.x * kWaves + wave) | ((uint64_t)P.b << 32) | ((uint64_t)tier_of(A.b[P.b], P.seq) << 40);
+      row[5] = (uint64_t)(P.v1 - P.v0) | ((uint64_t)P.seq << 32);
+    }
+#endif
   }
+#ifdef FS_TIMELINE
+  if (lane == 0 && blockIdx.x * kWaves + wave < kTimelineWaves) {
+    uint64_t* row = A.timeline + 8 * (blockIdx.x * kWaves + wave);
+    row[0] = tl_start;
+    row[1] = wall_clock64();
+    row[2] = tl_items;
+    row[3] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7;  // hwreg(HW_REG_XCC_ID, 0, 4)
+  }
+#endif
 }
 
 }  // namespace

@@ -302,3 +302,23 @@ def test_model_stats_count_slabs_per_key():
             fs.fs_model_stats(p, 7)
     finally:
         fs.fs_pool_destroy(p)
+
+
+def test_timeline_readings_are_in_the_profiling_twin_only():
+    """The product library carries no timeline code (no fs_timeline_bytes); the twin that bench_timeline.py loads does,
+    and exports everything the header declares as well."""
+    import ctypes
+    import os
+
+    import paper_2509_06261_amd as fs
+    from paper_2509_06261_amd import binding
+
+    assert not hasattr(binding._L, "fs_timeline_bytes")
+    twin = os.path.join(os.path.dirname(binding.LIB_PATH), "libfineserve_timeline.so")
+    if not os.path.exists(twin):
+        pytest.skip("the profiling twin is not built (python paper_2509_06261_amd/build.py --timeline)")
+    T = ctypes.CDLL(twin)
+    T.fs_timeline_bytes.restype = ctypes.c_uint64
+    assert T.fs_timeline_bytes(None, None) > 0
+    for name in fs.binding.EXPORTS:
+        assert hasattr(T, name), name
