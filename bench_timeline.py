@@ -10,6 +10,9 @@ streaming, output, pauses between items and idling at the end, how long items of
 tiers start.  The product library is never touched; the readings cost the kernel about 1 %.
 
     python bench_timeline.py [config ...]        (default: 5 2 4)
+    python bench_timeline.py --prefill [config ...]   the prefill workgroup kernel instead (default: 2 4): per workgroup
+        its start and end and the summed phases of its items, per item its begin and end; whole-prompt prefill as
+        bench_prefill.py launches it, the last launch read back
 """
 import os
 import sys
@@ -19,6 +22,66 @@ TWIN = os.path.join(ROOT, "paper_2509_06261_amd", "libfineserve_timeline.so")
 os.environ["FINESERVE_LIBRARY"] = TWIN  # before the package is imported
 sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+
+def prefill(configs):
+    import ctypes
+
+    import numpy as np
+    import torch  # noqa: F401
+
+    import bench_prefill
+    import paper_2509_06261_amd as fs
+    from paper_2509_06261_amd import binding
+
+    group_rows, item_rows = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    binding._L.fs_prefill_timeline_bytes.restype = ctypes.c_uint64
+    tl_bytes = int(binding._L.fs_prefill_timeline_bytes(ctypes.byref(group_rows), ctypes.byref(item_rows)))
+    group_rows = int(group_rows.value)
+    seen = {}
+    plain = fs.fs_prefill_attention
+
+    def watched(*a, **k):  # the workspace is the call's last argument: clear its readings, remember it
+        ws = a[-1]
+        ws[ws.numel() - tl_bytes:].zero_()
+        seen["ws"] = ws
+        return plain(*a, **k)
+
+    fs.fs_prefill_attention = binding.fs_prefill_attention = watched
+    pct = lambda x, p: np.percentile(x, p).round(1)
+    for cfg in configs:
+        sys.argv = ["bench_prefill.py", "--config", str(cfg), "--no-cpu-baseline", "--steps", "2", "--warmup", "1"]
+        try:
+            bench_prefill.main()
+        except SystemExit:
+            pass
+        ws = seen["ws"]
+        rows = ws[ws.numel() - tl_bytes:].cpu().numpy().view(np.uint64).reshape(-1, 8)
+        groups, items = rows[:group_rows], rows[group_rows:]
+        groups, items = groups[groups[:, 0] != 0], items[items[:, 0] != 0]
+        t0 = int(groups[:, 0].min())
+        us = lambda x: (x.astype(np.int64) - t0) / 100.0
+        g_end = us(groups[:, 1])
+        span = float(g_end.max())
+        begin, end = us(items[:, 0]), us(items[:, 1])
+        qt = (items[:, 2] & 0xfffff).astype(np.int64)
+        seq = (items[:, 2] >> 32).astype(np.int64)
+        draw = (items[:, 3] >> 32).astype(np.float64) / 100.0
+        dur = end - begin
+        total = len(groups) * span
+        ph = groups[:, 4:8].astype(np.float64).sum(axis=0) / 100.0
+        n = len(items)
+        fit, *_ = np.linalg.lstsq(np.vstack([np.ones(n), qt + 1]).T, dur, rcond=None)
+        print(f"prefill, config {cfg}: {len(groups)} workgroups, {n} work items (sequence, KV head, query tile), launch {span:.1f} us")
+        print(f"  workgroups end p0/p10/p50/p90/p100 {pct(g_end, [0, 10, 50, 90, 100])}; idle at the end {100 * float(np.sum(span - g_end)) / total:.1f} % "
+              f"of the workgroups' time, inside items {100 * float(dur.sum()) / total:.1f} %, draw and its barriers {100 * float(draw.sum()) / total:.1f} % "
+              f"({pct(draw, 50)} us per item)")
+        print(f"  an item takes {pct(dur, 50)} ({pct(dur, 10)}-{pct(dur, 90)}) us; least squares: {fit[0]:.2f} us + {fit[1]:.3f} us x (query tile index + 1); "
+              f"the fixed part is {100 * fit[0] * n / total:.1f} % of the workgroups' time")
+        names = ["entry -> address table in LDS", "-> first sub-tiles staged", "-> last step done", "-> output written"]
+        print("  phases per item (summed by the workgroups' first threads): " + ", ".join(f"{names[k]} {ph[k] / n:.2f} us" for k in range(4)))
+        late = np.argsort(-end)[:3]
+        print("  last items to end: " + "; ".join(f"sequence {seq[i]} tile {qt[i]}: {begin[i]:.0f} -> {end[i]:.0f} us" for i in late))
 
 
 def main():
@@ -33,6 +96,8 @@ def main():
         fs_build = importlib.util.module_from_spec(spec)
         spec.loader.exec_module(fs_build)
         fs_build.build(timeline=True)
+    if "--prefill" in sys.argv[1:]:
+        return prefill([int(a) for a in sys.argv[1:] if a != "--prefill"] or [2, 4])
     import torch
 
     import bench

@@ -42,7 +42,20 @@ struct PrefillArgs {
   int32_t tf_cache;          // workgroup kernels: 1 = tile_first is copied into LDS at kernel start
   int32_t whole_runs;        // 1 = tokens per block is a multiple of 8: run r starts at token 8 r, no run is shifted
   int32_t chunk_shift;       // workgroup kernels: log2 of the consecutive work items that go to one XCD
+#ifdef FS_TIMELINE
+  uint64_t* timeline;        // (timeline build) clock readings of the workgroup kernels, at the end of the workspace
+#endif
 };
+
+// Timeline build (-DFS_TIMELINE, bench_timeline.py; never the product library): the workgroup kernels leave clock
+// readings at the end of the workspace, which fs_prefill_workspace_bytes then includes.  Rows of eight 64-bit words:
+// kPfTimelineGroups rows of workgroups (start, end, items, XCD, then the items' summed phases: entry -> address table
+// in LDS, -> first sub-tiles staged, -> last step done, -> output written), then kPfTimelineItems rows of work items
+// by item index (begin, end, sequence << 32 | KV head << 20 | query tile, workgroup | draw-and-barriers time << 32).
+#ifdef FS_TIMELINE
+constexpr uint64_t kPfTimelineGroups = 1024, kPfTimelineItems = 1ull << 18;
+constexpr uint64_t kPfTimelineBytes = 64 * (kPfTimelineGroups + kPfTimelineItems);
+#endif
 
 constexpr int kPrepThreads = 1024;
 
@@ -940,6 +953,9 @@ __device__ __forceinline__ void wg_tile(const uint8_t* stage, int sub, const Ite
 template <int DT, int NW, int NCB, int SUBS, bool DEQ = false>
 __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt, uint8_t* smem, uint64_t* s_tab, int w) {
   static_assert(NW == SUBS || NW == 2 * SUBS, "staging roles");
+#ifdef FS_TIMELINE
+  uint64_t tl_ph[5] = {(uint64_t)wall_clock64(), 0, 0, 0, 0};
+#endif
   static_assert(!DEQ || Fmt<DT>::kParBytes != 0, "staged dequantization is for the formats with per-token parameters");
   constexpr int CDT = DEQ ? FS_KV_FP16 : DT;  // the format the consumer code sees
   // V fragments read ahead of the softmax: what the format's register budget leaves room for (two waves per SIMD)
@@ -1011,6 +1027,9 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       for (int i = threadIdx.x; i < nb; i += NW * 64)
         s_tab[i] = reinterpret_cast<uint64_t>(head_base + (uint64_t)checked_block(table[X.k0 + i], B.n_blocks, P.header) * g.block_budget);
       __syncthreads();
+#ifdef FS_TIMELINE
+      if (v0 == 0) tl_ph[1] = wall_clock64();
+#endif
     }
     const int n_super = (X.v_end - v0 + 4 * SUBS - 1) / (4 * SUBS);
     Tile<DT, 16> t;
@@ -1035,6 +1054,9 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
     fetch(v0 + 4 * sw);
     stage_to(smem, v0 + 4 * sw);
     __syncthreads();
+#ifdef FS_TIMELINE
+    if (v0 == 0) tl_ph[2] = wall_clock64();
+#endif
     // the query operands' loads, issued before the table and the first K/V fetch, are collected here
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) settle_q(qb[cb]);
@@ -1060,6 +1082,9 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       __syncthreads();  // (also after the last step: the next staging overwrites what other waves may still read)
     }
   }
+#ifdef FS_TIMELINE
+  tl_ph[3] = wall_clock64();
+#endif
   if (n_tok == 0) return;
 
   const float v_static = DT == FS_KV_FP8_E4M3 ? B.v_scale[head] : 1.0f;
@@ -1101,6 +1126,13 @@ __device__ void prefill_item_wg(const PrefillArgs& P, int seq, int head, int qt,
       }
     }
   }
+#ifdef FS_TIMELINE
+  if (threadIdx.x == 0 && blockIdx.x < kPfTimelineGroups) {
+    uint64_t* row = P.timeline + 8 * blockIdx.x;
+    tl_ph[4] = wall_clock64();
+    for (int k = 0; k < 4; ++k) row[4 + k] += tl_ph[k + 1] - tl_ph[k];
+  }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1439,9 +1471,16 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
     __syncthreads();
     tf = s_tf;
   }
+#ifdef FS_TIMELINE
+  const uint64_t tl_start = wall_clock64();
+  uint64_t tl_items = 0;
+#endif
   ItemDraw d{0u, 0u};
   if (wave == 0) d = first_draw(P.header, blockIdx.x >> 3, lane);
   for (;;) {
+#ifdef FS_TIMELINE
+    const uint64_t tl_top = wall_clock64();
+#endif
     if (wave == 0) {  // one wave draws for the workgroup
       uint32_t item;
       const bool ok = next_item(d, P.header, total, (uint32_t)P.chunk_shift, lane, item);
@@ -1453,9 +1492,31 @@ __global__ __launch_bounds__(NW * 64, WPC) void prefill_wg_kernel(PrefillArgs P)
     if (item == 0xffffffffu) break;
     int seq, head, qt;
     if (!decode_item(P, tf, item, H, seq, head, qt)) continue;
+#ifdef FS_TIMELINE
+    const uint64_t tl_begin = wall_clock64();
+#endif
     if constexpr (PIPE) prefill_item_wgp<DT>(P, seq, head, qt, smem, s_tab, wave);
     else prefill_item_wg<DT, NW, NCB, SUBS, DEQ>(P, seq, head, qt, smem, s_tab, wave);
+#ifdef FS_TIMELINE
+    ++tl_items;
+    if (threadIdx.x == 0 && item < kPfTimelineItems) {
+      uint64_t* row = P.timeline + 8 * (kPfTimelineGroups + item);
+      row[0] = tl_begin;
+      row[1] = wall_clock64();
+      row[2] = ((uint64_t)seq << 32) | ((uint64_t)head << 20) | (uint64_t)qt;
+      row[3] = (uint64_t)blockIdx.x | ((tl_begin - tl_top) << 32);
+    }
+#endif
   }
+#ifdef FS_TIMELINE
+  if (threadIdx.x == 0 && blockIdx.x < kPfTimelineGroups) {
+    uint64_t* row = P.timeline + 8 * blockIdx.x;
+    row[0] = tl_start;
+    row[1] = wall_clock64();
+    row[2] = tl_items;
+    row[3] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7;  // hwreg(HW_REG_XCC_ID, 0, 4)
+  }
+#endif
 }
 
 // The 16-column kernel; the only MFMA prefill kernel for head_dim 64 and 256 (HD: its tile code takes any of the three).
@@ -1488,9 +1549,22 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 
 using namespace fs;
 
+#ifdef FS_TIMELINE
+// (timeline build only) bytes of the clock readings at the end of a prefill workspace, and their layout
+extern "C" uint64_t fs_prefill_timeline_bytes(uint64_t* group_rows, uint64_t* item_rows) {
+  if (group_rows) *group_rows = kPfTimelineGroups;
+  if (item_rows) *item_rows = kPfTimelineItems;
+  return kPfTimelineBytes;
+}
+#endif
+
 uint64_t fs_prefill_workspace_bytes(int n_seq) {
   if (n_seq < 1) return 0;
+#ifdef FS_TIMELINE
+  return align256(kHeaderBytes + 4ull * ((uint64_t)n_seq + 1)) + kPfTimelineBytes;
+#else
   return align256(kHeaderBytes + 4ull * ((uint64_t)n_seq + 1));
+#endif
 }
 
 int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads, float sm_scale, const void* q,
@@ -1592,6 +1666,9 @@ int fs_prefill_attention(fs_pool* p, fs_model_t model, int layer, int n_q_heads,
   P.q_offsets = q_offsets;
   P.header = (uint32_t*)workspace;
   P.tile_first = (uint32_t*)((uint8_t*)workspace + kHeaderBytes);
+#ifdef FS_TIMELINE
+  P.timeline = (uint64_t*)((uint8_t*)workspace + align256(kHeaderBytes + 4ull * ((uint64_t)n_seq + 1)));
+#endif
   P.tpt = tpt;
   P.ncb = ncb;
   P.seg_runs = prefill_seg_runs(B.R);
